@@ -1,0 +1,97 @@
+"""An independent decoder forward built from PyTorch CPU library routines in fp64
+(F.rms_norm, F.scaled_dot_product_attention, F.silu, matmul, complex multiply for
+the rotary embedding).  It recomputes the whole sequence from scratch, with no KV
+cache and no row-by-row loop, so it shares neither code nor structure with the
+oracle; tests use it to pin the oracle's forward.
+"""
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+import oracle as O
+
+
+def np_round_bf16(x):
+    b = np.ascontiguousarray(x, dtype=np.float64).view(np.uint64)
+    drop = np.uint64(45)
+    lsb = (b >> drop) & np.uint64(1)
+    r = b + ((np.uint64(1) << np.uint64(44)) - np.uint64(1)) + lsb
+    r &= ~((np.uint64(1) << drop) - np.uint64(1))
+    return r.view(np.float64)
+
+
+def _rnd(t, bf16):
+    if not bf16:
+        return t
+    return torch.from_numpy(np_round_bf16(t.numpy()).reshape(tuple(t.shape)))
+
+
+def weights_of(model: O.Model):
+    c = model.cfg
+    d, hd, H, Hkv, Fd, V = c.d_model, c.head_dim, c.n_q_heads, c.n_kv_heads, c.d_ffn, c.vocab
+
+    def t(tid, layer, shape):
+        return torch.from_numpy(model.tensor(tid, layer).astype(np.float64).reshape(shape))
+
+    W = dict(emb=t(O.T_EMB, 0, (V, d)), lm=t(O.T_LM, 0, (V, d)), gf=t(O.T_GF, 0, (d,)), layers=[])
+    for l in range(c.n_layers):
+        W["layers"].append(dict(
+            g1=t(O.T_G1, l, (d,)), wq=t(O.T_WQ, l, (H * hd, d)), wk=t(O.T_WK, l, (Hkv * hd, d)),
+            wv=t(O.T_WV, l, (Hkv * hd, d)), gq=t(O.T_GQ, l, (hd,)), gk=t(O.T_GK, l, (hd,)),
+            wo=t(O.T_WO, l, (d, H * hd)), g2=t(O.T_G2, l, (d,)), wg=t(O.T_WG, l, (Fd, d)),
+            wu=t(O.T_WU, l, (Fd, d)), wd=t(O.T_WD, l, (d, Fd))))
+    return W
+
+
+def rope_complex(x, base):
+    """x: [T, heads, hd]; pairs (i, i+hd/2) rotated by pos * base^(-2i/hd)."""
+    T, _, hd = x.shape
+    half = hd // 2
+    inv = base ** (-2.0 * torch.arange(half, dtype=torch.float64) / hd)
+    ang = torch.arange(T, dtype=torch.float64)[:, None] * inv[None, :]
+    rot = torch.polar(torch.ones_like(ang), ang)[:, None, :]
+    z = torch.complex(x[..., :half], x[..., half:]) * rot
+    return torch.cat([z.real, z.imag], dim=-1)
+
+
+def forward_full(model: O.Model, tokens):
+    """Logits [T][V] for the whole token sequence, fp64, full recompute."""
+    c = model.cfg
+    W = weights_of(model)
+    bf = c.dtype == 1
+    hd, H, Hkv = c.head_dim, c.n_q_heads, c.n_kv_heads
+    tok = torch.as_tensor(np.asarray(tokens), dtype=torch.long)
+    T = tok.numel()
+    h = W["emb"][tok]
+    for L in W["layers"]:
+        a = _rnd(F.rms_norm(h, (c.d_model,), L["g1"], c.rms_eps), bf)
+        q = (a @ L["wq"].T).view(T, H, hd)
+        k = (a @ L["wk"].T).view(T, Hkv, hd)
+        v = (a @ L["wv"].T).view(T, Hkv, hd)
+        if c.qk_norm:
+            q = F.rms_norm(q, (hd,), L["gq"], c.rms_eps)
+            k = F.rms_norm(k, (hd,), L["gk"], c.rms_eps)
+        q = _rnd(rope_complex(q, c.rope_base), bf)
+        k = _rnd(rope_complex(k, c.rope_base), bf)
+        v = _rnd(v, bf)
+        g = H // Hkv
+        kx = k.repeat_interleave(g, dim=1)
+        vx = v.repeat_interleave(g, dim=1)
+        if bf:
+            # probabilities are rounded before weighting v, so the fused library
+            # attention cannot be used; softmax and matmul are still library calls
+            s = torch.einsum("thd,shd->hts", q, kx) / np.sqrt(hd)
+            mask = torch.ones(T, T, dtype=torch.bool).tril()
+            s = s.masked_fill(~mask, float("-inf"))
+            p = _rnd(torch.softmax(s, dim=-1), True)
+            att = torch.einsum("hts,shd->thd", p, vx)
+        else:
+            att = F.scaled_dot_product_attention(q.transpose(0, 1)[None], kx.transpose(0, 1)[None],
+                                                 vx.transpose(0, 1)[None], is_causal=True)[0].transpose(0, 1)
+        att = _rnd(att.reshape(T, H * hd), bf)
+        h = h + att @ L["wo"].T
+        m = _rnd(F.rms_norm(h, (c.d_model,), L["g2"], c.rms_eps), bf)
+        act = _rnd(F.silu(m @ L["wg"].T) * (m @ L["wu"].T), bf)
+        h = h + act @ L["wd"].T
+    a = _rnd(F.rms_norm(h, (c.d_model,), W["gf"], c.rms_eps), bf)
+    return (a @ W["lm"].T).numpy()
