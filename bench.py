@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the verify -> accept -> commit -> retrieve step on one MI355X.
+
+A "step" is one pass of the whole hot path for one batch of synthetic input:
+dbl_retrieve -> dbl_build_window -> dbl_verify_block -> dbl_accept -> dbl_kv_commit,
+chained on the device with no host decision in between.  Default workload: the
+LLaMA-3.3-70B-shaped bf16 target (80 layers, d 8192, 64/8 heads, FFN 28672, vocab
+128256; random weights from a seed, resident in HBM), a 2048-token KV cache built by
+real prefill of a Zipf(1.1) token stream with 20% repeated 16-grams, window k = 8,
+batch 1, greedy acceptance.
+
+Prints ONE JSON line (see the design doc for every field).  `--gpus N` with N > 1 is not
+supported: this build runs on one GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+
+WORKLOADS = {
+    # name: (shape key, context, k, batch, mode, temperature, repeat fraction, span lo, span hi)
+    "llama70b_ctx2048_k8_b1_greedy": ("llama70b", 2048, 8, 1, "greedy", 0.0, 0.20, 16, 16),
+    "llama1b_ctx1024_k8_b1_greedy": ("llama1b", 1024, 8, 1, "greedy", 0.0, 0.15, 16, 16),
+    "qwen32b_ctx8192_k16_b1_sample": ("qwen32b", 8192, 16, 1, "sample", 0.7, 0.20, 16, 16),
+    "tiny_ctx256_k4_b1_greedy": ("tiny", 256, 4, 1, "greedy", 0.0, 0.25, 8, 8),
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(shape_key: str, k: int, full_layers: int, full_vocab: int):
+    """The oracle, as it stands, timed on this host's cores on a bounded sample: one
+    full-width decoder layer plus a 1/8-vocabulary LM-head slice over k window rows at
+    an empty context; the full step is extrapolated as layers * t_layer + 8 * t_lm_slice."""
+    import numpy as np
+    import oracle as O
+    from paper_2601_05524_amd import synth
+    shape = dict(synth.CONFIGS[shape_key])
+    small = shape["d_model"] <= 2048
+    vdiv = 1 if small else 8
+    vs = shape["vocab"] // vdiv
+    shape.update(vocab=vs, max_ctx=64)
+    cores = len(os.sched_getaffinity(0))
+    win = (np.arange(k, dtype=np.int32) * 7919 + 13) % vs
+    times = {}
+    for nl in (0, 1):
+        m = O.Model(**dict(shape, n_layers=nl), seed=synth.BASE_SEED)
+        s = O.Seq(m, max_hist=64)
+        t0 = time.perf_counter()
+        s.verify_block(win)
+        times[nl] = time.perf_counter() - t0
+        s.close(); m.close()
+    t_lm = times[0]
+    t_layer = max(times[1] - times[0], 1e-9)
+    t_full = full_layers * t_layer + vdiv * t_lm
+    return {"value": k / t_full, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "1 full-width layer + 1/%d-vocab LM head, k=%d rows, empty context; "
+                      "extrapolated to %d layers + full vocab (t_layer=%.3fs, t_lm_slice=%.3fs)"
+                      % (vdiv, k, full_layers, t_layer, t_lm),
+            "extrapolated": True}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama70b_ctx2048_k8_b1_greedy", choices=sorted(WORKLOADS))
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the model's own)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-iters", type=int, default=40, help="launches per projection for the roofline line")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2601_05524_amd import binding as B
+    from paper_2601_05524_amd import synth
+
+    shape_key, P, k, Bn, mode, T, frac, slo, shi = WORKLOADS[args.workload]
+    shape = dict(synth.CONFIGS[shape_key])
+    if args.layers > 0:
+        shape["n_layers"] = args.layers
+    idx = list(synth.CONFIGS).index(shape_key)
+    seed = synth.BASE_SEED + idx
+    steps, warm = args.steps, args.warmup
+    chunk = 16
+    max_ctx = ((P + (steps + warm + 6) * k + 63) // 64 + 1) * 64
+    max_hist = P + 1 + (steps + warm + 6) * k + 64
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    t0 = time.perf_counter()
+    cfg = B.make_cfg(**shape, max_batch=Bn, max_ctx=max_ctx, max_window=max(chunk, k), max_hist=max_hist)
+    ctx = B.dbl_create(cfg, seed, torch.cuda.current_stream().cuda_stream)
+    wbytes, kv_per_tok = B.dbl_model_bytes(ctx)
+    log("[bench] context created in %.1fs: %.2f GB of weights streamed per step" % (time.perf_counter() - t0, wbytes / 1e9))
+
+    # history = P + 1 tokens; prefill the first P through verify_block + kv_commit
+    prompts = [synth.zipf_history(seed + 100 * b, P + 1, shape["vocab"], 1.1, frac, slo, shi) for b in range(Bn)]
+    for b, p in enumerate(prompts):
+        B.dbl_history_set(ctx, b, np.ascontiguousarray(p, dtype=np.int32))
+    keep = torch.empty(Bn, dtype=torch.int32, device=dev)
+    t0 = time.perf_counter()
+    i = 0
+    while i < P:
+        c = min(chunk, P - i)
+        w = torch.as_tensor(np.stack([p[i:i + c] for p in prompts]).astype(np.int32), device=dev)
+        keep.fill_(c)
+        B.dbl_verify_block(ctx, w, Bn, c)
+        B.dbl_kv_commit(ctx, keep)
+        i += c
+    torch.cuda.synchronize()
+    kv0 = np.zeros(Bn, np.int32)
+    B.dbl_kv_len(ctx, kv0)
+    log("[bench] prefill of %d tokens in %.1fs, kv_len=%s" % (P, time.perf_counter() - t0, kv0.tolist()))
+
+    max_cont = k - 1 if k > 1 else 1
+    cont = torch.empty((Bn, max_cont), dtype=torch.int32, device=dev)
+    cl, mn, mp = (torch.empty(Bn, dtype=torch.int32, device=dev) for _ in range(3))
+    window = torch.empty((Bn, k), dtype=torch.int32, device=dev)
+    n_acc = torch.empty(Bn, dtype=torch.int32, device=dev)
+    emit = torch.empty((Bn, k), dtype=torch.int32, device=dev)
+    guide = torch.empty((Bn, k), dtype=torch.int32, device=dev)
+    amode = B.DBL_SAMPLE if mode == "sample" else B.DBL_GREEDY
+
+    def step(i):
+        B.dbl_retrieve(ctx, Bn, 3, 1, max_cont, cont, cl, mn, mp)
+        B.dbl_build_window(ctx, Bn, k, max_cont, cont, cl, 0, window)
+        B.dbl_verify_block(ctx, window, Bn, k, T, seed, i)
+        B.dbl_accept(ctx, amode, None, n_acc, emit, guide)
+        B.dbl_kv_commit(ctx, None)
+
+    for i in range(warm):
+        step(i)
+    B.dbl_kv_len(ctx, kv0)          # synchronises
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(warm + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kv1 = np.zeros(Bn, np.int32)
+    B.dbl_kv_len(ctx, kv1)
+    emitted = int((kv1 - kv0).sum())      # sum over steps of n_acc + 1
+    ms_step = dt / steps * 1e3
+    ctx_mid = float(kv0.mean() + kv1.mean()) / 2 + k
+    step_bytes = wbytes + Bn * ctx_mid * kv_per_tok
+    step_gbps = step_bytes / (dt / steps) / 1e9
+
+    # per-call breakdown (events on the context's stream = torch's current stream)
+    names = ["retrieve", "build_window", "verify_block", "accept", "kv_commit"]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+    acc = [0.0] * 5
+    reps = 3
+    for r in range(reps):
+        ev[0].record()
+        B.dbl_retrieve(ctx, Bn, 3, 1, max_cont, cont, cl, mn, mp); ev[1].record()
+        B.dbl_build_window(ctx, Bn, k, max_cont, cont, cl, 0, window); ev[2].record()
+        B.dbl_verify_block(ctx, window, Bn, k, T, seed, steps + warm + r); ev[3].record()
+        B.dbl_accept(ctx, amode, None, n_acc, emit, guide); ev[4].record()
+        B.dbl_kv_commit(ctx, None); ev[5].record()
+        torch.cuda.synchronize()
+        for j in range(5):
+            acc[j] += ev[j].elapsed_time(ev[j + 1]) / reps
+    breakdown = {n: round(v, 4) for n, v in zip(names, acc)}
+
+    # dominant kernel: the fused gate/up + SwiGLU projection (55% of the bytes at 70B shape)
+    M = min(16, Bn * k)
+    proj = {}
+    for which, name in enumerate(["qkv", "o_proj", "gate_up_swiglu", "down_proj", "lm_head_stats"]):
+        if which < 4 and shape["n_layers"] < 1:
+            continue
+        ms, nbytes = B.dbl_bench_projection(ctx, which, M, args.kernel_iters if which != 4 else max(4, args.kernel_iters // 4))
+        proj[name] = {"ms": round(ms, 5), "GB/s": round(nbytes / ms / 1e6, 1), "bytes": nbytes}
+    dom = proj.get("gate_up_swiglu") or proj["lm_head_stats"]
+    roofline = {"bound": "hbm", "kernel": "gemm_stream_kernel<bf16, EPI_SWIGLU> (fused gate/up projection)",
+                "achieved": dom["GB/s"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(dom["GB/s"] / HBM_PEAK_GBPS, 4), "traffic": None,
+                "bytes_per_launch": dom["bytes"], "ms_per_launch": dom["ms"]}
+    B.dbl_destroy(ctx)
+
+    out = {
+        "metric": "verified tokens/s of target verify step (70B-shape, k=8) + achieved HBM GB/s",
+        "value": round(Bn * k / (dt / steps), 2), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warm,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape["dtype"] == 1 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "layers": shape["n_layers"], "ctx": P, "k": k, "batch": Bn,
+                   "accept": mode, "weights": "random N(0,0.02) from seed %d" % seed},
+        "hbm_GBps_step": round(step_gbps, 1), "hbm_frac_step": round(step_gbps / HBM_PEAK_GBPS, 4),
+        "algorithmic_bytes_per_step": int(step_bytes), "emitted_tokens_per_s": round(emitted / dt, 2),
+        "breakdown_ms": breakdown, "projections": proj, "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
+        full_layers = synth.CONFIGS[shape_key]["n_layers"] if args.layers <= 0 else args.layers
+        out["cpu_baseline"] = cpu_baseline(shape_key, k, full_layers, shape["vocab"])
+        log("[bench] oracle baseline took %.1fs" % (time.perf_counter() - t0))
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

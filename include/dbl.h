@@ -1,0 +1,228 @@
+/*
+ * dbl.h -- C ABI of libdbl: the target-side verify -> accept -> retrieve -> commit
+ * step of Double (Double Retrieval Speculative Parallelism, arxiv 2601.05524) for
+ * one AMD MI355X (gfx950).  Every step runs in HIP kernels of this library; there
+ * is no CPU fallback.
+ *
+ * One "Retrieval Forward" (paper Eq. 2) is, per sequence:
+ *     dbl_retrieve      d candidate tokens by n-gram match            (Alg. 3)
+ *     dbl_build_window  pending token + candidates -> k window rows
+ *     dbl_verify_block  one target forward over the k rows            (Sec. 2.1)
+ *     dbl_accept        s matched tokens + 1 correction               (Sec. 2.1, App. D.2)
+ *     dbl_kv_commit     keep the accepted rows' KV, extend the history (Alg. 1, Alg. 2)
+ *
+ * Conventions
+ *   - "dev" pointers are device memory the CALLER allocated on the context's GPU
+ *     and keeps owning; "host" pointers are ordinary host memory.  The library
+ *     never frees caller memory and does not keep caller pointers after the
+ *     stream work of the call that received them has finished.
+ *   - The context owns weights, KV cache, token history, per-sequence counters
+ *     and all scratch.  B sequences (0 <= b < B <= max_batch) advance in lockstep.
+ *   - The hot calls (retrieve, build_window, verify_block, accept, kv_commit) only
+ *     enqueue work on the context's stream and return; results are valid once the
+ *     caller has synchronised that stream.  Counters (kv_len, hist_len, n_acc) stay
+ *     on the device, so the five calls chain without a host round trip.
+ *   - Window convention: window[b][0] is the pending token (emitted by the last
+ *     step, its KV not yet written); window[b][1..k) are k-1 drafted tokens.
+ *     Row j sits at position kv_len[b]+j and its logits predict the token after
+ *     window[b][j].  Verifying gamma drafts is k = gamma+1.
+ *   - All functions return 0 (DBL_OK) or a negative dbl_status.  Argument checks
+ *     come before any GPU call.  Nothing throws or aborts across this boundary.
+ *   - Calls on one context are not thread-safe.
+ */
+#ifndef DBL_H
+#define DBL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dbl_ctx dbl_ctx;
+
+typedef enum {
+  DBL_OK = 0,
+  DBL_EINVAL = -1, /* bad argument: null pointer, size out of range, bad enum      */
+  DBL_ESTATE = -2, /* call out of order (accept without verify_block, ...)         */
+  DBL_ENOMEM = -3, /* host or device allocation failed                             */
+  DBL_EHIP = -4,   /* a HIP runtime call failed; text in dbl_last_error            */
+  DBL_ENODEV = -5  /* validate-only context: arguments were fine, nothing was run  */
+} dbl_status;
+
+enum { DBL_F32 = 0, DBL_BF16 = 1 };
+enum { DBL_GREEDY = 0, DBL_SAMPLE = 1 };
+enum { DBL_FLAG_VALIDATE_ONLY = 1 }; /* dbl_model_cfg.flags: no GPU is touched     */
+
+/* Tensor ids for dbl_set_weights / dbl_get_weights.  Matrices are logical
+ * row-major [out_features][in_features]. */
+enum {
+  DBL_T_EMB = 0,  /* [vocab][d_model]                 */
+  DBL_T_LM = 1,   /* [vocab][d_model]  (untied)       */
+  DBL_T_GF = 2,   /* final RMSNorm gain [d_model] f32 */
+  DBL_T_G1 = 10,  /* pre-attention RMSNorm gain [d_model] f32 */
+  DBL_T_WQ = 11,  /* [n_q_heads*head_dim][d_model]    */
+  DBL_T_WK = 12,  /* [n_kv_heads*head_dim][d_model]   */
+  DBL_T_WV = 13,  /* [n_kv_heads*head_dim][d_model]   */
+  DBL_T_GQ = 14,  /* per-head q RMSNorm gain [head_dim] f32 (qk_norm) */
+  DBL_T_GK = 15,  /* per-head k RMSNorm gain [head_dim] f32 (qk_norm) */
+  DBL_T_WO = 16,  /* [d_model][n_q_heads*head_dim]    */
+  DBL_T_G2 = 17,  /* pre-MLP RMSNorm gain [d_model] f32 */
+  DBL_T_WG = 18,  /* gate [d_ffn][d_model]            */
+  DBL_T_WU = 19,  /* up   [d_ffn][d_model]            */
+  DBL_T_WD = 20   /* down [d_model][d_ffn]            */
+};
+
+/* Decoder shape (the paper's model table, App. C.1, gives layers / dim / FFN dim /
+ * vocabulary; head counts are the public ones of those models) and capacities. */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_base;
+  int32_t qk_norm; /* 1: per-head RMSNorm on q and k before RoPE (Qwen3)           */
+  int32_t dtype;   /* DBL_F32 or DBL_BF16: type of weights, KV cache and of the
+                      activations that feed projections; accumulation, residual
+                      stream, norms, softmax and logits are always fp32           */
+  int32_t max_batch, max_ctx, max_window, max_hist;
+  int32_t flags;
+} dbl_model_cfg;
+
+/*
+ * Create a context on the current HIP device.  Weights are generated on the GPU
+ * from `weight_seed`: every matrix / embedding entry is 0.02 * (sum of the eight
+ * 16-bit halves of Philox4x32-10(counter = {elem_lo, elem_hi, tensor id, layer},
+ * key = seed) - 262140) / sqrt(8*(65536^2-1)/12), rounded to the model dtype;
+ * every norm gain is 1.  `hip_stream` (a hipStream_t, NULL = default stream) is
+ * borrowed: all later work of this context is enqueued on it.
+ * Limits: head_dim in {64, 128}; n_q_heads % n_kv_heads == 0;
+ * 1 <= max_window; max_batch*max_window <= 128; max_ctx % 64 == 0.
+ */
+int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream, dbl_ctx** out);
+int dbl_destroy(dbl_ctx* ctx);
+
+/* Text of the last error of this context (never NULL; "" if none). */
+const char* dbl_last_error(const dbl_ctx* ctx);
+
+/* Overwrite / read back one tensor.  `host` holds the logical row-major tensor in
+ * the model dtype (bf16 as uint16_t bit patterns, or float); norm gains are always
+ * float.  `bytes` must equal the tensor's size.  The library repacks into its own
+ * layout.  Synchronises the stream. */
+int dbl_set_weights(dbl_ctx* ctx, int tensor_id, int layer, const void* host, size_t bytes);
+int dbl_get_weights(dbl_ctx* ctx, int tensor_id, int layer, void* host, size_t bytes);
+
+/* Session flush (the paper's datastore is session-scoped, App. D.3): sequence
+ * `seq` (or every sequence when seq < 0) gets kv_len = hist_len = 0. */
+int dbl_reset(dbl_ctx* ctx, int seq);
+
+/* Replace the token history of sequence `seq` by `n` host tokens (the prompt).
+ * The history is what dbl_retrieve searches; it normally ends with the pending
+ * token, i.e. hist_len = kv_len + 1.  0 <= n <= max_hist. */
+int dbl_history_set(dbl_ctx* ctx, int seq, const int32_t* host_tokens, int n);
+
+/* Copy the history of sequence `seq` to the host: min(hist_len, cap) tokens into
+ * host_out, hist_len into *n_out.  Synchronises the stream. */
+int dbl_history_get(dbl_ctx* ctx, int seq, int32_t* host_out, int cap, int32_t* n_out);
+
+/*
+ * Retrieval (Alg. 3's descending n-gram search of the sequence in itself; Eq. 2's
+ * "retrieve d tokens").  For each sequence b < B: for n = min(n_max, len-1) down
+ * to n_min, every start s <= len-n-1 with hist[s..s+n) == hist[len-n..len) is a
+ * candidate whose continuation is the next min(max_cont, len-s-n) tokens; the
+ * first n with a candidate wins, then the longest continuation, then the latest s.
+ * Outputs (dev): cont[B][max_cont] (entries beyond cont_len are -1), cont_len[B],
+ * match_n[B] (0 = miss), match_pos[B] (-1 = miss).
+ * 1 <= n_min <= n_max <= 32, 1 <= max_cont <= 64.
+ */
+int dbl_retrieve(dbl_ctx* ctx, int B, int n_max, int n_min, int max_cont, int32_t* cont_dev,
+                 int32_t* cont_len_dev, int32_t* match_n_dev, int32_t* match_pos_dev);
+
+/* window[b][0] = last history token of b; window[b][1+i] = cont[b][i] for
+ * i < min(cont_len[b], k-1), else pad_id.  cont rows have stride max_cont.
+ * window_dev is [B][k].  Sequences with an empty history get pad_id in row 0. */
+int dbl_build_window(dbl_ctx* ctx, int B, int k, int max_cont, const int32_t* cont_dev,
+                     const int32_t* cont_len_dev, int32_t pad_id, int32_t* window_dev);
+
+/*
+ * Verify forward (Sec. 2.1: one parallel target forward over the drafted tokens;
+ * App. D.2: causal mask, row j conditioned on the prefix and rows < j).
+ * window_dev is [B][k] token ids in [0, vocab).  For every row: embedding, n_layers
+ * x [RMSNorm, q/k/v projections, (qk_norm), RoPE at position kv_len[b]+j, K/V
+ * written to cache slot kv_len[b]+j, GQA attention over slots 0..kv_len[b]+j,
+ * output projection + residual, RMSNorm, SwiGLU MLP + residual], final RMSNorm,
+ * LM head.  The LM-head kernel also leaves, per row, the statistics dbl_accept
+ * needs (arg-max; and when temperature > 0: log-sum-exp of logits/temperature, the
+ * draft token's logit and the two largest Gumbel-perturbed scores, noise from
+ * Philox4x32-10 keyed by `seed` with counter {step', b, j, 1 + v/4}, word v%4,
+ * where step' = step + number of dbl_kv_commit calls this context has run).
+ * kv_len is not advanced.  logits_opt_dev, if not NULL, receives the fp32 logits
+ * [B][k][vocab].  1 <= B <= max_batch, 1 <= k <= max_window, and for every b
+ * kv_len[b] + k <= max_ctx (checked against the host's upper bound of kv_len).
+ * temperature <= 0 means "greedy statistics only".
+ */
+int dbl_verify_block(dbl_ctx* ctx, const int32_t* window_dev, int B, int k, float temperature,
+                     uint64_t seed, uint64_t step, float* logits_opt_dev);
+
+/*
+ * Acceptance on the rows of the last dbl_verify_block (same B, k, window).
+ * mode DBL_GREEDY (App. D.2): y_j = argmax of row j (lowest id on ties); n_acc =
+ * number of leading drafts with window[j+1] == y_j; emit = those drafts then
+ * y_{n_acc}; guide[j] = y_j for all j.
+ * mode DBL_SAMPLE (Sec. 2.1; needs temperature > 0 in verify_block): p_j =
+ * softmax(logits_j / temperature); draft x = window[j+1] is accepted iff
+ * u_j * q_j(x) < p_j(x), u_j = ((w >> 9) + 0.5) / 2^23 with w = word 0 of
+ * Philox(counter {step', b, j, 0}); q_probs_dev [B][k-1][vocab] (fp32) are the
+ * draft distributions, NULL = deterministic (retrieved) drafts, q one-hot.  At the
+ * first rejected row n the emitted token is drawn from max(0, p_n - q_n) (from p_n
+ * if that is all zero); with no rejection the extra token is drawn from p_{k-1}.
+ * Draws are argmax_v [log weight_v + Gumbel_v] with the noise described above.
+ * guide[j] is row j's own draw from p_j for j <= n_acc and -1 after it (guidance
+ * behind a rejection is discarded, Sec. 5.3 / App. D.2).
+ * Outputs (dev): n_acc[B], emit[B][k] (entries beyond n_acc are -1), guide[B][k].
+ */
+int dbl_accept(dbl_ctx* ctx, int mode, const float* q_probs_dev, int32_t* n_acc_dev,
+               int32_t* emit_dev, int32_t* guide_dev);
+
+/*
+ * Commit (Alg. 1 "rollback", Alg. 2): keep the KV of the first n_keep[b] window
+ * rows (kv_len[b] += n_keep[b]; later rows are dead and get overwritten) and
+ * append emit[b][0..n_keep[b]) of the last dbl_accept to the history.
+ * n_keep_dev == NULL means n_keep[b] = n_acc[b] + 1 from the last dbl_accept.
+ * With an explicit n_keep_dev (dev, [B], clamped to 0..k) only kv_len advances and
+ * nothing is appended to the history (chunked prefill is verify_block + kv_commit
+ * with n_keep = k, the history having been set beforehand).
+ */
+int dbl_kv_commit(dbl_ctx* ctx, const int32_t* n_keep_dev);
+
+/* Synchronises the stream and copies kv_len[0..max_batch) / hist_len to the host;
+ * also refreshes the host-side upper bounds used for argument checks.  Returns
+ * DBL_ESTATE if a device-side capacity check (max_ctx, max_hist) had to clamp. */
+int dbl_kv_len(dbl_ctx* ctx, int32_t* host_out);
+int dbl_hist_len(dbl_ctx* ctx, int32_t* host_out);
+
+/* Read-only facts about the layout, for measurement: bytes of weights the verify
+ * step streams once per call (all layer matrices + LM head), and KV bytes per
+ * cached token (all layers). */
+int dbl_model_bytes(const dbl_ctx* ctx, uint64_t* weight_bytes, uint64_t* kv_bytes_per_token);
+
+/* Measurement: launch one projection kernel `iters` times (layer = launch index
+ * mod n_layers, so consecutive launches stream different weights, as in a real
+ * step) for M <= 16 rows on the context's stream between two HIP events, with the
+ * launch configuration dbl_verify_block uses.  which: 0 = fused q/k/v, 1 = output
+ * projection, 2 = fused gate/up + SwiGLU, 3 = down projection, 4 = LM head + row
+ * statistics.  *ms_out = mean milliseconds per launch; *bytes_out = logical weight
+ * bytes one launch must read.  Activations are whatever the scratch buffers hold;
+ * the residual stream and statistics are overwritten.  Synchronises. */
+int dbl_bench_projection(dbl_ctx* ctx, int which, int M, int iters, float* ms_out, uint64_t* bytes_out);
+
+/* Diagnostics: copy one of the context's scratch buffers, as left by the last
+ * dbl_verify_block, to the host (synchronises).  which: 0 = residual stream after
+ * the last layer [rows][ld] f32; 1 = last layer's attention output [rows][ld] in
+ * the model dtype; 2 = last layer's silu(gate)*up [rows][ld] in the model dtype.
+ * *ld_out receives the row stride in elements; `bytes` is the capacity of `host`
+ * and must cover max_batch*max_window rows. */
+int dbl_debug_buffer(dbl_ctx* ctx, int which, void* host, size_t bytes, int32_t* ld_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DBL_H */

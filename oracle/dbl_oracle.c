@@ -30,9 +30,9 @@
  * values; all arithmetic is fp64; values are rounded to bf16 (nearest-even) at
  *   r1 the output of every RMSNorm that feeds a projection,
  *   r2 q and k after (qk-norm and) RoPE, and v, i.e. what the KV cache holds,
- *   r3 the softmax probabilities before they weight v,
- *   r4 the attention output before the output projection,
- *   r5 silu(gate)*up before the down projection.
+ *   (the softmax probabilities are NOT rounded: they weight v in full precision),
+ *   r3 the attention output before the output projection,
+ *   r4 silu(gate)*up before the down projection.
  * Logits are never rounded.  fp32 models have no rounding points.
  *
  * Parity status: every function here is pinned by tests/test_oracle_*.py
@@ -50,7 +50,7 @@
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
   int32_t qk_norm; /* 1: per-head RMSNorm on q and k (Qwen3) */
-  int32_t dtype;   /* 0: fp32 model, 1: bf16 model (rounding points r1..r5) */
+  int32_t dtype;   /* 0: fp32 model, 1: bf16 model (rounding points r1..r4) */
   int32_t max_ctx;
   double rms_eps, rope_base;
 } orc_cfg;
@@ -361,11 +361,11 @@ static void layer_row(const orc_model *m, orc_seq *s, int l, int pos, double *h,
     }
     double den = 0.0;
     for (int t = 0; t <= pos; ++t) { sc[t] = exp(sc[t] - mx); den += sc[t]; }
-    for (int t = 0; t <= pos; ++t) sc[t] = rnd(c, sc[t] / den); /* r3 */
+    for (int t = 0; t <= pos; ++t) sc[t] = sc[t] / den;
     for (int i = 0; i < hd; ++i) {
       double acc = 0.0;
       for (int t = 0; t <= pos; ++t) acc += sc[t] * s->vc[kv_index(c, l, kvh, t) + i];
-      att[hh * hd + i] = rnd(c, acc); /* r4 */
+      att[hh * hd + i] = rnd(c, acc); /* r3 */
     }
   }
   matvec(L->wo, att, d, H * hd, o);
@@ -377,7 +377,7 @@ static void layer_row(const orc_model *m, orc_seq *s, int l, int pos, double *h,
   matvec(L->wu, a, F, d, up);
   for (int i = 0; i < F; ++i) {
     double silu = gt[i] / (1.0 + exp(-gt[i]));
-    gt[i] = rnd(c, silu * up[i]); /* r5 */
+    gt[i] = rnd(c, silu * up[i]); /* r4 */
   }
   matvec(L->wd, gt, d, F, o);
   for (int i = 0; i < d; ++i) h[i] += o[i];

@@ -1,0 +1,185 @@
+"""Thin ctypes binding of libdbl.so (include/dbl.h): argument marshalling only.
+
+Every function here has the name of the C entry point it calls.  PyTorch is used by
+callers for device memory (`tensor.data_ptr()`) and streams; nothing in this module
+computes anything, and there is no fallback: if the HIP library is missing or a
+call fails, a DblError is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdbl.so")
+
+DBL_OK, DBL_EINVAL, DBL_ESTATE, DBL_ENOMEM, DBL_EHIP, DBL_ENODEV = 0, -1, -2, -3, -4, -5
+DBL_F32, DBL_BF16 = 0, 1
+DBL_GREEDY, DBL_SAMPLE = 0, 1
+DBL_FLAG_VALIDATE_ONLY = 1
+T_EMB, T_LM, T_GF = 0, 1, 2
+T_G1, T_WQ, T_WK, T_WV, T_GQ, T_GK, T_WO, T_G2, T_WG, T_WU, T_WD = range(10, 21)
+
+EXPORTS = ["dbl_create", "dbl_destroy", "dbl_last_error", "dbl_set_weights", "dbl_get_weights", "dbl_reset",
+           "dbl_history_set", "dbl_history_get", "dbl_retrieve", "dbl_build_window", "dbl_verify_block", "dbl_accept",
+           "dbl_kv_commit", "dbl_kv_len", "dbl_hist_len", "dbl_model_bytes", "dbl_debug_buffer",
+           "dbl_bench_projection"]
+
+
+class DblError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("libdbl error %d: %s" % (code, msg))
+        self.code = code
+
+
+class ModelCfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("qk_norm", C.c_int32), ("dtype", C.c_int32),
+                ("max_batch", C.c_int32), ("max_ctx", C.c_int32), ("max_window", C.c_int32),
+                ("max_hist", C.c_int32), ("flags", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libdbl.so (built in-tree by build.py); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise DblError(DBL_EHIP, "libdbl.so is not built (run paper_2601_05524_amd/build.py); "
+                                     "there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        vp, i32p, i = C.c_void_p, C.c_void_p, C.c_int
+        L.dbl_create.argtypes = [C.POINTER(ModelCfg), C.c_uint64, vp, C.POINTER(vp)]
+        L.dbl_destroy.argtypes = [vp]
+        L.dbl_last_error.argtypes = [vp]
+        L.dbl_last_error.restype = C.c_char_p
+        L.dbl_set_weights.argtypes = [vp, i, i, vp, C.c_size_t]
+        L.dbl_get_weights.argtypes = [vp, i, i, vp, C.c_size_t]
+        L.dbl_reset.argtypes = [vp, i]
+        L.dbl_history_set.argtypes = [vp, i, vp, i]
+        L.dbl_history_get.argtypes = [vp, i, vp, i, C.POINTER(C.c_int32)]
+        L.dbl_retrieve.argtypes = [vp, i, i, i, i, i32p, i32p, i32p, i32p]
+        L.dbl_build_window.argtypes = [vp, i, i, i, i32p, i32p, C.c_int32, i32p]
+        L.dbl_verify_block.argtypes = [vp, i32p, i, i, C.c_float, C.c_uint64, C.c_uint64, vp]
+        L.dbl_accept.argtypes = [vp, i, vp, i32p, i32p, i32p]
+        L.dbl_kv_commit.argtypes = [vp, i32p]
+        L.dbl_kv_len.argtypes = [vp, vp]
+        L.dbl_hist_len.argtypes = [vp, vp]
+        L.dbl_model_bytes.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
+        L.dbl_bench_projection.argtypes = [vp, i, i, i, C.POINTER(C.c_float), C.POINTER(C.c_uint64)]
+        L.dbl_debug_buffer.argtypes = [vp, i, vp, C.c_size_t, C.POINTER(C.c_int32)]
+        for n in EXPORTS:
+            if n != "dbl_last_error":
+                getattr(L, n).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _chk(ctx, rc, allow=()):
+    if rc != DBL_OK and rc not in allow:
+        msg = lib().dbl_last_error(ctx).decode() if ctx else ""
+        raise DblError(rc, msg)
+    return rc
+
+
+def _ptr(x):
+    """Device pointer of a torch tensor, host pointer of a numpy array, or None."""
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return C.c_void_p(x.data_ptr())
+    return C.c_void_p(x.ctypes.data)
+
+
+def dbl_create(cfg: ModelCfg, weight_seed: int, hip_stream: int = 0):
+    h = C.c_void_p()
+    rc = lib().dbl_create(C.byref(cfg), weight_seed, C.c_void_p(hip_stream), C.byref(h))
+    if rc != DBL_OK:
+        raise DblError(rc, "dbl_create failed")
+    return h
+
+
+def dbl_destroy(ctx):
+    return _chk(None, lib().dbl_destroy(ctx))
+
+
+def dbl_last_error(ctx) -> str:
+    return lib().dbl_last_error(ctx).decode()
+
+
+def dbl_set_weights(ctx, tensor_id, layer, host_array):
+    return _chk(ctx, lib().dbl_set_weights(ctx, tensor_id, layer, _ptr(host_array), host_array.nbytes))
+
+
+def dbl_get_weights(ctx, tensor_id, layer, host_array):
+    return _chk(ctx, lib().dbl_get_weights(ctx, tensor_id, layer, _ptr(host_array), host_array.nbytes))
+
+
+def dbl_reset(ctx, seq=-1):
+    return _chk(ctx, lib().dbl_reset(ctx, seq))
+
+
+def dbl_history_set(ctx, seq, host_tokens):
+    return _chk(ctx, lib().dbl_history_set(ctx, seq, _ptr(host_tokens), int(host_tokens.size)))
+
+
+def dbl_history_get(ctx, seq, host_out):
+    n = C.c_int32(0)
+    _chk(ctx, lib().dbl_history_get(ctx, seq, _ptr(host_out), int(host_out.size), C.byref(n)))
+    return n.value
+
+
+def dbl_retrieve(ctx, B, n_max, n_min, max_cont, cont, cont_len, match_n, match_pos):
+    return _chk(ctx, lib().dbl_retrieve(ctx, B, n_max, n_min, max_cont, _ptr(cont), _ptr(cont_len),
+                                        _ptr(match_n), _ptr(match_pos)))
+
+
+def dbl_build_window(ctx, B, k, max_cont, cont, cont_len, pad_id, window):
+    return _chk(ctx, lib().dbl_build_window(ctx, B, k, max_cont, _ptr(cont), _ptr(cont_len), pad_id, _ptr(window)))
+
+
+def dbl_verify_block(ctx, window, B, k, temperature=0.0, seed=0, step=0, logits_opt=None):
+    return _chk(ctx, lib().dbl_verify_block(ctx, _ptr(window), B, k, temperature, seed, step, _ptr(logits_opt)))
+
+
+def dbl_accept(ctx, mode, q_probs, n_acc, emit, guide):
+    return _chk(ctx, lib().dbl_accept(ctx, mode, _ptr(q_probs), _ptr(n_acc), _ptr(emit), _ptr(guide)))
+
+
+def dbl_kv_commit(ctx, n_keep=None):
+    return _chk(ctx, lib().dbl_kv_commit(ctx, _ptr(n_keep)))
+
+
+def dbl_kv_len(ctx, host_out):
+    return _chk(ctx, lib().dbl_kv_len(ctx, _ptr(host_out)))
+
+
+def dbl_hist_len(ctx, host_out):
+    return _chk(ctx, lib().dbl_hist_len(ctx, _ptr(host_out)))
+
+
+def dbl_model_bytes(ctx):
+    w, kv = C.c_uint64(0), C.c_uint64(0)
+    _chk(ctx, lib().dbl_model_bytes(ctx, C.byref(w), C.byref(kv)))
+    return w.value, kv.value
+
+
+def dbl_bench_projection(ctx, which, M, iters):
+    ms, nbytes = C.c_float(0), C.c_uint64(0)
+    _chk(ctx, lib().dbl_bench_projection(ctx, which, M, iters, C.byref(ms), C.byref(nbytes)))
+    return ms.value, nbytes.value
+
+
+def dbl_debug_buffer(ctx, which, host_out):
+    ld = C.c_int32(0)
+    _chk(ctx, lib().dbl_debug_buffer(ctx, which, _ptr(host_out), host_out.nbytes, C.byref(ld)))
+    return ld.value
+
+
+def make_cfg(*, n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, rms_eps=1e-5, rope_base=1e4,
+             qk_norm=0, dtype=DBL_BF16, max_batch=1, max_ctx=4096, max_window=8, max_hist=4096, flags=0) -> ModelCfg:
+    return ModelCfg(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, rms_eps, rope_base, qk_norm,
+                    dtype, max_batch, max_ctx, max_window, max_hist, flags)

@@ -1,0 +1,790 @@
+// libdbl: context, launch logic and the C ABI declared in include/dbl.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/dbl.h"
+#include "dbl_kernels.h"
+
+using namespace dbl;
+
+namespace {
+
+constexpr int MAX_ROWS = 128;       // max_batch * max_window
+constexpr int MAX_WINDOW = 32;
+constexpr int MAX_SPLITS = 64;
+
+// How one projection is cut: NW waves per workgroup, each owning KS k-blocks of a
+// tile; SS workgroup super-slices when K is longer than NW*KS blocks.
+struct GemmPlan {
+  int N = 0, K = 0;      // logical sizes (N per half for gate/up)
+  int NT = 0;            // output tiles (pairs for gate/up)
+  int nacc = 1;          // tile rows per unit (2 for gate/up)
+  int KS = 0, NW = 0, SS = 0, KBp = 0;
+  int grid = 0;
+  size_t elems() const { return (size_t)NT * nacc * KBp * BLOCK_ELEMS; }
+  int ldx() const { return KBp * TILE_K; }
+  int ldo() const { return NT * TILE_N; }
+};
+
+bool make_plan(GemmPlan& p, int N, int K, int nacc, bool is_bf16, bool need_single_slice, int n_cu) {
+  p.N = N; p.K = K; p.nacc = nacc;
+  p.NT = (N + TILE_N - 1) / TILE_N;
+  const int KB = (K + TILE_K - 1) / TILE_K;
+  const int ks_big = is_bf16 ? 32 : 16, ks_small = is_bf16 ? 16 : 8;
+  p.KS = KB >= 2 * ks_big ? ks_big : ks_small;
+  const int nsl = (KB + p.KS - 1) / p.KS;
+  int best_nw = 1, best_pad = 1 << 30;
+  for (int nw = 8; nw >= 1; --nw) {
+    const int ss = (nsl + nw - 1) / nw;
+    if (need_single_slice && ss != 1) continue;
+    const int pad = nw * ss - nsl;
+    if (pad < best_pad) { best_pad = pad; best_nw = nw; }
+  }
+  if (best_pad == (1 << 30)) return false;
+  p.NW = best_nw;
+  p.SS = (nsl + p.NW - 1) / p.NW;
+  p.KBp = p.NW * p.SS * p.KS;
+  const int per_cu = std::max(1, 8 / p.NW);
+  int g = std::min(p.NT * p.SS, n_cu * per_cu);
+  g = std::max(p.SS, g / p.SS * p.SS);
+  p.grid = g;
+  return true;
+}
+
+}  // namespace
+
+struct dbl_ctx {
+  dbl_model_cfg cfg{};
+  bool bf16 = true, dry = false;
+  int device = 0, n_cu = 256;
+  hipStream_t stream = nullptr;
+  uint64_t seed = 0;
+  std::string err;
+  size_t esz = 2;
+
+  GemmPlan p_qkv, p_o, p_gu, p_d, p_lm;
+  int n_qkv = 0, hq = 0, hkv = 0;   // (H + 2 Hkv) * hd, H*hd, Hkv*hd
+
+  // device memory (all owned)
+  void *w_qkv = nullptr, *w_o = nullptr, *w_gu = nullptr, *w_d = nullptr, *w_lm = nullptr, *emb = nullptr;
+  float *g1 = nullptr, *g2 = nullptr, *gq = nullptr, *gk = nullptr, *gf = nullptr;
+  float *cosT = nullptr, *sinT = nullptr;
+  void *kc = nullptr, *vt = nullptr;
+  size_t kv_layer_elems = 0;
+  int32_t *kv_len = nullptr, *hist_len = nullptr, *hist = nullptr, *status = nullptr;
+  uint64_t* commits = nullptr;
+  float *h = nullptr, *qkv_part = nullptr, *d_part = nullptr, *o_part = nullptr, *logits = nullptr;
+  void *xn = nullptr, *qbuf = nullptr, *attn = nullptr, *act = nullptr;
+  float *pm = nullptr, *pl = nullptr, *po = nullptr;
+  LmStat* stats = nullptr;
+  int32_t *n_acc_i = nullptr, *emit_i = nullptr, *win_i = nullptr;
+  int qrows_pad = 0;
+
+  // host-side state
+  std::vector<int> kv_upper, hist_upper;
+  bool have_verify = false, have_accept = false, verify_sampling = false;
+  int last_B = 0, last_k = 0;
+  float last_T = 0.f;
+  uint64_t last_seed = 0, last_step = 0;
+  int d_nparts_pending = 0;  // down-projection partials waiting to be folded into h
+};
+
+namespace {
+
+int fail(dbl_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  return code;
+}
+
+#define HIPCHK(c, expr)                                                                   \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess)                                                                 \
+      return fail((c), DBL_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_));      \
+  } while (0)
+
+template <typename P>
+int dmalloc(dbl_ctx* c, P** p, size_t bytes, bool zero) {
+  void* v = nullptr;
+  hipError_t e = hipMalloc(&v, bytes ? bytes : 256);
+  if (e != hipSuccess) return fail(c, DBL_ENOMEM, std::string("hipMalloc: ") + hipGetErrorString(e));
+  if (zero) {
+    e = hipMemsetAsync(v, 0, bytes ? bytes : 256, c->stream);
+    if (e != hipSuccess) { (void)hipFree(v); return fail(c, DBL_EHIP, std::string("hipMemsetAsync: ") + hipGetErrorString(e)); }
+  }
+  *p = reinterpret_cast<P*>(v);
+  return DBL_OK;
+}
+
+int validate_cfg(const dbl_model_cfg* g, std::string& why) {
+  auto bad = [&](const char* m) { why = m; return DBL_EINVAL; };
+  if (g->n_layers < 0 || g->n_layers > 1024) return bad("n_layers out of range");
+  if (g->d_model < 16 || g->d_model % 16) return bad("d_model must be a positive multiple of 16");
+  if (g->head_dim != 64 && g->head_dim != 128) return bad("head_dim must be 64 or 128");
+  if (g->n_kv_heads < 1 || g->n_q_heads < 1 || g->n_q_heads % g->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
+  if (g->d_ffn < 16) return bad("d_ffn too small");
+  if (g->vocab < 2) return bad("vocab too small");
+  if (g->dtype != DBL_F32 && g->dtype != DBL_BF16) return bad("dtype must be DBL_F32 or DBL_BF16");
+  if (!(g->rms_eps > 0.f) || !(g->rope_base > 1.f)) return bad("rms_eps / rope_base out of range");
+  if (g->qk_norm != 0 && g->qk_norm != 1) return bad("qk_norm must be 0 or 1");
+  if (g->max_batch < 1 || g->max_window < 1 || g->max_window > MAX_WINDOW) return bad("max_batch / max_window out of range");
+  if ((int64_t)g->max_batch * g->max_window > MAX_ROWS) return bad("max_batch * max_window exceeds 128 rows");
+  if (g->max_ctx < 64 || g->max_ctx % 64) return bad("max_ctx must be a positive multiple of 64");
+  if (g->max_hist < 1) return bad("max_hist must be positive");
+  return DBL_OK;
+}
+
+int make_plans(dbl_ctx* c) {
+  const dbl_model_cfg& g = c->cfg;
+  c->hq = g.n_q_heads * g.head_dim; c->hkv = g.n_kv_heads * g.head_dim; c->n_qkv = c->hq + 2 * c->hkv;
+  bool ok = make_plan(c->p_qkv, c->n_qkv, g.d_model, 1, c->bf16, false, c->n_cu) &&
+            make_plan(c->p_o, g.d_model, c->hq, 1, c->bf16, false, c->n_cu) &&
+            make_plan(c->p_gu, g.d_ffn, g.d_model, 2, c->bf16, true, c->n_cu) &&
+            make_plan(c->p_d, g.d_model, g.d_ffn, 1, c->bf16, false, c->n_cu) &&
+            make_plan(c->p_lm, g.vocab, g.d_model, 1, c->bf16, true, c->n_cu);
+  if (!ok) return fail(c, DBL_EINVAL, "d_model too large for a single K slice (max 8192 bf16 / 4096 fp32)");
+  return DBL_OK;
+}
+
+// ----------------------------------------------------------------- launchers
+
+template <typename T, int EPI>
+void launch_gemm_t(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
+  const dim3 grid(p.grid), block(p.NW * 64);
+  constexpr bool is_bf = sizeof(T) == 2;
+  constexpr int KS_BIG = is_bf ? 32 : 16, KS_SMALL = is_bf ? 16 : 8;
+  if (p.KS == KS_BIG) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG>), grid, block, 0, c->stream, a);
+  else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL>), grid, block, 0, c->stream, a);
+}
+
+template <typename T>
+void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
+  a.NT = p.NT; a.N = p.N; a.KBp = p.KBp; a.SS = p.SS; a.Mtot = M;
+  for (int m0 = 0; m0 < M; m0 += 16) {
+    a.m0 = m0; a.mrows = std::min(16, M - m0);
+    switch (epi) {
+      case EPI_PARTIAL: launch_gemm_t<T, EPI_PARTIAL>(c, p, a); break;
+      case EPI_RESIDUAL: launch_gemm_t<T, EPI_RESIDUAL>(c, p, a); break;
+      case EPI_SWIGLU: launch_gemm_t<T, EPI_SWIGLU>(c, p, a); break;
+      default: launch_gemm_t<T, EPI_LMHEAD>(c, p, a); break;
+    }
+  }
+}
+
+template <typename T, int HD>
+void launch_attn_hd(dbl_ctx* c, const AttnArgs<T>& a, int QB, int nblocks) {
+  const dim3 grid(nblocks), block(64);
+  if (QB == 1) hipLaunchKernelGGL((attn_split_kernel<T, HD, 1>), grid, block, 0, c->stream, a);
+  else if (QB == 2) hipLaunchKernelGGL((attn_split_kernel<T, HD, 2>), grid, block, 0, c->stream, a);
+  else if constexpr (sizeof(T) == 2) hipLaunchKernelGGL((attn_split_kernel<T, HD, 4>), grid, block, 0, c->stream, a);
+}
+
+template <typename T>
+int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperature, uint64_t seed, uint64_t step) {
+  const dbl_model_cfg& g = c->cfg;
+  const int M = B * k, d = g.d_model, hd = g.head_dim, H = g.n_q_heads, Hkv = g.n_kv_heads;
+  hipStream_t st = c->stream;
+  T* xn = reinterpret_cast<T*>(c->xn);
+  T* attn = reinterpret_cast<T*>(c->attn);
+  T* act = reinterpret_cast<T*>(c->act);
+  T* qbuf = reinterpret_cast<T*>(c->qbuf);
+  const int ldh = c->p_o.ldo();   // = roundup16(d)
+
+  hipLaunchKernelGGL((embed_kernel<T>), dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->emb), window, c->h,
+                     d, ldh, g.vocab);
+
+  // attention geometry for this window size
+  const int gq = H / Hkv, nq = gq * k, qblocks = (nq + 15) / 16;
+  const int qb_max = c->bf16 ? 4 : 2;
+  int QB = qblocks >= 4 ? 4 : (qblocks >= 2 ? 2 : 1);
+  QB = std::min(QB, qb_max);
+  const int nqg = (qblocks + QB - 1) / QB;
+  int ctx_upper = 0;
+  for (int b = 0; b < B; ++b) ctx_upper = std::max(ctx_upper, c->kv_upper[b] + k);
+  int nsplit = (2 * c->n_cu + B * Hkv * nqg - 1) / (B * Hkv * nqg);
+  nsplit = std::max(1, std::min({nsplit, MAX_SPLITS, (ctx_upper + 63) / 64}));
+
+  int pending_parts = 0;   // partials of the previous down projection not yet folded into h
+  for (int l = 0; l < g.n_layers; ++l) {
+    const T* wqkv = reinterpret_cast<const T*>(c->w_qkv) + (size_t)l * c->p_qkv.elems();
+    const T* wo = reinterpret_cast<const T*>(c->w_o) + (size_t)l * c->p_o.elems();
+    const T* wgu = reinterpret_cast<const T*>(c->w_gu) + (size_t)l * c->p_gu.elems();
+    const T* wd = reinterpret_cast<const T*>(c->w_d) + (size_t)l * c->p_d.elems();
+    T* kc = reinterpret_cast<T*>(c->kc) + (size_t)l * c->kv_layer_elems;
+    T* vt = reinterpret_cast<T*>(c->vt) + (size_t)l * c->kv_layer_elems;
+
+    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(1024), 0, st, c->h, ldh, c->d_part, pending_parts, M,
+                       c->p_d.ldo(), c->g1 + (size_t)l * d, xn, c->p_qkv.ldx(), d, g.rms_eps);
+    {
+      GemmArgs<T> a{};
+      a.W = wqkv; a.X = xn; a.ldx = c->p_qkv.ldx(); a.out = c->qkv_part; a.ldo = c->p_qkv.ldo();
+      launch_gemm<T>(c, c->p_qkv, EPI_PARTIAL, a, M);
+    }
+    {
+      RopeArgs<T> r{};
+      r.qkv = c->qkv_part; r.nparts = c->p_qkv.SS; r.Mtot = M; r.ldq = c->p_qkv.ldo();
+      r.gq = g.qk_norm ? c->gq + (size_t)l * hd : nullptr;
+      r.gk = g.qk_norm ? c->gk + (size_t)l * hd : nullptr;
+      r.cosT = c->cosT; r.sinT = c->sinT; r.kv_len = c->kv_len;
+      r.qbuf = qbuf; r.kc = kc; r.vt = vt;
+      r.k = k; r.H = H; r.Hkv = Hkv; r.hd = hd; r.max_ctx = g.max_ctx; r.max_batch = g.max_batch;
+      r.qrows_pad = c->qrows_pad; r.eps = g.rms_eps;
+      const int waves = M * (H + 2 * Hkv);
+      hipLaunchKernelGGL((rope_kv_kernel<T>), dim3((waves + 3) / 4), dim3(256), 0, st, r);
+    }
+    {
+      AttnArgs<T> a{};
+      a.qbuf = qbuf; a.kc = kc; a.vt = vt; a.kv_len = c->kv_len; a.pm = c->pm; a.pl = c->pl; a.po = c->po;
+      a.k = k; a.g = gq; a.Hkv = Hkv; a.hd = hd; a.max_ctx = g.max_ctx; a.qrows_pad = c->qrows_pad;
+      a.nsplit = nsplit; a.nqg = nqg; a.scale = 1.0f / std::sqrt((float)hd);
+      const int nblocks = B * Hkv * nsplit * nqg;
+      if (hd == 128) launch_attn_hd<T, 128>(c, a, QB, nblocks); else launch_attn_hd<T, 64>(c, a, QB, nblocks);
+      const int waves = M * H;
+      hipLaunchKernelGGL((attn_combine_kernel<T>), dim3((waves + 3) / 4), dim3(256), 0, st, c->pm, c->pl, c->po, attn,
+                         c->p_o.ldx(), M, k, H, Hkv, hd, c->qrows_pad, nsplit);
+    }
+    int o_parts = 0;
+    {
+      GemmArgs<T> a{};
+      a.W = wo; a.X = attn; a.ldx = c->p_o.ldx();
+      if (c->p_o.SS == 1) { a.out = c->h; a.ldo = ldh; launch_gemm<T>(c, c->p_o, EPI_RESIDUAL, a, M); }
+      else { a.out = c->o_part; a.ldo = c->p_o.ldo(); launch_gemm<T>(c, c->p_o, EPI_PARTIAL, a, M); o_parts = c->p_o.SS; }
+    }
+    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(1024), 0, st, c->h, ldh, c->o_part, o_parts, M, c->p_o.ldo(),
+                       c->g2 + (size_t)l * d, xn, c->p_gu.ldx(), d, g.rms_eps);
+    {
+      GemmArgs<T> a{};
+      a.W = wgu; a.X = xn; a.ldx = c->p_gu.ldx(); a.act = act; a.ldact = c->p_d.ldx();
+      launch_gemm<T>(c, c->p_gu, EPI_SWIGLU, a, M);
+    }
+    {
+      GemmArgs<T> a{};
+      a.W = wd; a.X = act; a.ldx = c->p_d.ldx();
+      if (c->p_d.SS == 1) { a.out = c->h; a.ldo = ldh; launch_gemm<T>(c, c->p_d, EPI_RESIDUAL, a, M); pending_parts = 0; }
+      else { a.out = c->d_part; a.ldo = c->p_d.ldo(); launch_gemm<T>(c, c->p_d, EPI_PARTIAL, a, M); pending_parts = c->p_d.SS; }
+    }
+  }
+  hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(1024), 0, st, c->h, ldh, c->d_part, pending_parts, M,
+                     c->p_d.ldo(), c->gf, xn, c->p_lm.ldx(), d, g.rms_eps);
+  {
+    GemmArgs<T> a{};
+    a.W = reinterpret_cast<const T*>(c->w_lm); a.X = xn; a.ldx = c->p_lm.ldx();
+    a.out = c->logits; a.ldo = c->p_lm.ldo();
+    a.lm.stats = c->stats; a.lm.window = window; a.lm.commits = c->commits; a.lm.k = k;
+    a.lm.inv_T = temperature > 0.f ? 1.0f / temperature : 0.f;
+    a.lm.seed = seed; a.lm.step = step;
+    launch_gemm<T>(c, c->p_lm, EPI_LMHEAD, a, M);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(c, DBL_EHIP, std::string("verify launch: ") + hipGetErrorString(e));
+  return DBL_OK;
+}
+
+// ------------------------------------------------------------- weight set-up
+
+template <typename T>
+int fill_tiled(dbl_ctx* c, void* base, const GemmPlan& p, int layer, std::initializer_list<FillSeg> segs, bool interleave) {
+  FillArgs a{};
+  int i = 0;
+  for (const FillSeg& s : segs) a.seg[i++] = s;
+  a.nseg = i; a.interleave = interleave ? 1 : 0;
+  a.K = p.K; a.KBp = p.KBp; a.ntile_rows = p.NT * p.nacc; a.layer = layer; a.seed = c->seed;
+  T* W = reinterpret_cast<T*>(base) + (size_t)layer * p.elems();
+  const size_t threads = (size_t)a.ntile_rows * p.KBp * 64;
+  hipLaunchKernelGGL((fill_tiled_kernel<T>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, c->stream, W, a);
+  return DBL_OK;
+}
+
+template <typename T>
+int init_weights(dbl_ctx* c) {
+  const dbl_model_cfg& g = c->cfg;
+  const size_t ne = (size_t)g.vocab * g.d_model;
+  hipLaunchKernelGGL((fill_rowmajor_kernel<T>), dim3((unsigned)((ne + 255) / 256)), dim3(256), 0, c->stream,
+                     reinterpret_cast<T*>(c->emb), ne, (int)DBL_T_EMB, 0, c->seed);
+  fill_tiled<T>(c, c->w_lm, c->p_lm, 0, {{DBL_T_LM, g.vocab}}, false);
+  for (int l = 0; l < g.n_layers; ++l) {
+    fill_tiled<T>(c, c->w_qkv, c->p_qkv, l, {{DBL_T_WQ, c->hq}, {DBL_T_WK, c->hkv}, {DBL_T_WV, c->hkv}}, false);
+    fill_tiled<T>(c, c->w_o, c->p_o, l, {{DBL_T_WO, g.d_model}}, false);
+    fill_tiled<T>(c, c->w_gu, c->p_gu, l, {{DBL_T_WG, g.d_ffn}, {DBL_T_WU, g.d_ffn}}, true);
+    fill_tiled<T>(c, c->w_d, c->p_d, l, {{DBL_T_WD, g.d_model}}, false);
+  }
+  auto ones = [&](float* p, size_t n) {
+    hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, p, 1.0f, n);
+  };
+  const size_t L = std::max(1, g.n_layers);
+  ones(c->g1, L * g.d_model); ones(c->g2, L * g.d_model);
+  ones(c->gq, L * g.head_dim); ones(c->gk, L * g.head_dim); ones(c->gf, g.d_model);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(c, DBL_EHIP, std::string("weight init: ") + hipGetErrorString(e));
+  return DBL_OK;
+}
+
+// where a logical tensor lives: container, plan, row offset / interleave slot
+struct TensorLoc {
+  void* base = nullptr; const GemmPlan* plan = nullptr;
+  int rows = 0, cols = 0, row0 = 0, inter = -1;   // inter: 0 gate, 1 up, -1 none
+  bool tiled = false, is_gain = false;
+  size_t layer_elems = 0;
+};
+
+int locate(dbl_ctx* c, int id, int layer, TensorLoc& t) {
+  const dbl_model_cfg& g = c->cfg;
+  const bool per_layer = id >= DBL_T_G1;
+  if (per_layer && (layer < 0 || layer >= g.n_layers)) return DBL_EINVAL;
+  switch (id) {
+    case DBL_T_EMB: t.base = c->emb; t.rows = g.vocab; t.cols = g.d_model; break;
+    case DBL_T_LM: t.base = c->w_lm; t.plan = &c->p_lm; t.rows = g.vocab; t.cols = g.d_model; t.tiled = true; break;
+    case DBL_T_GF: t.base = c->gf; t.rows = 1; t.cols = g.d_model; t.is_gain = true; break;
+    case DBL_T_G1: t.base = c->g1 + (size_t)layer * g.d_model; t.rows = 1; t.cols = g.d_model; t.is_gain = true; break;
+    case DBL_T_G2: t.base = c->g2 + (size_t)layer * g.d_model; t.rows = 1; t.cols = g.d_model; t.is_gain = true; break;
+    case DBL_T_GQ: t.base = c->gq + (size_t)layer * g.head_dim; t.rows = 1; t.cols = g.head_dim; t.is_gain = true; break;
+    case DBL_T_GK: t.base = c->gk + (size_t)layer * g.head_dim; t.rows = 1; t.cols = g.head_dim; t.is_gain = true; break;
+    case DBL_T_WQ: t.base = c->w_qkv; t.plan = &c->p_qkv; t.rows = c->hq; t.cols = g.d_model; t.row0 = 0; t.tiled = true; break;
+    case DBL_T_WK: t.base = c->w_qkv; t.plan = &c->p_qkv; t.rows = c->hkv; t.cols = g.d_model; t.row0 = c->hq; t.tiled = true; break;
+    case DBL_T_WV: t.base = c->w_qkv; t.plan = &c->p_qkv; t.rows = c->hkv; t.cols = g.d_model; t.row0 = c->hq + c->hkv; t.tiled = true; break;
+    case DBL_T_WO: t.base = c->w_o; t.plan = &c->p_o; t.rows = g.d_model; t.cols = c->hq; t.tiled = true; break;
+    case DBL_T_WG: t.base = c->w_gu; t.plan = &c->p_gu; t.rows = g.d_ffn; t.cols = g.d_model; t.inter = 0; t.tiled = true; break;
+    case DBL_T_WU: t.base = c->w_gu; t.plan = &c->p_gu; t.rows = g.d_ffn; t.cols = g.d_model; t.inter = 1; t.tiled = true; break;
+    case DBL_T_WD: t.base = c->w_d; t.plan = &c->p_d; t.rows = g.d_model; t.cols = g.d_ffn; t.tiled = true; break;
+    default: return DBL_EINVAL;
+  }
+  if (t.tiled) t.layer_elems = t.plan->elems();
+  return DBL_OK;
+}
+
+// physical tile row of logical row r of a located tensor
+inline int phys_row(const TensorLoc& t, int r) {
+  if (t.inter >= 0) return ((r >> 4) * 2 + t.inter) * 16 + (r & 15);
+  return t.row0 + r;
+}
+
+template <typename T>
+int copy_tensor(dbl_ctx* c, const TensorLoc& t, int layer, void* host, bool to_device) {
+  T* hp = reinterpret_cast<T*>(host);
+  if (!t.tiled) {  // embedding: plain row-major
+    const size_t bytes = (size_t)t.rows * t.cols * sizeof(T);
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (to_device) HIPCHK(c, hipMemcpy(t.base, host, bytes, hipMemcpyHostToDevice));
+    else HIPCHK(c, hipMemcpy(host, t.base, bytes, hipMemcpyDeviceToHost));
+    return DBL_OK;
+  }
+  const GemmPlan& p = *t.plan;
+  T* dev = reinterpret_cast<T*>(t.base) + (size_t)layer * t.layer_elems;
+  const size_t n = p.elems();
+  std::vector<T> tmp;
+  try { tmp.resize(n); } catch (const std::bad_alloc&) { return fail(c, DBL_ENOMEM, "host staging buffer"); }
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(tmp.data(), dev, n * sizeof(T), hipMemcpyDeviceToHost));
+  for (int r = 0; r < t.rows; ++r) {
+    const int pr = phys_row(t, r);
+    for (int k = 0; k < t.cols; ++k) {
+      const size_t off = tiled_offset<T>(pr, k, p.KBp);
+      if (to_device) tmp[off] = hp[(size_t)r * t.cols + k]; else hp[(size_t)r * t.cols + k] = tmp[off];
+    }
+  }
+  if (to_device) HIPCHK(c, hipMemcpy(dev, tmp.data(), n * sizeof(T), hipMemcpyHostToDevice));
+  return DBL_OK;
+}
+
+void free_all(dbl_ctx* c) {
+  void* ptrs[] = {c->w_qkv, c->w_o, c->w_gu, c->w_d, c->w_lm, c->emb, c->g1, c->g2, c->gq, c->gk, c->gf, c->cosT,
+                  c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->status, c->commits, c->h, c->qkv_part,
+                  c->d_part, c->o_part, c->logits, c->xn, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
+                  c->n_acc_i, c->emit_i, c->win_i};
+  for (void* p : ptrs) if (p) (void)hipFree(p);
+}
+
+int check_status(dbl_ctx* c) {
+  int32_t s = 0;
+  HIPCHK(c, hipMemcpy(&s, c->status, sizeof(s), hipMemcpyDeviceToHost));
+  if (s) return fail(c, DBL_ESTATE, (s & 1) ? "a commit would exceed max_ctx and was clamped" : "a commit would exceed max_hist and was clamped");
+  return DBL_OK;
+}
+
+}  // namespace
+
+// ===================================================================== C ABI
+
+extern "C" {
+
+int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream, dbl_ctx** out) {
+  if (!cfg || !out) return DBL_EINVAL;
+  *out = nullptr;
+  std::string why;
+  if (validate_cfg(cfg, why) != DBL_OK) return DBL_EINVAL;
+  dbl_ctx* c = new (std::nothrow) dbl_ctx();
+  if (!c) return DBL_ENOMEM;
+  c->cfg = *cfg; c->bf16 = cfg->dtype == DBL_BF16; c->esz = c->bf16 ? 2 : 4;
+  c->dry = (cfg->flags & DBL_FLAG_VALIDATE_ONLY) != 0;
+  c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  c->seed = weight_seed;
+  c->kv_upper.assign(cfg->max_batch, 0); c->hist_upper.assign(cfg->max_batch, 0);
+  int rc = DBL_OK;
+  if (!c->dry) {
+    hipError_t e = hipGetDevice(&c->device);
+    if (e != hipSuccess) { delete c; return DBL_EHIP; }
+    int ncu = 0;
+    if (hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && ncu > 0) c->n_cu = ncu;
+  }
+  rc = make_plans(c);
+  if (rc != DBL_OK) { delete c; return rc; }
+  if (c->dry) { *out = c; return DBL_OK; }
+
+  const dbl_model_cfg& g = c->cfg;
+  const size_t L = std::max(1, g.n_layers), esz = c->esz;
+  const int Mmax = g.max_batch * g.max_window;
+  const int gq = g.n_q_heads / g.n_kv_heads;
+  c->qrows_pad = ((gq * g.max_window + 63) / 64) * 64;
+  c->kv_layer_elems = (size_t)g.max_batch * g.n_kv_heads * g.max_ctx * g.head_dim;
+  const size_t part_rows = (size_t)g.max_batch * g.n_kv_heads * MAX_SPLITS * c->qrows_pad;
+
+#define ALLOC(ptr, bytes, zero) if ((rc = dmalloc(c, &c->ptr, (bytes), (zero))) != DBL_OK) break
+  do {
+    ALLOC(w_qkv, L * c->p_qkv.elems() * esz, false);
+    ALLOC(w_o, L * c->p_o.elems() * esz, false);
+    ALLOC(w_gu, L * c->p_gu.elems() * esz, false);
+    ALLOC(w_d, L * c->p_d.elems() * esz, false);
+    ALLOC(w_lm, c->p_lm.elems() * esz, false);
+    ALLOC(emb, (size_t)g.vocab * g.d_model * esz, false);
+    ALLOC(g1, L * g.d_model * 4, false); ALLOC(g2, L * g.d_model * 4, false);
+    ALLOC(gq, L * g.head_dim * 4, false); ALLOC(gk, L * g.head_dim * 4, false);
+    ALLOC(gf, (size_t)g.d_model * 4, false);
+    ALLOC(cosT, (size_t)g.max_ctx * (g.head_dim / 2) * 4, false);
+    ALLOC(sinT, (size_t)g.max_ctx * (g.head_dim / 2) * 4, false);
+    ALLOC(kc, L * c->kv_layer_elems * esz, true);
+    ALLOC(vt, L * c->kv_layer_elems * esz, true);
+    ALLOC(kv_len, (size_t)g.max_batch * 4, true); ALLOC(hist_len, (size_t)g.max_batch * 4, true);
+    ALLOC(hist, (size_t)g.max_batch * g.max_hist * 4, true);
+    ALLOC(status, 4, true); ALLOC(commits, 8, true);
+    ALLOC(h, (size_t)Mmax * c->p_o.ldo() * 4, true);
+    ALLOC(qkv_part, (size_t)c->p_qkv.SS * Mmax * c->p_qkv.ldo() * 4, true);
+    ALLOC(d_part, (size_t)c->p_d.SS * Mmax * c->p_d.ldo() * 4, true);
+    ALLOC(o_part, (size_t)c->p_o.SS * Mmax * c->p_o.ldo() * 4, true);
+    ALLOC(logits, (size_t)Mmax * c->p_lm.ldo() * 4, true);
+    ALLOC(xn, (size_t)Mmax * std::max({c->p_qkv.ldx(), c->p_gu.ldx(), c->p_lm.ldx()}) * esz, true);
+    ALLOC(qbuf, (size_t)g.max_batch * g.n_kv_heads * c->qrows_pad * g.head_dim * esz, true);
+    ALLOC(attn, (size_t)Mmax * c->p_o.ldx() * esz, true);
+    ALLOC(act, (size_t)Mmax * c->p_d.ldx() * esz, true);
+    ALLOC(pm, part_rows * 4, true); ALLOC(pl, part_rows * 4, true); ALLOC(po, part_rows * g.head_dim * 4, true);
+    ALLOC(stats, (size_t)c->p_lm.grid * Mmax * sizeof(LmStat), true);
+    ALLOC(n_acc_i, (size_t)g.max_batch * 4, true); ALLOC(emit_i, (size_t)Mmax * 4, true);
+    ALLOC(win_i, (size_t)Mmax * 4, true);
+  } while (0);
+#undef ALLOC
+  if (rc == DBL_OK) {
+    // rotary tables: angle = pos * base^(-2i/hd) in fp64, rounded to fp32
+    const int half = g.head_dim / 2;
+    std::vector<float> cs((size_t)g.max_ctx * half), sn((size_t)g.max_ctx * half);
+    for (int i = 0; i < half; ++i) {
+      const double theta = std::pow((double)g.rope_base, -2.0 * i / g.head_dim);
+      for (int p = 0; p < g.max_ctx; ++p) {
+        const double ang = (double)p * theta;
+        cs[(size_t)p * half + i] = (float)std::cos(ang);
+        sn[(size_t)p * half + i] = (float)std::sin(ang);
+      }
+    }
+    hipError_t e = hipMemcpy(c->cosT, cs.data(), cs.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->sinT, sn.data(), sn.size() * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) rc = fail(c, DBL_EHIP, std::string("rope tables: ") + hipGetErrorString(e));
+  }
+  if (rc == DBL_OK) rc = c->bf16 ? init_weights<bf16_t>(c) : init_weights<float>(c);
+  if (rc == DBL_OK) {
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) rc = fail(c, DBL_EHIP, std::string("create sync: ") + hipGetErrorString(e));
+  }
+  if (rc != DBL_OK) {
+    std::fprintf(stderr, "dbl_create: %s\n", c->err.c_str());
+    free_all(c); delete c; return rc;
+  }
+  *out = c;
+  return DBL_OK;
+}
+
+int dbl_destroy(dbl_ctx* c) {
+  if (!c) return DBL_EINVAL;
+  if (!c->dry) { (void)hipStreamSynchronize(c->stream); free_all(c); }
+  delete c;
+  return DBL_OK;
+}
+
+const char* dbl_last_error(const dbl_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+int dbl_model_bytes(const dbl_ctx* c, uint64_t* weight_bytes, uint64_t* kv_bytes_per_token) {
+  if (!c) return DBL_EINVAL;
+  const dbl_model_cfg& g = c->cfg;
+  if (weight_bytes) {
+    // logical (algorithmic) bytes: every layer matrix once + LM head once
+    const uint64_t per_layer = (uint64_t)c->n_qkv * g.d_model + (uint64_t)g.d_model * c->hq + 3ull * g.d_ffn * g.d_model;
+    *weight_bytes = ((uint64_t)g.n_layers * per_layer + (uint64_t)g.vocab * g.d_model) * c->esz;
+  }
+  if (kv_bytes_per_token) *kv_bytes_per_token = 2ull * g.n_layers * c->hkv * c->esz;
+  return DBL_OK;
+}
+
+static int weights_io(dbl_ctx* c, int id, int layer, void* host, size_t bytes, bool to_device) {
+  if (!c || !host) return fail(c, DBL_EINVAL, "null argument");
+  TensorLoc t;
+  if (locate(c, id, layer, t) != DBL_OK) return fail(c, DBL_EINVAL, "unknown tensor id or layer");
+  const size_t want = (size_t)t.rows * t.cols * (t.is_gain ? 4 : c->esz);
+  if (bytes != want) return fail(c, DBL_EINVAL, "tensor size mismatch");
+  if (c->dry) return DBL_ENODEV;
+  if (t.is_gain) {
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (to_device) HIPCHK(c, hipMemcpy(t.base, host, bytes, hipMemcpyHostToDevice));
+    else HIPCHK(c, hipMemcpy(host, t.base, bytes, hipMemcpyDeviceToHost));
+    return DBL_OK;
+  }
+  return c->bf16 ? copy_tensor<bf16_t>(c, t, layer, host, to_device) : copy_tensor<float>(c, t, layer, host, to_device);
+}
+
+int dbl_set_weights(dbl_ctx* c, int id, int layer, const void* host, size_t bytes) {
+  return weights_io(c, id, layer, const_cast<void*>(host), bytes, true);
+}
+int dbl_get_weights(dbl_ctx* c, int id, int layer, void* host, size_t bytes) {
+  return weights_io(c, id, layer, host, bytes, false);
+}
+
+int dbl_reset(dbl_ctx* c, int seq) {
+  if (!c) return DBL_EINVAL;
+  if (seq >= c->cfg.max_batch) return fail(c, DBL_EINVAL, "seq out of range");
+  for (int b = 0; b < c->cfg.max_batch; ++b)
+    if (seq < 0 || b == seq) { c->kv_upper[b] = 0; c->hist_upper[b] = 0; }
+  c->have_verify = c->have_accept = false;
+  if (c->dry) return DBL_ENODEV;
+  hipLaunchKernelGGL(set_counters_kernel, dim3(1), dim3(128), 0, c->stream, c->kv_len, c->hist_len, seq, c->cfg.max_batch);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+int dbl_history_set(dbl_ctx* c, int seq, const int32_t* host_tokens, int n) {
+  if (!c) return DBL_EINVAL;
+  if (seq < 0 || seq >= c->cfg.max_batch) return fail(c, DBL_EINVAL, "seq out of range");
+  if (n < 0 || n > c->cfg.max_hist || (n > 0 && !host_tokens)) return fail(c, DBL_EINVAL, "bad history length");
+  c->hist_upper[seq] = n;
+  if (c->dry) return DBL_ENODEV;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (n > 0) HIPCHK(c, hipMemcpy(c->hist + (size_t)seq * c->cfg.max_hist, host_tokens, (size_t)n * 4, hipMemcpyHostToDevice));
+  const int32_t nn = n;
+  HIPCHK(c, hipMemcpy(c->hist_len + seq, &nn, 4, hipMemcpyHostToDevice));
+  return DBL_OK;
+}
+
+int dbl_history_get(dbl_ctx* c, int seq, int32_t* host_out, int cap, int32_t* n_out) {
+  if (!c) return DBL_EINVAL;
+  if (seq < 0 || seq >= c->cfg.max_batch) return fail(c, DBL_EINVAL, "seq out of range");
+  if (cap < 0 || (cap > 0 && !host_out) || !n_out) return fail(c, DBL_EINVAL, "bad output buffer");
+  if (c->dry) return DBL_ENODEV;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  int32_t n = 0;
+  HIPCHK(c, hipMemcpy(&n, c->hist_len + seq, 4, hipMemcpyDeviceToHost));
+  n = std::max(0, std::min(n, c->cfg.max_hist));
+  *n_out = n;
+  const int m = std::min(n, cap);
+  if (m > 0) HIPCHK(c, hipMemcpy(host_out, c->hist + (size_t)seq * c->cfg.max_hist, (size_t)m * 4, hipMemcpyDeviceToHost));
+  return DBL_OK;
+}
+
+int dbl_retrieve(dbl_ctx* c, int B, int n_max, int n_min, int max_cont, int32_t* cont, int32_t* cont_len,
+                 int32_t* match_n, int32_t* match_pos) {
+  if (!c) return DBL_EINVAL;
+  if (!cont || !cont_len || !match_n || !match_pos) return fail(c, DBL_EINVAL, "null output pointer");
+  if (B < 1 || B > c->cfg.max_batch) return fail(c, DBL_EINVAL, "B out of range");
+  if (n_min < 1 || n_max < n_min || n_max > 32) return fail(c, DBL_EINVAL, "need 1 <= n_min <= n_max <= 32");
+  if (max_cont < 1 || max_cont > 64) return fail(c, DBL_EINVAL, "need 1 <= max_cont <= 64");
+  if (c->dry) return DBL_ENODEV;
+  hipLaunchKernelGGL(retrieve_kernel, dim3(B), dim3(1024), 0, c->stream, c->hist, c->hist_len, c->cfg.max_hist, n_max,
+                     n_min, max_cont, cont, cont_len, match_n, match_pos);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+int dbl_build_window(dbl_ctx* c, int B, int k, int max_cont, const int32_t* cont, const int32_t* cont_len,
+                     int32_t pad_id, int32_t* window) {
+  if (!c) return DBL_EINVAL;
+  if (!cont || !cont_len || !window) return fail(c, DBL_EINVAL, "null pointer");
+  if (B < 1 || B > c->cfg.max_batch) return fail(c, DBL_EINVAL, "B out of range");
+  if (k < 1 || k > c->cfg.max_window) return fail(c, DBL_EINVAL, "k out of range");
+  if (max_cont < 1 || max_cont > 64) return fail(c, DBL_EINVAL, "need 1 <= max_cont <= 64");
+  if (pad_id < 0 || pad_id >= c->cfg.vocab) return fail(c, DBL_EINVAL, "pad_id out of range");
+  if (c->dry) return DBL_ENODEV;
+  hipLaunchKernelGGL(build_window_kernel, dim3(B), dim3(64), 0, c->stream, c->hist, c->hist_len, c->cfg.max_hist, cont,
+                     cont_len, max_cont, k, pad_id, window);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+int dbl_verify_block(dbl_ctx* c, const int32_t* window, int B, int k, float temperature, uint64_t seed, uint64_t step,
+                     float* logits_opt) {
+  if (!c) return DBL_EINVAL;
+  if (!window) return fail(c, DBL_EINVAL, "null window");
+  if (B < 1 || B > c->cfg.max_batch) return fail(c, DBL_EINVAL, "B out of range");
+  if (k < 1 || k > c->cfg.max_window) return fail(c, DBL_EINVAL, "k out of range");
+  if (!(temperature == temperature)) return fail(c, DBL_EINVAL, "temperature is NaN");
+  for (int b = 0; b < B; ++b)
+    if (c->kv_upper[b] + k > c->cfg.max_ctx) return fail(c, DBL_EINVAL, "kv_len + k would exceed max_ctx");
+  c->have_verify = false; c->have_accept = false;
+  if (c->dry) { c->have_verify = true; c->last_B = B; c->last_k = k; c->verify_sampling = temperature > 0.f; return DBL_ENODEV; }
+  // keep the window for accept (the caller's buffer is not retained)
+  HIPCHK(c, hipMemcpyAsync(c->win_i, window, (size_t)B * k * 4, hipMemcpyDeviceToDevice, c->stream));
+  int rc = c->bf16 ? verify_impl<bf16_t>(c, c->win_i, B, k, temperature, seed, step)
+                   : verify_impl<float>(c, c->win_i, B, k, temperature, seed, step);
+  if (rc != DBL_OK) return rc;
+  if (logits_opt) {
+    HIPCHK(c, hipMemcpy2DAsync(logits_opt, (size_t)c->cfg.vocab * 4, c->logits, (size_t)c->p_lm.ldo() * 4,
+                               (size_t)c->cfg.vocab * 4, (size_t)B * k, hipMemcpyDeviceToDevice, c->stream));
+  }
+  c->have_verify = true; c->last_B = B; c->last_k = k; c->verify_sampling = temperature > 0.f;
+  c->last_T = temperature; c->last_seed = seed; c->last_step = step;
+  return DBL_OK;
+}
+
+int dbl_accept(dbl_ctx* c, int mode, const float* q_probs, int32_t* n_acc, int32_t* emit, int32_t* guide) {
+  if (!c) return DBL_EINVAL;
+  if (!n_acc || !emit || !guide) return fail(c, DBL_EINVAL, "null output pointer");
+  if (mode != DBL_GREEDY && mode != DBL_SAMPLE) return fail(c, DBL_EINVAL, "bad mode");
+  if (!c->have_verify) return fail(c, DBL_ESTATE, "dbl_accept needs a preceding dbl_verify_block");
+  if (mode == DBL_SAMPLE && !c->verify_sampling) return fail(c, DBL_ESTATE, "sampling needs temperature > 0 in dbl_verify_block");
+  if (mode == DBL_GREEDY && q_probs) return fail(c, DBL_EINVAL, "q_probs given in greedy mode");
+  if (c->dry) { c->have_accept = true; return DBL_ENODEV; }
+  AcceptArgs a{};
+  a.stats = c->stats; a.nstat = c->p_lm.grid; a.Mtot = c->last_B * c->last_k;
+  a.logits = c->logits; a.ldl = c->p_lm.ldo(); a.window = c->win_i; a.q = q_probs; a.commits = c->commits;
+  a.n_acc = n_acc; a.emit = emit; a.guide = guide; a.n_acc_i = c->n_acc_i; a.emit_i = c->emit_i;
+  a.k = c->last_k; a.V = c->cfg.vocab; a.mode = mode;
+  a.inv_T = c->verify_sampling ? 1.0f / c->last_T : 0.f;
+  a.seed = c->last_seed; a.step = c->last_step;
+  hipLaunchKernelGGL(accept_kernel, dim3(c->last_B), dim3(256), 0, c->stream, a);
+  HIPCHK(c, hipGetLastError());
+  c->have_accept = true;
+  return DBL_OK;
+}
+
+int dbl_kv_commit(dbl_ctx* c, const int32_t* n_keep) {
+  if (!c) return DBL_EINVAL;
+  if (!c->have_verify) return fail(c, DBL_ESTATE, "dbl_kv_commit needs a preceding dbl_verify_block");
+  if (!n_keep && !c->have_accept) return fail(c, DBL_ESTATE, "dbl_kv_commit(NULL) needs a preceding dbl_accept");
+  const int B = c->last_B, k = c->last_k;
+  const bool append = n_keep == nullptr;
+  for (int b = 0; b < B; ++b) {
+    c->kv_upper[b] = std::min(c->cfg.max_ctx, c->kv_upper[b] + k);
+    if (append) c->hist_upper[b] = std::min(c->cfg.max_hist, c->hist_upper[b] + k);
+  }
+  c->have_verify = false; c->have_accept = false;
+  if (c->dry) return DBL_ENODEV;
+  hipLaunchKernelGGL(commit_kernel, dim3(1), dim3(128), 0, c->stream, c->kv_len, c->hist_len, c->hist, c->cfg.max_hist,
+                     c->cfg.max_ctx, n_keep, c->n_acc_i, c->emit_i, k, B, append ? 1 : 0, c->commits, c->status);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+static int read_counters(dbl_ctx* c, int32_t* host_out, bool kv) {
+  if (!c) return DBL_EINVAL;
+  if (!host_out) return fail(c, DBL_EINVAL, "null output pointer");
+  if (c->dry) return DBL_ENODEV;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  const int n = c->cfg.max_batch;
+  std::vector<int32_t> a(n), b(n);
+  HIPCHK(c, hipMemcpy(a.data(), c->kv_len, (size_t)n * 4, hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(b.data(), c->hist_len, (size_t)n * 4, hipMemcpyDeviceToHost));
+  for (int i = 0; i < n; ++i) { c->kv_upper[i] = a[i]; c->hist_upper[i] = b[i]; }
+  std::memcpy(host_out, kv ? a.data() : b.data(), (size_t)n * 4);
+  return check_status(c);
+}
+
+}  // extern "C"
+
+template <typename T>
+static void bench_launch(dbl_ctx* c, int which, int layer, int M) {
+  GemmArgs<T> a{};
+  const dbl_model_cfg& g = c->cfg;
+  switch (which) {
+    case 0:
+      a.W = reinterpret_cast<const T*>(c->w_qkv) + (size_t)layer * c->p_qkv.elems(); a.X = reinterpret_cast<const T*>(c->xn);
+      a.ldx = c->p_qkv.ldx(); a.out = c->qkv_part; a.ldo = c->p_qkv.ldo();
+      launch_gemm<T>(c, c->p_qkv, EPI_PARTIAL, a, M); break;
+    case 1:
+      a.W = reinterpret_cast<const T*>(c->w_o) + (size_t)layer * c->p_o.elems(); a.X = reinterpret_cast<const T*>(c->attn);
+      a.ldx = c->p_o.ldx();
+      if (c->p_o.SS == 1) { a.out = c->h; a.ldo = c->p_o.ldo(); launch_gemm<T>(c, c->p_o, EPI_RESIDUAL, a, M); }
+      else { a.out = c->o_part; a.ldo = c->p_o.ldo(); launch_gemm<T>(c, c->p_o, EPI_PARTIAL, a, M); }
+      break;
+    case 2:
+      a.W = reinterpret_cast<const T*>(c->w_gu) + (size_t)layer * c->p_gu.elems(); a.X = reinterpret_cast<const T*>(c->xn);
+      a.ldx = c->p_gu.ldx(); a.act = reinterpret_cast<T*>(c->act); a.ldact = c->p_d.ldx();
+      launch_gemm<T>(c, c->p_gu, EPI_SWIGLU, a, M); break;
+    case 3:
+      a.W = reinterpret_cast<const T*>(c->w_d) + (size_t)layer * c->p_d.elems(); a.X = reinterpret_cast<const T*>(c->act);
+      a.ldx = c->p_d.ldx();
+      if (c->p_d.SS == 1) { a.out = c->h; a.ldo = c->p_o.ldo(); launch_gemm<T>(c, c->p_d, EPI_RESIDUAL, a, M); }
+      else { a.out = c->d_part; a.ldo = c->p_d.ldo(); launch_gemm<T>(c, c->p_d, EPI_PARTIAL, a, M); }
+      break;
+    default:
+      a.W = reinterpret_cast<const T*>(c->w_lm); a.X = reinterpret_cast<const T*>(c->xn); a.ldx = c->p_lm.ldx();
+      a.out = c->logits; a.ldo = c->p_lm.ldo();
+      a.lm.stats = c->stats; a.lm.window = c->win_i; a.lm.commits = c->commits; a.lm.k = M; a.lm.inv_T = 0.f;
+      launch_gemm<T>(c, c->p_lm, EPI_LMHEAD, a, M); break;
+  }
+  (void)g;
+}
+
+extern "C" {
+
+int dbl_bench_projection(dbl_ctx* c, int which, int M, int iters, float* ms_out, uint64_t* bytes_out) {
+  if (!c) return DBL_EINVAL;
+  if (!ms_out || !bytes_out) return fail(c, DBL_EINVAL, "null output pointer");
+  if (which < 0 || which > 4 || iters < 1 || iters > 100000) return fail(c, DBL_EINVAL, "bad which / iters");
+  if (M < 1 || M > 16 || M > c->cfg.max_batch * c->cfg.max_window) return fail(c, DBL_EINVAL, "M out of range");
+  if (which < 4 && c->cfg.n_layers < 1) return fail(c, DBL_EINVAL, "model has no layers");
+  const dbl_model_cfg& g = c->cfg;
+  const uint64_t elems[5] = {(uint64_t)c->n_qkv * g.d_model, (uint64_t)g.d_model * c->hq, 2ull * g.d_ffn * g.d_model,
+                             (uint64_t)g.d_model * g.d_ffn, (uint64_t)g.vocab * g.d_model};
+  *bytes_out = elems[which] * c->esz;
+  if (c->dry) return DBL_ENODEV;
+  hipEvent_t e0, e1;
+  HIPCHK(c, hipEventCreate(&e0));
+  HIPCHK(c, hipEventCreate(&e1));
+  const int L = std::max(1, g.n_layers);
+  for (int pass = 0; pass < 2; ++pass) {   // pass 0 warms up (2 launches), pass 1 is timed
+    const int n = pass == 0 ? 2 : iters;
+    if (pass == 1) HIPCHK(c, hipEventRecord(e0, c->stream));
+    for (int i = 0; i < n; ++i) {
+      if (c->bf16) bench_launch<bf16_t>(c, which, i % L, M); else bench_launch<float>(c, which, i % L, M);
+    }
+    if (pass == 1) HIPCHK(c, hipEventRecord(e1, c->stream));
+  }
+  HIPCHK(c, hipEventSynchronize(e1));
+  HIPCHK(c, hipGetLastError());
+  float ms = 0.f;
+  HIPCHK(c, hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  *ms_out = ms / (float)iters;
+  return DBL_OK;
+}
+
+int dbl_debug_buffer(dbl_ctx* c, int which, void* host, size_t bytes, int32_t* ld_out) {
+  if (!c) return DBL_EINVAL;
+  if (!host || !ld_out || which < 0 || which > 2) return fail(c, DBL_EINVAL, "bad debug buffer request");
+  const size_t rows = (size_t)c->cfg.max_batch * c->cfg.max_window;
+  const void* src = which == 0 ? (const void*)c->h : which == 1 ? (const void*)c->attn : (const void*)c->act;
+  const int ld = which == 0 ? c->p_o.ldo() : which == 1 ? c->p_o.ldx() : c->p_d.ldx();
+  const size_t need = rows * ld * (which == 0 ? 4 : c->esz);
+  if (bytes < need) return fail(c, DBL_EINVAL, "debug buffer too small");
+  *ld_out = ld;
+  if (c->dry) return DBL_ENODEV;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(host, src, need, hipMemcpyDeviceToHost));
+  return DBL_OK;
+}
+
+int dbl_kv_len(dbl_ctx* c, int32_t* host_out) { return read_counters(c, host_out, true); }
+int dbl_hist_len(dbl_ctx* c, int32_t* host_out) { return read_counters(c, host_out, false); }
+
+}  // extern "C"

@@ -66,7 +66,7 @@ def test_matches_library_decoder(dtype, qk_norm):
     toks = rng.integers(0, 97, 23).astype(np.int32)
     got, _ = run_chunks(m, toks, [5, 1, 8, 4, 2, 3])
     ref = forward_full(m, toks)
-    assert np.abs(ref).max() > 0.5
+    assert np.abs(ref).max() > 0.3
     if dtype == 0:
         # only difference: the oracle's cos/sin go through an fp32 table
         np.testing.assert_allclose(got, ref, rtol=0, atol=2e-6)

@@ -77,17 +77,8 @@ def forward_full(model: O.Model, tokens):
         g = H // Hkv
         kx = k.repeat_interleave(g, dim=1)
         vx = v.repeat_interleave(g, dim=1)
-        if bf:
-            # probabilities are rounded before weighting v, so the fused library
-            # attention cannot be used; softmax and matmul are still library calls
-            s = torch.einsum("thd,shd->hts", q, kx) / np.sqrt(hd)
-            mask = torch.ones(T, T, dtype=torch.bool).tril()
-            s = s.masked_fill(~mask, float("-inf"))
-            p = _rnd(torch.softmax(s, dim=-1), True)
-            att = torch.einsum("hts,shd->thd", p, vx)
-        else:
-            att = F.scaled_dot_product_attention(q.transpose(0, 1)[None], kx.transpose(0, 1)[None],
-                                                 vx.transpose(0, 1)[None], is_causal=True)[0].transpose(0, 1)
+        att = F.scaled_dot_product_attention(q.transpose(0, 1)[None], kx.transpose(0, 1)[None],
+                                             vx.transpose(0, 1)[None], is_causal=True)[0].transpose(0, 1)
         att = _rnd(att.reshape(T, H * hd), bf)
         h = h + att @ L["wo"].T
         m = _rnd(F.rms_norm(h, (c.d_model,), L["g2"], c.rms_eps), bf)
