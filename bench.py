@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the model's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=40, help="launches per projection for the roofline line")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus)
@@ -189,6 +191,12 @@ def main():
                 "achieved": dom["GB/s"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(dom["GB/s"] / HBM_PEAK_GBPS, 4), "traffic": None,
                 "bytes_per_launch": dom["bytes"], "ms_per_launch": dom["ms"]}
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     B.dbl_destroy(ctx)
 
     out = {

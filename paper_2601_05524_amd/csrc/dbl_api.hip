@@ -151,6 +151,8 @@ int make_plans(dbl_ctx* c) {
             make_plan(c->p_d, g.d_model, g.d_ffn, 1, c->bf16, false, c->n_cu) &&
             make_plan(c->p_lm, g.vocab, g.d_model, 1, c->bf16, true, c->n_cu);
   if (!ok) return fail(c, DBL_EINVAL, "d_model too large for a single K slice (max 8192 bf16 / 4096 fp32)");
+  if (c->p_qkv.SS > RMS_MAXP || c->p_o.SS > RMS_MAXP || c->p_d.SS > RMS_MAXP)
+    return fail(c, DBL_EINVAL, "a projection needs more than 8 K super-slices (n_q_heads*head_dim or d_ffn too large)");
   return DBL_OK;
 }
 
@@ -180,11 +182,11 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
 }
 
 template <typename T, int HD>
-void launch_attn_hd(dbl_ctx* c, const AttnArgs<T>& a, int QB, int nblocks) {
-  const dim3 grid(nblocks), block(64);
-  if (QB == 1) hipLaunchKernelGGL((attn_split_kernel<T, HD, 1>), grid, block, 0, c->stream, a);
-  else if (QB == 2) hipLaunchKernelGGL((attn_split_kernel<T, HD, 2>), grid, block, 0, c->stream, a);
-  else if constexpr (sizeof(T) == 2) hipLaunchKernelGGL((attn_split_kernel<T, HD, 4>), grid, block, 0, c->stream, a);
+void launch_attn_hd(dbl_ctx* c, const AttnArgs<T>& a, int waves_per_group, int nblocks, T* attn, int M, int H) {
+  hipLaunchKernelGGL((attn_split_kernel<T, HD>), dim3(nblocks), dim3(64 * waves_per_group), 0, c->stream, a);
+  const int waves = M * H;
+  hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3((waves + 3) / 4), dim3(256), 0, c->stream, c->pm, c->pl, c->po,
+                     attn, c->p_o.ldx(), M, a.k, H, a.Hkv, c->qrows_pad, a.nsplit);
 }
 
 template <typename T>
@@ -203,10 +205,8 @@ int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperatu
 
   // attention geometry for this window size
   const int gq = H / Hkv, nq = gq * k, qblocks = (nq + 15) / 16;
-  const int qb_max = c->bf16 ? 4 : 2;
-  int QB = qblocks >= 4 ? 4 : (qblocks >= 2 ? 2 : 1);
-  QB = std::min(QB, qb_max);
-  const int nqg = (qblocks + QB - 1) / QB;
+  const int wpg = std::min(qblocks, 4);              // waves (query blocks) per workgroup
+  const int nqg = (qblocks + wpg - 1) / wpg;
   int ctx_upper = 0;
   for (int b = 0; b < B; ++b) ctx_upper = std::max(ctx_upper, c->kv_upper[b] + k);
   int nsplit = (2 * c->n_cu + B * Hkv * nqg - 1) / (B * Hkv * nqg);
@@ -246,10 +246,8 @@ int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperatu
       a.k = k; a.g = gq; a.Hkv = Hkv; a.hd = hd; a.max_ctx = g.max_ctx; a.qrows_pad = c->qrows_pad;
       a.nsplit = nsplit; a.nqg = nqg; a.scale = 1.0f / std::sqrt((float)hd);
       const int nblocks = B * Hkv * nsplit * nqg;
-      if (hd == 128) launch_attn_hd<T, 128>(c, a, QB, nblocks); else launch_attn_hd<T, 64>(c, a, QB, nblocks);
-      const int waves = M * H;
-      hipLaunchKernelGGL((attn_combine_kernel<T>), dim3((waves + 3) / 4), dim3(256), 0, st, c->pm, c->pl, c->po, attn,
-                         c->p_o.ldx(), M, k, H, Hkv, hd, c->qrows_pad, nsplit);
+      if (hd == 128) launch_attn_hd<T, 128>(c, a, wpg, nblocks, attn, M, H);
+      else launch_attn_hd<T, 64>(c, a, wpg, nblocks, attn, M, H);
     }
     int o_parts = 0;
     {

@@ -45,6 +45,18 @@ __global__ void embed_kernel(const T* __restrict__ E, const int32_t* __restrict_
 
 // h[m] += sum_p part[p][m] (written back when nparts > 0), then
 // xn[m][i] = T( h[m][i] * rsqrt(mean(h[m]^2) + eps) * gain[i] ).   grid = rows.
+// d % 4 == 0.  A thread owns up to RMS_VPT float4 columns (d <= 4*1024*RMS_VPT); all
+// its loads are issued before the first use, so the kernel costs one memory latency,
+// one workgroup reduction and one store.
+constexpr int RMS_VPT = 4;
+constexpr int RMS_MAXP = 8;
+
+__device__ __forceinline__ void store4(float* p, const f32x4& v) { *reinterpret_cast<f32x4*>(p) = v; }
+__device__ __forceinline__ void store4(bf16_t* p, const f32x4& v) {
+  *reinterpret_cast<u32x2*>(p) = u32x2{(uint32_t)f2bf(v.x) | ((uint32_t)f2bf(v.y) << 16),
+                                       (uint32_t)f2bf(v.z) | ((uint32_t)f2bf(v.w) << 16)};
+}
+
 template <typename T>
 __global__ void __launch_bounds__(1024) rmsnorm_kernel(float* __restrict__ h, int ldh, const float* __restrict__ part,
                                                        int nparts, int Mtot, int ldp, const float* __restrict__ gain,
@@ -52,19 +64,40 @@ __global__ void __launch_bounds__(1024) rmsnorm_kernel(float* __restrict__ h, in
   __shared__ float scratch[16];
   const int m = blockIdx.x;
   float* hr = h + (size_t)m * ldh;
-  float ss = 0.f;
-  // each thread owns the same elements in both passes, so the updated h can be
-  // re-read without a barrier
-  for (int i = threadIdx.x; i < d; i += blockDim.x) {
-    float v = hr[i];
-    for (int p = 0; p < nparts; ++p) v += part[((size_t)p * Mtot + m) * ldp + i];
-    if (nparts > 0) hr[i] = v;
-    ss += v * v;
+  const int nv = d >> 2;
+  f32x4 v[RMS_VPT], gn[RMS_VPT];
+#pragma unroll
+  for (int u = 0; u < RMS_VPT; ++u) {
+    const int i = threadIdx.x + u * blockDim.x;
+    v[u] = f32x4{0.f, 0.f, 0.f, 0.f}; gn[u] = v[u];
+    if (i < nv) { v[u] = reinterpret_cast<const f32x4*>(hr)[i]; gn[u] = reinterpret_cast<const f32x4*>(gain)[i]; }
   }
+  if (nparts > 0) {
+#pragma unroll
+    for (int p = 0; p < RMS_MAXP; ++p) {
+      if (p < nparts) {
+        const float* pr = part + ((size_t)p * Mtot + m) * ldp;
+#pragma unroll
+        for (int u = 0; u < RMS_VPT; ++u) {
+          const int i = threadIdx.x + u * blockDim.x;
+          if (i < nv) v[u] += reinterpret_cast<const f32x4*>(pr)[i];
+        }
+      }
+    }
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int u = 0; u < RMS_VPT; ++u) ss += v[u].x * v[u].x + v[u].y * v[u].y + v[u].z * v[u].z + v[u].w * v[u].w;
   ss = block_sum(ss, scratch);
   const float r = rsqrtf(ss / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += blockDim.x)
-    xn[(size_t)m * ldx + i] = Elem<T>::from_f(hr[i] * r * gain[i]);
+#pragma unroll
+  for (int u = 0; u < RMS_VPT; ++u) {
+    const int i = threadIdx.x + u * blockDim.x;
+    if (i < nv) {
+      if (nparts > 0) reinterpret_cast<f32x4*>(hr)[i] = v[u];
+      store4(xn + (size_t)m * ldx + 4 * i, f32x4{v[u].x * r * gn[u].x, v[u].y * r * gn[u].y, v[u].z * r * gn[u].z, v[u].w * r * gn[u].w});
+    }
+  }
 }
 
 // ---------------------------------------------- q/k norm + RoPE + KV append
@@ -198,126 +231,128 @@ __device__ __forceinline__ void pv_accumulate(f32x4 (&o)[HT], const Frag<float> 
   for (int h = 0; h < HT; ++h) o[h] = mma(vf[h], pf, o[h]);
 }
 
-template <typename T, int HD, int QB>
-__global__ void __launch_bounds__(64) attn_split_kernel(const AttnArgs<T> a) {
+template <typename T, int HD>
+struct KvFrags { Frag<T> kf[2][HD / 32]; Frag<T> vf[HD / 16]; };
+
+template <typename T, int HD>
+__device__ __forceinline__ void load_kv(KvFrags<T, HD>& f, const T* kbase, const T* vbase, int tb, int c, int g4) {
+  // K fragments (A operand) of the two 16-token tiles: token = tb + 16*h + c  (< max_ctx:
+  // tb + 31 < roundup32(len) <= max_ctx)
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const T* kp = kbase + (size_t)(tb + 16 * h + c) * HD + g4 * 8;
+#pragma unroll
+    for (int ks = 0; ks < HD / 32; ++ks) f.kf[h][ks] = frag_load_row(kp + ks * 32);
+  }
+  // V^T fragments: dim row = ht*16 + c; tokens tb + 4*g4 + {0..3} and tb + 16 + 4*g4 + {0..3}
+  const T* vp = vbase + (size_t)(tb / VT_BLOCK) * HD * VT_BLOCK + (tb % VT_BLOCK) + 4 * g4;
+#pragma unroll
+  for (int h = 0; h < HD / 16; ++h) {
+    const T* r = vp + (size_t)(h * 16 + c) * VT_BLOCK;
+    f.vf[h] = vt_frag<T>(r, r + 16);
+  }
+}
+
+// grid = B * Hkv * nsplit * nqg workgroups of (query blocks per group) waves; wave w of
+// a workgroup owns query block qg*wpg + w; all waves of a workgroup read the same K/V
+// range, so those reads are shared through the CU's L1.
+template <typename T, int HD>
+__global__ void __launch_bounds__(256) attn_split_kernel(const AttnArgs<T> a) {
   constexpr int KSTEPS = HD / 32, HT = HD / 16;
-  const int lane = threadIdx.x, c = lane & 15, g4 = lane >> 4;
+  const int lane = threadIdx.x & 63, c = lane & 15, g4 = lane >> 4;
+  const int wpg = blockDim.x >> 6;
   int id = blockIdx.x;
   const int qg = id % a.nqg; id /= a.nqg;
   const int sp = id % a.nsplit; id /= a.nsplit;
   const int kvh = id % a.Hkv; const int b = id / a.Hkv;
+  const int qb = qg * wpg + (threadIdx.x >> 6);
   const int P = a.kv_len[b];
   const int len = min(P + a.k, a.max_ctx);          // slots visible to the last row
   int per = (len + a.nsplit - 1) / a.nsplit;
   per = (per + 31) & ~31;                            // token ranges start on 32-token steps
   const int t0 = sp * per, t1 = min(len, t0 + per);
   const int nq = a.g * a.k;
+  const int row = qb * 16 + c;
+  if (qb * 16 >= a.qrows_pad) return;                // (whole wave) no such query block
 
-  // query fragments (B operand): row = qb*16 + c, dims ks*32 + 8*g4 ..
-  Frag<T> qf[QB][KSTEPS];
-  int jrow[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int row = (qg * QB + qb) * 16 + c;
-    jrow[qb] = row < nq ? row / a.g : -1;
+  // query fragments (B operand): dims ks*32 + 8*g4 ..
+  Frag<T> qf[KSTEPS];
+  const int jrow = row < nq ? row / a.g : -1;
+  {
     const T* qp = a.qbuf + ((size_t)(b * a.Hkv + kvh) * a.qrows_pad + row) * HD + g4 * 8;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
-      if (row < nq) qf[qb][ks] = frag_load_row(qp + ks * 32); else frag_zero(qf[qb][ks]);
+      if (row < nq) qf[ks] = frag_load_row(qp + ks * 32); else frag_zero(qf[ks]);
     }
   }
-  f32x4 o[QB][HT];
-  float mrun[QB], lrun[QB];
+  f32x4 o[HT];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    mrun[qb] = -INFINITY; lrun[qb] = 0.f;
-#pragma unroll
-    for (int h = 0; h < HT; ++h) o[qb][h] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
+  for (int h = 0; h < HT; ++h) o[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float mrun = -INFINITY, lrun = 0.f;
   const T* kbase = a.kc + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
   const T* vbase = a.vt + (size_t)(b * a.Hkv + kvh) * (a.max_ctx / VT_BLOCK) * HD * VT_BLOCK;
+  const int lim = jrow < 0 ? -1 : min(P + jrow, t1 - 1);   // last slot this query row may see
 
+  KvFrags<T, HD> cur, nxt;
+  if (t0 < t1) load_kv<T, HD>(cur, kbase, vbase, t0, c, g4);
   for (int tb = t0; tb < t1; tb += 32) {
-    // K fragments (A operand) of the two 16-token tiles: token = tb + 16*h + c
-    Frag<T> kf[2][KSTEPS];
+    if (tb + 32 < t1) load_kv<T, HD>(nxt, kbase, vbase, tb + 32, c, g4);
+    f32x4 s[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int tok = tb + 16 * h + c;   // < max_ctx: tb + 31 < roundup32(len) <= max_ctx
-      const T* kp = kbase + (size_t)tok * HD + g4 * 8;
+      s[h] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) kf[h][ks] = frag_load_row(kp + ks * 32);
+      for (int ks = 0; ks < KSTEPS; ++ks) s[h] = mma(cur.kf[h][ks], qf[ks], s[h]);
     }
-    // V^T fragments: dim row = ht*16 + c; tokens tb + 4*g4 + {0..3} and tb + 16 + 4*g4 + {0..3}
-    Frag<T> vf[HT];
-    {
-      const T* vp = vbase + (size_t)(tb / VT_BLOCK) * HD * VT_BLOCK + (tb % VT_BLOCK) + 4 * g4;
+    // lane holds scores of query row c for tokens tb + 16*h + 4*g4 + i
+    float mx = -INFINITY;
 #pragma unroll
-      for (int h = 0; h < HT; ++h) {
-        const T* r = vp + (size_t)(h * 16 + c) * VT_BLOCK;
-        vf[h] = vt_frag<T>(r, r + 16);
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int tok = tb + 16 * h + 4 * g4 + i;
+        const float v = tok <= lim ? s[h][i] * a.scale : -INFINITY;
+        s[h][i] = v; mx = fmaxf(mx, v);
       }
-    }
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      f32x4 s[2];
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        s[h] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) s[h] = mma(kf[h][ks], qf[qb][ks], s[h]);
-      }
-      // lane holds scores of query row c for tokens tb + 16*h + 4*g4 + i
-      const int lim = jrow[qb] < 0 ? -1 : min(P + jrow[qb], t1 - 1);   // last visible slot
-      float mx = -INFINITY;
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float mnew = fmaxf(mrun, mx);
+    float alpha = 1.f, psum = 0.f;
+    if (mnew > -INFINITY) {
+      alpha = expf(mrun - mnew);   // exp(-inf) = 0 on the first visible step
 #pragma unroll
       for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int tok = tb + 16 * h + 4 * g4 + i;
-          const float v = tok <= lim ? s[h][i] * a.scale : -INFINITY;
-          s[h][i] = v; mx = fmaxf(mx, v);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float mnew = fmaxf(mrun[qb], mx);
-      float alpha = 1.f, psum = 0.f;
-      if (mnew > -INFINITY) {
-        alpha = expf(mrun[qb] - mnew);   // exp(-inf) = 0 on the first visible step
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) { const float p = expf(s[h][i] - mnew); s[h][i] = p; psum += p; }
-      } else {
-        s[0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[1] = s[0];
-      }
-      mrun[qb] = mnew;
-      lrun[qb] = lrun[qb] * alpha + psum;       // per-lane share; lane groups are summed at the end
-#pragma unroll
-      for (int h = 0; h < HT; ++h) o[qb][h] = o[qb][h] * alpha;
-      pv_accumulate<HT>(o[qb], vf, s[0], s[1]);
+        for (int i = 0; i < 4; ++i) { const float p = expf(s[h][i] - mnew); s[h][i] = p; psum += p; }
+    } else {
+      s[0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[1] = s[0];
     }
-  }
-  // write partials
+    mrun = mnew;
+    lrun = lrun * alpha + psum;       // per-lane share; lane groups are summed at the end
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    float l = lrun[qb];
-    l += __shfl_xor(l, 16); l += __shfl_xor(l, 32);
-    const int row = (qg * QB + qb) * 16 + c;
-    const size_t pidx = ((size_t)(b * a.Hkv + kvh) * a.nsplit + sp) * a.qrows_pad + row;
-    if (g4 == 0) { a.pm[pidx] = mrun[qb]; a.pl[pidx] = l; }
-#pragma unroll
-    for (int h = 0; h < HT; ++h)
-      *reinterpret_cast<f32x4*>(a.po + pidx * HD + h * 16 + 4 * g4) = o[qb][h];
+    for (int h = 0; h < HT; ++h) o[h] = o[h] * alpha;
+    pv_accumulate<HT>(o, cur.vf, s[0], s[1]);
+    cur = nxt;
   }
+  // write the partial
+  float l = lrun;
+  l += __shfl_xor(l, 16); l += __shfl_xor(l, 32);
+  const size_t pidx = ((size_t)(b * a.Hkv + kvh) * a.nsplit + sp) * a.qrows_pad + row;
+  if (g4 == 0) { a.pm[pidx] = mrun; a.pl[pidx] = l; }
+#pragma unroll
+  for (int h = 0; h < HT; ++h)
+    *reinterpret_cast<f32x4*>(a.po + pidx * HD + h * 16 + 4 * g4) = o[h];
 }
 
 // Merge the split partials of one (row m, query head): softmax-weighted sum,
-// normalise, round to T, write attn[m][head*hd + :].  One wave per (m, head).
-template <typename T>
+// normalise, round to T, write attn[m][head*hd + :].  One wave per (m, head);
+// nsplit <= 64: lane s first handles split s's (m, l), then every lane owns HD/64
+// consecutive output dims and walks the splits with the weights broadcast by shuffle.
+template <typename T, int HD>
 __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restrict__ pm, const float* __restrict__ pl,
                                                            const float* __restrict__ po, T* __restrict__ attn, int ldat,
-                                                           int Mtot, int k, int H, int Hkv, int hd, int qrows_pad,
-                                                           int nsplit) {
+                                                           int Mtot, int k, int H, int Hkv, int qrows_pad, int nsplit) {
+  constexpr int DPL = HD / 64;   // dims per lane
   const int lane = threadIdx.x & 63;
   const int wid = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (wid >= Mtot * H) return;
@@ -325,23 +360,41 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restri
   const int b = m / k, j = m % k, g = H / Hkv, kvh = hh / g, hg = hh % g;
   const int row = j * g + hg;
   const size_t base = (size_t)(b * Hkv + kvh) * nsplit;
-  float M = -INFINITY;
-  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, pm[(base + s) * qrows_pad + row]);
-  float L = 0.f, acc0 = 0.f, acc1 = 0.f;
-  for (int s = 0; s < nsplit; ++s) {
-    const size_t pidx = (base + s) * qrows_pad + row;
-    const float ms = pm[pidx];
-    if (ms == -INFINITY) continue;
-    const float w = expf(ms - M);
-    L += pl[pidx] * w;
-    const float* o = po + pidx * hd;
-    if (lane < hd) acc0 += o[lane] * w;
-    if (lane + 64 < hd) acc1 += o[lane + 64] * w;
+  float ms = -INFINITY, ls = 0.f;
+  if (lane < nsplit) { ms = pm[(base + lane) * qrows_pad + row]; ls = pl[(base + lane) * qrows_pad + row]; }
+  float M = ms;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+  const float w = ms > -INFINITY ? expf(ms - M) : 0.f;
+  const float L = wave_sum(ls * w);
+  float acc[DPL];
+#pragma unroll
+  for (int i = 0; i < DPL; ++i) acc[i] = 0.f;
+  const float* o = po + (base * qrows_pad + row) * HD + lane * DPL;
+  const size_t sstride = (size_t)qrows_pad * HD;
+  int s = 0;
+  for (; s + 4 <= nsplit; s += 4) {
+    float v[4][DPL];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < DPL; ++i) v[u][i] = o[(size_t)(s + u) * sstride + i];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float wu = __shfl(w, s + u);
+#pragma unroll
+      for (int i = 0; i < DPL; ++i) acc[i] += v[u][i] * wu;
+    }
+  }
+  for (; s < nsplit; ++s) {
+    const float wu = __shfl(w, s);
+#pragma unroll
+    for (int i = 0; i < DPL; ++i) acc[i] += o[(size_t)s * sstride + i] * wu;
   }
   const float inv = L > 0.f ? 1.f / L : 0.f;
-  T* dst = attn + (size_t)m * ldat + (size_t)hh * hd;
-  if (lane < hd) dst[lane] = Elem<T>::from_f(acc0 * inv);
-  if (lane + 64 < hd) dst[lane + 64] = Elem<T>::from_f(acc1 * inv);
+  T* dst = attn + (size_t)m * ldat + (size_t)hh * HD + lane * DPL;
+#pragma unroll
+  for (int i = 0; i < DPL; ++i) dst[i] = Elem<T>::from_f(acc[i] * inv);
 }
 
 // ------------------------------------------------------------------- accept
