@@ -39,24 +39,30 @@ bool make_plan(GemmPlan& p, int N, int K, int nacc, bool is_bf16, bool need_sing
   p.NT = (N + TILE_N - 1) / TILE_N;
   const int KB = (K + TILE_K - 1) / TILE_K;
   const int ks_big = is_bf16 ? 32 : 16, ks_small = is_bf16 ? 16 : 8;
-  p.KS = KB >= 2 * ks_big ? ks_big : ks_small;
-  const int nsl = (KB + p.KS - 1) / p.KS;
-  int best_nw = 1, best_pad = 1 << 30;
-  for (int nw = 8; nw >= 1; --nw) {
-    const int ss = (nsl + nw - 1) / nw;
-    if (need_single_slice && ss != 1) continue;
-    const int pad = nw * ss - nsl;
-    if (pad < best_pad) { best_pad = pad; best_nw = nw; }
+  // candidates (KS, NW, SS): least K padding first, then the best balance of work units
+  // over the workgroups one launch keeps resident, then the fewest super slices
+  double best_cost = 1e30;
+  bool found = false;
+  for (int ks : {ks_big, ks_small}) {
+    if (ks == ks_big && KB < 2 * ks_big) continue;
+    const int nsl = (KB + ks - 1) / ks;
+    for (int nw = 8; nw >= 1; --nw) {
+      const int ss = (nsl + nw - 1) / nw;
+      if (need_single_slice && ss != 1) continue;
+      if (ss > 8) continue;
+      const int kbp = nw * ss * ks;
+      const int per_cu = std::max(1, 8 / nw);
+      int g = std::min(p.NT * ss, n_cu * per_cu);
+      g = std::max(ss, g / ss * ss);
+      const long units = (long)p.NT * ss;
+      const long rounds = (units + g - 1) / g;
+      // time model: rounds of (blocks per wave) with every wave slot of the chip busy or idle
+      const double streamed = (double)rounds * g * nw * ks / (double)(n_cu * 8);
+      const double cost = streamed * (1.0 + 0.02 * (ss - 1)) + 1e-3 * (8 - nw) + (double)(kbp - KB) * p.NT * 1e-6;
+      if (cost < best_cost) { best_cost = cost; p.KS = ks; p.NW = nw; p.SS = ss; p.KBp = kbp; p.grid = g; found = true; }
+    }
   }
-  if (best_pad == (1 << 30)) return false;
-  p.NW = best_nw;
-  p.SS = (nsl + p.NW - 1) / p.NW;
-  p.KBp = p.NW * p.SS * p.KS;
-  const int per_cu = std::max(1, 8 / p.NW);
-  int g = std::min(p.NT * p.SS, n_cu * per_cu);
-  g = std::max(p.SS, g / p.SS * p.SS);
-  p.grid = g;
-  return true;
+  return found;
 }
 
 }  // namespace
@@ -151,6 +157,13 @@ int make_plans(dbl_ctx* c) {
             make_plan(c->p_d, g.d_model, g.d_ffn, 1, c->bf16, false, c->n_cu) &&
             make_plan(c->p_lm, g.vocab, g.d_model, 1, c->bf16, true, c->n_cu);
   if (!ok) return fail(c, DBL_EINVAL, "d_model too large for a single K slice (max 8192 bf16 / 4096 fp32)");
+  if (std::getenv("DBL_VERBOSE")) {
+    const GemmPlan* ps[5] = {&c->p_qkv, &c->p_o, &c->p_gu, &c->p_d, &c->p_lm};
+    const char* nm[5] = {"qkv", "o", "gate_up", "down", "lm_head"};
+    for (int i = 0; i < 5; ++i)
+      std::fprintf(stderr, "[dbl] plan %-8s N=%d K=%d tiles=%d KS=%d NW=%d SS=%d KBp=%d grid=%d\n", nm[i], ps[i]->N,
+                   ps[i]->K, ps[i]->NT, ps[i]->KS, ps[i]->NW, ps[i]->SS, ps[i]->KBp, ps[i]->grid);
+  }
   if (c->p_qkv.SS > RMS_MAXP || c->p_o.SS > RMS_MAXP || c->p_d.SS > RMS_MAXP)
     return fail(c, DBL_EINVAL, "a projection needs more than 8 K super-slices (n_q_heads*head_dim or d_ffn too large)");
   return DBL_OK;
@@ -210,7 +223,13 @@ int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperatu
   int ctx_upper = 0;
   for (int b = 0; b < B; ++b) ctx_upper = std::max(ctx_upper, c->kv_upper[b] + k);
   int nsplit = (2 * c->n_cu + B * Hkv * nqg - 1) / (B * Hkv * nqg);
-  nsplit = std::max(1, std::min({nsplit, MAX_SPLITS, (ctx_upper + 63) / 64}));
+  // at least 128 tokens per split: the partials (m, l, O) are written and read back, so
+  // finer splits cost more in traffic than they gain in parallelism
+  nsplit = std::max(1, std::min({nsplit, MAX_SPLITS, (ctx_upper + 127) / 128}));
+  if (const char* e = std::getenv("DBL_ATTN_SPLIT_TOKENS")) {   // tuning aid
+    const int tok = std::max(32, std::atoi(e));
+    nsplit = std::max(1, std::min(MAX_SPLITS, (ctx_upper + tok - 1) / tok));
+  }
 
   int pending_parts = 0;   // partials of the previous down projection not yet folded into h
   for (int l = 0; l < g.n_layers; ++l) {
@@ -244,7 +263,7 @@ int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperatu
       AttnArgs<T> a{};
       a.qbuf = qbuf; a.kc = kc; a.vt = vt; a.kv_len = c->kv_len; a.pm = c->pm; a.pl = c->pl; a.po = c->po;
       a.k = k; a.g = gq; a.Hkv = Hkv; a.hd = hd; a.max_ctx = g.max_ctx; a.qrows_pad = c->qrows_pad;
-      a.nsplit = nsplit; a.nqg = nqg; a.scale = 1.0f / std::sqrt((float)hd);
+      a.nsplit = nsplit; a.nqg = nqg; a.scale = (float)(1.4426950408889634 / std::sqrt((double)hd));
       const int nblocks = B * Hkv * nsplit * nqg;
       if (hd == 128) launch_attn_hd<T, 128>(c, a, wpg, nblocks, attn, M, H);
       else launch_attn_hd<T, 64>(c, a, wpg, nblocks, attn, M, H);

@@ -29,6 +29,14 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
   return (bf16_t)(u >> 16);
 }
 
+// two floats -> packed bf16 pair (x in the low half), round-to-nearest-even (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16(float x, float y) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{x, y}, bf16x2_t));
+}
+// 2^x by the hardware instruction (about 1 ulp; -inf -> 0)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 template <typename T> struct Elem;
 template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ float to_f(bf16_t v) { return bf2f(v); }

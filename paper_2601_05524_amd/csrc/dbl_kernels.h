@@ -53,8 +53,7 @@ constexpr int RMS_MAXP = 8;
 
 __device__ __forceinline__ void store4(float* p, const f32x4& v) { *reinterpret_cast<f32x4*>(p) = v; }
 __device__ __forceinline__ void store4(bf16_t* p, const f32x4& v) {
-  *reinterpret_cast<u32x2*>(p) = u32x2{(uint32_t)f2bf(v.x) | ((uint32_t)f2bf(v.y) << 16),
-                                       (uint32_t)f2bf(v.z) | ((uint32_t)f2bf(v.w) << 16)};
+  *reinterpret_cast<u32x2*>(p) = u32x2{pack_bf16(v.x, v.y), pack_bf16(v.z, v.w)};
 }
 
 template <typename T>
@@ -191,7 +190,7 @@ struct AttnArgs {
   const int32_t* kv_len;
   float *pm, *pl, *po;              // [B][Hkv][nsplit][qrows_pad] / ...[hd]
   int k, g, Hkv, hd, max_ctx, qrows_pad, nsplit, nqg;
-  float scale;
+  float scale;                      // log2(e) / sqrt(hd): scores and running maxima are kept in the log2 domain
 };
 
 template <typename T> __device__ __forceinline__ Frag<T> vt_frag(const T* v0, const T* v1);
@@ -211,21 +210,26 @@ template <> __device__ __forceinline__ Frag<float> vt_frag<float>(const float* v
 // into a bf16 head and a bf16 tail (p = hi + lo up to 2^-17 relative), so the PV
 // product sees ~16 significant bits of every probability at the cost of a second,
 // HBM-free MFMA per V^T tile.
-__device__ __forceinline__ uint32_t pack_bf16(float x, float y) { return (uint32_t)f2bf(x) | ((uint32_t)f2bf(y) << 16); }
-__device__ __forceinline__ f32x4 bf16_tail(const f32x4& a) {
-  return f32x4{a.x - bf2f(f2bf(a.x)), a.y - bf2f(f2bf(a.y)), a.z - bf2f(f2bf(a.z)), a.w - bf2f(f2bf(a.w))};
+// heads = bf16 of the four values (two packed words); `a` is replaced by the remainders
+__device__ __forceinline__ void split_bf16(f32x4& a, uint32_t& h0, uint32_t& h1) {
+  h0 = pack_bf16(a.x, a.y);
+  h1 = pack_bf16(a.z, a.w);
+  a = a - f32x4{__uint_as_float(h0 << 16), __uint_as_float(h0 & 0xffff0000u), __uint_as_float(h1 << 16),
+                __uint_as_float(h1 & 0xffff0000u)};
 }
 template <int HT>
-__device__ __forceinline__ void pv_accumulate(f32x4 (&o)[HT], const Frag<bf16_t> (&vf)[HT], const f32x4& a, const f32x4& b) {
+__device__ __forceinline__ void pv_accumulate(f32x4 (&o)[HT], const Frag<bf16_t> (&vf)[HT], f32x4 a, f32x4 b) {
   Frag<bf16_t> hi, lo;
-  hi.v = u32x4{pack_bf16(a.x, a.y), pack_bf16(a.z, a.w), pack_bf16(b.x, b.y), pack_bf16(b.z, b.w)};
-  const f32x4 ta = bf16_tail(a), tb = bf16_tail(b);
-  lo.v = u32x4{pack_bf16(ta.x, ta.y), pack_bf16(ta.z, ta.w), pack_bf16(tb.x, tb.y), pack_bf16(tb.z, tb.w)};
+  uint32_t h0, h1, h2, h3;
+  split_bf16(a, h0, h1);
+  split_bf16(b, h2, h3);
+  hi.v = u32x4{h0, h1, h2, h3};
+  lo.v = u32x4{pack_bf16(a.x, a.y), pack_bf16(a.z, a.w), pack_bf16(b.x, b.y), pack_bf16(b.z, b.w)};
 #pragma unroll
   for (int h = 0; h < HT; ++h) { o[h] = mma(vf[h], lo, o[h]); o[h] = mma(vf[h], hi, o[h]); }
 }
 template <int HT>
-__device__ __forceinline__ void pv_accumulate(f32x4 (&o)[HT], const Frag<float> (&vf)[HT], const f32x4& a, const f32x4& b) {
+__device__ __forceinline__ void pv_accumulate(f32x4 (&o)[HT], const Frag<float> (&vf)[HT], f32x4 a, f32x4 b) {
   Frag<float> pf; pf.lo = a; pf.hi = b;
 #pragma unroll
   for (int h = 0; h < HT; ++h) o[h] = mma(vf[h], pf, o[h]);
@@ -319,11 +323,11 @@ __global__ void __launch_bounds__(256) attn_split_kernel(const AttnArgs<T> a) {
     const float mnew = fmaxf(mrun, mx);
     float alpha = 1.f, psum = 0.f;
     if (mnew > -INFINITY) {
-      alpha = expf(mrun - mnew);   // exp(-inf) = 0 on the first visible step
+      alpha = fast_exp2(mrun - mnew);   // 2^(-inf) = 0 on the first visible step
 #pragma unroll
       for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { const float p = expf(s[h][i] - mnew); s[h][i] = p; psum += p; }
+        for (int i = 0; i < 4; ++i) { const float p = fast_exp2(s[h][i] - mnew); s[h][i] = p; psum += p; }
     } else {
       s[0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[1] = s[0];
     }
@@ -365,7 +369,7 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restri
   float M = ms;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
-  const float w = ms > -INFINITY ? expf(ms - M) : 0.f;
+  const float w = ms > -INFINITY ? fast_exp2(ms - M) : 0.f;
   const float L = wave_sum(ls * w);
   float acc[DPL];
 #pragma unroll
