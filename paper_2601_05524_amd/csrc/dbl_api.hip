@@ -12,6 +12,7 @@
 
 #include "../../include/dbl.h"
 #include "dbl_kernels.h"
+#include "dbl_layer.h"
 
 using namespace dbl;
 
@@ -100,7 +101,10 @@ struct dbl_ctx {
   int last_B = 0, last_k = 0;
   float last_T = 0.f;
   uint64_t last_seed = 0, last_step = 0;
-  int d_nparts_pending = 0;  // down-projection partials waiting to be folded into h
+  GridBar* bar = nullptr;           // barrier state of the persistent layer kernel
+  unsigned max_spin = 1u << 22;
+  bool use_persistent = false;      // opt-in (DBL_PERSISTENT=1) until its code generation is sorted out
+  long persistent_launches = 0;
 };
 
 namespace {
@@ -194,35 +198,52 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
   }
 }
 
-template <typename T, int HD>
-void launch_attn_hd(dbl_ctx* c, const AttnArgs<T>& a, int waves_per_group, int nblocks, T* attn, int M, int H) {
-  hipLaunchKernelGGL((attn_split_kernel<T, HD>), dim3(nblocks), dim3(64 * waves_per_group), 0, c->stream, a);
-  const int waves = M * H;
-  hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3((waves + 3) / 4), dim3(256), 0, c->stream, c->pm, c->pl, c->po,
-                     attn, c->p_o.ldx(), M, a.k, H, a.Hkv, c->qrows_pad, a.nsplit);
-}
+// Arguments of every per-layer step, for layer `l`, window (B, k).
+template <typename T>
+struct LayerSteps {
+  NormArgs<T> n1, n2;
+  GemmArgs<T> qkv, o, gu, dn;
+  int epi_o, epi_dn;
+  RopeArgs<T> rope;
+  AttnArgs<T> attn;
+  CombineArgs<T> comb;
+  int wpg, nqg;     // attention: waves per workgroup, workgroups per (b, kv head, split)
+};
 
 template <typename T>
-int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperature, uint64_t seed, uint64_t step) {
+LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k, int pending_parts) {
   const dbl_model_cfg& g = c->cfg;
   const int M = B * k, d = g.d_model, hd = g.head_dim, H = g.n_q_heads, Hkv = g.n_kv_heads;
-  hipStream_t st = c->stream;
   T* xn = reinterpret_cast<T*>(c->xn);
   T* attn = reinterpret_cast<T*>(c->attn);
   T* act = reinterpret_cast<T*>(c->act);
   T* qbuf = reinterpret_cast<T*>(c->qbuf);
+  T* kc = reinterpret_cast<T*>(c->kc) + (size_t)l * c->kv_layer_elems;
+  T* vt = reinterpret_cast<T*>(c->vt) + (size_t)l * c->kv_layer_elems;
   const int ldh = c->p_o.ldo();   // = roundup16(d)
-
-  hipLaunchKernelGGL((embed_kernel<T>), dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->emb), window, c->h,
-                     d, ldh, g.vocab);
-
+  LayerSteps<T> s{};
+  auto fill = [&](GemmArgs<T>& a, const GemmPlan& p) {
+    a.NT = p.NT; a.N = p.N; a.KBp = p.KBp; a.SS = p.SS; a.Mtot = M; a.m0 = 0; a.mrows = std::min(16, M);
+  };
+  s.n1 = NormArgs<T>{c->h, ldh, c->d_part, pending_parts, M, c->p_d.ldo(), c->g1 + (size_t)l * d, xn, c->p_qkv.ldx(), d, g.rms_eps};
+  s.qkv.W = reinterpret_cast<const T*>(c->w_qkv) + (size_t)l * c->p_qkv.elems();
+  s.qkv.X = xn; s.qkv.ldx = c->p_qkv.ldx(); s.qkv.out = c->qkv_part; s.qkv.ldo = c->p_qkv.ldo();
+  fill(s.qkv, c->p_qkv);
+  RopeArgs<T>& r = s.rope;
+  r.qkv = c->qkv_part; r.nparts = c->p_qkv.SS; r.Mtot = M; r.ldq = c->p_qkv.ldo();
+  r.gq = g.qk_norm ? c->gq + (size_t)l * hd : nullptr;
+  r.gk = g.qk_norm ? c->gk + (size_t)l * hd : nullptr;
+  r.cosT = c->cosT; r.sinT = c->sinT; r.kv_len = c->kv_len;
+  r.qbuf = qbuf; r.kc = kc; r.vt = vt;
+  r.k = k; r.H = H; r.Hkv = Hkv; r.hd = hd; r.max_ctx = g.max_ctx; r.max_batch = g.max_batch;
+  r.qrows_pad = c->qrows_pad; r.eps = g.rms_eps;
   // attention geometry for this window size
   const int gq = H / Hkv, nq = gq * k, qblocks = (nq + 15) / 16;
-  const int wpg = std::min(qblocks, 4);              // waves (query blocks) per workgroup
-  const int nqg = (qblocks + wpg - 1) / wpg;
+  s.wpg = std::min(qblocks, 4);              // waves (query blocks) per workgroup
+  s.nqg = (qblocks + s.wpg - 1) / s.wpg;
   int ctx_upper = 0;
   for (int b = 0; b < B; ++b) ctx_upper = std::max(ctx_upper, c->kv_upper[b] + k);
-  int nsplit = (2 * c->n_cu + B * Hkv * nqg - 1) / (B * Hkv * nqg);
+  int nsplit = (2 * c->n_cu + B * Hkv * s.nqg - 1) / (B * Hkv * s.nqg);
   // at least 128 tokens per split: the partials (m, l, O) are written and read back, so
   // finer splits cost more in traffic than they gain in parallelism
   nsplit = std::max(1, std::min({nsplit, MAX_SPLITS, (ctx_upper + 127) / 128}));
@@ -230,67 +251,116 @@ int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperatu
     const int tok = std::max(32, std::atoi(e));
     nsplit = std::max(1, std::min(MAX_SPLITS, (ctx_upper + tok - 1) / tok));
   }
+  AttnArgs<T>& at = s.attn;
+  at.qbuf = qbuf; at.kc = kc; at.vt = vt; at.kv_len = c->kv_len; at.pm = c->pm; at.pl = c->pl; at.po = c->po;
+  at.k = k; at.g = gq; at.Hkv = Hkv; at.hd = hd; at.max_ctx = g.max_ctx; at.qrows_pad = c->qrows_pad;
+  at.nsplit = nsplit; at.nqb = qblocks; at.scale = (float)(1.4426950408889634 / std::sqrt((double)hd));
+  s.comb = CombineArgs<T>{c->pm, c->pl, c->po, attn, c->p_o.ldx(), M, k, H, Hkv, c->qrows_pad, nsplit};
+  s.o.W = reinterpret_cast<const T*>(c->w_o) + (size_t)l * c->p_o.elems();
+  s.o.X = attn; s.o.ldx = c->p_o.ldx();
+  fill(s.o, c->p_o);
+  int o_parts = 0;
+  if (c->p_o.SS == 1) { s.o.out = c->h; s.o.ldo = ldh; s.epi_o = EPI_RESIDUAL; }
+  else { s.o.out = c->o_part; s.o.ldo = c->p_o.ldo(); s.epi_o = EPI_PARTIAL; o_parts = c->p_o.SS; }
+  s.n2 = NormArgs<T>{c->h, ldh, c->o_part, o_parts, M, c->p_o.ldo(), c->g2 + (size_t)l * d, xn, c->p_gu.ldx(), d, g.rms_eps};
+  s.gu.W = reinterpret_cast<const T*>(c->w_gu) + (size_t)l * c->p_gu.elems();
+  s.gu.X = xn; s.gu.ldx = c->p_gu.ldx(); s.gu.act = act; s.gu.ldact = c->p_d.ldx();
+  fill(s.gu, c->p_gu);
+  s.dn.W = reinterpret_cast<const T*>(c->w_d) + (size_t)l * c->p_d.elems();
+  s.dn.X = act; s.dn.ldx = c->p_d.ldx();
+  fill(s.dn, c->p_d);
+  if (c->p_d.SS == 1) { s.dn.out = c->h; s.dn.ldo = ldh; s.epi_dn = EPI_RESIDUAL; }
+  else { s.dn.out = c->d_part; s.dn.ldo = c->p_d.ldo(); s.epi_dn = EPI_PARTIAL; }
+  return s;
+}
+
+template <typename T, int HD>
+void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
+  const int nblocks = B * s.attn.Hkv * s.attn.nsplit * s.nqg;
+  hipLaunchKernelGGL((attn_split_kernel<T, HD>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+  const int waves = M * H;
+  hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3((waves + 3) / 4), dim3(256), 0, c->stream, s.comb);
+}
+
+// One launch for all layers (bf16, at most 16 rows, output projection not K-split).
+// Returns false if this context / window cannot use it; the caller then launches
+// the layers kernel by kernel.
+bool persistent_eligible(const dbl_ctx* c, int M) {
+  if (!c->bf16 || !c->use_persistent || M > 16 || c->cfg.n_layers < 1) return false;
+  if (c->p_o.SS != 1) return false;           // the output projection adds into the residual stream
+  if (c->cfg.d_model > 8192) return false;    // one workgroup of 512 threads normalises a row
+  for (const GemmPlan* p : {&c->p_qkv, &c->p_o, &c->p_gu, &c->p_d})
+    if (p->NW > 8) return false;
+  const int ks[4] = {c->p_qkv.KS, c->p_o.KS, c->p_gu.KS, c->p_d.KS};
+  return ks[0] == 16 && ks[1] == 32 && ks[2] == 32 && ks[3] == 32;   // the instantiated combination
+}
+
+int launch_persistent(dbl_ctx* c, int B, int k) {
+  const dbl_model_cfg& g = c->cfg;
+  const int M = B * k;
+  const LayerSteps<bf16_t> s = layer_steps<bf16_t>(c, 0, B, k, 0);
+  LayerLoopArgs a{};
+  a.qkv = s.qkv; a.o = s.o; a.gu = s.gu; a.dn = s.dn;
+  a.dn.out = c->d_part; a.dn.ldo = c->p_d.ldo();     // always through partials, also when SS == 1
+  a.s_qkv = c->p_qkv.elems(); a.s_o = c->p_o.elems(); a.s_gu = c->p_gu.elems(); a.s_dn = c->p_d.elems();
+  a.nw_qkv = c->p_qkv.NW; a.nw_o = c->p_o.NW; a.nw_gu = c->p_gu.NW; a.nw_dn = c->p_d.NW;
+  a.n1 = s.n1; a.n2 = s.n2; a.rope = s.rope; a.attn = s.attn; a.comb = s.comb;
+  a.s_kv = c->kv_layer_elems; a.n_layers = g.n_layers; a.M = M; a.d_parts = c->p_d.SS;
+  a.bar = c->bar; a.max_spin = c->max_spin;
+  // the grid must divide by every projection's SS; take the largest such size <= CUs
+  int grid = c->n_cu;
+  const int ss[4] = {c->p_qkv.SS, c->p_o.SS, c->p_gu.SS, c->p_d.SS};
+  auto ok = [&](int gsz) { for (int v : ss) if (gsz % v) return false; return true; };
+  while (grid > 0 && !ok(grid)) --grid;
+  if (grid < std::max(M, 8)) return DBL_EINVAL;
+  HIPCHK(c, hipMemsetAsync(c->bar, 0, sizeof(GridBar), c->stream));
+  void* args[] = {&a};
+  const void* fn = g.head_dim == 128 ? (const void*)layer_loop_kernel<128, 16, 32, 32, 32>
+                                     : (const void*)layer_loop_kernel<64, 16, 32, 32, 32>;
+  hipError_t e = hipLaunchCooperativeKernel(fn, dim3(grid), dim3(512), args, 0, c->stream);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(c, DBL_EHIP, std::string("cooperative launch: ") + hipGetErrorString(e));
+  }
+  c->persistent_launches++;
+  return DBL_OK;
+}
+
+template <typename T>
+int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperature, uint64_t seed, uint64_t step) {
+  const dbl_model_cfg& g = c->cfg;
+  const int M = B * k, d = g.d_model, hd = g.head_dim, H = g.n_q_heads;
+  hipStream_t st = c->stream;
+  T* xn = reinterpret_cast<T*>(c->xn);
+  const int ldh = c->p_o.ldo();   // = roundup16(d)
+
+  hipLaunchKernelGGL((embed_kernel<T>), dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->emb), window, c->h,
+                     d, ldh, g.vocab);
 
   int pending_parts = 0;   // partials of the previous down projection not yet folded into h
-  for (int l = 0; l < g.n_layers; ++l) {
-    const T* wqkv = reinterpret_cast<const T*>(c->w_qkv) + (size_t)l * c->p_qkv.elems();
-    const T* wo = reinterpret_cast<const T*>(c->w_o) + (size_t)l * c->p_o.elems();
-    const T* wgu = reinterpret_cast<const T*>(c->w_gu) + (size_t)l * c->p_gu.elems();
-    const T* wd = reinterpret_cast<const T*>(c->w_d) + (size_t)l * c->p_d.elems();
-    T* kc = reinterpret_cast<T*>(c->kc) + (size_t)l * c->kv_layer_elems;
-    T* vt = reinterpret_cast<T*>(c->vt) + (size_t)l * c->kv_layer_elems;
-
-    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(1024), 0, st, c->h, ldh, c->d_part, pending_parts, M,
-                       c->p_d.ldo(), c->g1 + (size_t)l * d, xn, c->p_qkv.ldx(), d, g.rms_eps);
-    {
-      GemmArgs<T> a{};
-      a.W = wqkv; a.X = xn; a.ldx = c->p_qkv.ldx(); a.out = c->qkv_part; a.ldo = c->p_qkv.ldo();
-      launch_gemm<T>(c, c->p_qkv, EPI_PARTIAL, a, M);
-    }
-    {
-      RopeArgs<T> r{};
-      r.qkv = c->qkv_part; r.nparts = c->p_qkv.SS; r.Mtot = M; r.ldq = c->p_qkv.ldo();
-      r.gq = g.qk_norm ? c->gq + (size_t)l * hd : nullptr;
-      r.gk = g.qk_norm ? c->gk + (size_t)l * hd : nullptr;
-      r.cosT = c->cosT; r.sinT = c->sinT; r.kv_len = c->kv_len;
-      r.qbuf = qbuf; r.kc = kc; r.vt = vt;
-      r.k = k; r.H = H; r.Hkv = Hkv; r.hd = hd; r.max_ctx = g.max_ctx; r.max_batch = g.max_batch;
-      r.qrows_pad = c->qrows_pad; r.eps = g.rms_eps;
-      const int waves = M * (H + 2 * Hkv);
-      hipLaunchKernelGGL((rope_kv_kernel<T>), dim3((waves + 3) / 4), dim3(256), 0, st, r);
-    }
-    {
-      AttnArgs<T> a{};
-      a.qbuf = qbuf; a.kc = kc; a.vt = vt; a.kv_len = c->kv_len; a.pm = c->pm; a.pl = c->pl; a.po = c->po;
-      a.k = k; a.g = gq; a.Hkv = Hkv; a.hd = hd; a.max_ctx = g.max_ctx; a.qrows_pad = c->qrows_pad;
-      a.nsplit = nsplit; a.nqg = nqg; a.scale = (float)(1.4426950408889634 / std::sqrt((double)hd));
-      const int nblocks = B * Hkv * nsplit * nqg;
-      if (hd == 128) launch_attn_hd<T, 128>(c, a, wpg, nblocks, attn, M, H);
-      else launch_attn_hd<T, 64>(c, a, wpg, nblocks, attn, M, H);
-    }
-    int o_parts = 0;
-    {
-      GemmArgs<T> a{};
-      a.W = wo; a.X = attn; a.ldx = c->p_o.ldx();
-      if (c->p_o.SS == 1) { a.out = c->h; a.ldo = ldh; launch_gemm<T>(c, c->p_o, EPI_RESIDUAL, a, M); }
-      else { a.out = c->o_part; a.ldo = c->p_o.ldo(); launch_gemm<T>(c, c->p_o, EPI_PARTIAL, a, M); o_parts = c->p_o.SS; }
-    }
-    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(1024), 0, st, c->h, ldh, c->o_part, o_parts, M, c->p_o.ldo(),
-                       c->g2 + (size_t)l * d, xn, c->p_gu.ldx(), d, g.rms_eps);
-    {
-      GemmArgs<T> a{};
-      a.W = wgu; a.X = xn; a.ldx = c->p_gu.ldx(); a.act = act; a.ldact = c->p_d.ldx();
-      launch_gemm<T>(c, c->p_gu, EPI_SWIGLU, a, M);
-    }
-    {
-      GemmArgs<T> a{};
-      a.W = wd; a.X = act; a.ldx = c->p_d.ldx();
-      if (c->p_d.SS == 1) { a.out = c->h; a.ldo = ldh; launch_gemm<T>(c, c->p_d, EPI_RESIDUAL, a, M); pending_parts = 0; }
-      else { a.out = c->d_part; a.ldo = c->p_d.ldo(); launch_gemm<T>(c, c->p_d, EPI_PARTIAL, a, M); pending_parts = c->p_d.SS; }
-    }
+  bool done = false;
+  if (persistent_eligible(c, M)) {
+    const int rc = launch_persistent(c, B, k);
+    if (rc == DBL_OK) { done = true; pending_parts = c->p_d.SS; }
+    else if (rc != DBL_EINVAL) return rc;
   }
-  hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(1024), 0, st, c->h, ldh, c->d_part, pending_parts, M,
-                     c->p_d.ldo(), c->gf, xn, c->p_lm.ldx(), d, g.rms_eps);
+  for (int l = 0; !done && l < g.n_layers; ++l) {
+    const LayerSteps<T> s = layer_steps<T>(c, l, B, k, pending_parts);
+    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(1024), 0, st, s.n1);
+    launch_gemm<T>(c, c->p_qkv, EPI_PARTIAL, s.qkv, M);
+    const int waves = M * (H + 2 * g.n_kv_heads);
+    hipLaunchKernelGGL((rope_kv_kernel<T>), dim3((waves + 3) / 4), dim3(256), 0, st, s.rope);
+    if (hd == 128) launch_attn_hd<T, 128>(c, s, B, M, H); else launch_attn_hd<T, 64>(c, s, B, M, H);
+    launch_gemm<T>(c, c->p_o, s.epi_o, s.o, M);
+    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(1024), 0, st, s.n2);
+    launch_gemm<T>(c, c->p_gu, EPI_SWIGLU, s.gu, M);
+    launch_gemm<T>(c, c->p_d, s.epi_dn, s.dn, M);
+    pending_parts = s.epi_dn == EPI_PARTIAL ? c->p_d.SS : 0;
+  }
+  {
+    const NormArgs<T> nf{c->h, ldh, c->d_part, pending_parts, M, c->p_d.ldo(), c->gf, xn, c->p_lm.ldx(), d, g.rms_eps};
+    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(1024), 0, st, nf);
+  }
   {
     GemmArgs<T> a{};
     a.W = reinterpret_cast<const T*>(c->w_lm); a.X = xn; a.ldx = c->p_lm.ldx();
@@ -415,7 +485,7 @@ void free_all(dbl_ctx* c) {
   void* ptrs[] = {c->w_qkv, c->w_o, c->w_gu, c->w_d, c->w_lm, c->emb, c->g1, c->g2, c->gq, c->gk, c->gf, c->cosT,
                   c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->status, c->commits, c->h, c->qkv_part,
                   c->d_part, c->o_part, c->logits, c->xn, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
-                  c->n_acc_i, c->emit_i, c->win_i};
+                  c->n_acc_i, c->emit_i, c->win_i, c->bar};
   for (void* p : ptrs) if (p) (void)hipFree(p);
 }
 
@@ -444,6 +514,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
   c->seed = weight_seed;
   c->kv_upper.assign(cfg->max_batch, 0); c->hist_upper.assign(cfg->max_batch, 0);
+  if (const char* e = std::getenv("DBL_PERSISTENT")) c->use_persistent = std::atoi(e) != 0;
   int rc = DBL_OK;
   if (!c->dry) {
     hipError_t e = hipGetDevice(&c->device);
@@ -494,6 +565,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(stats, (size_t)c->p_lm.grid * Mmax * sizeof(LmStat), true);
     ALLOC(n_acc_i, (size_t)g.max_batch * 4, true); ALLOC(emit_i, (size_t)Mmax * 4, true);
     ALLOC(win_i, (size_t)Mmax * 4, true);
+    ALLOC(bar, sizeof(GridBar), true);
   } while (0);
 #undef ALLOC
   if (rc == DBL_OK) {

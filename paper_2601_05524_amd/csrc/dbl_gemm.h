@@ -13,9 +13,14 @@
 //     (deterministic, no atomics) and wave 0 applies the epilogue;
 //   * loads run RING blocks ahead of the MFMAs and the ring runs across output
 //     tiles, so the memory pipe never drains inside a kernel;
-//   * a workgroup walks output tiles blockIdx/SS, +grid/SS, ...; if K is too long
+//   * a workgroup walks output tiles wg/SS, +nwg/SS, ...; if K is too long
 //     for 8 waves x KS blocks, SS workgroup "super slices" split K and each writes
 //     its own partial result (summed by the consumer kernel).
+// The body is a device function so that the same code runs as a stand-alone kernel
+// and as a phase of the persistent layer kernel (dbl_layer.h); there (COH = true)
+// activations and results cross workgroups inside one launch and are accessed with
+// agent-coherent loads / stores, and the first ring of weights can be fetched
+// before the phase starts.
 #pragma once
 #include "dbl_dev.h"
 
@@ -51,7 +56,7 @@ struct GemmArgs {
   int NT;           // output tiles (tile pairs for EPI_SWIGLU)
   int N;            // valid output features (per half for EPI_SWIGLU)
   int KBp;          // k-blocks per tile row
-  int SS;           // super slices; gridDim.x % SS == 0
+  int SS;           // super slices; number of workgroups % SS == 0
   float* out;       // PARTIAL: [SS][Mtot][ldo] ; RESIDUAL: h[Mtot][ldo] (+=) ; LMHEAD: logits[Mtot][ldo]
   int ldo;
   T* act;           // SWIGLU: [Mtot][ldact]
@@ -63,36 +68,52 @@ template <typename T> struct GemmCfg;
 template <> struct GemmCfg<bf16_t> { static constexpr int RING = 16; };
 template <> struct GemmCfg<float> { static constexpr int RING = 8; };
 
-template <typename T, int EPI, int KS>
-__global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
-  constexpr int RING = GemmCfg<T>::RING;
+typedef f32x4 GemmRed[8][2][WAVE];   // one LDS reduction buffer: [wave][accumulator][lane]
+
+template <typename T, int NACC>
+__device__ __forceinline__ size_t gemm_blk(const GemmArgs<T>& a, int tile, int sub, int kb) {
+  return ((size_t)tile * NACC + sub) * a.KBp + kb;
+}
+
+// Issue the first RING weight loads of workgroup `wg` for this projection.  Weights do
+// not depend on any activation, so this may run before the producer of X has finished.
+template <typename T, int EPI, int KS, int RING = GemmCfg<T>::RING>
+__device__ __forceinline__ void gemm_prefetch(const GemmArgs<T>& a, int wg, int nwg, int nw, Frag<T> (&ring)[RING]) {
+  constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ss = wg % a.SS, t = wg / a.SS;
+  if (wave >= nw || t >= a.NT) return;
+  const int kb0 = (ss * nw + wave) * KS;
+#pragma unroll
+  for (int j = 0; j < RING; ++j) ring[j] = frag_load_w(a.W, gemm_blk<T, NACC>(a, t, 0, kb0 + j), lane);
+}
+
+template <typename T, int EPI, int KS, bool COH, int RING = GemmCfg<T>::RING>
+__device__ __forceinline__ void gemm_body(const GemmArgs<T>& a, int wg, int nwg, int nw, GemmRed* red,
+                                          Frag<T> (&ring)[RING], bool prefetched) {
   constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
   static_assert(KS % RING == 0, "slice must be a whole number of rings");
-  __shared__ f32x4 red[2][8][NACC][WAVE];
+  static_assert(!(COH && EPI == EPI_LMHEAD), "the LM head runs as its own kernel");
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bool active = wave < nw;             // waves beyond nw only keep the barriers company
   const int c = lane & 15, g = lane >> 4;
-  const int ss = blockIdx.x % a.SS;
-  const int tstep = gridDim.x / a.SS;
-  int t = blockIdx.x / a.SS;
-  const int kb0 = (ss * NW + wave) * KS;
+  const int ss = wg % a.SS;
+  const int tstep = nwg / a.SS;
+  int t = wg / a.SS;
+  const int kb0 = (ss * nw + wave) * KS;
 
-  // activations of this wave's K slice -> registers
+  if (!prefetched) gemm_prefetch<T, EPI, KS, RING>(a, wg, nwg, nw, ring);
+
+  // activations of this wave's K slice -> registers.  Output column j of a tile depends
+  // only on activation row j, so lanes of the unused rows (c >= mrows) simply re-read the
+  // last valid row: all loads are unconditional and stay in flight together.
   Frag<T> breg[KS];
+  {
+    const int wv = active ? wave : 0;
+    const T* xrow = a.X + (size_t)(a.m0 + min(c, a.mrows - 1)) * a.ldx + (size_t)((ss * nw + wv) * KS) * TILE_K + g * 8;
 #pragma unroll
-  for (int j = 0; j < KS; ++j) {
-    if (c < a.mrows) breg[j] = frag_load_row(a.X + (size_t)(a.m0 + c) * a.ldx + (size_t)(kb0 + j) * TILE_K + g * 8);
-    else frag_zero(breg[j]);
-  }
-
-  auto blk = [&](int tile, int sub, int j) -> size_t {
-    return ((size_t)tile * NACC + sub) * a.KBp + kb0 + j;
-  };
-
-  Frag<T> ring[RING];
-  if (t < a.NT) {
-#pragma unroll
-    for (int j = 0; j < RING; ++j) ring[j] = frag_load_w(a.W, blk(t, 0, j), lane);
+    for (int j = 0; j < KS; ++j) breg[j] = frag_load_row<COH>(xrow + (size_t)j * TILE_K);
   }
 
   // LM-head running statistics (wave 0 only)
@@ -106,31 +127,41 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
     stepv = a.lm.step + *a.lm.commits;
   }
 
+  // Per-lane pointer to block 0 of this wave's slice of tile row 0; a tile row is KBp
+  // blocks of BLOCK_ELEMS elements.  All weight addresses below are this plus a
+  // tile-row offset plus a compile-time block offset: no branches around the loads, so
+  // the compiler can count outstanding loads exactly (s_waitcnt vmcnt(N) with N > 0).
+  const T* wlane = a.W + (size_t)kb0 * BLOCK_ELEMS;
+  const size_t row_elems = (size_t)a.KBp * BLOCK_ELEMS;
   for (int it = 0; t < a.NT; t += tstep, ++it) {
-    const int tn = t + tstep;
-    const bool has_next = tn < a.NT;
+    // after the last tile the refill loads go on, harmlessly, into tile 0 (an L2 hit)
+    const int tn = (t + tstep < a.NT) ? t + tstep : 0;
     f32x4 acc[NACC];
 #pragma unroll
     for (int s = 0; s < NACC; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (active) {
+      const T* wcur = wlane + (size_t)t * NACC * row_elems;
+      const T* wnext = wlane + (size_t)tn * NACC * row_elems;
 #pragma unroll
-    for (int s = 0; s < NACC; ++s) {
+      for (int s = 0; s < NACC; ++s) {
 #pragma unroll
-      for (int j = 0; j < KS; ++j) {
-        acc[s] = mma(ring[j % RING], breg[j], acc[s]);
-        const int jn = j + RING;
-        if (jn < KS) ring[j % RING] = frag_load_w(a.W, blk(t, s, jn), lane);
-        else if (s + 1 < NACC) ring[j % RING] = frag_load_w(a.W, blk(t, s + 1, jn - KS), lane);
-        else if (has_next) ring[j % RING] = frag_load_w(a.W, blk(tn, 0, jn - KS), lane);
+        for (int j = 0; j < KS; ++j) {
+          acc[s] = mma(ring[j % RING], breg[j], acc[s]);
+          const int jn = j + RING;
+          if (jn < KS) ring[j % RING] = frag_load_w(wcur + s * row_elems, jn, lane);
+          else if (s + 1 < NACC) ring[j % RING] = frag_load_w(wcur + (s + 1) * row_elems, jn - KS, lane);
+          else ring[j % RING] = frag_load_w(wnext, jn - KS, lane);
+        }
       }
     }
     const int buf = it & 1;
-    if (wave != 0) {
+    if (active && wave != 0) {
 #pragma unroll
       for (int s = 0; s < NACC; ++s) red[buf][wave][s][lane] = acc[s];
     }
     __syncthreads();
     if (wave == 0) {
-      for (int w = 1; w < NW; ++w) {
+      for (int w = 1; w < nw; ++w) {
 #pragma unroll
         for (int s = 0; s < NACC; ++s) acc[s] += red[buf][w][s][lane];
       }
@@ -138,18 +169,18 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
         const int m = a.m0 + c;
         const int n = t * TILE_N + 4 * g;   // first of this lane's 4 output features
         if (EPI == EPI_PARTIAL) {
-          *reinterpret_cast<f32x4*>(a.out + ((size_t)ss * a.Mtot + m) * a.ldo + n) = acc[0];
+          st_f4<COH>(a.out + ((size_t)ss * a.Mtot + m) * a.ldo + n, acc[0]);
         } else if (EPI == EPI_RESIDUAL) {
-          f32x4* p = reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n);
-          *p = *p + acc[0];
+          float* p = a.out + (size_t)m * a.ldo + n;
+          st_f4<COH>(p, ld_f4<COH>(p) + acc[0]);
         } else if (EPI == EPI_SWIGLU) {
-          T* p = a.act + (size_t)m * a.ldact + n;
+          f32x4 v;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const float gt = acc[0][i], up = acc[1][i];
-            const float v = gt / (1.f + expf(-gt)) * up;
-            p[i] = (n + i < a.N) ? Elem<T>::from_f(v) : Elem<T>::from_f(0.f);
+            v[i] = (n + i < a.N) ? gt / (1.f + expf(-gt)) * up : 0.f;
           }
+          st_round4<COH>(a.act + (size_t)m * a.ldact + n, v);
         } else {  // EPI_LMHEAD
           *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = acc[0];
           Philox4 rnd{0, 0, 0, 0};
@@ -203,9 +234,16 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
       LmStat s;
       s.best = best; s.best_id = best_id; s.smax = smax; s.ssum = ssum; s.zdraft = zdraft;
       s.p1 = p1; s.p1_id = p1_id; s.p2 = p2; s.p2_id = p2_id;
-      a.lm.stats[(size_t)blockIdx.x * a.Mtot + a.m0 + c] = s;
+      a.lm.stats[(size_t)wg * a.Mtot + a.m0 + c] = s;
     }
   }
+}
+
+template <typename T, int EPI, int KS>
+__global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
+  __shared__ GemmRed red[2];
+  Frag<T> ring[GemmCfg<T>::RING];
+  gemm_body<T, EPI, KS, false>(a, blockIdx.x, gridDim.x, blockDim.x >> 6, red, ring, false);
 }
 
 }  // namespace dbl

@@ -1,32 +1,11 @@
-// The small kernels around the projections: embedding gather, residual + RMSNorm,
-// q/k-norm + RoPE + KV append, split-KV GQA attention and its combine, acceptance,
-// n-gram retrieval, window build, commit, and the seeded weight generator.
+// The kernels outside the layer loop: embedding gather, acceptance, n-gram retrieval,
+// window build, commit, and the seeded weight generator.
 #pragma once
 #include "dbl_dev.h"
 #include "dbl_gemm.h"
+#include "dbl_phases.h"
 
 namespace dbl {
-
-// ------------------------------------------------------------------ reductions
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-  return v;
-}
-
-// sum over a workgroup (blockDim.x multiple of 64, <= 1024); every thread gets the
-// result; scratch must hold 16 floats
-__device__ __forceinline__ float block_sum(float v, float* scratch) {
-  v = wave_sum(v);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  __syncthreads();
-  if (lane == 0) scratch[wave] = v;
-  __syncthreads();
-  float t = 0.f;
-  for (int w = 0; w < nw; ++w) t += scratch[w];
-  return t;
-}
 
 // ------------------------------------------------------------------ embedding
 
@@ -39,366 +18,6 @@ __global__ void embed_kernel(const T* __restrict__ E, const int32_t* __restrict_
   tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
   const T* e = E + (size_t)tok * d;
   for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)m * ldh + i] = Elem<T>::to_f(e[i]);
-}
-
-// ------------------------------------------------------- residual + RMSNorm
-
-// h[m] += sum_p part[p][m] (written back when nparts > 0), then
-// xn[m][i] = T( h[m][i] * rsqrt(mean(h[m]^2) + eps) * gain[i] ).   grid = rows.
-// d % 4 == 0.  A thread owns up to RMS_VPT float4 columns (d <= 4*1024*RMS_VPT); all
-// its loads are issued before the first use, so the kernel costs one memory latency,
-// one workgroup reduction and one store.
-constexpr int RMS_VPT = 4;
-constexpr int RMS_MAXP = 8;
-
-__device__ __forceinline__ void store4(float* p, const f32x4& v) { *reinterpret_cast<f32x4*>(p) = v; }
-__device__ __forceinline__ void store4(bf16_t* p, const f32x4& v) {
-  *reinterpret_cast<u32x2*>(p) = u32x2{pack_bf16(v.x, v.y), pack_bf16(v.z, v.w)};
-}
-
-template <typename T>
-__global__ void __launch_bounds__(1024) rmsnorm_kernel(float* __restrict__ h, int ldh, const float* __restrict__ part,
-                                                       int nparts, int Mtot, int ldp, const float* __restrict__ gain,
-                                                       T* __restrict__ xn, int ldx, int d, float eps) {
-  __shared__ float scratch[16];
-  const int m = blockIdx.x;
-  float* hr = h + (size_t)m * ldh;
-  const int nv = d >> 2;
-  f32x4 v[RMS_VPT], gn[RMS_VPT];
-#pragma unroll
-  for (int u = 0; u < RMS_VPT; ++u) {
-    const int i = threadIdx.x + u * blockDim.x;
-    v[u] = f32x4{0.f, 0.f, 0.f, 0.f}; gn[u] = v[u];
-    if (i < nv) { v[u] = reinterpret_cast<const f32x4*>(hr)[i]; gn[u] = reinterpret_cast<const f32x4*>(gain)[i]; }
-  }
-  if (nparts > 0) {
-#pragma unroll
-    for (int p = 0; p < RMS_MAXP; ++p) {
-      if (p < nparts) {
-        const float* pr = part + ((size_t)p * Mtot + m) * ldp;
-#pragma unroll
-        for (int u = 0; u < RMS_VPT; ++u) {
-          const int i = threadIdx.x + u * blockDim.x;
-          if (i < nv) v[u] += reinterpret_cast<const f32x4*>(pr)[i];
-        }
-      }
-    }
-  }
-  float ss = 0.f;
-#pragma unroll
-  for (int u = 0; u < RMS_VPT; ++u) ss += v[u].x * v[u].x + v[u].y * v[u].y + v[u].z * v[u].z + v[u].w * v[u].w;
-  ss = block_sum(ss, scratch);
-  const float r = rsqrtf(ss / (float)d + eps);
-#pragma unroll
-  for (int u = 0; u < RMS_VPT; ++u) {
-    const int i = threadIdx.x + u * blockDim.x;
-    if (i < nv) {
-      if (nparts > 0) reinterpret_cast<f32x4*>(hr)[i] = v[u];
-      store4(xn + (size_t)m * ldx + 4 * i, f32x4{v[u].x * r * gn[u].x, v[u].y * r * gn[u].y, v[u].z * r * gn[u].z, v[u].w * r * gn[u].w});
-    }
-  }
-}
-
-// ---------------------------------------------- q/k norm + RoPE + KV append
-
-// One wave per (row m, head hh) with hh in [0, H + 2*Hkv): q heads, then k heads,
-// then v heads.  Sums the QKV partials, applies the optional per-head RMSNorm and
-// the rotary embedding (pairs (i, i+hd/2); cos/sin from the fp32 table at the
-// row's position kv_len[b] + j), rounds to T, and writes
-//   q  -> qbuf[b][kvh][j*g + hg][hd]
-//   k  -> kc[layer][b][kvh][pos][hd]
-//   v  -> vt[layer][b][kvh][pos/64][hd][pos%64]      (transposed, 64-token blocks)
-template <typename T>
-struct RopeArgs {
-  const float* qkv; int nparts, Mtot, ldq;   // partials [nparts][Mtot][ldq]
-  const float *gq, *gk;                      // per-head gains (qk_norm) or nullptr
-  const float *cosT, *sinT;                  // [max_ctx][hd/2]
-  const int32_t* kv_len;                     // [B]
-  T *qbuf, *kc, *vt;                         // kc / vt already offset to the layer
-  int k, H, Hkv, hd, max_ctx, max_batch, qrows_pad;
-  float eps;
-};
-
-template <typename T>
-__global__ void __launch_bounds__(256) rope_kv_kernel(const RopeArgs<T> a) {
-  const int lane = threadIdx.x & 63;
-  const int wid = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  const int heads = a.H + 2 * a.Hkv;
-  if (wid >= a.Mtot * heads) return;
-  const int m = wid / heads, hh = wid % heads;
-  const int b = m / a.k, j = m % a.k;
-  const int pos = a.kv_len[b] + j;
-  if (pos >= a.max_ctx) return;   // capacity guard; the host refuses such calls
-  const int hd = a.hd, half = hd >> 1;
-  // lane i < half holds the pair (i, i+half); hd = 128 -> 64 lanes, hd = 64 -> 32 lanes
-  const bool act = lane < half;
-  float x0 = 0.f, x1 = 0.f;
-  if (act) {
-    for (int p = 0; p < a.nparts; ++p) {
-      const float* src = a.qkv + ((size_t)p * a.Mtot + m) * a.ldq + (size_t)hh * hd;
-      x0 += src[lane]; x1 += src[lane + half];
-    }
-  }
-  const bool is_q = hh < a.H, is_k = !is_q && hh < a.H + a.Hkv;
-  if (!is_q && !is_k) {  // v head: no norm, no rotation
-    if (act) {
-      const int kvh = hh - a.H - a.Hkv;
-      T* dst = a.vt + ((size_t)(b * a.Hkv + kvh) * (a.max_ctx / VT_BLOCK) + pos / VT_BLOCK) * hd * VT_BLOCK + pos % VT_BLOCK;
-      dst[(size_t)lane * VT_BLOCK] = Elem<T>::from_f(x0);
-      dst[(size_t)(lane + half) * VT_BLOCK] = Elem<T>::from_f(x1);
-    }
-    return;
-  }
-  const float* gn = is_q ? a.gq : a.gk;
-  if (gn) {
-    float ss = wave_sum(act ? x0 * x0 + x1 * x1 : 0.f);
-    const float r = rsqrtf(ss / (float)hd + a.eps);
-    if (act) { x0 = x0 * r * gn[lane]; x1 = x1 * r * gn[lane + half]; }
-  }
-  if (act) {
-    const float cs = a.cosT[(size_t)pos * half + lane], sn = a.sinT[(size_t)pos * half + lane];
-    const float y0 = x0 * cs - x1 * sn, y1 = x0 * sn + x1 * cs;
-    T* dst;
-    if (is_q) {
-      const int g = a.H / a.Hkv, kvh = hh / g, hg = hh % g;
-      dst = a.qbuf + ((size_t)(b * a.Hkv + kvh) * a.qrows_pad + (j * g + hg)) * hd;
-    } else {
-      const int kvh = hh - a.H;
-      dst = a.kc + ((size_t)(b * a.Hkv + kvh) * a.max_ctx + pos) * hd;
-    }
-    dst[lane] = Elem<T>::from_f(y0);
-    dst[lane + half] = Elem<T>::from_f(y1);
-  }
-}
-
-// ------------------------------------------------------------ GQA attention
-
-// Split-KV ("flash-decode") attention for a short query window.  The g query heads
-// of one KV head and the k window rows form g*k query rows (row = j*g + hg); one
-// wave owns QB 16-row query blocks and one token range of one (b, kv head), so each
-// K/V byte is read once per QB blocks.  Per 32-token step:
-//   S^T = K Q^T    (K tile is the MFMA A operand: 16 tokens x 32 dims per block)
-//   online soft-max per query row (a row lives in the 4 lanes l%16 == row)
-//   O^T += V^T P^T (V^T tile from the transposed cache is A, probabilities are B)
-// The two 16-token score tiles give each lane tokens {4g..4g+3} and {16+4g..}, which
-// is taken as that lane's 8 contraction elements of the second product; the V^T
-// fragment gathers the same tokens, so no data moves between lanes.
-// Output: unnormalised partial (m, l, O) per split; attn_combine_kernel merges.
-template <typename T>
-struct AttnArgs {
-  const T *qbuf, *kc, *vt;          // kc / vt offset to the layer
-  const int32_t* kv_len;
-  float *pm, *pl, *po;              // [B][Hkv][nsplit][qrows_pad] / ...[hd]
-  int k, g, Hkv, hd, max_ctx, qrows_pad, nsplit, nqg;
-  float scale;                      // log2(e) / sqrt(hd): scores and running maxima are kept in the log2 domain
-};
-
-template <typename T> __device__ __forceinline__ Frag<T> vt_frag(const T* v0, const T* v1);
-template <> __device__ __forceinline__ Frag<bf16_t> vt_frag<bf16_t>(const bf16_t* v0, const bf16_t* v1) {
-  Frag<bf16_t> f;
-  const u32x2 a = *reinterpret_cast<const u32x2*>(v0), b = *reinterpret_cast<const u32x2*>(v1);
-  f.v = u32x4{a.x, a.y, b.x, b.y};
-  return f;
-}
-template <> __device__ __forceinline__ Frag<float> vt_frag<float>(const float* v0, const float* v1) {
-  Frag<float> f;
-  f.lo = *reinterpret_cast<const f32x4*>(v0);
-  f.hi = *reinterpret_cast<const f32x4*>(v1);
-  return f;
-}
-// Probabilities (fp32, in [0,1]) as MFMA B operands.  For bf16 models they are split
-// into a bf16 head and a bf16 tail (p = hi + lo up to 2^-17 relative), so the PV
-// product sees ~16 significant bits of every probability at the cost of a second,
-// HBM-free MFMA per V^T tile.
-// heads = bf16 of the four values (two packed words); `a` is replaced by the remainders
-__device__ __forceinline__ void split_bf16(f32x4& a, uint32_t& h0, uint32_t& h1) {
-  h0 = pack_bf16(a.x, a.y);
-  h1 = pack_bf16(a.z, a.w);
-  a = a - f32x4{__uint_as_float(h0 << 16), __uint_as_float(h0 & 0xffff0000u), __uint_as_float(h1 << 16),
-                __uint_as_float(h1 & 0xffff0000u)};
-}
-template <int HT>
-__device__ __forceinline__ void pv_accumulate(f32x4 (&o)[HT], const Frag<bf16_t> (&vf)[HT], f32x4 a, f32x4 b) {
-  Frag<bf16_t> hi, lo;
-  uint32_t h0, h1, h2, h3;
-  split_bf16(a, h0, h1);
-  split_bf16(b, h2, h3);
-  hi.v = u32x4{h0, h1, h2, h3};
-  lo.v = u32x4{pack_bf16(a.x, a.y), pack_bf16(a.z, a.w), pack_bf16(b.x, b.y), pack_bf16(b.z, b.w)};
-#pragma unroll
-  for (int h = 0; h < HT; ++h) { o[h] = mma(vf[h], lo, o[h]); o[h] = mma(vf[h], hi, o[h]); }
-}
-template <int HT>
-__device__ __forceinline__ void pv_accumulate(f32x4 (&o)[HT], const Frag<float> (&vf)[HT], f32x4 a, f32x4 b) {
-  Frag<float> pf; pf.lo = a; pf.hi = b;
-#pragma unroll
-  for (int h = 0; h < HT; ++h) o[h] = mma(vf[h], pf, o[h]);
-}
-
-template <typename T, int HD>
-struct KvFrags { Frag<T> kf[2][HD / 32]; Frag<T> vf[HD / 16]; };
-
-template <typename T, int HD>
-__device__ __forceinline__ void load_kv(KvFrags<T, HD>& f, const T* kbase, const T* vbase, int tb, int c, int g4) {
-  // K fragments (A operand) of the two 16-token tiles: token = tb + 16*h + c  (< max_ctx:
-  // tb + 31 < roundup32(len) <= max_ctx)
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const T* kp = kbase + (size_t)(tb + 16 * h + c) * HD + g4 * 8;
-#pragma unroll
-    for (int ks = 0; ks < HD / 32; ++ks) f.kf[h][ks] = frag_load_row(kp + ks * 32);
-  }
-  // V^T fragments: dim row = ht*16 + c; tokens tb + 4*g4 + {0..3} and tb + 16 + 4*g4 + {0..3}
-  const T* vp = vbase + (size_t)(tb / VT_BLOCK) * HD * VT_BLOCK + (tb % VT_BLOCK) + 4 * g4;
-#pragma unroll
-  for (int h = 0; h < HD / 16; ++h) {
-    const T* r = vp + (size_t)(h * 16 + c) * VT_BLOCK;
-    f.vf[h] = vt_frag<T>(r, r + 16);
-  }
-}
-
-// grid = B * Hkv * nsplit * nqg workgroups of (query blocks per group) waves; wave w of
-// a workgroup owns query block qg*wpg + w; all waves of a workgroup read the same K/V
-// range, so those reads are shared through the CU's L1.
-template <typename T, int HD>
-__global__ void __launch_bounds__(256) attn_split_kernel(const AttnArgs<T> a) {
-  constexpr int KSTEPS = HD / 32, HT = HD / 16;
-  const int lane = threadIdx.x & 63, c = lane & 15, g4 = lane >> 4;
-  const int wpg = blockDim.x >> 6;
-  int id = blockIdx.x;
-  const int qg = id % a.nqg; id /= a.nqg;
-  const int sp = id % a.nsplit; id /= a.nsplit;
-  const int kvh = id % a.Hkv; const int b = id / a.Hkv;
-  const int qb = qg * wpg + (threadIdx.x >> 6);
-  const int P = a.kv_len[b];
-  const int len = min(P + a.k, a.max_ctx);          // slots visible to the last row
-  int per = (len + a.nsplit - 1) / a.nsplit;
-  per = (per + 31) & ~31;                            // token ranges start on 32-token steps
-  const int t0 = sp * per, t1 = min(len, t0 + per);
-  const int nq = a.g * a.k;
-  const int row = qb * 16 + c;
-  if (qb * 16 >= a.qrows_pad) return;                // (whole wave) no such query block
-
-  // query fragments (B operand): dims ks*32 + 8*g4 ..
-  Frag<T> qf[KSTEPS];
-  const int jrow = row < nq ? row / a.g : -1;
-  {
-    const T* qp = a.qbuf + ((size_t)(b * a.Hkv + kvh) * a.qrows_pad + row) * HD + g4 * 8;
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      if (row < nq) qf[ks] = frag_load_row(qp + ks * 32); else frag_zero(qf[ks]);
-    }
-  }
-  f32x4 o[HT];
-#pragma unroll
-  for (int h = 0; h < HT; ++h) o[h] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float mrun = -INFINITY, lrun = 0.f;
-  const T* kbase = a.kc + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
-  const T* vbase = a.vt + (size_t)(b * a.Hkv + kvh) * (a.max_ctx / VT_BLOCK) * HD * VT_BLOCK;
-  const int lim = jrow < 0 ? -1 : min(P + jrow, t1 - 1);   // last slot this query row may see
-
-  KvFrags<T, HD> cur, nxt;
-  if (t0 < t1) load_kv<T, HD>(cur, kbase, vbase, t0, c, g4);
-  for (int tb = t0; tb < t1; tb += 32) {
-    if (tb + 32 < t1) load_kv<T, HD>(nxt, kbase, vbase, tb + 32, c, g4);
-    f32x4 s[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      s[h] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) s[h] = mma(cur.kf[h][ks], qf[ks], s[h]);
-    }
-    // lane holds scores of query row c for tokens tb + 16*h + 4*g4 + i
-    float mx = -INFINITY;
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int tok = tb + 16 * h + 4 * g4 + i;
-        const float v = tok <= lim ? s[h][i] * a.scale : -INFINITY;
-        s[h][i] = v; mx = fmaxf(mx, v);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float mnew = fmaxf(mrun, mx);
-    float alpha = 1.f, psum = 0.f;
-    if (mnew > -INFINITY) {
-      alpha = fast_exp2(mrun - mnew);   // 2^(-inf) = 0 on the first visible step
-#pragma unroll
-      for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { const float p = fast_exp2(s[h][i] - mnew); s[h][i] = p; psum += p; }
-    } else {
-      s[0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[1] = s[0];
-    }
-    mrun = mnew;
-    lrun = lrun * alpha + psum;       // per-lane share; lane groups are summed at the end
-#pragma unroll
-    for (int h = 0; h < HT; ++h) o[h] = o[h] * alpha;
-    pv_accumulate<HT>(o, cur.vf, s[0], s[1]);
-    cur = nxt;
-  }
-  // write the partial
-  float l = lrun;
-  l += __shfl_xor(l, 16); l += __shfl_xor(l, 32);
-  const size_t pidx = ((size_t)(b * a.Hkv + kvh) * a.nsplit + sp) * a.qrows_pad + row;
-  if (g4 == 0) { a.pm[pidx] = mrun; a.pl[pidx] = l; }
-#pragma unroll
-  for (int h = 0; h < HT; ++h)
-    *reinterpret_cast<f32x4*>(a.po + pidx * HD + h * 16 + 4 * g4) = o[h];
-}
-
-// Merge the split partials of one (row m, query head): softmax-weighted sum,
-// normalise, round to T, write attn[m][head*hd + :].  One wave per (m, head);
-// nsplit <= 64: lane s first handles split s's (m, l), then every lane owns HD/64
-// consecutive output dims and walks the splits with the weights broadcast by shuffle.
-template <typename T, int HD>
-__global__ void __launch_bounds__(256) attn_combine_kernel(const float* __restrict__ pm, const float* __restrict__ pl,
-                                                           const float* __restrict__ po, T* __restrict__ attn, int ldat,
-                                                           int Mtot, int k, int H, int Hkv, int qrows_pad, int nsplit) {
-  constexpr int DPL = HD / 64;   // dims per lane
-  const int lane = threadIdx.x & 63;
-  const int wid = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (wid >= Mtot * H) return;
-  const int m = wid / H, hh = wid % H;
-  const int b = m / k, j = m % k, g = H / Hkv, kvh = hh / g, hg = hh % g;
-  const int row = j * g + hg;
-  const size_t base = (size_t)(b * Hkv + kvh) * nsplit;
-  float ms = -INFINITY, ls = 0.f;
-  if (lane < nsplit) { ms = pm[(base + lane) * qrows_pad + row]; ls = pl[(base + lane) * qrows_pad + row]; }
-  float M = ms;
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
-  const float w = ms > -INFINITY ? fast_exp2(ms - M) : 0.f;
-  const float L = wave_sum(ls * w);
-  float acc[DPL];
-#pragma unroll
-  for (int i = 0; i < DPL; ++i) acc[i] = 0.f;
-  const float* o = po + (base * qrows_pad + row) * HD + lane * DPL;
-  const size_t sstride = (size_t)qrows_pad * HD;
-  int s = 0;
-  for (; s + 4 <= nsplit; s += 4) {
-    float v[4][DPL];
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-#pragma unroll
-      for (int i = 0; i < DPL; ++i) v[u][i] = o[(size_t)(s + u) * sstride + i];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const float wu = __shfl(w, s + u);
-#pragma unroll
-      for (int i = 0; i < DPL; ++i) acc[i] += v[u][i] * wu;
-    }
-  }
-  for (; s < nsplit; ++s) {
-    const float wu = __shfl(w, s);
-#pragma unroll
-    for (int i = 0; i < DPL; ++i) acc[i] += o[(size_t)s * sstride + i] * wu;
-  }
-  const float inv = L > 0.f ? 1.f / L : 0.f;
-  T* dst = attn + (size_t)m * ldat + (size_t)hh * HD + lane * DPL;
-#pragma unroll
-  for (int i = 0; i < DPL; ++i) dst[i] = Elem<T>::from_f(acc[i] * inv);
 }
 
 // ------------------------------------------------------------------- accept
