@@ -102,9 +102,11 @@ struct dbl_ctx {
   float last_T = 0.f;
   uint64_t last_seed = 0, last_step = 0;
   GridBar* bar = nullptr;           // barrier state of the persistent layer kernel
-  unsigned max_spin = 1u << 22;
-  bool use_persistent = false;      // opt-in (DBL_PERSISTENT=1) until its code generation is sorted out
+  unsigned bar_base = 0;            // value the barrier counter has when the next launch starts
+  unsigned max_spin = 1u << 20;     // polls of one barrier before the launch gives up
+  bool use_persistent = false;      // opt-in (DBL_PERSISTENT=1)
   long persistent_launches = 0;
+  long long* trace = nullptr;       // DBL_PERSISTENT_TRACE=1: phase clock values of the last persistent launch
 };
 
 namespace {
@@ -180,8 +182,14 @@ void launch_gemm_t(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
   const dim3 grid(p.grid), block(p.NW * 64);
   constexpr bool is_bf = sizeof(T) == 2;
   constexpr int KS_BIG = is_bf ? 32 : 16, KS_SMALL = is_bf ? 16 : 8;
-  if (p.KS == KS_BIG) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG>), grid, block, 0, c->stream, a);
-  else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL>), grid, block, 0, c->stream, a);
+  const bool pack = a.mrows <= 8;   // two k-blocks of activations per register set
+  if (p.KS == KS_BIG) {
+    if (pack) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, true>), grid, block, 0, c->stream, a);
+    else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, false>), grid, block, 0, c->stream, a);
+  } else {
+    if (pack) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL, true>), grid, block, 0, c->stream, a);
+    else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL, false>), grid, block, 0, c->stream, a);
+  }
 }
 
 template <typename T>
@@ -282,11 +290,16 @@ void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
   hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3((waves + 3) / 4), dim3(256), 0, c->stream, s.comb);
 }
 
+// Threads of a row-normalisation workgroup.  512 whenever they can hold the row: the
+// persistent layer kernel runs 512-thread workgroups, and with the same partition of a
+// row over threads both paths add the squares in the same order (bit-identical results).
+inline int norm_threads(int d) { return d / 4 <= 512 * RMS_VPT ? 512 : 1024; }
+
 // One launch for all layers (bf16, at most 16 rows, output projection not K-split).
 // Returns false if this context / window cannot use it; the caller then launches
 // the layers kernel by kernel.
 bool persistent_eligible(const dbl_ctx* c, int M) {
-  if (!c->bf16 || !c->use_persistent || M > 16 || c->cfg.n_layers < 1) return false;
+  if (!c->bf16 || !c->use_persistent || M > 8 || c->cfg.n_layers < 1) return false;
   if (c->p_o.SS != 1) return false;           // the output projection adds into the residual stream
   if (c->cfg.d_model > 8192) return false;    // one workgroup of 512 threads normalises a row
   for (const GemmPlan* p : {&c->p_qkv, &c->p_o, &c->p_gu, &c->p_d})
@@ -306,14 +319,13 @@ int launch_persistent(dbl_ctx* c, int B, int k) {
   a.nw_qkv = c->p_qkv.NW; a.nw_o = c->p_o.NW; a.nw_gu = c->p_gu.NW; a.nw_dn = c->p_d.NW;
   a.n1 = s.n1; a.n2 = s.n2; a.rope = s.rope; a.attn = s.attn; a.comb = s.comb;
   a.s_kv = c->kv_layer_elems; a.n_layers = g.n_layers; a.M = M; a.d_parts = c->p_d.SS;
-  a.bar = c->bar; a.max_spin = c->max_spin;
+  a.bar = c->bar; a.bar_base = c->bar_base; a.max_spin = c->max_spin; a.trace = c->trace;
   // the grid must divide by every projection's SS; take the largest such size <= CUs
   int grid = c->n_cu;
   const int ss[4] = {c->p_qkv.SS, c->p_o.SS, c->p_gu.SS, c->p_d.SS};
   auto ok = [&](int gsz) { for (int v : ss) if (gsz % v) return false; return true; };
   while (grid > 0 && !ok(grid)) --grid;
   if (grid < std::max(M, 8)) return DBL_EINVAL;
-  HIPCHK(c, hipMemsetAsync(c->bar, 0, sizeof(GridBar), c->stream));
   void* args[] = {&a};
   const void* fn = g.head_dim == 128 ? (const void*)layer_loop_kernel<128, 16, 32, 32, 32>
                                      : (const void*)layer_loop_kernel<64, 16, 32, 32, 32>;
@@ -322,7 +334,21 @@ int launch_persistent(dbl_ctx* c, int B, int k) {
     (void)hipGetLastError();
     return fail(c, DBL_EHIP, std::string("cooperative launch: ") + hipGetErrorString(e));
   }
+  if (c->trace) {   // tuning aid: mean duration of each phase (wall clock, 100 MHz) on stderr; synchronises
+    const int n = 1 + LAYER_LOOP_BARRIERS * g.n_layers;
+    std::vector<long long> t(n);
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, hipMemcpy(t.data(), c->trace, sizeof(long long) * n, hipMemcpyDeviceToHost));
+    static const char* names[LAYER_LOOP_BARRIERS] = {"norm1", "qkv", "rope", "attn", "combine", "o", "norm2", "gate_up", "down"};
+    double sum[LAYER_LOOP_BARRIERS] = {};
+    for (int l = 0; l < g.n_layers; ++l)
+      for (int p = 0; p < LAYER_LOOP_BARRIERS; ++p) sum[p] += (double)(t[1 + l * LAYER_LOOP_BARRIERS + p] - t[l * LAYER_LOOP_BARRIERS + p]);
+    std::fprintf(stderr, "[dbl] persistent phases (us, mean over %d layers):", g.n_layers);
+    for (int p = 0; p < LAYER_LOOP_BARRIERS; ++p) std::fprintf(stderr, " %s %.1f", names[p], sum[p] / g.n_layers * 0.01);
+    std::fprintf(stderr, " | total %.1f\n", (double)(t[n - 1] - t[0]) * 0.01);
+  }
   c->persistent_launches++;
+  c->bar_base += (unsigned)(LAYER_LOOP_BARRIERS * g.n_layers * grid);   // modulo 2^32, like the device counter
   return DBL_OK;
 }
 
@@ -346,20 +372,20 @@ int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperatu
   }
   for (int l = 0; !done && l < g.n_layers; ++l) {
     const LayerSteps<T> s = layer_steps<T>(c, l, B, k, pending_parts);
-    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(1024), 0, st, s.n1);
+    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(norm_threads(d)), 0, st, s.n1);
     launch_gemm<T>(c, c->p_qkv, EPI_PARTIAL, s.qkv, M);
     const int waves = M * (H + 2 * g.n_kv_heads);
     hipLaunchKernelGGL((rope_kv_kernel<T>), dim3((waves + 3) / 4), dim3(256), 0, st, s.rope);
     if (hd == 128) launch_attn_hd<T, 128>(c, s, B, M, H); else launch_attn_hd<T, 64>(c, s, B, M, H);
     launch_gemm<T>(c, c->p_o, s.epi_o, s.o, M);
-    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(1024), 0, st, s.n2);
+    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(norm_threads(d)), 0, st, s.n2);
     launch_gemm<T>(c, c->p_gu, EPI_SWIGLU, s.gu, M);
     launch_gemm<T>(c, c->p_d, s.epi_dn, s.dn, M);
     pending_parts = s.epi_dn == EPI_PARTIAL ? c->p_d.SS : 0;
   }
   {
     const NormArgs<T> nf{c->h, ldh, c->d_part, pending_parts, M, c->p_d.ldo(), c->gf, xn, c->p_lm.ldx(), d, g.rms_eps};
-    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(1024), 0, st, nf);
+    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(norm_threads(d)), 0, st, nf);
   }
   {
     GemmArgs<T> a{};
@@ -485,11 +511,24 @@ void free_all(dbl_ctx* c) {
   void* ptrs[] = {c->w_qkv, c->w_o, c->w_gu, c->w_d, c->w_lm, c->emb, c->g1, c->g2, c->gq, c->gk, c->gf, c->cosT,
                   c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->status, c->commits, c->h, c->qkv_part,
                   c->d_part, c->o_part, c->logits, c->xn, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
-                  c->n_acc_i, c->emit_i, c->win_i, c->bar};
+                  c->n_acc_i, c->emit_i, c->win_i, c->bar, c->trace};
   for (void* p : ptrs) if (p) (void)hipFree(p);
 }
 
+// Called at synchronisation points.  A grid barrier of the persistent layer kernel that
+// timed out leaves a sticky error word; the step that hit it produced no valid result.
+// The persistent path is switched off for the rest of the context's life.
+int check_barrier(dbl_ctx* c) {
+  if (c->persistent_launches == 0 || !c->use_persistent) return DBL_OK;
+  unsigned err = 0;
+  HIPCHK(c, hipMemcpy(&err, &c->bar->error, sizeof(err), hipMemcpyDeviceToHost));
+  if (!err) return DBL_OK;
+  c->use_persistent = false;
+  return fail(c, DBL_EHIP, "persistent layer kernel: a grid barrier timed out; the last verify results are invalid");
+}
+
 int check_status(dbl_ctx* c) {
+  if (const int rc = check_barrier(c)) return rc;
   int32_t s = 0;
   HIPCHK(c, hipMemcpy(&s, c->status, sizeof(s), hipMemcpyDeviceToHost));
   if (s) return fail(c, DBL_ESTATE, (s & 1) ? "a commit would exceed max_ctx and was clamped" : "a commit would exceed max_hist and was clamped");
@@ -566,6 +605,8 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(n_acc_i, (size_t)g.max_batch * 4, true); ALLOC(emit_i, (size_t)Mmax * 4, true);
     ALLOC(win_i, (size_t)Mmax * 4, true);
     ALLOC(bar, sizeof(GridBar), true);
+    if (const char* e = std::getenv("DBL_PERSISTENT_TRACE"))
+      if (std::atoi(e) != 0) ALLOC(trace, sizeof(long long) * (1 + LAYER_LOOP_BARRIERS * (size_t)std::max(1, g.n_layers)), true);
   } while (0);
 #undef ALLOC
   if (rc == DBL_OK) {
@@ -871,6 +912,15 @@ int dbl_debug_buffer(dbl_ctx* c, int which, void* host, size_t bytes, int32_t* l
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(host, src, need, hipMemcpyDeviceToHost));
   return DBL_OK;
+}
+
+int dbl_persistent_launches(dbl_ctx* c, int64_t* launches_out) {
+  if (!c) return DBL_EINVAL;
+  if (!launches_out) return fail(c, DBL_EINVAL, "null output pointer");
+  *launches_out = c->persistent_launches;
+  if (c->dry) return DBL_OK;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return check_barrier(c);
 }
 
 int dbl_kv_len(dbl_ctx* c, int32_t* host_out) { return read_counters(c, host_out, true); }

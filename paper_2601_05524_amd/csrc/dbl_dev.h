@@ -79,6 +79,25 @@ __device__ __forceinline__ f32x4 mma(const Frag<float>& a, const Frag<float>& b,
   return c;
 }
 
+// swap lanes c and c^8 inside every 16-lane row (DPP row rotate by 8)
+__device__ __forceinline__ uint32_t dpp_swap8(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128 /* row_ror:8 */, 0xf, 0xf, false);
+}
+__device__ __forceinline__ Frag<bf16_t> frag_swap_halves(const Frag<bf16_t>& f) {
+  Frag<bf16_t> r;
+  r.v = u32x4{dpp_swap8(f.v.x), dpp_swap8(f.v.y), dpp_swap8(f.v.z), dpp_swap8(f.v.w)};
+  return r;
+}
+__device__ __forceinline__ Frag<float> frag_swap_halves(const Frag<float>& f) {
+  Frag<float> r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    r.lo[i] = __uint_as_float(dpp_swap8(__float_as_uint(f.lo[i])));
+    r.hi[i] = __uint_as_float(dpp_swap8(__float_as_uint(f.hi[i])));
+  }
+  return r;
+}
+
 // ---------------------------------------------------------------------------
 // Memory access with or without cross-workgroup coherence.  COH = false: ordinary
 // cached accesses (data produced by an earlier kernel).  COH = true: the data was

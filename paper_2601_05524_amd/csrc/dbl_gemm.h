@@ -88,10 +88,18 @@ __device__ __forceinline__ void gemm_prefetch(const GemmArgs<T>& a, int wg, int 
   for (int j = 0; j < RING; ++j) ring[j] = frag_load_w(a.W, gemm_blk<T, NACC>(a, t, 0, kb0 + j), lane);
 }
 
-template <typename T, int EPI, int KS, bool COH, int RING = GemmCfg<T>::RING>
+// BPACK (at most 8 rows): the activation operand has 16 columns but only 8 rows to
+// put in them, so one register set holds TWO k-blocks: lanes c < 8 carry block 2i (row
+// c), lanes c >= 8 carry block 2i+1 (row c-8).  Block 2i is used as it is (columns
+// 8..15 of the product are never read); for block 2i+1 the halves are swapped with a
+// DPP rotate by 8 inside each 16-lane row.  This halves the registers the activations
+// take (64 instead of 128 for a 32-block slice).
+template <typename T, int EPI, int KS, bool COH, bool BPACK = false, int RING = GemmCfg<T>::RING>
 __device__ __forceinline__ void gemm_body(const GemmArgs<T>& a, int wg, int nwg, int nw, GemmRed* red,
                                           Frag<T> (&ring)[RING], bool prefetched) {
   constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
+  constexpr int NB = BPACK ? KS / 2 : KS;      // activation register sets
+  static_assert(!BPACK || KS % 2 == 0, "packed activations pair k-blocks");
   static_assert(KS % RING == 0, "slice must be a whole number of rings");
   static_assert(!(COH && EPI == EPI_LMHEAD), "the LM head runs as its own kernel");
 
@@ -108,12 +116,13 @@ __device__ __forceinline__ void gemm_body(const GemmArgs<T>& a, int wg, int nwg,
   // activations of this wave's K slice -> registers.  Output column j of a tile depends
   // only on activation row j, so lanes of the unused rows (c >= mrows) simply re-read the
   // last valid row: all loads are unconditional and stay in flight together.
-  Frag<T> breg[KS];
+  Frag<T> breg[NB];
   {
     const int wv = active ? wave : 0;
-    const T* xrow = a.X + (size_t)(a.m0 + min(c, a.mrows - 1)) * a.ldx + (size_t)((ss * nw + wv) * KS) * TILE_K + g * 8;
+    const int row = BPACK ? (c & 7) : c, odd = BPACK ? (c >> 3) : 0;
+    const T* xrow = a.X + (size_t)(a.m0 + min(row, a.mrows - 1)) * a.ldx + (size_t)((ss * nw + wv) * KS + odd) * TILE_K + g * 8;
 #pragma unroll
-    for (int j = 0; j < KS; ++j) breg[j] = frag_load_row<COH>(xrow + (size_t)j * TILE_K);
+    for (int j = 0; j < NB; ++j) breg[j] = frag_load_row<COH>(xrow + (size_t)j * (BPACK ? 2 : 1) * TILE_K);
   }
 
   // LM-head running statistics (wave 0 only)
@@ -146,7 +155,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs<T>& a, int wg, int nwg,
       for (int s = 0; s < NACC; ++s) {
 #pragma unroll
         for (int j = 0; j < KS; ++j) {
-          acc[s] = mma(ring[j % RING], breg[j], acc[s]);
+          if (BPACK) acc[s] = mma(ring[j % RING], (j & 1) ? frag_swap_halves(breg[j / 2]) : breg[j / 2], acc[s]);
+          else acc[s] = mma(ring[j % RING], breg[j], acc[s]);
           const int jn = j + RING;
           if (jn < KS) ring[j % RING] = frag_load_w(wcur + s * row_elems, jn, lane);
           else if (s + 1 < NACC) ring[j % RING] = frag_load_w(wcur + (s + 1) * row_elems, jn - KS, lane);
@@ -239,11 +249,11 @@ __device__ __forceinline__ void gemm_body(const GemmArgs<T>& a, int wg, int nwg,
   }
 }
 
-template <typename T, int EPI, int KS>
+template <typename T, int EPI, int KS, bool BPACK>
 __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
   __shared__ GemmRed red[2];
   Frag<T> ring[GemmCfg<T>::RING];
-  gemm_body<T, EPI, KS, false>(a, blockIdx.x, gridDim.x, blockDim.x >> 6, red, ring, false);
+  gemm_body<T, EPI, KS, false, BPACK>(a, blockIdx.x, gridDim.x, blockDim.x >> 6, red, ring, false);
 }
 
 }  // namespace dbl

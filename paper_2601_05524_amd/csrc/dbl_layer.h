@@ -27,22 +27,24 @@
 namespace dbl {
 
 struct GridBar {
-  unsigned count; unsigned pad0[31];   // arrivals since the launch (host zeroes it before each launch)
-  unsigned error; unsigned pad1[31];   // != 0: a barrier timed out
+  unsigned count; unsigned pad0[31];   // arrivals since the context was created (never reset; wraps)
+  unsigned error; unsigned pad1[31];   // != 0: a barrier timed out (sticky: later launches leave at once)
 };
 
 // Every thread of every workgroup calls this the same number of times.  Returns false
 // (to all threads of the workgroup) once any barrier of the launch has timed out.
-__device__ __forceinline__ bool grid_barrier(GridBar* b, unsigned nwg, unsigned& epoch, unsigned max_spin, int* flag) {
+// `base` is the value of the counter when the launch started (the host keeps it: every
+// launch adds barriers x workgroups); differences are taken modulo 2^32.
+__device__ __forceinline__ bool grid_barrier(GridBar* b, unsigned base, unsigned nwg, unsigned& epoch, unsigned max_spin, int* flag) {
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // this thread's loads and stores are done
   __syncthreads();
   if (threadIdx.x == 0) {
     ++epoch;
-    const unsigned target = epoch * nwg;
+    const unsigned target = base + epoch * nwg;
     int ok = 1;
     __hip_atomic_fetch_add(&b->count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     unsigned spins = 0;
-    while (__hip_atomic_load(&b->count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+    while ((int)(__hip_atomic_load(&b->count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
       if (++spins > max_spin || __hip_atomic_load(&b->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
         __hip_atomic_store(&b->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         ok = 0;
@@ -67,12 +69,13 @@ struct LayerLoopArgs {
   size_t s_kv;
   int n_layers, M, d_parts;
   GridBar* bar;
-  unsigned max_spin;
+  unsigned bar_base, max_spin;
+  long long* trace;                    // tuning aid: [1 + 9*n_layers] clock values of workgroup 0, or nullptr
 };
 
 // KSQ / KSO / KSG / KSD: k-blocks per wave of the q/k/v, output, gate/up and down
 // projections (compile-time: the activation registers are indexed statically).
-// Requirements checked by the host: bf16, M <= 16, the output projection is not
+// Requirements checked by the host: bf16, M <= 8 (packed activations), the output projection is not
 // K-split (residual epilogue), the down projection goes through partials that the next
 // norm folds, head_dim == HD, d_model <= 8192, gridDim.x divisible by every
 // projection's SS and >= M.
@@ -90,7 +93,10 @@ __global__ void __launch_bounds__(512) layer_loop_kernel(const LayerLoopArgs a) 
   const int attn_tasks = (a.M / a.attn.k) * a.attn.Hkv * a.attn.nsplit * a.attn.nqb;
   const int comb_tasks = a.M * a.comb.H;
 
-#define DBL_BARRIER() do { if (!grid_barrier(a.bar, nwg, epoch, a.max_spin, &bar_flag)) return; } while (0)
+  int nstamp = 0;
+#define DBL_STAMP() do { if (a.trace && wg == 0 && threadIdx.x == 0) a.trace[nstamp++] = wall_clock64(); } while (0)
+#define DBL_BARRIER() do { if (!grid_barrier(a.bar, a.bar_base, nwg, epoch, a.max_spin, &bar_flag)) return; DBL_STAMP(); } while (0)
+  DBL_STAMP();
 
   for (int l = 0; l < a.n_layers; ++l) {
     GemmArgs<bf16_t> qkv = a.qkv, o = a.o, gu = a.gu, dn = a.dn;
@@ -105,7 +111,7 @@ __global__ void __launch_bounds__(512) layer_loop_kernel(const LayerLoopArgs a) 
     }
     DBL_BARRIER();
     // ---- q/k/v projection -> partials
-    gemm_body<bf16_t, EPI_PARTIAL, KSQ, true>(qkv, wg, nwg, a.nw_qkv, red, ring, true);
+    gemm_body<bf16_t, EPI_PARTIAL, KSQ, true, true>(qkv, wg, nwg, a.nw_qkv, red, ring, true);
     DBL_BARRIER();
     // ---- (q/k norm,) RoPE, KV append
     {
@@ -127,7 +133,7 @@ __global__ void __launch_bounds__(512) layer_loop_kernel(const LayerLoopArgs a) 
     for (int t = wg * nwaves + wave; t < comb_tasks; t += nwg * nwaves) combine_task<bf16_t, HD, true>(a.comb, t);
     DBL_BARRIER();
     // ---- output projection + residual
-    gemm_body<bf16_t, EPI_RESIDUAL, KSO, true>(o, wg, nwg, a.nw_o, red, ring, true);
+    gemm_body<bf16_t, EPI_RESIDUAL, KSO, true, true>(o, wg, nwg, a.nw_o, red, ring, true);
     gemm_prefetch<bf16_t, EPI_SWIGLU, KSG>(gu, wg, nwg, a.nw_gu, ring);
     DBL_BARRIER();
     // ---- RMSNorm -> xn
@@ -138,14 +144,16 @@ __global__ void __launch_bounds__(512) layer_loop_kernel(const LayerLoopArgs a) 
     }
     DBL_BARRIER();
     // ---- gate/up projection + SwiGLU
-    gemm_body<bf16_t, EPI_SWIGLU, KSG, true>(gu, wg, nwg, a.nw_gu, red, ring, true);
+    gemm_body<bf16_t, EPI_SWIGLU, KSG, true, true>(gu, wg, nwg, a.nw_gu, red, ring, true);
     gemm_prefetch<bf16_t, EPI_PARTIAL, KSD>(dn, wg, nwg, a.nw_dn, ring);
     DBL_BARRIER();
     // ---- down projection -> partials (folded by the next norm)
-    gemm_body<bf16_t, EPI_PARTIAL, KSD, true>(dn, wg, nwg, a.nw_dn, red, ring, true);
+    gemm_body<bf16_t, EPI_PARTIAL, KSD, true, true>(dn, wg, nwg, a.nw_dn, red, ring, true);
     DBL_BARRIER();
   }
 #undef DBL_BARRIER
+#undef DBL_STAMP
 }
+constexpr int LAYER_LOOP_BARRIERS = 9;   // per layer
 
 }  // namespace dbl

@@ -1,0 +1,159 @@
+"""GPU parity at full layer width: two-layer slices of the 70B-shaped and the 32B-shaped
+models.  Every projection, the attention and the LM head run with the tile plans, grids
+and workgroup sizes of the full-depth model; only the depth is cut so that the oracle
+finishes in about a minute.  Logits are compared element by element over the whole
+vocabulary.
+
+Two bars.  A bf16 pipeline rounds at four points per layer; two implementations whose
+pre-rounding values differ by a few fp32 ulps round a small fraction of elements to
+neighbouring bf16 values, and each later rounding point amplifies that until the
+difference sits at the bf16 quantisation-noise level (about 2^-9 relative per stage).
+With N(0, 0.02) weights at d_model = 8192 the logits have rms 1.8 and maxima near 9, and
+the maximum over a million logits of that noise exceeds 2e-2 after one full layer.
+So (1) every kernel is held to the 2e-2 bar on paths where the noise has not yet
+compounded: the LM head alone, the attention half of a layer alone, the MLP half alone;
+(2) the composite two-layer run is held to COMPOSITE_REL of the logit rms (rms error) and
+COMPOSITE_MAX (max-abs), and (3) the persistent one-launch path must reproduce the
+kernel-per-step path bit for bit, since both use the same tiles and summation order.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from paper_2601_05524_amd import binding as B
+from paper_2601_05524_amd import synth
+from tests.gpu_util import Gpu, Ref
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+COMPOSITE_REL = 1e-2     # rms error / rms logits, two full layers
+COMPOSITE_MAX = 8e-2     # max-abs over all logits, two full layers
+
+
+def slice_of(name):
+    s = dict(synth.CONFIGS[name])
+    s["n_layers"] = 2
+    return s
+
+
+_REF = {}
+
+
+def reference(name, seed):
+    """The oracle model of a slice is built once (its weights take longest); the tests
+    zero some of its tensors and restore them afterwards."""
+    key = (name, seed)
+    if key not in _REF:
+        _REF.clear()                # one wide model at a time: they are several GB each
+        r = Ref(slice_of(name), seed=seed, max_ctx=512)
+        saved = {(t, l): r.get_tensor(t, l) for t in ("wo", "wd") for l in (0, 1)}
+        _REF[key] = (r, saved)
+    return _REF[key]
+
+
+def make_gpu(shape, seed, window, persistent):
+    old = os.environ.get("DBL_PERSISTENT")
+    os.environ["DBL_PERSISTENT"] = "1" if persistent else "0"
+    try:
+        return Gpu(shape, seed=seed, max_ctx=512, max_window=window)
+    finally:
+        if old is None:
+            del os.environ["DBL_PERSISTENT"]
+        else:
+            os.environ["DBL_PERSISTENT"] = old
+
+
+def run_slice(name, seed, zero, ctx_tokens, k, chunk, persistent=False):
+    """zero: set of (tensor, layer) replaced by zeros on both sides.  Returns per-window
+    (gpu logits, oracle logits) and the number of persistent launches."""
+    shape = slice_of(name)
+    r, saved = reference(name, seed)
+    g = make_gpu(shape, seed, max(k, chunk), persistent)
+    for (t, l), v in saved.items():
+        if (t, l) in zero:
+            z = np.zeros_like(v)
+            r.set_tensor(t, l, z)
+            g.set_tensor(t, l, z)
+        else:
+            r.set_tensor(t, l, v)
+    V = shape["vocab"]
+    prompt = synth.zipf_history(seed, ctx_tokens + 1, V)
+    g.prefill([prompt], chunk)
+    r.prefill([prompt], chunk)
+    rng = np.random.default_rng(seed)
+    out = []
+    for it in range(2):
+        first = [prompt[-1]] if it == 0 else rng.integers(0, V, 1)
+        w = np.concatenate([first, rng.integers(0, V, k - 1)]).astype(np.int32)
+        got = g.verify([w])[0]
+        ref = r.verify([w])[0]
+        assert np.isfinite(got).all()
+        assert np.abs(ref).max() > 0.3          # the comparison is not between two zero tensors
+        out.append((got, ref))
+        g.commit([3])
+        r.seqs[0].commit(3, [])
+    launches = B.dbl_persistent_launches(g.ctx)
+    assert g.kv_len()[0] == ctx_tokens + 6
+    g.close()
+    return out, launches
+
+
+def max_err(got, ref):
+    return float(np.abs(got.astype(np.float64) - ref).max())
+
+
+LAYER1_OFF = {("wo", 1), ("wd", 1)}
+PATHS = {
+    "lm_head": LAYER1_OFF | {("wo", 0), ("wd", 0)},      # embedding -> final norm -> LM head
+    "attention": LAYER1_OFF | {("wd", 0)},               # + norm, q/k/v, RoPE, attention, output projection
+    "mlp": LAYER1_OFF | {("wo", 0)},                     # + norm, gate/up + SwiGLU, down projection
+}
+
+
+def one_path(name, k, chunk, path):
+    out, _ = run_slice(name, 31, PATHS[path], ctx_tokens=24 if chunk == 8 else 37, k=k, chunk=chunk)
+    errs = [max_err(g, r) for g, r in out]
+    print("%s %s: logits max-abs errors %s" % (name, path, errs))
+    assert max(errs) <= TOL_BF16
+
+
+# the tests of one model stay together: its oracle weights are generated once
+@pytest.mark.parametrize("path", list(PATHS))
+def test_llama70b_width_one_path_at_a_time(path):
+    one_path("llama70b", 8, 8, path)
+
+
+_COMPOSITE = {}
+
+
+@pytest.mark.parametrize("persistent", [False, True], ids=["kernel_per_step", "persistent"])
+def test_llama70b_width_two_layers(persistent):
+    out, launches = run_slice("llama70b", 31, set(), ctx_tokens=40, k=8, chunk=8, persistent=persistent)
+    assert (launches > 0) == persistent
+    for got, ref in out:
+        d = got.astype(np.float64) - ref
+        rel = np.sqrt((d ** 2).mean()) / np.sqrt((ref ** 2).mean())
+        print("70B-width, persistent=%s: rms error / rms logits %.3g, max-abs %.3g" % (persistent, rel, np.abs(d).max()))
+        assert rel <= COMPOSITE_REL
+        assert np.abs(d).max() <= COMPOSITE_MAX
+    _COMPOSITE[persistent] = [g for g, _ in out]
+    if len(_COMPOSITE) == 2:        # same tiles, same summation order: identical bits
+        for a, b in zip(_COMPOSITE[False], _COMPOSITE[True]):
+            assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+def test_qwen32b_width_one_path_at_a_time(path):
+    one_path("qwen32b", 6, 16, path)
+
+
+def test_qwen32b_width_two_layers():
+    out, _ = run_slice("qwen32b", 31, set(), ctx_tokens=37, k=6, chunk=16)
+    for got, ref in out:
+        d = got.astype(np.float64) - ref
+        rel = np.sqrt((d ** 2).mean()) / np.sqrt((ref ** 2).mean())
+        print("32B-width: rms error / rms logits %.3g, max-abs %.3g" % (rel, np.abs(d).max()))
+        assert rel <= COMPOSITE_REL
+        assert np.abs(d).max() <= COMPOSITE_MAX
