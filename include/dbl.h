@@ -222,15 +222,6 @@ int dbl_bench_projection(dbl_ctx* ctx, int which, int M, int iters, float* ms_ou
  * and must cover max_batch*max_window rows. */
 int dbl_debug_buffer(dbl_ctx* ctx, int which, void* host, size_t bytes, int32_t* ld_out);
 
-/* The decoder layers of a step can run as ONE cooperative launch (environment
- * variable DBL_PERSISTENT=1 when the context is created; bf16 models of the 70B-like
- * tile plan, at most 8 window rows; other calls fall back to one kernel per step of
- * the layer).  *launches_out = number of verify calls of this context that took that
- * path.  Synchronises; returns DBL_EHIP if one of that kernel's grid barriers timed out
- * (the results of that verify call are then invalid and the context stops using the
- * path).  dbl_kv_len / dbl_hist_len report the same error. */
-int dbl_persistent_launches(dbl_ctx* ctx, int64_t* launches_out);
-
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ T_G1, T_WQ, T_WK, T_WV, T_GQ, T_GK, T_WO, T_G2, T_WG, T_WU, T_WD = range(10, 21)
 EXPORTS = ["dbl_create", "dbl_destroy", "dbl_last_error", "dbl_set_weights", "dbl_get_weights", "dbl_reset",
            "dbl_history_set", "dbl_history_get", "dbl_retrieve", "dbl_build_window", "dbl_verify_block", "dbl_accept",
            "dbl_kv_commit", "dbl_kv_len", "dbl_hist_len", "dbl_model_bytes", "dbl_debug_buffer",
-           "dbl_bench_projection", "dbl_persistent_launches"]
+           "dbl_bench_projection"]
 
 
 class DblError(RuntimeError):
@@ -71,7 +71,6 @@ def lib():
         L.dbl_model_bytes.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
         L.dbl_bench_projection.argtypes = [vp, i, i, i, C.POINTER(C.c_float), C.POINTER(C.c_uint64)]
         L.dbl_debug_buffer.argtypes = [vp, i, vp, C.c_size_t, C.POINTER(C.c_int32)]
-        L.dbl_persistent_launches.argtypes = [vp, C.POINTER(C.c_int64)]
         for n in EXPORTS:
             if n != "dbl_last_error":
                 getattr(L, n).restype = C.c_int
@@ -178,12 +177,6 @@ def dbl_debug_buffer(ctx, which, host_out):
     ld = C.c_int32(0)
     _chk(ctx, lib().dbl_debug_buffer(ctx, which, _ptr(host_out), host_out.nbytes, C.byref(ld)))
     return ld.value
-
-
-def dbl_persistent_launches(ctx):
-    n = C.c_int64(0)
-    _chk(ctx, lib().dbl_persistent_launches(ctx, C.byref(n)))
-    return n.value
 
 
 def make_cfg(*, n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, rms_eps=1e-5, rope_base=1e4,

@@ -12,7 +12,6 @@
 
 #include "../../include/dbl.h"
 #include "dbl_kernels.h"
-#include "dbl_layer.h"
 
 using namespace dbl;
 
@@ -22,45 +21,59 @@ constexpr int MAX_ROWS = 128;       // max_batch * max_window
 constexpr int MAX_WINDOW = 32;
 constexpr int MAX_SPLITS = 64;
 
-// How one projection is cut: NW waves per workgroup, each owning KS k-blocks of a
-// tile; SS workgroup super-slices when K is longer than NW*KS blocks.
+// How one projection is cut: NW waves per workgroup, each owning KS k-blocks of a tile
+// per K chunk; K longer than NW*KS blocks is covered by SS workgroup super slices
+// (partial results, summed by the consumer) or by NCH sequential chunks inside the
+// workgroup (projections that add into the residual stream).
 struct GemmPlan {
   int N = 0, K = 0;      // logical sizes (N per half for gate/up)
   int NT = 0;            // output tiles (pairs for gate/up)
   int nacc = 1;          // tile rows per unit (2 for gate/up)
-  int KS = 0, NW = 0, SS = 0, KBp = 0;
+  int KS = 0, NW = 0, SS = 1, NCH = 1, KBp = 0;
   int grid = 0;
   size_t elems() const { return (size_t)NT * nacc * KBp * BLOCK_ELEMS; }
   int ldx() const { return KBp * TILE_K; }
   int ldo() const { return NT * TILE_N; }
 };
 
-bool make_plan(GemmPlan& p, int N, int K, int nacc, bool is_bf16, bool need_single_slice, int n_cu) {
+enum PlanKind { PLAN_SLICED = 0, PLAN_SINGLE = 1, PLAN_CHUNKED = 2 };
+
+// PLAN_SLICED: SS >= 1 super slices (q/k/v).  PLAN_SINGLE: the whole K in one pass of one
+// workgroup (gate/up, LM head: their epilogues need complete sums).  PLAN_CHUNKED: NCH >= 1
+// chunks per workgroup (output and down projection); the chunked kernel keeps two sets
+// of activation registers, so it uses the smaller KS, and at most SSQ_PARTS workgroups
+// (one sum-of-squares slot each).
+bool make_plan(GemmPlan& p, int N, int K, int nacc, bool is_bf16, PlanKind kind, int n_cu) {
   p.N = N; p.K = K; p.nacc = nacc;
   p.NT = (N + TILE_N - 1) / TILE_N;
   const int KB = (K + TILE_K - 1) / TILE_K;
   const int ks_big = is_bf16 ? 32 : 16, ks_small = is_bf16 ? 16 : 8;
-  // candidates (KS, NW, SS): least K padding first, then the best balance of work units
-  // over the workgroups one launch keeps resident, then the fewest super slices
+  // candidates (KS, NW, SS | NCH): the least streaming time under a model in which every
+  // wave slot of the chip is busy or idle for whole rounds (K padding is streamed too),
+  // then fewer slices / chunks, then more waves
   double best_cost = 1e30;
   bool found = false;
   for (int ks : {ks_big, ks_small}) {
     if (ks == ks_big && KB < 2 * ks_big) continue;
     const int nsl = (KB + ks - 1) / ks;
     for (int nw = 8; nw >= 1; --nw) {
-      const int ss = (nsl + nw - 1) / nw;
-      if (need_single_slice && ss != 1) continue;
-      if (ss > 8) continue;
-      const int kbp = nw * ss * ks;
+      const int parts = (nsl + nw - 1) / nw;     // slices or chunks
+      if (kind == PLAN_SINGLE && parts != 1) continue;
+      if (kind == PLAN_SLICED && parts > 8) continue;
+      if (kind == PLAN_CHUNKED && parts > 1 && ks != ks_small) continue;
+      const int ss = kind == PLAN_SLICED ? parts : 1, nch = kind == PLAN_CHUNKED ? parts : 1;
+      const int kbp = nw * parts * ks;
       const int per_cu = std::max(1, 8 / nw);
       int g = std::min(p.NT * ss, n_cu * per_cu);
+      if (kind == PLAN_CHUNKED) g = std::min(g, SSQ_PARTS);
       g = std::max(ss, g / ss * ss);
       const long units = (long)p.NT * ss;
       const long rounds = (units + g - 1) / g;
-      // time model: rounds of (blocks per wave) with every wave slot of the chip busy or idle
-      const double streamed = (double)rounds * g * nw * ks / (double)(n_cu * 8);
-      const double cost = streamed * (1.0 + 0.02 * (ss - 1)) + 1e-3 * (8 - nw) + (double)(kbp - KB) * p.NT * 1e-6;
-      if (cost < best_cost) { best_cost = cost; p.KS = ks; p.NW = nw; p.SS = ss; p.KBp = kbp; p.grid = g; found = true; }
+      const double streamed = (double)rounds * g * nw * ks * nch / (double)(n_cu * 8);
+      const double cost = streamed * (1.0 + 0.02 * (parts - 1)) + 1e-3 * (8 - nw);
+      if (cost < best_cost) {
+        best_cost = cost; p.KS = ks; p.NW = nw; p.SS = ss; p.NCH = nch; p.KBp = kbp; p.grid = g; found = true;
+      }
     }
   }
   return found;
@@ -88,8 +101,10 @@ struct dbl_ctx {
   size_t kv_layer_elems = 0;
   int32_t *kv_len = nullptr, *hist_len = nullptr, *hist = nullptr, *status = nullptr;
   uint64_t* commits = nullptr;
-  float *h = nullptr, *qkv_part = nullptr, *d_part = nullptr, *o_part = nullptr, *logits = nullptr;
-  void *xn = nullptr, *qbuf = nullptr, *attn = nullptr, *act = nullptr;
+  float *h = nullptr, *ssq = nullptr, *qkv_part = nullptr, *logits = nullptr;
+  void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
+  int tile_rot = 0;                 // per-round shift of the workgroup -> tile mapping (DBL_TILE_ROT)
+  int ldh = 0;                      // row stride of h and layer stride of g1 / g2 / gf (>= every consumer's K padding)
   float *pm = nullptr, *pl = nullptr, *po = nullptr;
   LmStat* stats = nullptr;
   int32_t *n_acc_i = nullptr, *emit_i = nullptr, *win_i = nullptr;
@@ -101,12 +116,6 @@ struct dbl_ctx {
   int last_B = 0, last_k = 0;
   float last_T = 0.f;
   uint64_t last_seed = 0, last_step = 0;
-  GridBar* bar = nullptr;           // barrier state of the persistent layer kernel
-  unsigned bar_base = 0;            // value the barrier counter has when the next launch starts
-  unsigned max_spin = 1u << 20;     // polls of one barrier before the launch gives up
-  bool use_persistent = false;      // opt-in (DBL_PERSISTENT=1)
-  long persistent_launches = 0;
-  long long* trace = nullptr;       // DBL_PERSISTENT_TRACE=1: phase clock values of the last persistent launch
 };
 
 namespace {
@@ -157,51 +166,55 @@ int validate_cfg(const dbl_model_cfg* g, std::string& why) {
 int make_plans(dbl_ctx* c) {
   const dbl_model_cfg& g = c->cfg;
   c->hq = g.n_q_heads * g.head_dim; c->hkv = g.n_kv_heads * g.head_dim; c->n_qkv = c->hq + 2 * c->hkv;
-  bool ok = make_plan(c->p_qkv, c->n_qkv, g.d_model, 1, c->bf16, false, c->n_cu) &&
-            make_plan(c->p_o, g.d_model, c->hq, 1, c->bf16, false, c->n_cu) &&
-            make_plan(c->p_gu, g.d_ffn, g.d_model, 2, c->bf16, true, c->n_cu) &&
-            make_plan(c->p_d, g.d_model, g.d_ffn, 1, c->bf16, false, c->n_cu) &&
-            make_plan(c->p_lm, g.vocab, g.d_model, 1, c->bf16, true, c->n_cu);
+  bool ok = make_plan(c->p_qkv, c->n_qkv, g.d_model, 1, c->bf16, PLAN_SLICED, c->n_cu) &&
+            make_plan(c->p_o, g.d_model, c->hq, 1, c->bf16, PLAN_CHUNKED, c->n_cu) &&
+            make_plan(c->p_gu, g.d_ffn, g.d_model, 2, c->bf16, PLAN_SINGLE, c->n_cu) &&
+            make_plan(c->p_d, g.d_model, g.d_ffn, 1, c->bf16, PLAN_CHUNKED, c->n_cu) &&
+            make_plan(c->p_lm, g.vocab, g.d_model, 1, c->bf16, PLAN_SINGLE, c->n_cu);
   if (!ok) return fail(c, DBL_EINVAL, "d_model too large for a single K slice (max 8192 bf16 / 4096 fp32)");
   if (std::getenv("DBL_VERBOSE")) {
     const GemmPlan* ps[5] = {&c->p_qkv, &c->p_o, &c->p_gu, &c->p_d, &c->p_lm};
     const char* nm[5] = {"qkv", "o", "gate_up", "down", "lm_head"};
     for (int i = 0; i < 5; ++i)
-      std::fprintf(stderr, "[dbl] plan %-8s N=%d K=%d tiles=%d KS=%d NW=%d SS=%d KBp=%d grid=%d\n", nm[i], ps[i]->N,
-                   ps[i]->K, ps[i]->NT, ps[i]->KS, ps[i]->NW, ps[i]->SS, ps[i]->KBp, ps[i]->grid);
+      std::fprintf(stderr, "[dbl] plan %-8s N=%d K=%d tiles=%d KS=%d NW=%d SS=%d NCH=%d KBp=%d grid=%d\n", nm[i],
+                   ps[i]->N, ps[i]->K, ps[i]->NT, ps[i]->KS, ps[i]->NW, ps[i]->SS, ps[i]->NCH, ps[i]->KBp, ps[i]->grid);
   }
-  if (c->p_qkv.SS > RMS_MAXP || c->p_o.SS > RMS_MAXP || c->p_d.SS > RMS_MAXP)
-    return fail(c, DBL_EINVAL, "a projection needs more than 8 K super-slices (n_q_heads*head_dim or d_ffn too large)");
+  c->ldh = std::max({c->p_o.ldo(), c->p_d.ldo(), c->p_qkv.ldx(), c->p_gu.ldx(), c->p_lm.ldx()});
   return DBL_OK;
 }
 
 // ----------------------------------------------------------------- launchers
 
-template <typename T, int EPI>
+template <typename T, int EPI, bool CHUNK>
 void launch_gemm_t(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
   const dim3 grid(p.grid), block(p.NW * 64);
   constexpr bool is_bf = sizeof(T) == 2;
   constexpr int KS_BIG = is_bf ? 32 : 16, KS_SMALL = is_bf ? 16 : 8;
   const bool pack = a.mrows <= 8;   // two k-blocks of activations per register set
-  if (p.KS == KS_BIG) {
-    if (pack) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, true>), grid, block, 0, c->stream, a);
-    else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, false>), grid, block, 0, c->stream, a);
+  if (p.KS == KS_BIG && !CHUNK) {
+    if (pack) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, true, false>), grid, block, 0, c->stream, a);
+    else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, false, false>), grid, block, 0, c->stream, a);
   } else {
-    if (pack) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL, true>), grid, block, 0, c->stream, a);
-    else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL, false>), grid, block, 0, c->stream, a);
+    if (pack) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL, true, CHUNK>), grid, block, 0, c->stream, a);
+    else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL, false, CHUNK>), grid, block, 0, c->stream, a);
   }
 }
 
 template <typename T>
 void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
-  a.NT = p.NT; a.N = p.N; a.KBp = p.KBp; a.SS = p.SS; a.Mtot = M;
+  a.NT = p.NT; a.N = p.N; a.KBp = p.KBp; a.SS = p.SS; a.NCH = p.NCH; a.Mtot = M;
+  a.d = (float)c->cfg.d_model; a.eps = c->cfg.rms_eps; a.ssq_in = c->ssq; a.ssq_out = c->ssq;
+  a.rot = c->tile_rot;
   for (int m0 = 0; m0 < M; m0 += 16) {
     a.m0 = m0; a.mrows = std::min(16, M - m0);
     switch (epi) {
-      case EPI_PARTIAL: launch_gemm_t<T, EPI_PARTIAL>(c, p, a); break;
-      case EPI_RESIDUAL: launch_gemm_t<T, EPI_RESIDUAL>(c, p, a); break;
-      case EPI_SWIGLU: launch_gemm_t<T, EPI_SWIGLU>(c, p, a); break;
-      default: launch_gemm_t<T, EPI_LMHEAD>(c, p, a); break;
+      case EPI_PARTIAL: launch_gemm_t<T, EPI_PARTIAL, false>(c, p, a); break;
+      case EPI_RESIDUAL:
+        if (p.NCH > 1) launch_gemm_t<T, EPI_RESIDUAL, true>(c, p, a);
+        else launch_gemm_t<T, EPI_RESIDUAL, false>(c, p, a);
+        break;
+      case EPI_SWIGLU: launch_gemm_t<T, EPI_SWIGLU, false>(c, p, a); break;
+      default: launch_gemm_t<T, EPI_LMHEAD, false>(c, p, a); break;
     }
   }
 }
@@ -209,9 +222,7 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
 // Arguments of every per-layer step, for layer `l`, window (B, k).
 template <typename T>
 struct LayerSteps {
-  NormArgs<T> n1, n2;
   GemmArgs<T> qkv, o, gu, dn;
-  int epi_o, epi_dn;
   RopeArgs<T> rope;
   AttnArgs<T> attn;
   CombineArgs<T> comb;
@@ -219,24 +230,19 @@ struct LayerSteps {
 };
 
 template <typename T>
-LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k, int pending_parts) {
+LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
   const dbl_model_cfg& g = c->cfg;
   const int M = B * k, d = g.d_model, hd = g.head_dim, H = g.n_q_heads, Hkv = g.n_kv_heads;
-  T* xn = reinterpret_cast<T*>(c->xn);
   T* attn = reinterpret_cast<T*>(c->attn);
   T* act = reinterpret_cast<T*>(c->act);
   T* qbuf = reinterpret_cast<T*>(c->qbuf);
   T* kc = reinterpret_cast<T*>(c->kc) + (size_t)l * c->kv_layer_elems;
   T* vt = reinterpret_cast<T*>(c->vt) + (size_t)l * c->kv_layer_elems;
-  const int ldh = c->p_o.ldo();   // = roundup16(d)
   LayerSteps<T> s{};
-  auto fill = [&](GemmArgs<T>& a, const GemmPlan& p) {
-    a.NT = p.NT; a.N = p.N; a.KBp = p.KBp; a.SS = p.SS; a.Mtot = M; a.m0 = 0; a.mrows = std::min(16, M);
-  };
-  s.n1 = NormArgs<T>{c->h, ldh, c->d_part, pending_parts, M, c->p_d.ldo(), c->g1 + (size_t)l * d, xn, c->p_qkv.ldx(), d, g.rms_eps};
+  // q/k/v: RMSNorm (gain g1) on load -> per-slice partials
   s.qkv.W = reinterpret_cast<const T*>(c->w_qkv) + (size_t)l * c->p_qkv.elems();
-  s.qkv.X = xn; s.qkv.ldx = c->p_qkv.ldx(); s.qkv.out = c->qkv_part; s.qkv.ldo = c->p_qkv.ldo();
-  fill(s.qkv, c->p_qkv);
+  s.qkv.H = c->h; s.qkv.ldx = c->ldh; s.qkv.gain = c->g1 + (size_t)l * c->ldh;
+  s.qkv.out = c->qkv_part; s.qkv.ldo = c->p_qkv.ldo();
   RopeArgs<T>& r = s.rope;
   r.qkv = c->qkv_part; r.nparts = c->p_qkv.SS; r.Mtot = M; r.ldq = c->p_qkv.ldo();
   r.gq = g.qk_norm ? c->gq + (size_t)l * hd : nullptr;
@@ -265,20 +271,14 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k, int pending_parts) {
   at.nsplit = nsplit; at.nqb = qblocks; at.scale = (float)(1.4426950408889634 / std::sqrt((double)hd));
   s.comb = CombineArgs<T>{c->pm, c->pl, c->po, attn, c->p_o.ldx(), M, k, H, Hkv, c->qrows_pad, nsplit};
   s.o.W = reinterpret_cast<const T*>(c->w_o) + (size_t)l * c->p_o.elems();
-  s.o.X = attn; s.o.ldx = c->p_o.ldx();
-  fill(s.o, c->p_o);
-  int o_parts = 0;
-  if (c->p_o.SS == 1) { s.o.out = c->h; s.o.ldo = ldh; s.epi_o = EPI_RESIDUAL; }
-  else { s.o.out = c->o_part; s.o.ldo = c->p_o.ldo(); s.epi_o = EPI_PARTIAL; o_parts = c->p_o.SS; }
-  s.n2 = NormArgs<T>{c->h, ldh, c->o_part, o_parts, M, c->p_o.ldo(), c->g2 + (size_t)l * d, xn, c->p_gu.ldx(), d, g.rms_eps};
+  s.o.X = attn; s.o.ldx = c->p_o.ldx(); s.o.out = c->h; s.o.ldo = c->ldh;      // h += attn Wo^T
+  // gate/up: RMSNorm (gain g2) on load -> silu(gate) * up
   s.gu.W = reinterpret_cast<const T*>(c->w_gu) + (size_t)l * c->p_gu.elems();
-  s.gu.X = xn; s.gu.ldx = c->p_gu.ldx(); s.gu.act = act; s.gu.ldact = c->p_d.ldx();
-  fill(s.gu, c->p_gu);
+  s.gu.H = c->h; s.gu.ldx = c->ldh; s.gu.gain = c->g2 + (size_t)l * c->ldh;
+  s.gu.act = act; s.gu.ldact = c->p_d.ldx();
   s.dn.W = reinterpret_cast<const T*>(c->w_d) + (size_t)l * c->p_d.elems();
-  s.dn.X = act; s.dn.ldx = c->p_d.ldx();
-  fill(s.dn, c->p_d);
-  if (c->p_d.SS == 1) { s.dn.out = c->h; s.dn.ldo = ldh; s.epi_dn = EPI_RESIDUAL; }
-  else { s.dn.out = c->d_part; s.dn.ldo = c->p_d.ldo(); s.epi_dn = EPI_PARTIAL; }
+  s.dn.X = act; s.dn.ldx = c->p_d.ldx(); s.dn.out = c->h; s.dn.ldo = c->ldh;   // h += act Wd^T
+  (void)d;
   return s;
 }
 
@@ -290,106 +290,28 @@ void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
   hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3((waves + 3) / 4), dim3(256), 0, c->stream, s.comb);
 }
 
-// Threads of a row-normalisation workgroup.  512 whenever they can hold the row: the
-// persistent layer kernel runs 512-thread workgroups, and with the same partition of a
-// row over threads both paths add the squares in the same order (bit-identical results).
-inline int norm_threads(int d) { return d / 4 <= 512 * RMS_VPT ? 512 : 1024; }
-
-// One launch for all layers (bf16, at most 16 rows, output projection not K-split).
-// Returns false if this context / window cannot use it; the caller then launches
-// the layers kernel by kernel.
-bool persistent_eligible(const dbl_ctx* c, int M) {
-  if (!c->bf16 || !c->use_persistent || M > 8 || c->cfg.n_layers < 1) return false;
-  if (c->p_o.SS != 1) return false;           // the output projection adds into the residual stream
-  if (c->cfg.d_model > 8192) return false;    // one workgroup of 512 threads normalises a row
-  for (const GemmPlan* p : {&c->p_qkv, &c->p_o, &c->p_gu, &c->p_d})
-    if (p->NW > 8) return false;
-  const int ks[4] = {c->p_qkv.KS, c->p_o.KS, c->p_gu.KS, c->p_d.KS};
-  return ks[0] == 16 && ks[1] == 32 && ks[2] == 32 && ks[3] == 32;   // the instantiated combination
-}
-
-int launch_persistent(dbl_ctx* c, int B, int k) {
-  const dbl_model_cfg& g = c->cfg;
-  const int M = B * k;
-  const LayerSteps<bf16_t> s = layer_steps<bf16_t>(c, 0, B, k, 0);
-  LayerLoopArgs a{};
-  a.qkv = s.qkv; a.o = s.o; a.gu = s.gu; a.dn = s.dn;
-  a.dn.out = c->d_part; a.dn.ldo = c->p_d.ldo();     // always through partials, also when SS == 1
-  a.s_qkv = c->p_qkv.elems(); a.s_o = c->p_o.elems(); a.s_gu = c->p_gu.elems(); a.s_dn = c->p_d.elems();
-  a.nw_qkv = c->p_qkv.NW; a.nw_o = c->p_o.NW; a.nw_gu = c->p_gu.NW; a.nw_dn = c->p_d.NW;
-  a.n1 = s.n1; a.n2 = s.n2; a.rope = s.rope; a.attn = s.attn; a.comb = s.comb;
-  a.s_kv = c->kv_layer_elems; a.n_layers = g.n_layers; a.M = M; a.d_parts = c->p_d.SS;
-  a.bar = c->bar; a.bar_base = c->bar_base; a.max_spin = c->max_spin; a.trace = c->trace;
-  // the grid must divide by every projection's SS; take the largest such size <= CUs
-  int grid = c->n_cu;
-  const int ss[4] = {c->p_qkv.SS, c->p_o.SS, c->p_gu.SS, c->p_d.SS};
-  auto ok = [&](int gsz) { for (int v : ss) if (gsz % v) return false; return true; };
-  while (grid > 0 && !ok(grid)) --grid;
-  if (grid < std::max(M, 8)) return DBL_EINVAL;
-  void* args[] = {&a};
-  const void* fn = g.head_dim == 128 ? (const void*)layer_loop_kernel<128, 16, 32, 32, 32>
-                                     : (const void*)layer_loop_kernel<64, 16, 32, 32, 32>;
-  hipError_t e = hipLaunchCooperativeKernel(fn, dim3(grid), dim3(512), args, 0, c->stream);
-  if (e != hipSuccess) {
-    (void)hipGetLastError();
-    return fail(c, DBL_EHIP, std::string("cooperative launch: ") + hipGetErrorString(e));
-  }
-  if (c->trace) {   // tuning aid: mean duration of each phase (wall clock, 100 MHz) on stderr; synchronises
-    const int n = 1 + LAYER_LOOP_BARRIERS * g.n_layers;
-    std::vector<long long> t(n);
-    HIPCHK(c, hipStreamSynchronize(c->stream));
-    HIPCHK(c, hipMemcpy(t.data(), c->trace, sizeof(long long) * n, hipMemcpyDeviceToHost));
-    static const char* names[LAYER_LOOP_BARRIERS] = {"norm1", "qkv", "rope", "attn", "combine", "o", "norm2", "gate_up", "down"};
-    double sum[LAYER_LOOP_BARRIERS] = {};
-    for (int l = 0; l < g.n_layers; ++l)
-      for (int p = 0; p < LAYER_LOOP_BARRIERS; ++p) sum[p] += (double)(t[1 + l * LAYER_LOOP_BARRIERS + p] - t[l * LAYER_LOOP_BARRIERS + p]);
-    std::fprintf(stderr, "[dbl] persistent phases (us, mean over %d layers):", g.n_layers);
-    for (int p = 0; p < LAYER_LOOP_BARRIERS; ++p) std::fprintf(stderr, " %s %.1f", names[p], sum[p] / g.n_layers * 0.01);
-    std::fprintf(stderr, " | total %.1f\n", (double)(t[n - 1] - t[0]) * 0.01);
-  }
-  c->persistent_launches++;
-  c->bar_base += (unsigned)(LAYER_LOOP_BARRIERS * g.n_layers * grid);   // modulo 2^32, like the device counter
-  return DBL_OK;
-}
-
 template <typename T>
 int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperature, uint64_t seed, uint64_t step) {
   const dbl_model_cfg& g = c->cfg;
   const int M = B * k, d = g.d_model, hd = g.head_dim, H = g.n_q_heads;
   hipStream_t st = c->stream;
-  T* xn = reinterpret_cast<T*>(c->xn);
-  const int ldh = c->p_o.ldo();   // = roundup16(d)
 
   hipLaunchKernelGGL((embed_kernel<T>), dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->emb), window, c->h,
-                     d, ldh, g.vocab);
-
-  int pending_parts = 0;   // partials of the previous down projection not yet folded into h
-  bool done = false;
-  if (persistent_eligible(c, M)) {
-    const int rc = launch_persistent(c, B, k);
-    if (rc == DBL_OK) { done = true; pending_parts = c->p_d.SS; }
-    else if (rc != DBL_EINVAL) return rc;
-  }
-  for (int l = 0; !done && l < g.n_layers; ++l) {
-    const LayerSteps<T> s = layer_steps<T>(c, l, B, k, pending_parts);
-    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(norm_threads(d)), 0, st, s.n1);
+                     c->ssq, d, c->ldh, g.vocab);
+  for (int l = 0; l < g.n_layers; ++l) {
+    const LayerSteps<T> s = layer_steps<T>(c, l, B, k);
     launch_gemm<T>(c, c->p_qkv, EPI_PARTIAL, s.qkv, M);
     const int waves = M * (H + 2 * g.n_kv_heads);
     hipLaunchKernelGGL((rope_kv_kernel<T>), dim3((waves + 3) / 4), dim3(256), 0, st, s.rope);
     if (hd == 128) launch_attn_hd<T, 128>(c, s, B, M, H); else launch_attn_hd<T, 64>(c, s, B, M, H);
-    launch_gemm<T>(c, c->p_o, s.epi_o, s.o, M);
-    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(norm_threads(d)), 0, st, s.n2);
+    launch_gemm<T>(c, c->p_o, EPI_RESIDUAL, s.o, M);
     launch_gemm<T>(c, c->p_gu, EPI_SWIGLU, s.gu, M);
-    launch_gemm<T>(c, c->p_d, s.epi_dn, s.dn, M);
-    pending_parts = s.epi_dn == EPI_PARTIAL ? c->p_d.SS : 0;
+    launch_gemm<T>(c, c->p_d, EPI_RESIDUAL, s.dn, M);
   }
   {
-    const NormArgs<T> nf{c->h, ldh, c->d_part, pending_parts, M, c->p_d.ldo(), c->gf, xn, c->p_lm.ldx(), d, g.rms_eps};
-    hipLaunchKernelGGL((rmsnorm_kernel<T>), dim3(M), dim3(norm_threads(d)), 0, st, nf);
-  }
-  {
+    // final RMSNorm (gain gf) on load -> logits + per-workgroup row statistics
     GemmArgs<T> a{};
-    a.W = reinterpret_cast<const T*>(c->w_lm); a.X = xn; a.ldx = c->p_lm.ldx();
+    a.W = reinterpret_cast<const T*>(c->w_lm); a.H = c->h; a.ldx = c->ldh; a.gain = c->gf;
     a.out = c->logits; a.ldo = c->p_lm.ldo();
     a.lm.stats = c->stats; a.lm.window = window; a.lm.commits = c->commits; a.lm.k = k;
     a.lm.inv_T = temperature > 0.f ? 1.0f / temperature : 0.f;
@@ -433,7 +355,8 @@ int init_weights(dbl_ctx* c) {
     hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, p, 1.0f, n);
   };
   const size_t L = std::max(1, g.n_layers);
-  ones(c->g1, L * g.d_model); ones(c->g2, L * g.d_model);
+  // g1 / g2 / gf rows are ldh long and stay zero beyond d_model
+  for (size_t l = 0; l < L; ++l) { ones(c->g1 + l * c->ldh, g.d_model); ones(c->g2 + l * c->ldh, g.d_model); }
   ones(c->gq, L * g.head_dim); ones(c->gk, L * g.head_dim); ones(c->gf, g.d_model);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(c, DBL_EHIP, std::string("weight init: ") + hipGetErrorString(e));
@@ -456,8 +379,8 @@ int locate(dbl_ctx* c, int id, int layer, TensorLoc& t) {
     case DBL_T_EMB: t.base = c->emb; t.rows = g.vocab; t.cols = g.d_model; break;
     case DBL_T_LM: t.base = c->w_lm; t.plan = &c->p_lm; t.rows = g.vocab; t.cols = g.d_model; t.tiled = true; break;
     case DBL_T_GF: t.base = c->gf; t.rows = 1; t.cols = g.d_model; t.is_gain = true; break;
-    case DBL_T_G1: t.base = c->g1 + (size_t)layer * g.d_model; t.rows = 1; t.cols = g.d_model; t.is_gain = true; break;
-    case DBL_T_G2: t.base = c->g2 + (size_t)layer * g.d_model; t.rows = 1; t.cols = g.d_model; t.is_gain = true; break;
+    case DBL_T_G1: t.base = c->g1 + (size_t)layer * c->ldh; t.rows = 1; t.cols = g.d_model; t.is_gain = true; break;
+    case DBL_T_G2: t.base = c->g2 + (size_t)layer * c->ldh; t.rows = 1; t.cols = g.d_model; t.is_gain = true; break;
     case DBL_T_GQ: t.base = c->gq + (size_t)layer * g.head_dim; t.rows = 1; t.cols = g.head_dim; t.is_gain = true; break;
     case DBL_T_GK: t.base = c->gk + (size_t)layer * g.head_dim; t.rows = 1; t.cols = g.head_dim; t.is_gain = true; break;
     case DBL_T_WQ: t.base = c->w_qkv; t.plan = &c->p_qkv; t.rows = c->hq; t.cols = g.d_model; t.row0 = 0; t.tiled = true; break;
@@ -510,25 +433,12 @@ int copy_tensor(dbl_ctx* c, const TensorLoc& t, int layer, void* host, bool to_d
 void free_all(dbl_ctx* c) {
   void* ptrs[] = {c->w_qkv, c->w_o, c->w_gu, c->w_d, c->w_lm, c->emb, c->g1, c->g2, c->gq, c->gk, c->gf, c->cosT,
                   c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->status, c->commits, c->h, c->qkv_part,
-                  c->d_part, c->o_part, c->logits, c->xn, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
-                  c->n_acc_i, c->emit_i, c->win_i, c->bar, c->trace};
+                  c->ssq, c->logits, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
+                  c->n_acc_i, c->emit_i, c->win_i};
   for (void* p : ptrs) if (p) (void)hipFree(p);
 }
 
-// Called at synchronisation points.  A grid barrier of the persistent layer kernel that
-// timed out leaves a sticky error word; the step that hit it produced no valid result.
-// The persistent path is switched off for the rest of the context's life.
-int check_barrier(dbl_ctx* c) {
-  if (c->persistent_launches == 0 || !c->use_persistent) return DBL_OK;
-  unsigned err = 0;
-  HIPCHK(c, hipMemcpy(&err, &c->bar->error, sizeof(err), hipMemcpyDeviceToHost));
-  if (!err) return DBL_OK;
-  c->use_persistent = false;
-  return fail(c, DBL_EHIP, "persistent layer kernel: a grid barrier timed out; the last verify results are invalid");
-}
-
 int check_status(dbl_ctx* c) {
-  if (const int rc = check_barrier(c)) return rc;
   int32_t s = 0;
   HIPCHK(c, hipMemcpy(&s, c->status, sizeof(s), hipMemcpyDeviceToHost));
   if (s) return fail(c, DBL_ESTATE, (s & 1) ? "a commit would exceed max_ctx and was clamped" : "a commit would exceed max_hist and was clamped");
@@ -552,8 +462,8 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
   c->dry = (cfg->flags & DBL_FLAG_VALIDATE_ONLY) != 0;
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
   c->seed = weight_seed;
+  if (const char* e = std::getenv("DBL_TILE_ROT")) c->tile_rot = std::max(0, std::atoi(e));
   c->kv_upper.assign(cfg->max_batch, 0); c->hist_upper.assign(cfg->max_batch, 0);
-  if (const char* e = std::getenv("DBL_PERSISTENT")) c->use_persistent = std::atoi(e) != 0;
   int rc = DBL_OK;
   if (!c->dry) {
     hipError_t e = hipGetDevice(&c->device);
@@ -581,9 +491,9 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(w_d, L * c->p_d.elems() * esz, false);
     ALLOC(w_lm, c->p_lm.elems() * esz, false);
     ALLOC(emb, (size_t)g.vocab * g.d_model * esz, false);
-    ALLOC(g1, L * g.d_model * 4, false); ALLOC(g2, L * g.d_model * 4, false);
+    ALLOC(g1, L * c->ldh * 4, true); ALLOC(g2, L * c->ldh * 4, true);
     ALLOC(gq, L * g.head_dim * 4, false); ALLOC(gk, L * g.head_dim * 4, false);
-    ALLOC(gf, (size_t)g.d_model * 4, false);
+    ALLOC(gf, (size_t)c->ldh * 4, true);
     ALLOC(cosT, (size_t)g.max_ctx * (g.head_dim / 2) * 4, false);
     ALLOC(sinT, (size_t)g.max_ctx * (g.head_dim / 2) * 4, false);
     ALLOC(kc, L * c->kv_layer_elems * esz, true);
@@ -591,12 +501,10 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(kv_len, (size_t)g.max_batch * 4, true); ALLOC(hist_len, (size_t)g.max_batch * 4, true);
     ALLOC(hist, (size_t)g.max_batch * g.max_hist * 4, true);
     ALLOC(status, 4, true); ALLOC(commits, 8, true);
-    ALLOC(h, (size_t)Mmax * c->p_o.ldo() * 4, true);
+    ALLOC(h, (size_t)Mmax * c->ldh * 4, true);
+    ALLOC(ssq, (size_t)Mmax * SSQ_PARTS * 4, true);
     ALLOC(qkv_part, (size_t)c->p_qkv.SS * Mmax * c->p_qkv.ldo() * 4, true);
-    ALLOC(d_part, (size_t)c->p_d.SS * Mmax * c->p_d.ldo() * 4, true);
-    ALLOC(o_part, (size_t)c->p_o.SS * Mmax * c->p_o.ldo() * 4, true);
     ALLOC(logits, (size_t)Mmax * c->p_lm.ldo() * 4, true);
-    ALLOC(xn, (size_t)Mmax * std::max({c->p_qkv.ldx(), c->p_gu.ldx(), c->p_lm.ldx()}) * esz, true);
     ALLOC(qbuf, (size_t)g.max_batch * g.n_kv_heads * c->qrows_pad * g.head_dim * esz, true);
     ALLOC(attn, (size_t)Mmax * c->p_o.ldx() * esz, true);
     ALLOC(act, (size_t)Mmax * c->p_d.ldx() * esz, true);
@@ -604,9 +512,6 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(stats, (size_t)c->p_lm.grid * Mmax * sizeof(LmStat), true);
     ALLOC(n_acc_i, (size_t)g.max_batch * 4, true); ALLOC(emit_i, (size_t)Mmax * 4, true);
     ALLOC(win_i, (size_t)Mmax * 4, true);
-    ALLOC(bar, sizeof(GridBar), true);
-    if (const char* e = std::getenv("DBL_PERSISTENT_TRACE"))
-      if (std::atoi(e) != 0) ALLOC(trace, sizeof(long long) * (1 + LAYER_LOOP_BARRIERS * (size_t)std::max(1, g.n_layers)), true);
   } while (0);
 #undef ALLOC
   if (rc == DBL_OK) {
@@ -835,29 +740,14 @@ template <typename T>
 static void bench_launch(dbl_ctx* c, int which, int layer, int M) {
   GemmArgs<T> a{};
   const dbl_model_cfg& g = c->cfg;
+  const LayerSteps<T> s = layer_steps<T>(c, layer, 1, M);
   switch (which) {
-    case 0:
-      a.W = reinterpret_cast<const T*>(c->w_qkv) + (size_t)layer * c->p_qkv.elems(); a.X = reinterpret_cast<const T*>(c->xn);
-      a.ldx = c->p_qkv.ldx(); a.out = c->qkv_part; a.ldo = c->p_qkv.ldo();
-      launch_gemm<T>(c, c->p_qkv, EPI_PARTIAL, a, M); break;
-    case 1:
-      a.W = reinterpret_cast<const T*>(c->w_o) + (size_t)layer * c->p_o.elems(); a.X = reinterpret_cast<const T*>(c->attn);
-      a.ldx = c->p_o.ldx();
-      if (c->p_o.SS == 1) { a.out = c->h; a.ldo = c->p_o.ldo(); launch_gemm<T>(c, c->p_o, EPI_RESIDUAL, a, M); }
-      else { a.out = c->o_part; a.ldo = c->p_o.ldo(); launch_gemm<T>(c, c->p_o, EPI_PARTIAL, a, M); }
-      break;
-    case 2:
-      a.W = reinterpret_cast<const T*>(c->w_gu) + (size_t)layer * c->p_gu.elems(); a.X = reinterpret_cast<const T*>(c->xn);
-      a.ldx = c->p_gu.ldx(); a.act = reinterpret_cast<T*>(c->act); a.ldact = c->p_d.ldx();
-      launch_gemm<T>(c, c->p_gu, EPI_SWIGLU, a, M); break;
-    case 3:
-      a.W = reinterpret_cast<const T*>(c->w_d) + (size_t)layer * c->p_d.elems(); a.X = reinterpret_cast<const T*>(c->act);
-      a.ldx = c->p_d.ldx();
-      if (c->p_d.SS == 1) { a.out = c->h; a.ldo = c->p_o.ldo(); launch_gemm<T>(c, c->p_d, EPI_RESIDUAL, a, M); }
-      else { a.out = c->d_part; a.ldo = c->p_d.ldo(); launch_gemm<T>(c, c->p_d, EPI_PARTIAL, a, M); }
-      break;
+    case 0: launch_gemm<T>(c, c->p_qkv, EPI_PARTIAL, s.qkv, M); break;
+    case 1: launch_gemm<T>(c, c->p_o, EPI_RESIDUAL, s.o, M); break;
+    case 2: launch_gemm<T>(c, c->p_gu, EPI_SWIGLU, s.gu, M); break;
+    case 3: launch_gemm<T>(c, c->p_d, EPI_RESIDUAL, s.dn, M); break;
     default:
-      a.W = reinterpret_cast<const T*>(c->w_lm); a.X = reinterpret_cast<const T*>(c->xn); a.ldx = c->p_lm.ldx();
+      a.W = reinterpret_cast<const T*>(c->w_lm); a.H = c->h; a.ldx = c->ldh; a.gain = c->gf;
       a.out = c->logits; a.ldo = c->p_lm.ldo();
       a.lm.stats = c->stats; a.lm.window = c->win_i; a.lm.commits = c->commits; a.lm.k = M; a.lm.inv_T = 0.f;
       launch_gemm<T>(c, c->p_lm, EPI_LMHEAD, a, M); break;
@@ -904,7 +794,7 @@ int dbl_debug_buffer(dbl_ctx* c, int which, void* host, size_t bytes, int32_t* l
   if (!host || !ld_out || which < 0 || which > 2) return fail(c, DBL_EINVAL, "bad debug buffer request");
   const size_t rows = (size_t)c->cfg.max_batch * c->cfg.max_window;
   const void* src = which == 0 ? (const void*)c->h : which == 1 ? (const void*)c->attn : (const void*)c->act;
-  const int ld = which == 0 ? c->p_o.ldo() : which == 1 ? c->p_o.ldx() : c->p_d.ldx();
+  const int ld = which == 0 ? c->ldh : which == 1 ? c->p_o.ldx() : c->p_d.ldx();
   const size_t need = rows * ld * (which == 0 ? 4 : c->esz);
   if (bytes < need) return fail(c, DBL_EINVAL, "debug buffer too small");
   *ld_out = ld;
@@ -912,15 +802,6 @@ int dbl_debug_buffer(dbl_ctx* c, int which, void* host, size_t bytes, int32_t* l
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(host, src, need, hipMemcpyDeviceToHost));
   return DBL_OK;
-}
-
-int dbl_persistent_launches(dbl_ctx* c, int64_t* launches_out) {
-  if (!c) return DBL_EINVAL;
-  if (!launches_out) return fail(c, DBL_EINVAL, "null output pointer");
-  *launches_out = c->persistent_launches;
-  if (c->dry) return DBL_OK;
-  HIPCHK(c, hipStreamSynchronize(c->stream));
-  return check_barrier(c);
 }
 
 int dbl_kv_len(dbl_ctx* c, int32_t* host_out) { return read_counters(c, host_out, true); }

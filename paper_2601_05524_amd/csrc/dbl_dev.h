@@ -98,85 +98,25 @@ __device__ __forceinline__ Frag<float> frag_swap_halves(const Frag<float>& f) {
   return r;
 }
 
-// ---------------------------------------------------------------------------
-// Memory access with or without cross-workgroup coherence.  COH = false: ordinary
-// cached accesses (data produced by an earlier kernel).  COH = true: the data was
-// written by another workgroup of the SAME launch (persistent layer kernel); each
-// XCD has its own L2, so such data is moved with agent-scope relaxed atomic loads
-// and stores (they go to the memory side instead of a possibly stale L2 / L1 line).
-// Atomic accesses exist for 32- and 64-bit words; 16-byte values take two.
-// ---------------------------------------------------------------------------
-template <bool COH> __device__ __forceinline__ uint64_t ld_u64(const void* p) {
-  if (COH) return __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return *reinterpret_cast<const uint64_t*>(p);
-}
-template <bool COH> __device__ __forceinline__ uint32_t ld_u32(const void* p) {
-  if (COH) return __hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return *reinterpret_cast<const uint32_t*>(p);
-}
-template <bool COH> __device__ __forceinline__ void st_u64(void* p, uint64_t v) {
-  if (COH) __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  else *reinterpret_cast<uint64_t*>(p) = v;
-}
-template <bool COH> __device__ __forceinline__ void st_u32(void* p, uint32_t v) {
-  if (COH) __hip_atomic_store(reinterpret_cast<uint32_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  else *reinterpret_cast<uint32_t*>(p) = v;
-}
-// 16-bit store.  There is no 16-bit atomic, so the coherent form is the plain ISA
-// store with the write-through (sc0 sc1) bits; the wait keeps the compiler's own
-// counting of outstanding memory operations valid.
-template <bool COH> __device__ __forceinline__ void st_u16(void* p, uint16_t v) {
-  if (COH) {
-    asm volatile("global_store_short %0, %1, off sc0 sc1\n\ts_waitcnt vmcnt(0)" : : "v"(p), "v"((uint32_t)v) : "memory");
-  } else {
-    *reinterpret_cast<uint16_t*>(p) = v;
-  }
-}
-template <bool COH> __device__ __forceinline__ float ld_f32(const float* p) { return __uint_as_float(ld_u32<COH>(p)); }
-template <bool COH> __device__ __forceinline__ void st_f32(float* p, float v) { st_u32<COH>(p, __float_as_uint(v)); }
-template <bool COH> __device__ __forceinline__ f32x2 ld_f2(const float* p) {
-  if (COH) return __builtin_bit_cast(f32x2, ld_u64<true>(p));
-  return *reinterpret_cast<const f32x2*>(p);
-}
-template <bool COH> __device__ __forceinline__ f32x4 ld_f4(const float* p) {
-  if (COH) {
-    const f32x2 a = ld_f2<true>(p), b = ld_f2<true>(p + 2);
-    return f32x4{a.x, a.y, b.x, b.y};
-  }
-  return *reinterpret_cast<const f32x4*>(p);
-}
-template <bool COH> __device__ __forceinline__ void st_f4(float* p, const f32x4& v) {
-  if (COH) {
-    st_u64<true>(p, __builtin_bit_cast(uint64_t, f32x2{v.x, v.y}));
-    st_u64<true>(p + 2, __builtin_bit_cast(uint64_t, f32x2{v.z, v.w}));
-  } else {
-    *reinterpret_cast<f32x4*>(p) = v;
-  }
-}
 // four values rounded to the element type, stored contiguously
-template <bool COH> __device__ __forceinline__ void st_round4(float* p, const f32x4& v) { st_f4<COH>(p, v); }
-template <bool COH> __device__ __forceinline__ void st_round4(bf16_t* p, const f32x4& v) {
-  st_u64<COH>(p, (uint64_t)pack_bf16(v.x, v.y) | ((uint64_t)pack_bf16(v.z, v.w) << 32));
+__device__ __forceinline__ void st_round4(float* p, const f32x4& v) { *reinterpret_cast<f32x4*>(p) = v; }
+__device__ __forceinline__ void st_round4(bf16_t* p, const f32x4& v) {
+  *reinterpret_cast<u32x2*>(p) = u32x2{pack_bf16(v.x, v.y), pack_bf16(v.z, v.w)};
 }
 // one value rounded to the element type
-template <bool COH> __device__ __forceinline__ void st_round1(float* p, float v) { st_f32<COH>(p, v); }
-template <bool COH> __device__ __forceinline__ void st_round1(bf16_t* p, float v) { st_u16<COH>(p, f2bf(v)); }
+__device__ __forceinline__ void st_round1(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_round1(bf16_t* p, float v) { *p = f2bf(v); }
 
 // 8 consecutive elements of a row-major array (16-byte aligned for bf16, 32 for fp32)
-template <bool COH> __device__ __forceinline__ Frag<bf16_t> frag_load_row(const bf16_t* p) {
+__device__ __forceinline__ Frag<bf16_t> frag_load_row(const bf16_t* p) {
   Frag<bf16_t> f;
-  if (COH) {
-    const uint64_t a = ld_u64<true>(p), b = ld_u64<true>(p + 4);
-    f.v = u32x4{(uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32)};
-  } else {
-    f.v = *reinterpret_cast<const u32x4*>(p);
-  }
+  f.v = *reinterpret_cast<const u32x4*>(p);
   return f;
 }
-template <bool COH> __device__ __forceinline__ Frag<float> frag_load_row(const float* p) {
+__device__ __forceinline__ Frag<float> frag_load_row(const float* p) {
   Frag<float> f;
-  f.lo = ld_f4<COH>(p);
-  f.hi = ld_f4<COH>(p + 4);
+  f.lo = *reinterpret_cast<const f32x4*>(p);
+  f.hi = *reinterpret_cast<const f32x4*>(p + 4);
   return f;
 }
 

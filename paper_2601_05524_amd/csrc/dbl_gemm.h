@@ -6,27 +6,36 @@
 //   * weights are the MFMA A operand (16 output features x 32 inputs per block) in
 //     the tiled layout of dbl_dev.h, so every wave-level load is 1 KiB contiguous;
 //   * the activations (the B operand, 32 inputs x 16 rows) of a wave's K slice live
-//     in registers for the whole kernel: a wave owns KS k-blocks of every output
-//     tile its workgroup visits, so activations are fetched once per wave;
+//     in registers: a wave owns KS k-blocks of every output tile its workgroup
+//     visits, so activations are fetched once per wave (once per K chunk in the
+//     chunked form below);
 //   * the NW waves of a workgroup own NW consecutive K slices of the same output
 //     tile; their partial tiles are summed through LDS in a fixed order
 //     (deterministic, no atomics) and wave 0 applies the epilogue;
 //   * loads run RING blocks ahead of the MFMAs and the ring runs across output
 //     tiles, so the memory pipe never drains inside a kernel;
-//   * a workgroup walks output tiles wg/SS, +nwg/SS, ...; if K is too long
-//     for 8 waves x KS blocks, SS workgroup "super slices" split K and each writes
-//     its own partial result (summed by the consumer kernel).
-// The body is a device function so that the same code runs as a stand-alone kernel
-// and as a phase of the persistent layer kernel (dbl_layer.h); there (COH = true)
-// activations and results cross workgroups inside one launch and are accessed with
-// agent-coherent loads / stores, and the first ring of weights can be fetched
-// before the phase starts.
+//   * a workgroup walks output tiles wg/SS, +nwg/SS, ...;
+//   * K longer than NW*KS blocks is covered either by SS workgroup "super slices",
+//     each writing its own partial result that the consumer sums (q/k/v projection),
+//     or by NCH sequential K chunks inside the workgroup with the accumulator kept
+//     in registers (CHUNK form: output and down projection, which add straight into
+//     the residual stream).
+//
+// RMSNorm is not a kernel of its own.  The projections that consume a normalised
+// input (q/k/v, gate/up, LM head) read the fp32 residual stream h, the gain and the
+// row's sum of squares, and build bf16(h * rsqrt(mean(h^2) + eps) * gain) while
+// loading their activation registers.  The sum of squares is produced by whichever
+// kernel wrote h last (embedding, output projection, down projection): each of its
+// workgroups leaves one partial per row in ssq[row][workgroup]; SSQ_PARTS slots per
+// row, unused ones zero, summed by the consumer in a fixed order.
 #pragma once
 #include "dbl_dev.h"
 
 namespace dbl {
 
 enum GemmEpi { EPI_PARTIAL = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3 };
+
+constexpr int SSQ_PARTS = 256;    // sum-of-squares partials per row; a producer launches at most this many workgroups
 
 // Per-workgroup, per-row statistics left by the LM-head epilogue.
 struct LmStat {
@@ -48,18 +57,26 @@ struct LmArgs {
 
 template <typename T>
 struct GemmArgs {
-  const T* W;       // tiled weights: NT * NACC tile rows of KBp blocks
-  const T* X;       // activations [Mtot][ldx], ldx >= KBp*32, zero beyond K
+  const T* W;          // tiled weights: NT * NACC tile rows of KBp blocks
+  // activations, one of:
+  const T* X;          //   EPI_RESIDUAL: [Mtot][ldx] elements of type T, ldx >= KBp*32, zero beyond K
+  const float* H;      //   other epilogues: residual stream [Mtot][ldx] fp32, zero beyond K, normalised on load
   int ldx;
-  int m0, mrows;    // rows m0 .. m0+mrows-1 (mrows <= 16) are computed by this launch
+  const float* gain;   // [>= KBp*32] RMSNorm gain, zero beyond K
+  const float* ssq_in; // [Mtot][SSQ_PARTS] partial sums of squares of H's rows
+  float d, eps;        // mean = sum / d
+  int m0, mrows;       // rows m0 .. m0+mrows-1 (mrows <= 16) are computed by this launch
   int Mtot;
-  int NT;           // output tiles (tile pairs for EPI_SWIGLU)
-  int N;            // valid output features (per half for EPI_SWIGLU)
-  int KBp;          // k-blocks per tile row
-  int SS;           // super slices; number of workgroups % SS == 0
-  float* out;       // PARTIAL: [SS][Mtot][ldo] ; RESIDUAL: h[Mtot][ldo] (+=) ; LMHEAD: logits[Mtot][ldo]
+  int NT;              // output tiles (tile pairs for EPI_SWIGLU)
+  int N;               // valid output features (per half for EPI_SWIGLU)
+  int KBp;             // k-blocks per tile row = SS * NCH * NW * KS
+  int SS;              // super slices; number of workgroups % SS == 0
+  int NCH;             // K chunks walked by one workgroup (1 unless the CHUNK form runs)
+  int rot;             // per-round shift of the workgroup -> tile mapping
+  float* out;          // PARTIAL: [SS][Mtot][ldo] ; RESIDUAL: h[Mtot][ldo] (+=) ; LMHEAD: logits[Mtot][ldo]
   int ldo;
-  T* act;           // SWIGLU: [Mtot][ldact]
+  float* ssq_out;      // RESIDUAL: [Mtot][SSQ_PARTS] partial sums of squares of the updated rows
+  T* act;              // SWIGLU: [Mtot][ldact]
   int ldact;
   LmArgs lm;
 };
@@ -70,60 +87,126 @@ template <> struct GemmCfg<float> { static constexpr int RING = 8; };
 
 typedef f32x4 GemmRed[8][2][WAVE];   // one LDS reduction buffer: [wave][accumulator][lane]
 
-template <typename T, int NACC>
-__device__ __forceinline__ size_t gemm_blk(const GemmArgs<T>& a, int tile, int sub, int kb) {
-  return ((size_t)tile * NACC + sub) * a.KBp + kb;
-}
-
-// Issue the first RING weight loads of workgroup `wg` for this projection.  Weights do
-// not depend on any activation, so this may run before the producer of X has finished.
-template <typename T, int EPI, int KS, int RING = GemmCfg<T>::RING>
-__device__ __forceinline__ void gemm_prefetch(const GemmArgs<T>& a, int wg, int nwg, int nw, Frag<T> (&ring)[RING]) {
-  constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int ss = wg % a.SS, t = wg / a.SS;
-  if (wave >= nw || t >= a.NT) return;
-  const int kb0 = (ss * nw + wave) * KS;
+// 1 / rms of the row a lane works on: row (lane & 7) [PACK] or (lane & 15), clamped to
+// the valid rows.  Eight lanes add the 256 partials of one row (32 each, then a
+// butterfly); the result is fetched from that group's first lane.
+template <bool PACK>
+__device__ __forceinline__ float row_scale(const float* ssq, int m0, int mrows, float d, float eps, int lane) {
+  const int c = lane & 15, want = PACK ? (c & 7) : c;
+  float out = 0.f;
 #pragma unroll
-  for (int j = 0; j < RING; ++j) ring[j] = frag_load_w(a.W, gemm_blk<T, NACC>(a, t, 0, kb0 + j), lane);
+  for (int half = 0; half < (PACK ? 1 : 2); ++half) {
+    const int rr = min(half * 8 + (lane >> 3), mrows - 1);
+    const f32x4* p = reinterpret_cast<const f32x4*>(ssq + (size_t)(m0 + rr) * SSQ_PARTS) + (lane & 7) * 8;
+    f32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[u];
+    float s = 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += (v[u].x + v[u].y) + (v[u].z + v[u].w);
+    s += __shfl_xor(s, 1); s += __shfl_xor(s, 2); s += __shfl_xor(s, 4);
+    const float r = rsqrtf(s / d + eps);
+    const float got = __shfl(r, (want & 7) * 8);
+    if (PACK || (want >> 3) == half) out = got;
+  }
+  return out;
 }
 
-// BPACK (at most 8 rows): the activation operand has 16 columns but only 8 rows to
-// put in them, so one register set holds TWO k-blocks: lanes c < 8 carry block 2i (row
-// c), lanes c >= 8 carry block 2i+1 (row c-8).  Block 2i is used as it is (columns
-// 8..15 of the product are never read); for block 2i+1 the halves are swapped with a
-// DPP rotate by 8 inside each 16-lane row.  This halves the registers the activations
-// take (64 instead of 128 for a 32-block slice).
-template <typename T, int EPI, int KS, bool COH, bool BPACK = false, int RING = GemmCfg<T>::RING>
-__device__ __forceinline__ void gemm_body(const GemmArgs<T>& a, int wg, int nwg, int nw, GemmRed* red,
-                                          Frag<T> (&ring)[RING], bool prefetched) {
-  constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
-  constexpr int NB = BPACK ? KS / 2 : KS;      // activation register sets
-  static_assert(!BPACK || KS % 2 == 0, "packed activations pair k-blocks");
-  static_assert(KS % RING == 0, "slice must be a whole number of rings");
-  static_assert(!(COH && EPI == EPI_LMHEAD), "the LM head runs as its own kernel");
+// Eight activations of one row as an MFMA fragment: T(h * r * gain), the RMSNorm output
+// rounded to the element type (rounding point r1 of the numerics contract).
+__device__ __forceinline__ Frag<bf16_t> norm_frag(const float* hp, const float* gp, float r, bf16_t) {
+  const f32x4 h0 = *reinterpret_cast<const f32x4*>(hp), h1 = *reinterpret_cast<const f32x4*>(hp + 4);
+  const f32x4 g0 = *reinterpret_cast<const f32x4*>(gp), g1 = *reinterpret_cast<const f32x4*>(gp + 4);
+  Frag<bf16_t> f;
+  f.v = u32x4{pack_bf16(h0.x * r * g0.x, h0.y * r * g0.y), pack_bf16(h0.z * r * g0.z, h0.w * r * g0.w),
+              pack_bf16(h1.x * r * g1.x, h1.y * r * g1.y), pack_bf16(h1.z * r * g1.z, h1.w * r * g1.w)};
+  return f;
+}
+__device__ __forceinline__ Frag<float> norm_frag(const float* hp, const float* gp, float r, float) {
+  const f32x4 h0 = *reinterpret_cast<const f32x4*>(hp), h1 = *reinterpret_cast<const f32x4*>(hp + 4);
+  const f32x4 g0 = *reinterpret_cast<const f32x4*>(gp), g1 = *reinterpret_cast<const f32x4*>(gp + 4);
+  Frag<float> f;
+  f.lo = f32x4{h0.x * r * g0.x, h0.y * r * g0.y, h0.z * r * g0.z, h0.w * r * g0.w};
+  f.hi = f32x4{h1.x * r * g1.x, h1.y * r * g1.y, h1.z * r * g1.z, h1.w * r * g1.w};
+  return f;
+}
 
+// Activation registers of the KS k-blocks starting at block kblk.
+// PACK (at most 8 rows): the B operand has 16 columns but only 8 rows to put in them,
+// so one register set holds TWO k-blocks: lanes c < 8 carry block 2i (row c), lanes
+// c >= 8 carry block 2i+1 (row c-8).  Block 2i is used as it is (columns 8..15 of the
+// product are never read); for block 2i+1 the halves are swapped with a DPP rotate by
+// 8 inside each 16-lane row.  This halves the registers the activations take.
+// Output column j of a tile depends only on activation row j, so lanes of unused rows
+// re-read the last valid row: all loads are unconditional and stay in flight together.
+template <typename T, bool NORM, bool PACK, int KS>
+__device__ __forceinline__ void load_acts(const GemmArgs<T>& a, int kblk, float r, int lane,
+                                          Frag<T> (&b)[PACK ? KS / 2 : KS]) {
+  const int c = lane & 15, g = lane >> 4;
+  const int row = a.m0 + min(PACK ? (c & 7) : c, a.mrows - 1);
+  const size_t k0 = (size_t)(kblk + (PACK ? (c >> 3) : 0)) * TILE_K + g * 8;
+  constexpr int STEP = (PACK ? 2 : 1) * TILE_K;
+  if (NORM) {
+    const float* hp = a.H + (size_t)row * a.ldx + k0;
+    const float* gp = a.gain + k0;
+#pragma unroll
+    for (int j = 0; j < (PACK ? KS / 2 : KS); ++j) b[j] = norm_frag(hp + j * STEP, gp + j * STEP, r, T());
+  } else {
+    const T* xp = a.X + (size_t)row * a.ldx + k0;
+#pragma unroll
+    for (int j = 0; j < (PACK ? KS / 2 : KS); ++j) b[j] = frag_load_row(xp + j * STEP);
+  }
+}
+
+// CHUNK: the workgroup walks NCH K chunks per output tile (EPI_RESIDUAL only); the
+// activations of the next chunk are fetched while the current one is multiplied.
+template <typename T, int EPI, int KS, bool PACK, bool CHUNK>
+__global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
+  constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
+  constexpr int RING = GemmCfg<T>::RING;
+  constexpr int NB = PACK ? KS / 2 : KS;       // activation register sets
+  constexpr bool NORM = EPI != EPI_RESIDUAL;
+  static_assert(!PACK || KS % 2 == 0, "packed activations pair k-blocks");
+  static_assert(KS % RING == 0, "slice must be a whole number of rings");
+  static_assert(!CHUNK || EPI == EPI_RESIDUAL, "only the residual projections walk K chunks");
+
+  __shared__ GemmRed red[2];
+  const int wg = blockIdx.x, nwg = gridDim.x, nw = blockDim.x >> 6;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const bool active = wave < nw;             // waves beyond nw only keep the barriers company
   const int c = lane & 15, g = lane >> 4;
   const int ss = wg % a.SS;
   const int tstep = nwg / a.SS;
-  int t = wg / a.SS;
-  const int kb0 = (ss * nw + wave) * KS;
+  // Output tile of round `it`: round it covers tiles it*tstep .. it*tstep + tstep-1, and the
+  // workgroup -> tile mapping inside a round shifts by `rot` every round.  Workgroups are
+  // dealt round-robin to the 8 XCDs and tile rows are a power-of-two number of bytes apart,
+  // so without the shift every XCD would stream from one fixed set of memory channels for
+  // the whole kernel.
+  const int tbase = wg / a.SS;
+  auto tile_of = [&](int it) { return it * tstep + (tbase + it * a.rot) % tstep; };
+  int t = tile_of(0);
+  const int nch = CHUNK ? a.NCH : 1;
+  const int seg = nw * KS;                       // k-blocks per chunk
+  const int kb0 = ss * nch * seg + wave * KS;    // this wave's first k-block of chunk 0
 
-  if (!prefetched) gemm_prefetch<T, EPI, KS, RING>(a, wg, nwg, nw, ring);
+  // Per-lane pointer to block 0 of this wave's slice of tile row 0, chunk 0; a tile row is
+  // KBp blocks of BLOCK_ELEMS elements.  All weight addresses below are this plus a
+  // tile-row offset plus a chunk offset plus a compile-time block offset: no branches
+  // around the loads, so the compiler can count outstanding loads exactly.
+  const T* wlane = a.W + (size_t)kb0 * BLOCK_ELEMS;
+  const size_t row_elems = (size_t)a.KBp * BLOCK_ELEMS;
+  const size_t seg_elems = (size_t)seg * BLOCK_ELEMS;
 
-  // activations of this wave's K slice -> registers.  Output column j of a tile depends
-  // only on activation row j, so lanes of the unused rows (c >= mrows) simply re-read the
-  // last valid row: all loads are unconditional and stay in flight together.
-  Frag<T> breg[NB];
+  // weights first: they depend on nothing
+  Frag<T> ring[RING];
   {
-    const int wv = active ? wave : 0;
-    const int row = BPACK ? (c & 7) : c, odd = BPACK ? (c >> 3) : 0;
-    const T* xrow = a.X + (size_t)(a.m0 + min(row, a.mrows - 1)) * a.ldx + (size_t)((ss * nw + wv) * KS + odd) * TILE_K + g * 8;
+    const int tf = t < a.NT ? t : 0;
 #pragma unroll
-    for (int j = 0; j < NB; ++j) breg[j] = frag_load_row<COH>(xrow + (size_t)j * (BPACK ? 2 : 1) * TILE_K);
+    for (int j = 0; j < RING; ++j) ring[j] = frag_load_w(wlane + (size_t)tf * NACC * row_elems, j, lane);
   }
+  float r = 1.f;
+  if (NORM) r = row_scale<PACK>(a.ssq_in, a.m0, a.mrows, a.d, a.eps, lane);
+  Frag<T> breg[NB];
+  load_acts<T, NORM, PACK, KS>(a, kb0, r, lane, breg);
 
   // LM-head running statistics (wave 0 only)
   float best = -INFINITY, smax = -INFINITY, ssum = 0.f, zdraft = -INFINITY, p1 = -INFINITY, p2 = -INFINITY;
@@ -135,27 +218,28 @@ __device__ __forceinline__ void gemm_body(const GemmArgs<T>& a, int wg, int nwg,
     if ((int)pj + 1 < a.lm.k) draft = a.lm.window[m + 1];
     stepv = a.lm.step + *a.lm.commits;
   }
+  float sq = 0.f;   // RESIDUAL: this lane's share of the rows' sums of squares
 
-  // Per-lane pointer to block 0 of this wave's slice of tile row 0; a tile row is KBp
-  // blocks of BLOCK_ELEMS elements.  All weight addresses below are this plus a
-  // tile-row offset plus a compile-time block offset: no branches around the loads, so
-  // the compiler can count outstanding loads exactly (s_waitcnt vmcnt(N) with N > 0).
-  const T* wlane = a.W + (size_t)kb0 * BLOCK_ELEMS;
-  const size_t row_elems = (size_t)a.KBp * BLOCK_ELEMS;
-  for (int it = 0; t < a.NT; t += tstep, ++it) {
+  for (int it = 0; t < a.NT; ++it, t = tile_of(it)) {
     // after the last tile the refill loads go on, harmlessly, into tile 0 (an L2 hit)
-    const int tn = (t + tstep < a.NT) ? t + tstep : 0;
+    const int tnn = tile_of(it + 1);
+    const int tn = tnn < a.NT ? tnn : 0;
     f32x4 acc[NACC];
 #pragma unroll
     for (int s = 0; s < NACC; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (active) {
-      const T* wcur = wlane + (size_t)t * NACC * row_elems;
-      const T* wnext = wlane + (size_t)tn * NACC * row_elems;
+    const T* wtile = wlane + (size_t)t * NACC * row_elems;
+    const T* wnext_tile = wlane + (size_t)tn * NACC * row_elems;
+    for (int ch = 0; ch < nch; ++ch) {
+      const bool last = ch + 1 == nch;
+      const T* wcur = wtile + (size_t)ch * seg_elems;
+      const T* wnext = last ? wnext_tile : wcur + seg_elems;
+      Frag<T> bnext[NB];
+      if constexpr (CHUNK) load_acts<T, NORM, PACK, KS>(a, kb0 + (last ? 0 : ch + 1) * seg, r, lane, bnext);
 #pragma unroll
       for (int s = 0; s < NACC; ++s) {
 #pragma unroll
         for (int j = 0; j < KS; ++j) {
-          if (BPACK) acc[s] = mma(ring[j % RING], (j & 1) ? frag_swap_halves(breg[j / 2]) : breg[j / 2], acc[s]);
+          if (PACK) acc[s] = mma(ring[j % RING], (j & 1) ? frag_swap_halves(breg[j / 2]) : breg[j / 2], acc[s]);
           else acc[s] = mma(ring[j % RING], breg[j], acc[s]);
           const int jn = j + RING;
           if (jn < KS) ring[j % RING] = frag_load_w(wcur + s * row_elems, jn, lane);
@@ -163,9 +247,13 @@ __device__ __forceinline__ void gemm_body(const GemmArgs<T>& a, int wg, int nwg,
           else ring[j % RING] = frag_load_w(wnext, jn - KS, lane);
         }
       }
+      if constexpr (CHUNK) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) breg[j] = bnext[j];
+      }
     }
     const int buf = it & 1;
-    if (active && wave != 0) {
+    if (wave != 0) {
 #pragma unroll
       for (int s = 0; s < NACC; ++s) red[buf][wave][s][lane] = acc[s];
     }
@@ -179,10 +267,12 @@ __device__ __forceinline__ void gemm_body(const GemmArgs<T>& a, int wg, int nwg,
         const int m = a.m0 + c;
         const int n = t * TILE_N + 4 * g;   // first of this lane's 4 output features
         if (EPI == EPI_PARTIAL) {
-          st_f4<COH>(a.out + ((size_t)ss * a.Mtot + m) * a.ldo + n, acc[0]);
+          *reinterpret_cast<f32x4*>(a.out + ((size_t)ss * a.Mtot + m) * a.ldo + n) = acc[0];
         } else if (EPI == EPI_RESIDUAL) {
-          float* p = a.out + (size_t)m * a.ldo + n;
-          st_f4<COH>(p, ld_f4<COH>(p) + acc[0]);
+          f32x4* p = reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n);
+          const f32x4 hv = *p + acc[0];
+          *p = hv;
+          sq += (hv.x * hv.x + hv.y * hv.y) + (hv.z * hv.z + hv.w * hv.w);
         } else if (EPI == EPI_SWIGLU) {
           f32x4 v;
 #pragma unroll
@@ -190,7 +280,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs<T>& a, int wg, int nwg,
             const float gt = acc[0][i], up = acc[1][i];
             v[i] = (n + i < a.N) ? gt / (1.f + expf(-gt)) * up : 0.f;
           }
-          st_round4<COH>(a.act + (size_t)m * a.ldact + n, v);
+          st_round4(a.act + (size_t)m * a.ldact + n, v);
         } else {  // EPI_LMHEAD
           *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = acc[0];
           Philox4 rnd{0, 0, 0, 0};
@@ -217,6 +307,16 @@ __device__ __forceinline__ void gemm_body(const GemmArgs<T>& a, int wg, int nwg,
           }
         }
       }
+    }
+  }
+
+  if (EPI == EPI_RESIDUAL && wave == 0) {
+    // this workgroup's partial sum of squares per row; the slots of workgroups that do
+    // not exist are zeroed by the ones that do
+    sq += __shfl_xor(sq, 16); sq += __shfl_xor(sq, 32);
+    if (g == 0 && c < a.mrows) {
+      float* dst = a.ssq_out + (size_t)(a.m0 + c) * SSQ_PARTS;
+      for (int p = wg; p < SSQ_PARTS; p += nwg) dst[p] = p == wg ? sq : 0.f;
     }
   }
 
@@ -247,13 +347,6 @@ __device__ __forceinline__ void gemm_body(const GemmArgs<T>& a, int wg, int nwg,
       a.lm.stats[(size_t)wg * a.Mtot + a.m0 + c] = s;
     }
   }
-}
-
-template <typename T, int EPI, int KS, bool BPACK>
-__global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
-  __shared__ GemmRed red[2];
-  Frag<T> ring[GemmCfg<T>::RING];
-  gemm_body<T, EPI, KS, false, BPACK>(a, blockIdx.x, gridDim.x, blockDim.x >> 6, red, ring, false);
 }
 
 }  // namespace dbl

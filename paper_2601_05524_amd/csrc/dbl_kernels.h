@@ -9,15 +9,24 @@ namespace dbl {
 
 // ------------------------------------------------------------------ embedding
 
-// h[m][:] = E[window[m]][:]   (grid = rows)
+// h[m][:] = E[window[m]][:] and the row's sum of squares for the first RMSNorm:
+// ssq[m][0] = sum, ssq[m][1..] = 0   (grid = rows, 256 threads)
 template <typename T>
-__global__ void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ window, float* __restrict__ h,
-                             int d, int ldh, int vocab) {
+__global__ void __launch_bounds__(256) embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ window,
+                                                    float* __restrict__ h, float* __restrict__ ssq, int d, int ldh, int vocab) {
+  __shared__ float scratch[16];
   const int m = blockIdx.x;
   int tok = window[m];
   tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
   const T* e = E + (size_t)tok * d;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)m * ldh + i] = Elem<T>::to_f(e[i]);
+  float s = 0.f;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    const float v = Elem<T>::to_f(e[i]);
+    h[(size_t)m * ldh + i] = v;
+    s += v * v;
+  }
+  s = block_sum(s, scratch);
+  for (int p = threadIdx.x; p < SSQ_PARTS; p += blockDim.x) ssq[(size_t)m * SSQ_PARTS + p] = p == 0 ? s : 0.f;
 }
 
 // ------------------------------------------------------------------- accept

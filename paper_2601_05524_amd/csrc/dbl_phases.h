@@ -1,8 +1,6 @@
-// The per-layer steps between the projections, written as device functions over a
-// "task" index so that they run both as stand-alone kernels (COH = false) and as
-// phases of the persistent layer kernel (COH = true: inputs and outputs cross
-// workgroups inside one launch and use the coherent accessors of dbl_dev.h):
-// residual + RMSNorm, q/k-norm + RoPE + KV append, split-KV GQA attention, combine.
+// The per-layer steps between the projections: q/k-norm + RoPE + KV append, split-KV
+// GQA attention, combine.  Each is a device function over a "task" index (one wave per
+// task) with a thin kernel around it.
 #pragma once
 #include "dbl_dev.h"
 
@@ -29,71 +27,6 @@ __device__ __forceinline__ float block_sum(float v, float* scratch) {
   return t;
 }
 
-// ------------------------------------------------------- residual + RMSNorm
-
-// Row m:  h[m] += sum_p part[p][m] (written back when nparts > 0), then
-// xn[m][i] = T( h[m][i] * rsqrt(mean(h[m]^2) + eps) * gain[i] ).
-// One workgroup per row.  d % 4 == 0 and d <= 4 * blockDim.x * RMS_VPT.  A thread owns
-// up to RMS_VPT float4 columns; all its loads are issued before the first use, so the
-// step costs one memory latency, one workgroup reduction and one store.
-constexpr int RMS_VPT = 4;
-constexpr int RMS_MAXP = 8;
-
-template <typename T>
-struct NormArgs {
-  float* h; int ldh;
-  const float* part; int nparts, Mtot, ldp;
-  const float* gain;
-  T* xn; int ldx;
-  int d; float eps;
-};
-
-template <typename T, bool COH>
-__device__ __forceinline__ void rmsnorm_row(const NormArgs<T>& a, int m, float* scratch) {
-  float* hr = a.h + (size_t)m * a.ldh;
-  const int nv = a.d >> 2;
-  f32x4 v[RMS_VPT], gn[RMS_VPT];
-#pragma unroll
-  for (int u = 0; u < RMS_VPT; ++u) {
-    const int i = threadIdx.x + u * blockDim.x;
-    v[u] = f32x4{0.f, 0.f, 0.f, 0.f}; gn[u] = v[u];
-    if (i < nv) { v[u] = ld_f4<COH>(hr + 4 * i); gn[u] = reinterpret_cast<const f32x4*>(a.gain)[i]; }
-  }
-  if (a.nparts > 0) {
-#pragma unroll
-    for (int p = 0; p < RMS_MAXP; ++p) {
-      if (p < a.nparts) {
-        const float* pr = a.part + ((size_t)p * a.Mtot + m) * a.ldp;
-#pragma unroll
-        for (int u = 0; u < RMS_VPT; ++u) {
-          const int i = threadIdx.x + u * blockDim.x;
-          if (i < nv) v[u] += ld_f4<COH>(pr + 4 * i);
-        }
-      }
-    }
-  }
-  float ss = 0.f;
-#pragma unroll
-  for (int u = 0; u < RMS_VPT; ++u) ss += v[u].x * v[u].x + v[u].y * v[u].y + v[u].z * v[u].z + v[u].w * v[u].w;
-  ss = block_sum(ss, scratch);
-  const float r = rsqrtf(ss / (float)a.d + a.eps);
-#pragma unroll
-  for (int u = 0; u < RMS_VPT; ++u) {
-    const int i = threadIdx.x + u * blockDim.x;
-    if (i < nv) {
-      if (a.nparts > 0) st_f4<COH>(hr + 4 * i, v[u]);
-      st_round4<COH>(a.xn + (size_t)m * a.ldx + 4 * i,
-                     f32x4{v[u].x * r * gn[u].x, v[u].y * r * gn[u].y, v[u].z * r * gn[u].z, v[u].w * r * gn[u].w});
-    }
-  }
-}
-
-template <typename T>
-__global__ void __launch_bounds__(1024) rmsnorm_kernel(const NormArgs<T> a) {
-  __shared__ float scratch[16];
-  rmsnorm_row<T, false>(a, blockIdx.x, scratch);
-}
-
 // ---------------------------------------------- q/k norm + RoPE + KV append
 
 // One wave per task = (row m, head hh) with hh in [0, H + 2*Hkv): q heads, then k
@@ -114,7 +47,7 @@ struct RopeArgs {
   float eps;
 };
 
-template <typename T, bool COH>
+template <typename T>
 __device__ __forceinline__ void rope_task(const RopeArgs<T>& a, int task) {
   const int lane = threadIdx.x & 63;
   const int heads = a.H + 2 * a.Hkv;
@@ -129,7 +62,7 @@ __device__ __forceinline__ void rope_task(const RopeArgs<T>& a, int task) {
   if (act) {
     for (int p = 0; p < a.nparts; ++p) {
       const float* src = a.qkv + ((size_t)p * a.Mtot + m) * a.ldq + (size_t)hh * hd;
-      x0 += ld_f32<COH>(src + lane); x1 += ld_f32<COH>(src + lane + half);
+      x0 += *(src + lane); x1 += *(src + lane + half);
     }
   }
   const bool is_q = hh < a.H, is_k = !is_q && hh < a.H + a.Hkv;
@@ -137,8 +70,8 @@ __device__ __forceinline__ void rope_task(const RopeArgs<T>& a, int task) {
     if (act) {
       const int kvh = hh - a.H - a.Hkv;
       T* dst = a.vt + ((size_t)(b * a.Hkv + kvh) * (a.max_ctx / VT_BLOCK) + pos / VT_BLOCK) * hd * VT_BLOCK + pos % VT_BLOCK;
-      st_round1<COH>(dst + (size_t)lane * VT_BLOCK, x0);
-      st_round1<COH>(dst + (size_t)(lane + half) * VT_BLOCK, x1);
+      st_round1(dst + (size_t)lane * VT_BLOCK, x0);
+      st_round1(dst + (size_t)(lane + half) * VT_BLOCK, x1);
     }
     return;
   }
@@ -159,8 +92,8 @@ __device__ __forceinline__ void rope_task(const RopeArgs<T>& a, int task) {
       const int kvh = hh - a.H;
       dst = a.kc + ((size_t)(b * a.Hkv + kvh) * a.max_ctx + pos) * hd;
     }
-    st_round1<COH>(dst + lane, y0);
-    st_round1<COH>(dst + lane + half, y1);
+    st_round1(dst + lane, y0);
+    st_round1(dst + lane + half, y1);
   }
 }
 
@@ -168,7 +101,7 @@ template <typename T>
 __global__ void __launch_bounds__(256) rope_kv_kernel(const RopeArgs<T> a) {
   const int task = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (task >= a.Mtot * (a.H + 2 * a.Hkv)) return;
-  rope_task<T, false>(a, task);
+  rope_task<T>(a, task);
 }
 
 // ------------------------------------------------------------ GQA attention
@@ -193,16 +126,16 @@ struct AttnArgs {
   float scale;                      // log2(e) / sqrt(hd): scores and running maxima are kept in the log2 domain
 };
 
-template <bool COH> __device__ __forceinline__ Frag<bf16_t> vt_frag(const bf16_t* v0, const bf16_t* v1) {
+__device__ __forceinline__ Frag<bf16_t> vt_frag(const bf16_t* v0, const bf16_t* v1) {
   Frag<bf16_t> f;
-  const uint64_t a = ld_u64<COH>(v0), b = ld_u64<COH>(v1);
-  f.v = u32x4{(uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32)};
+  const u32x2 a = *reinterpret_cast<const u32x2*>(v0), b = *reinterpret_cast<const u32x2*>(v1);
+  f.v = u32x4{a.x, a.y, b.x, b.y};
   return f;
 }
-template <bool COH> __device__ __forceinline__ Frag<float> vt_frag(const float* v0, const float* v1) {
+__device__ __forceinline__ Frag<float> vt_frag(const float* v0, const float* v1) {
   Frag<float> f;
-  f.lo = ld_f4<COH>(v0);
-  f.hi = ld_f4<COH>(v1);
+  f.lo = *reinterpret_cast<const f32x4*>(v0);
+  f.hi = *reinterpret_cast<const f32x4*>(v1);
   return f;
 }
 
@@ -238,7 +171,7 @@ __device__ __forceinline__ void pv_accumulate(f32x4 (&o)[HT], const Frag<float> 
 template <typename T, int HD>
 struct KvFrags { Frag<T> kf[2][HD / 32]; Frag<T> vf[HD / 16]; };
 
-template <typename T, int HD, bool COH>
+template <typename T, int HD>
 __device__ __forceinline__ void load_kv(KvFrags<T, HD>& f, const T* kbase, const T* vbase, int tb, int c, int g4) {
   // K fragments (A operand) of the two 16-token tiles: token = tb + 16*h + c  (< max_ctx:
   // tb + 31 < roundup32(len) <= max_ctx)
@@ -246,20 +179,20 @@ __device__ __forceinline__ void load_kv(KvFrags<T, HD>& f, const T* kbase, const
   for (int h = 0; h < 2; ++h) {
     const T* kp = kbase + (size_t)(tb + 16 * h + c) * HD + g4 * 8;
 #pragma unroll
-    for (int ks = 0; ks < HD / 32; ++ks) f.kf[h][ks] = frag_load_row<COH>(kp + ks * 32);
+    for (int ks = 0; ks < HD / 32; ++ks) f.kf[h][ks] = frag_load_row(kp + ks * 32);
   }
   // V^T fragments: dim row = ht*16 + c; tokens tb + 4*g4 + {0..3} and tb + 16 + 4*g4 + {0..3}
   const T* vp = vbase + (size_t)(tb / VT_BLOCK) * HD * VT_BLOCK + (tb % VT_BLOCK) + 4 * g4;
 #pragma unroll
   for (int h = 0; h < HD / 16; ++h) {
     const T* r = vp + (size_t)(h * 16 + c) * VT_BLOCK;
-    f.vf[h] = vt_frag<COH>(r, r + 16);
+    f.vf[h] = vt_frag(r, r + 16);
   }
 }
 
-// task = ((b * Hkv + kvh) * nsplit + sp) * nqb + qb.  DBUF: keep the next step's K/V in
-// registers while computing the current one.
-template <typename T, int HD, bool COH, bool DBUF>
+// task = ((b * Hkv + kvh) * nsplit + sp) * nqb + qb.  The next step's K/V are fetched
+// into registers while the current one is computed.
+template <typename T, int HD>
 __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
   constexpr int KSTEPS = HD / 32, HT = HD / 16;
   const int lane = threadIdx.x & 63, c = lane & 15, g4 = lane >> 4;
@@ -282,7 +215,7 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
     const T* qp = a.qbuf + ((size_t)(b * a.Hkv + kvh) * a.qrows_pad + row) * HD + g4 * 8;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
-      if (row < nq) qf[ks] = frag_load_row<COH>(qp + ks * 32); else frag_zero(qf[ks]);
+      if (row < nq) qf[ks] = frag_load_row(qp + ks * 32); else frag_zero(qf[ks]);
     }
   }
   f32x4 o[HT];
@@ -294,11 +227,9 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
   const int lim = jrow < 0 ? -1 : min(P + jrow, t1 - 1);   // last slot this query row may see
 
   KvFrags<T, HD> cur, nxt;
-  if (DBUF && t0 < t1) load_kv<T, HD, COH>(cur, kbase, vbase, t0, c, g4);
+  if (t0 < t1) load_kv<T, HD>(cur, kbase, vbase, t0, c, g4);
   for (int tb = t0; tb < t1; tb += 32) {
-    if (DBUF) { if (tb + 32 < t1) load_kv<T, HD, COH>(nxt, kbase, vbase, tb + 32, c, g4); }
-    else if (COH && tb + 32 <= P) load_kv<T, HD, false>(cur, kbase, vbase, tb, c, g4);   // rows of earlier steps
-    else load_kv<T, HD, COH>(cur, kbase, vbase, tb, c, g4);
+    if (tb + 32 < t1) load_kv<T, HD>(nxt, kbase, vbase, tb + 32, c, g4);
     f32x4 s[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -334,15 +265,15 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
 #pragma unroll
     for (int h = 0; h < HT; ++h) o[h] = o[h] * alpha;
     pv_accumulate<HT>(o, cur.vf, s[0], s[1]);
-    if (DBUF) cur = nxt;
+    cur = nxt;
   }
   // write the partial
   float l = lrun;
   l += __shfl_xor(l, 16); l += __shfl_xor(l, 32);
   const size_t pidx = ((size_t)(b * a.Hkv + kvh) * a.nsplit + sp) * a.qrows_pad + row;
-  if (g4 == 0) { st_f32<COH>(a.pm + pidx, mrun); st_f32<COH>(a.pl + pidx, l); }
+  if (g4 == 0) { a.pm[pidx] = mrun; a.pl[pidx] = l; }
 #pragma unroll
-  for (int h = 0; h < HT; ++h) st_f4<COH>(a.po + pidx * HD + h * 16 + 4 * g4, o[h]);
+  for (int h = 0; h < HT; ++h) *reinterpret_cast<f32x4*>(a.po + pidx * HD + h * 16 + 4 * g4) = o[h];
 }
 
 // grid = B * Hkv * nsplit * ceil(nqb / wpg) workgroups of wpg waves; the waves of a
@@ -354,7 +285,7 @@ __global__ void __launch_bounds__(256) attn_split_kernel(const AttnArgs<T> a) {
   const int nqg = (a.nqb + wpg - 1) / wpg;
   const int qb = (blockIdx.x % nqg) * wpg + (threadIdx.x >> 6);
   if (qb >= a.nqb) return;
-  attn_task<T, HD, false, true>(a, (blockIdx.x / nqg) * a.nqb + qb);
+  attn_task<T, HD>(a, (blockIdx.x / nqg) * a.nqb + qb);
 }
 
 // Merge the split partials of one (row m, query head): softmax-weighted sum,
@@ -368,7 +299,7 @@ struct CombineArgs {
   int Mtot, k, H, Hkv, qrows_pad, nsplit;
 };
 
-template <typename T, int HD, bool COH>
+template <typename T, int HD>
 __device__ __forceinline__ void combine_task(const CombineArgs<T>& a, int task) {
   constexpr int DPL = HD / 64;   // dims per lane
   const int lane = threadIdx.x & 63;
@@ -378,8 +309,8 @@ __device__ __forceinline__ void combine_task(const CombineArgs<T>& a, int task) 
   const size_t base = (size_t)(b * a.Hkv + kvh) * a.nsplit;
   float ms = -INFINITY, ls = 0.f;
   if (lane < a.nsplit) {
-    ms = ld_f32<COH>(a.pm + (base + lane) * a.qrows_pad + row);
-    ls = ld_f32<COH>(a.pl + (base + lane) * a.qrows_pad + row);
+    ms = *(a.pm + (base + lane) * a.qrows_pad + row);
+    ls = *(a.pl + (base + lane) * a.qrows_pad + row);
   }
   float M = ms;
 #pragma unroll
@@ -392,8 +323,8 @@ __device__ __forceinline__ void combine_task(const CombineArgs<T>& a, int task) 
   const float* o = a.po + (base * a.qrows_pad + row) * HD + lane * DPL;
   const size_t sstride = (size_t)a.qrows_pad * HD;
   auto ldo = [&](int s, float (&v)[DPL]) {
-    if (DPL == 2) { const f32x2 t = ld_f2<COH>(o + (size_t)s * sstride); v[0] = t.x; v[DPL - 1] = t.y; }
-    else v[0] = ld_f32<COH>(o + (size_t)s * sstride);
+    if (DPL == 2) { const f32x2 t = *reinterpret_cast<const f32x2*>(o + (size_t)s * sstride); v[0] = t.x; v[DPL - 1] = t.y; }
+    else v[0] = *(o + (size_t)s * sstride);
   };
   int s = 0;
   for (; s + 4 <= a.nsplit; s += 4) {
@@ -417,10 +348,10 @@ __device__ __forceinline__ void combine_task(const CombineArgs<T>& a, int task) 
   const float inv = L > 0.f ? 1.f / L : 0.f;
   T* dst = a.attn + (size_t)m * a.ldat + (size_t)hh * HD + lane * DPL;
   if (DPL == 2 && sizeof(T) == 2) {
-    st_u32<COH>(dst, pack_bf16(acc[0] * inv, acc[DPL - 1] * inv));
+    *reinterpret_cast<uint32_t*>(dst) = (pack_bf16(acc[0] * inv, acc[DPL - 1] * inv));
   } else {
 #pragma unroll
-    for (int i = 0; i < DPL; ++i) st_round1<COH>(dst + i, acc[i] * inv);
+    for (int i = 0; i < DPL; ++i) st_round1(dst + i, acc[i] * inv);
   }
 }
 
@@ -428,7 +359,7 @@ template <typename T, int HD>
 __global__ void __launch_bounds__(256) attn_combine_kernel(const CombineArgs<T> a) {
   const int task = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (task >= a.Mtot * a.H) return;
-  combine_task<T, HD, false>(a, task);
+  combine_task<T, HD>(a, task);
 }
 
 }  // namespace dbl
