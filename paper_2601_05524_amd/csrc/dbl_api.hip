@@ -101,9 +101,9 @@ struct dbl_ctx {
   size_t kv_layer_elems = 0;
   int32_t *kv_len = nullptr, *hist_len = nullptr, *hist = nullptr, *status = nullptr;
   uint64_t* commits = nullptr;
-  float *h = nullptr, *ssq = nullptr, *qkv_part = nullptr, *logits = nullptr;
+  float *h = nullptr, *hg = nullptr, *ssq = nullptr, *qkv_part = nullptr, *logits = nullptr;
   void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
-  int tile_rot = 0;                 // per-round shift of the workgroup -> tile mapping (DBL_TILE_ROT)
+  unsigned* tile_ctr = nullptr;     // dynamic tile scheduling: counters, zero between launches
   int ldh = 0;                      // row stride of h and layer stride of g1 / g2 / gf (>= every consumer's K padding)
   float *pm = nullptr, *pl = nullptr, *po = nullptr;
   LmStat* stats = nullptr;
@@ -190,7 +190,8 @@ void launch_gemm_t(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
   const dim3 grid(p.grid), block(p.NW * 64);
   constexpr bool is_bf = sizeof(T) == 2;
   constexpr int KS_BIG = is_bf ? 32 : 16, KS_SMALL = is_bf ? 16 : 8;
-  const bool pack = a.mrows <= 8;   // two k-blocks of activations per register set
+  static const bool no_pack = std::getenv("DBL_NO_PACK") != nullptr;   // tuning aid
+  const bool pack = a.mrows <= 8 && !no_pack;   // two k-blocks of activations per register set
   if (p.KS == KS_BIG && !CHUNK) {
     if (pack) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, true, false>), grid, block, 0, c->stream, a);
     else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, false, false>), grid, block, 0, c->stream, a);
@@ -204,7 +205,7 @@ template <typename T>
 void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
   a.NT = p.NT; a.N = p.N; a.KBp = p.KBp; a.SS = p.SS; a.NCH = p.NCH; a.Mtot = M;
   a.d = (float)c->cfg.d_model; a.eps = c->cfg.rms_eps; a.ssq_in = c->ssq; a.ssq_out = c->ssq;
-  a.rot = c->tile_rot;
+  a.tile_ctr = c->tile_ctr;
   for (int m0 = 0; m0 < M; m0 += 16) {
     a.m0 = m0; a.mrows = std::min(16, M - m0);
     switch (epi) {
@@ -241,7 +242,7 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
   LayerSteps<T> s{};
   // q/k/v: RMSNorm (gain g1) on load -> per-slice partials
   s.qkv.W = reinterpret_cast<const T*>(c->w_qkv) + (size_t)l * c->p_qkv.elems();
-  s.qkv.H = c->h; s.qkv.ldx = c->ldh; s.qkv.gain = c->g1 + (size_t)l * c->ldh;
+  s.qkv.HG = c->hg; s.qkv.ldx = c->ldh;
   s.qkv.out = c->qkv_part; s.qkv.ldo = c->p_qkv.ldo();
   RopeArgs<T>& r = s.rope;
   r.qkv = c->qkv_part; r.nparts = c->p_qkv.SS; r.Mtot = M; r.ldq = c->p_qkv.ldo();
@@ -272,12 +273,14 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
   s.comb = CombineArgs<T>{c->pm, c->pl, c->po, attn, c->p_o.ldx(), M, k, H, Hkv, c->qrows_pad, nsplit};
   s.o.W = reinterpret_cast<const T*>(c->w_o) + (size_t)l * c->p_o.elems();
   s.o.X = attn; s.o.ldx = c->p_o.ldx(); s.o.out = c->h; s.o.ldo = c->ldh;      // h += attn Wo^T
+  s.o.hg_out = c->hg; s.o.gain_out = c->g2 + (size_t)l * c->ldh;
   // gate/up: RMSNorm (gain g2) on load -> silu(gate) * up
   s.gu.W = reinterpret_cast<const T*>(c->w_gu) + (size_t)l * c->p_gu.elems();
-  s.gu.H = c->h; s.gu.ldx = c->ldh; s.gu.gain = c->g2 + (size_t)l * c->ldh;
+  s.gu.HG = c->hg; s.gu.ldx = c->ldh;
   s.gu.act = act; s.gu.ldact = c->p_d.ldx();
   s.dn.W = reinterpret_cast<const T*>(c->w_d) + (size_t)l * c->p_d.elems();
   s.dn.X = act; s.dn.ldx = c->p_d.ldx(); s.dn.out = c->h; s.dn.ldo = c->ldh;   // h += act Wd^T
+  s.dn.hg_out = c->hg; s.dn.gain_out = l + 1 < g.n_layers ? c->g1 + (size_t)(l + 1) * c->ldh : c->gf;
   (void)d;
   return s;
 }
@@ -297,7 +300,7 @@ int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperatu
   hipStream_t st = c->stream;
 
   hipLaunchKernelGGL((embed_kernel<T>), dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->emb), window, c->h,
-                     c->ssq, d, c->ldh, g.vocab);
+                     c->hg, g.n_layers > 0 ? c->g1 : c->gf, c->ssq, d, c->ldh, g.vocab);
   for (int l = 0; l < g.n_layers; ++l) {
     const LayerSteps<T> s = layer_steps<T>(c, l, B, k);
     launch_gemm<T>(c, c->p_qkv, EPI_PARTIAL, s.qkv, M);
@@ -311,7 +314,7 @@ int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperatu
   {
     // final RMSNorm (gain gf) on load -> logits + per-workgroup row statistics
     GemmArgs<T> a{};
-    a.W = reinterpret_cast<const T*>(c->w_lm); a.H = c->h; a.ldx = c->ldh; a.gain = c->gf;
+    a.W = reinterpret_cast<const T*>(c->w_lm); a.HG = c->hg; a.ldx = c->ldh;
     a.out = c->logits; a.ldo = c->p_lm.ldo();
     a.lm.stats = c->stats; a.lm.window = window; a.lm.commits = c->commits; a.lm.k = k;
     a.lm.inv_T = temperature > 0.f ? 1.0f / temperature : 0.f;
@@ -432,7 +435,7 @@ int copy_tensor(dbl_ctx* c, const TensorLoc& t, int layer, void* host, bool to_d
 
 void free_all(dbl_ctx* c) {
   void* ptrs[] = {c->w_qkv, c->w_o, c->w_gu, c->w_d, c->w_lm, c->emb, c->g1, c->g2, c->gq, c->gk, c->gf, c->cosT,
-                  c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->status, c->commits, c->h, c->qkv_part,
+                  c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->status, c->commits, c->h, c->hg, c->tile_ctr, c->qkv_part,
                   c->ssq, c->logits, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
                   c->n_acc_i, c->emit_i, c->win_i};
   for (void* p : ptrs) if (p) (void)hipFree(p);
@@ -462,7 +465,6 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
   c->dry = (cfg->flags & DBL_FLAG_VALIDATE_ONLY) != 0;
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
   c->seed = weight_seed;
-  if (const char* e = std::getenv("DBL_TILE_ROT")) c->tile_rot = std::max(0, std::atoi(e));
   c->kv_upper.assign(cfg->max_batch, 0); c->hist_upper.assign(cfg->max_batch, 0);
   int rc = DBL_OK;
   if (!c->dry) {
@@ -502,7 +504,9 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(hist, (size_t)g.max_batch * g.max_hist * 4, true);
     ALLOC(status, 4, true); ALLOC(commits, 8, true);
     ALLOC(h, (size_t)Mmax * c->ldh * 4, true);
+    ALLOC(hg, (size_t)Mmax * c->ldh * 4, true);
     ALLOC(ssq, (size_t)Mmax * SSQ_PARTS * 4, true);
+    ALLOC(tile_ctr, (DYN_DONE + 1) * sizeof(unsigned), true);
     ALLOC(qkv_part, (size_t)c->p_qkv.SS * Mmax * c->p_qkv.ldo() * 4, true);
     ALLOC(logits, (size_t)Mmax * c->p_lm.ldo() * 4, true);
     ALLOC(qbuf, (size_t)g.max_batch * g.n_kv_heads * c->qrows_pad * g.head_dim * esz, true);
@@ -747,7 +751,7 @@ static void bench_launch(dbl_ctx* c, int which, int layer, int M) {
     case 2: launch_gemm<T>(c, c->p_gu, EPI_SWIGLU, s.gu, M); break;
     case 3: launch_gemm<T>(c, c->p_d, EPI_RESIDUAL, s.dn, M); break;
     default:
-      a.W = reinterpret_cast<const T*>(c->w_lm); a.H = c->h; a.ldx = c->ldh; a.gain = c->gf;
+      a.W = reinterpret_cast<const T*>(c->w_lm); a.HG = c->hg; a.ldx = c->ldh;
       a.out = c->logits; a.ldo = c->p_lm.ldo();
       a.lm.stats = c->stats; a.lm.window = c->win_i; a.lm.commits = c->commits; a.lm.k = M; a.lm.inv_T = 0.f;
       launch_gemm<T>(c, c->p_lm, EPI_LMHEAD, a, M); break;

@@ -14,20 +14,20 @@
 //     (deterministic, no atomics) and wave 0 applies the epilogue;
 //   * loads run RING blocks ahead of the MFMAs and the ring runs across output
 //     tiles, so the memory pipe never drains inside a kernel;
-//   * a workgroup walks output tiles wg/SS, +nwg/SS, ...;
+//   * a workgroup starts at output tile wg/SS and then either steps by nwg/SS or draws
+//     further tiles from a device counter (see the kernel);
 //   * K longer than NW*KS blocks is covered either by SS workgroup "super slices",
 //     each writing its own partial result that the consumer sums (q/k/v projection),
 //     or by NCH sequential K chunks inside the workgroup with the accumulator kept
 //     in registers (CHUNK form: output and down projection, which add straight into
 //     the residual stream).
 //
-// RMSNorm is not a kernel of its own.  The projections that consume a normalised
-// input (q/k/v, gate/up, LM head) read the fp32 residual stream h, the gain and the
-// row's sum of squares, and build bf16(h * rsqrt(mean(h^2) + eps) * gain) while
-// loading their activation registers.  The sum of squares is produced by whichever
-// kernel wrote h last (embedding, output projection, down projection): each of its
-// workgroups leaves one partial per row in ssq[row][workgroup]; SSQ_PARTS slots per
-// row, unused ones zero, summed by the consumer in a fixed order.
+// RMSNorm is not a kernel of its own.  Whichever kernel wrote the residual stream h last
+// (embedding, output projection, down projection) also stores hg = h * gain of the next
+// norm, and each of its workgroups leaves one partial sum of squares per row in
+// ssq[row][workgroup] (SSQ_PARTS slots per row, unused ones zero).  The projections that
+// consume a normalised input (q/k/v, gate/up, LM head) add the partials in a fixed order
+// and build bf16(hg * rsqrt(mean(h^2) + eps)) while loading their activation registers.
 #pragma once
 #include "dbl_dev.h"
 
@@ -35,6 +35,7 @@ namespace dbl {
 
 enum GemmEpi { EPI_PARTIAL = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3 };
 
+constexpr int DYN_DONE = 8;       // tile_ctr[0..7]: tiles drawn per super slice; tile_ctr[DYN_DONE]: workgroups that left
 constexpr int SSQ_PARTS = 256;    // sum-of-squares partials per row; a producer launches at most this many workgroups
 
 // Per-workgroup, per-row statistics left by the LM-head epilogue.
@@ -60,10 +61,10 @@ struct GemmArgs {
   const T* W;          // tiled weights: NT * NACC tile rows of KBp blocks
   // activations, one of:
   const T* X;          //   EPI_RESIDUAL: [Mtot][ldx] elements of type T, ldx >= KBp*32, zero beyond K
-  const float* H;      //   other epilogues: residual stream [Mtot][ldx] fp32, zero beyond K, normalised on load
+  const float* HG;     //   other epilogues: residual stream times the RMSNorm gain, [Mtot][ldx] fp32, zero
+                       //   beyond K; scaled by 1/rms and rounded on load
   int ldx;
-  const float* gain;   // [>= KBp*32] RMSNorm gain, zero beyond K
-  const float* ssq_in; // [Mtot][SSQ_PARTS] partial sums of squares of H's rows
+  const float* ssq_in; // [Mtot][SSQ_PARTS] partial sums of squares of the residual rows
   float d, eps;        // mean = sum / d
   int m0, mrows;       // rows m0 .. m0+mrows-1 (mrows <= 16) are computed by this launch
   int Mtot;
@@ -72,10 +73,12 @@ struct GemmArgs {
   int KBp;             // k-blocks per tile row = SS * NCH * NW * KS
   int SS;              // super slices; number of workgroups % SS == 0
   int NCH;             // K chunks walked by one workgroup (1 unless the CHUNK form runs)
-  int rot;             // per-round shift of the workgroup -> tile mapping
+  unsigned* tile_ctr;  // SWIGLU: [DYN_DONE + 1] tile counters per super slice + departures, all zero between launches
   float* out;          // PARTIAL: [SS][Mtot][ldo] ; RESIDUAL: h[Mtot][ldo] (+=) ; LMHEAD: logits[Mtot][ldo]
   int ldo;
   float* ssq_out;      // RESIDUAL: [Mtot][SSQ_PARTS] partial sums of squares of the updated rows
+  float* hg_out;       // RESIDUAL: [Mtot][ldo] updated rows times gain_out (input of the next RMSNorm)
+  const float* gain_out;   // RESIDUAL: [>= NT*16] gain of the next RMSNorm
   T* act;              // SWIGLU: [Mtot][ldact]
   int ldact;
   LmArgs lm;
@@ -112,22 +115,20 @@ __device__ __forceinline__ float row_scale(const float* ssq, int m0, int mrows, 
   return out;
 }
 
-// Eight activations of one row as an MFMA fragment: T(h * r * gain), the RMSNorm output
-// rounded to the element type (rounding point r1 of the numerics contract).
-__device__ __forceinline__ Frag<bf16_t> norm_frag(const float* hp, const float* gp, float r, bf16_t) {
-  const f32x4 h0 = *reinterpret_cast<const f32x4*>(hp), h1 = *reinterpret_cast<const f32x4*>(hp + 4);
-  const f32x4 g0 = *reinterpret_cast<const f32x4*>(gp), g1 = *reinterpret_cast<const f32x4*>(gp + 4);
+// Eight activations of one row as an MFMA fragment: T((h * gain) * r), the RMSNorm output
+// rounded to the element type (rounding point r1 of the numerics contract).  hg = h * gain
+// was stored by the producer of h.
+__device__ __forceinline__ Frag<bf16_t> norm_frag(const float* hg, float r, bf16_t) {
+  const f32x4 h0 = *reinterpret_cast<const f32x4*>(hg), h1 = *reinterpret_cast<const f32x4*>(hg + 4);
   Frag<bf16_t> f;
-  f.v = u32x4{pack_bf16(h0.x * r * g0.x, h0.y * r * g0.y), pack_bf16(h0.z * r * g0.z, h0.w * r * g0.w),
-              pack_bf16(h1.x * r * g1.x, h1.y * r * g1.y), pack_bf16(h1.z * r * g1.z, h1.w * r * g1.w)};
+  f.v = u32x4{pack_bf16(h0.x * r, h0.y * r), pack_bf16(h0.z * r, h0.w * r),
+              pack_bf16(h1.x * r, h1.y * r), pack_bf16(h1.z * r, h1.w * r)};
   return f;
 }
-__device__ __forceinline__ Frag<float> norm_frag(const float* hp, const float* gp, float r, float) {
-  const f32x4 h0 = *reinterpret_cast<const f32x4*>(hp), h1 = *reinterpret_cast<const f32x4*>(hp + 4);
-  const f32x4 g0 = *reinterpret_cast<const f32x4*>(gp), g1 = *reinterpret_cast<const f32x4*>(gp + 4);
+__device__ __forceinline__ Frag<float> norm_frag(const float* hg, float r, float) {
   Frag<float> f;
-  f.lo = f32x4{h0.x * r * g0.x, h0.y * r * g0.y, h0.z * r * g0.z, h0.w * r * g0.w};
-  f.hi = f32x4{h1.x * r * g1.x, h1.y * r * g1.y, h1.z * r * g1.z, h1.w * r * g1.w};
+  f.lo = *reinterpret_cast<const f32x4*>(hg) * r;
+  f.hi = *reinterpret_cast<const f32x4*>(hg + 4) * r;
   return f;
 }
 
@@ -147,10 +148,9 @@ __device__ __forceinline__ void load_acts(const GemmArgs<T>& a, int kblk, float 
   const size_t k0 = (size_t)(kblk + (PACK ? (c >> 3) : 0)) * TILE_K + g * 8;
   constexpr int STEP = (PACK ? 2 : 1) * TILE_K;
   if (NORM) {
-    const float* hp = a.H + (size_t)row * a.ldx + k0;
-    const float* gp = a.gain + k0;
+    const float* hp = a.HG + (size_t)row * a.ldx + k0;
 #pragma unroll
-    for (int j = 0; j < (PACK ? KS / 2 : KS); ++j) b[j] = norm_frag(hp + j * STEP, gp + j * STEP, r, T());
+    for (int j = 0; j < (PACK ? KS / 2 : KS); ++j) b[j] = norm_frag(hp + j * STEP, r, T());
   } else {
     const T* xp = a.X + (size_t)row * a.ldx + k0;
 #pragma unroll
@@ -162,6 +162,10 @@ __device__ __forceinline__ void load_acts(const GemmArgs<T>& a, int kblk, float 
 // activations of the next chunk are fetched while the current one is multiplied.
 template <typename T, int EPI, int KS, bool PACK, bool CHUNK>
 __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
+  // Tiles are drawn dynamically where the epilogue keeps no state across tiles and a tile
+  // lasts much longer than a round trip to the counter: the gate/up projection (~19 us per
+  // tile; the q/k/v projection's ~5 us tiles lose more to the counter than they gain).
+  constexpr bool DYN = EPI == EPI_SWIGLU;
   constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
   constexpr int RING = GemmCfg<T>::RING;
   constexpr int NB = PACK ? KS / 2 : KS;       // activation register sets
@@ -176,14 +180,20 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
   const int c = lane & 15, g = lane >> 4;
   const int ss = wg % a.SS;
   const int tstep = nwg / a.SS;
-  // Output tile of round `it`: round it covers tiles it*tstep .. it*tstep + tstep-1, and the
-  // workgroup -> tile mapping inside a round shifts by `rot` every round.  Workgroups are
-  // dealt round-robin to the 8 XCDs and tile rows are a power-of-two number of bytes apart,
-  // so without the shift every XCD would stream from one fixed set of memory channels for
-  // the whole kernel.
-  const int tbase = wg / a.SS;
-  auto tile_of = [&](int it) { return it * tstep + (tbase + it * a.rot) % tstep; };
-  int t = tile_of(0);
+  // Tile order.  The first tile of a workgroup is wg/SS.  Static form: then +tstep each
+  // round.  DYN form: the second tile too, every further one is taken from a device counter
+  // (one per super slice), so workgroups that stream faster take more tiles.  Under a saturating read the
+  // odd-numbered XCDs of an MI355X get 7-10% less bandwidth than the even ones; with
+  // equal shares the even half of the chip idles at the end of every long kernel.
+  // A tile's result does not depend on who computes it (same K split, same reduction
+  // order), so the result stays deterministic as long as the epilogue keeps no state
+  // across tiles.
+  // The id of the tile after the current one must be known when the current one starts
+  // (the weight ring runs across the boundary), so ids are drawn two tiles ahead by
+  // thread 0 and handed to the other waves at the barrier that ends each tile.
+  __shared__ int s_next[2];
+  int t = wg / a.SS;
+  int tn = t + tstep;
   const int nch = CHUNK ? a.NCH : 1;
   const int seg = nw * KS;                       // k-blocks per chunk
   const int kb0 = ss * nch * seg + wave * KS;    // this wave's first k-block of chunk 0
@@ -220,39 +230,70 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
   }
   float sq = 0.f;   // RESIDUAL: this lane's share of the rows' sums of squares
 
-  for (int it = 0; t < a.NT; ++it, t = tile_of(it)) {
+  // Everything requested so far has to be there before the first product anyway (the
+  // activations were requested after the ring).  Waiting for all of it here, once, also
+  // lets the compiler enter the loop with nothing but the ring in flight, which it needs to
+  // keep exact counts inside the loop.
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+
+  // One iteration = one K chunk of one output tile (a whole tile unless CHUNK); a single
+  // flat loop, so that the loads in flight (weight ring, next chunk's activations) are
+  // carried by one loop only and the compiler keeps exact counts of them.
+  int ch = 0;
+  f32x4 acc[NACC];
+#pragma unroll
+  for (int s = 0; s < NACC; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; t < a.NT;) {
+    const bool last = !CHUNK || ch + 1 == nch;
+    // DYN, thread 0 only: the tile after the next one.  Left without a value in the other
+    // threads on purpose: a defined value there would make the compiler wait for the
+    // counter's answer (and with it for every weight load in flight) right here.
+    int drawn;
+    if constexpr (DYN) {
+      if (threadIdx.x == 0)
+        drawn = (int)__hip_atomic_fetch_add(a.tile_ctr + ss, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     // after the last tile the refill loads go on, harmlessly, into tile 0 (an L2 hit)
-    const int tnn = tile_of(it + 1);
-    const int tn = tnn < a.NT ? tnn : 0;
-    f32x4 acc[NACC];
+    const int tnc = tn < a.NT ? tn : 0;
+    const T* wcur = wlane + (size_t)t * NACC * row_elems + (size_t)ch * seg_elems;
+    const T* wnext = last ? wlane + (size_t)tnc * NACC * row_elems : wcur + seg_elems;
+    Frag<T> bnext[NB];
+    f32x4 hold, gout;
 #pragma unroll
-    for (int s = 0; s < NACC; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const T* wtile = wlane + (size_t)t * NACC * row_elems;
-    const T* wnext_tile = wlane + (size_t)tn * NACC * row_elems;
-    for (int ch = 0; ch < nch; ++ch) {
-      const bool last = ch + 1 == nch;
-      const T* wcur = wtile + (size_t)ch * seg_elems;
-      const T* wnext = last ? wnext_tile : wcur + seg_elems;
-      Frag<T> bnext[NB];
-      if constexpr (CHUNK) load_acts<T, NORM, PACK, KS>(a, kb0 + (last ? 0 : ch + 1) * seg, r, lane, bnext);
+    for (int s = 0; s < NACC; ++s) {
 #pragma unroll
-      for (int s = 0; s < NACC; ++s) {
-#pragma unroll
-        for (int j = 0; j < KS; ++j) {
-          if (PACK) acc[s] = mma(ring[j % RING], (j & 1) ? frag_swap_halves(breg[j / 2]) : breg[j / 2], acc[s]);
-          else acc[s] = mma(ring[j % RING], breg[j], acc[s]);
-          const int jn = j + RING;
-          if (jn < KS) ring[j % RING] = frag_load_w(wcur + s * row_elems, jn, lane);
-          else if (s + 1 < NACC) ring[j % RING] = frag_load_w(wcur + (s + 1) * row_elems, jn - KS, lane);
-          else ring[j % RING] = frag_load_w(wnext, jn - KS, lane);
+      for (int j = 0; j < KS; ++j) {
+        if (PACK) acc[s] = mma(ring[j % RING], (j & 1) ? frag_swap_halves(breg[j / 2]) : breg[j / 2], acc[s]);
+        else acc[s] = mma(ring[j % RING], breg[j], acc[s]);
+        const int jn = j + RING;
+        if (jn < KS) ring[j % RING] = frag_load_w(wcur + s * row_elems, jn, lane);
+        else if (s + 1 < NACC) ring[j % RING] = frag_load_w(wcur + (s + 1) * row_elems, jn - KS, lane);
+        else ring[j % RING] = frag_load_w(wnext, jn - KS, lane);
+        if (s == 0 && j == 0) {
+          // (after the first product, so that the loop starts with the oldest weight load)
+          if constexpr (CHUNK) load_acts<T, NORM, PACK, KS>(a, kb0 + (last ? 0 : ch + 1) * seg, r, lane, bnext);
+          // RESIDUAL: this lane's old h values and gains, fetched ahead of the epilogue (every
+          // chunk, unconditionally; only this workgroup writes them, and only after the last chunk)
+          if constexpr (EPI == EPI_RESIDUAL) {
+            const int n = t * TILE_N + 4 * g;
+            hold = *reinterpret_cast<const f32x4*>(a.out + (size_t)(a.m0 + min(c, a.mrows - 1)) * a.ldo + n);
+            gout = *reinterpret_cast<const f32x4*>(a.gain_out + n);
+          }
         }
-      }
-      if constexpr (CHUNK) {
-#pragma unroll
-        for (int j = 0; j < NB; ++j) breg[j] = bnext[j];
+        // keep program order: the scheduler would otherwise start the next accumulator's
+        // products early, which makes it wait for loads issued only a few slots before
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
+    if constexpr (CHUNK) {
+#pragma unroll
+      for (int j = 0; j < NB; ++j) breg[j] = bnext[j];
+      if (!last) { ++ch; continue; }
+    }
     const int buf = it & 1;
+    if constexpr (DYN) {
+      if (threadIdx.x == 0) s_next[(it + 1) & 1] = drawn + 2 * tstep;   // first use of the counter's answer
+    }
     if (wave != 0) {
 #pragma unroll
       for (int s = 0; s < NACC; ++s) red[buf][wave][s][lane] = acc[s];
@@ -269,9 +310,9 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
         if (EPI == EPI_PARTIAL) {
           *reinterpret_cast<f32x4*>(a.out + ((size_t)ss * a.Mtot + m) * a.ldo + n) = acc[0];
         } else if (EPI == EPI_RESIDUAL) {
-          f32x4* p = reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n);
-          const f32x4 hv = *p + acc[0];
-          *p = hv;
+          const f32x4 hv = hold + acc[0];
+          *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = hv;
+          *reinterpret_cast<f32x4*>(a.hg_out + (size_t)m * a.ldo + n) = hv * gout;
           sq += (hv.x * hv.x + hv.y * hv.y) + (hv.z * hv.z + hv.w * hv.w);
         } else if (EPI == EPI_SWIGLU) {
           f32x4 v;
@@ -306,6 +347,22 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
             }
           }
         }
+      }
+    }
+    t = tn;
+    tn = DYN ? s_next[(it + 1) & 1] : tn + tstep;
+    ++it; ch = 0;
+#pragma unroll
+    for (int s = 0; s < NACC; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  if constexpr (DYN) {
+    // the last workgroup to leave rewinds the counters for the next launch that uses them
+    if (threadIdx.x == 0) {
+      const unsigned left = __hip_atomic_fetch_add(a.tile_ctr + DYN_DONE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (left == (unsigned)nwg - 1) {
+        for (int i = 0; i < a.SS; ++i) __hip_atomic_store(a.tile_ctr + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.tile_ctr + DYN_DONE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
   }

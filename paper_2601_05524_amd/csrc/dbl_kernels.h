@@ -9,11 +9,13 @@ namespace dbl {
 
 // ------------------------------------------------------------------ embedding
 
-// h[m][:] = E[window[m]][:] and the row's sum of squares for the first RMSNorm:
-// ssq[m][0] = sum, ssq[m][1..] = 0   (grid = rows, 256 threads)
+// h[m][:] = E[window[m]][:], hg = h * gain of the first RMSNorm, and the row's sum of
+// squares: ssq[m][0] = sum, ssq[m][1..] = 0   (grid = rows, 256 threads)
 template <typename T>
 __global__ void __launch_bounds__(256) embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ window,
-                                                    float* __restrict__ h, float* __restrict__ ssq, int d, int ldh, int vocab) {
+                                                    float* __restrict__ h, float* __restrict__ hg,
+                                                    const float* __restrict__ gain, float* __restrict__ ssq, int d,
+                                                    int ldh, int vocab) {
   __shared__ float scratch[16];
   const int m = blockIdx.x;
   int tok = window[m];
@@ -23,6 +25,7 @@ __global__ void __launch_bounds__(256) embed_kernel(const T* __restrict__ E, con
   for (int i = threadIdx.x; i < d; i += blockDim.x) {
     const float v = Elem<T>::to_f(e[i]);
     h[(size_t)m * ldh + i] = v;
+    hg[(size_t)m * ldh + i] = v * gain[i];
     s += v * v;
   }
   s = block_sum(s, scratch);
