@@ -101,7 +101,9 @@ struct dbl_ctx {
   size_t kv_layer_elems = 0;
   int32_t *kv_len = nullptr, *hist_len = nullptr, *hist = nullptr, *status = nullptr;
   uint64_t* commits = nullptr;
-  float *h = nullptr, *hg = nullptr, *ssq = nullptr, *qkv_part = nullptr, *logits = nullptr;
+  float *h = nullptr, *hg = nullptr, *ssq = nullptr;
+  void* xn = nullptr;               // RMSNorm output of the current 16-row pass (windows of more than 8 rows)
+  float *qkv_part = nullptr, *logits = nullptr;
   void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
   unsigned* tile_ctr = nullptr;     // dynamic tile scheduling: counters, zero between launches
   int ldh = 0;                      // row stride of h and layer stride of g1 / g2 / gf (>= every consumer's K padding)
@@ -206,8 +208,15 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
   a.NT = p.NT; a.N = p.N; a.KBp = p.KBp; a.SS = p.SS; a.NCH = p.NCH; a.Mtot = M;
   a.d = (float)c->cfg.d_model; a.eps = c->cfg.rms_eps; a.ssq_in = c->ssq; a.ssq_out = c->ssq;
   a.tile_ctr = c->tile_ctr;
+  static_assert(SSQ_PARTS == 256, "xn_kernel adds one partial per thread");
   for (int m0 = 0; m0 < M; m0 += 16) {
     a.m0 = m0; a.mrows = std::min(16, M - m0);
+    if (epi != EPI_RESIDUAL && a.mrows > 8) {
+      // more than 8 rows: the RMSNorm output is stored first and read like any activation
+      T* xn = reinterpret_cast<T*>(c->xn);
+      hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, a.d, a.eps);
+      a.X = xn;
+    }
     switch (epi) {
       case EPI_PARTIAL: launch_gemm_t<T, EPI_PARTIAL, false>(c, p, a); break;
       case EPI_RESIDUAL:
@@ -435,7 +444,7 @@ int copy_tensor(dbl_ctx* c, const TensorLoc& t, int layer, void* host, bool to_d
 
 void free_all(dbl_ctx* c) {
   void* ptrs[] = {c->w_qkv, c->w_o, c->w_gu, c->w_d, c->w_lm, c->emb, c->g1, c->g2, c->gq, c->gk, c->gf, c->cosT,
-                  c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->status, c->commits, c->h, c->hg, c->tile_ctr, c->qkv_part,
+                  c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->status, c->commits, c->h, c->hg, c->xn, c->tile_ctr, c->qkv_part,
                   c->ssq, c->logits, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
                   c->n_acc_i, c->emit_i, c->win_i};
   for (void* p : ptrs) if (p) (void)hipFree(p);
@@ -505,6 +514,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(status, 4, true); ALLOC(commits, 8, true);
     ALLOC(h, (size_t)Mmax * c->ldh * 4, true);
     ALLOC(hg, (size_t)Mmax * c->ldh * 4, true);
+    ALLOC(xn, (size_t)Mmax * c->ldh * esz, true);
     ALLOC(ssq, (size_t)Mmax * SSQ_PARTS * 4, true);
     ALLOC(tile_ctr, (DYN_DONE + 1) * sizeof(unsigned), true);
     ALLOC(qkv_part, (size_t)c->p_qkv.SS * Mmax * c->p_qkv.ldo() * 4, true);

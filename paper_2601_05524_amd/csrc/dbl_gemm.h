@@ -60,9 +60,10 @@ template <typename T>
 struct GemmArgs {
   const T* W;          // tiled weights: NT * NACC tile rows of KBp blocks
   // activations, one of:
-  const T* X;          //   EPI_RESIDUAL: [Mtot][ldx] elements of type T, ldx >= KBp*32, zero beyond K
-  const float* HG;     //   other epilogues: residual stream times the RMSNorm gain, [Mtot][ldx] fp32, zero
-                       //   beyond K; scaled by 1/rms and rounded on load
+  const T* X;          //   EPI_RESIDUAL, or more than 8 rows: [Mtot][ldx] elements of type T, ldx >= KBp*32,
+                       //   zero beyond K
+  const float* HG;     //   other epilogues, at most 8 rows: residual stream times the RMSNorm gain,
+                       //   [Mtot][ldx] fp32, zero beyond K; scaled by 1/rms and rounded on load
   int ldx;
   const float* ssq_in; // [Mtot][SSQ_PARTS] partial sums of squares of the residual rows
   float d, eps;        // mean = sum / d
@@ -169,7 +170,10 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
   constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
   constexpr int RING = GemmCfg<T>::RING;
   constexpr int NB = PACK ? KS / 2 : KS;       // activation register sets
-  constexpr bool NORM = EPI != EPI_RESIDUAL;
+  // Normalise-on-load only in the packed form (at most 8 rows): for 9..16 rows the fp32
+  // loads it needs do not fit beside 16 rows of activation registers, and the host runs
+  // xn_kernel first and passes its output as X.
+  constexpr bool NORM = PACK && EPI != EPI_RESIDUAL;
   static_assert(!PACK || KS % 2 == 0, "packed activations pair k-blocks");
   static_assert(KS % RING == 0, "slice must be a whole number of rings");
   static_assert(!CHUNK || EPI == EPI_RESIDUAL, "only the residual projections walk K chunks");
@@ -282,7 +286,7 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
         }
         // keep program order: the scheduler would otherwise start the next accumulator's
         // products early, which makes it wait for loads issued only a few slots before
-        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0x6);   // scalar and vector ALU work may cross, products and loads may not
       }
     }
     if constexpr (CHUNK) {
@@ -404,6 +408,25 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
       a.lm.stats[(size_t)wg * a.Mtot + a.m0 + c] = s;
     }
   }
+}
+
+// xn[row][:] = T(hg[row][:] * rsqrt(mean(h[row]^2) + eps)) for rows m0 + blockIdx.x: the
+// RMSNorm output as a stored tensor, for projection passes of more than 8 rows.
+// 256 threads; thread p adds slot p of the row's sum-of-squares partials.
+template <typename T>
+__global__ void __launch_bounds__(256) xn_kernel(const float* __restrict__ hg, const float* __restrict__ ssq,
+                                                 T* __restrict__ xn, int ld, int m0, float d, float eps) {
+  __shared__ float part[4];
+  const int row = m0 + blockIdx.x;
+  float s = ssq[(size_t)row * SSQ_PARTS + threadIdx.x];
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  const float r = rsqrtf(((part[0] + part[1]) + (part[2] + part[3])) / d + eps);
+  const float* src = hg + (size_t)row * ld;
+  T* dst = xn + (size_t)row * ld;
+  for (int i = 4 * threadIdx.x; i < ld; i += 4 * 256) st_round4(dst + i, *reinterpret_cast<const f32x4*>(src + i) * r);
 }
 
 }  // namespace dbl
