@@ -25,6 +25,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
+# HBM bytes one launch of the dominant kernel (fused gate/up projection) moves, from two
+# rocprofv3 --pmc runs (FETCH_SIZE scaled by 2.000, the factor a plain 1 GiB copy gives on
+# this box, plus WRITE_SIZE); summary in profiles/gate_up_projection_llama70b_traffic.txt.
+# Counters cannot be read inside this process, so the figure is the recorded one.
+MEASURED_TRAFFIC = {"llama70b_ctx2048_k8_b1_greedy": 944_825_344}
 
 WORKLOADS = {
     # name: (shape key, context, k, batch, mode, temperature, repeat fraction, span lo, span hi)
@@ -191,6 +196,10 @@ def main():
                 "achieved": dom["GB/s"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(dom["GB/s"] / HBM_PEAK_GBPS, 4), "traffic": None,
                 "bytes_per_launch": dom["bytes"], "ms_per_launch": dom["ms"]}
+    if args.workload in MEASURED_TRAFFIC and args.layers <= 0 and "gate_up_swiglu" in proj:
+        roofline["traffic"] = MEASURED_TRAFFIC[args.workload]
+        roofline["traffic_unit"] = "bytes per launch (rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE, offline)"
+        roofline["traffic_vs_algorithmic"] = round(MEASURED_TRAFFIC[args.workload] / dom["bytes"], 4)
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB
         dst = torch.empty_like(src)
