@@ -1,0 +1,95 @@
+"""Properties of the hot path at the full benchmark size: the LLaMA-3.3-70B-shaped model
+(80 layers, 141 GB of weights resident), a 2048-token KV cache built by real prefill,
+window k = 8, batch 1 -- the launch configuration bench.py times.
+
+The oracle cannot run 80 full-width layers, and at this depth bf16 rounding noise decorrelates
+any two implementations anyway (the two-layer full-width slices in test_gpu_wide.py are the
+element-wise check).  What is checked here holds at any size:
+  * the logits are finite and not degenerate;
+  * the acceptance results agree, bit for bit, with the greedy rule re-evaluated in numpy on
+    the logits the same call returned (the fused LM-head statistics over 256 workgroups and
+    the acceptance kernel against a plain arg-max over 128 256 logits per row);
+  * the device counters move by exactly the accepted length + 1;
+  * a second run from a reset context reproduces every logit bit for bit, although the
+    gate/up projection hands out its tiles dynamically.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_05524_amd import binding as B
+from paper_2601_05524_amd import synth
+from tests.gpu_util import Gpu
+
+pytestmark = pytest.mark.gpu
+
+CTX, K, STEPS = 2048, 8, 3
+
+
+def greedy_rule(logits, window):
+    """Paper Sec. 2.1 / App. D.2 at T = 0: draft j+1 survives iff it equals the arg-max of row j
+    (lowest id on ties); the emitted tokens are the surviving drafts plus the arg-max of the
+    first row that disagrees (or of the last row)."""
+    best = logits.argmax(axis=1)          # numpy returns the first (lowest) index of the maximum
+    k = len(window)
+    n = 0
+    while n < k - 1 and window[n + 1] == best[n]:
+        n += 1
+    return n, list(window[1:n + 1]) + [int(best[n])], best
+
+
+def test_llama70b_full_depth_properties():
+    free, _ = torch.cuda.mem_get_info(0)
+    if free < 170e9:
+        pytest.skip("needs about 150 GB of free device memory")
+    shape = dict(synth.CONFIGS["llama70b"])
+    V = shape["vocab"]
+    seed = synth.BASE_SEED + 2
+    g = Gpu(shape, seed=seed, max_ctx=CTX + 128, max_window=16, max_hist=CTX + 256)
+    prompt = synth.zipf_history(seed, CTX + 1, V, 1.1, 0.20, 16, 16)
+    rng = np.random.default_rng(5)
+    first = [np.concatenate([[prompt[-1]], rng.integers(0, V, K - 1)]).astype(np.int32)]
+
+    # run 1: window i+1 starts with the token step i emitted last
+    windows, res = list(first), []
+    g.prefill([prompt], 16)
+    assert g.kv_len()[0] == CTX
+    for i in range(STEPS):
+        w = windows[i]
+        if i == 1:
+            # make the first two drafts right: verify without committing, copy the model's own
+            # continuation into the window, twice (row j only sees rows <= j, so row 0's
+            # arg-max is unchanged by the drafts behind it)
+            for d in (1, 2):
+                best = g.verify([w])[0].argmax(axis=1)
+                w = w.copy()
+                w[d] = best[d - 1]
+            windows[i] = w
+        logits = g.verify([w])[0]
+        n_acc, emit, guide = g.accept(B.DBL_GREEDY)
+        before = g.kv_len()[0]
+        g.commit()
+        after = g.kv_len()[0]
+        assert np.isfinite(logits).all()
+        assert logits.std() > 0.1
+        n_ref, emit_ref, best = greedy_rule(logits, w)
+        assert int(n_acc[0]) == n_ref, (i, int(n_acc[0]), n_ref)
+        assert emit[0][:n_ref + 1].tolist() == emit_ref, i
+        assert after - before == n_ref + 1
+        res.append(logits)
+        # next window: pending = last emitted token; drafts = what this step's rows predicted
+        # after it (a correct guess for the first draft whenever the model repeats itself)
+        nxt = np.concatenate([[emit_ref[-1]], best[n_ref:n_ref + 1], rng.integers(0, V, K - 2)]).astype(np.int32)
+        windows.append(nxt)
+    accepted = [greedy_rule(l, w)[0] for l, w in zip(res, windows)]
+    print("accepted lengths:", accepted)
+    assert accepted[1] >= 2
+
+    # run 2 from a reset context: identical bits
+    g.prefill([prompt], 16)            # resets the context first
+    for i in range(STEPS):
+        logits = g.verify([windows[i]])[0]
+        g.accept(B.DBL_GREEDY)
+        g.commit()
+        assert np.array_equal(logits, res[i]), "step %d differs between two runs" % i
+    g.close()
