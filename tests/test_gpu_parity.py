@@ -310,6 +310,71 @@ def test_sampling_accept_parity(dense):
     g.close()
 
 
+def test_stress_shape_batch4_ragged_contexts_windows_4_to_32():
+    """The long-context stress workload's structure at a width the oracle can follow: batch 4
+    with different context lengths, verify windows k = 4, 8, 16, 32 (up to 128 rows = eight
+    16-row passes over the weights), speculative sampling at temperature 1.0."""
+    shape = SMALL_BF16
+    Bn, T, seed = 4, 1.0, 0x5EED5EED
+    g, r = pair(shape, 15, max_batch=Bn, max_ctx=1280, max_window=32, max_hist=2048)
+    sharpen(g, r, 8.0)
+    V = shape["vocab"]
+    rng = np.random.default_rng(6)
+    lens = [97, 333, 650, 1021]
+    prompts = [synth.zipf_history(40 + b, lens[b] + 1, V) for b in range(Bn)]
+    # ragged prefill: 16-row chunks; a sequence that is done keeps 0 rows of its (dummy) chunk
+    B.dbl_reset(g.ctx, -1)
+    done = [0] * Bn
+    for b in range(Bn):
+        B.dbl_history_set(g.ctx, b, np.ascontiguousarray(prompts[b], dtype=np.int32))
+    while any(done[b] < lens[b] for b in range(Bn)):
+        ws, keep = [], []
+        for b in range(Bn):
+            n = min(16, lens[b] - done[b])
+            w = np.zeros(16, np.int32)
+            w[:n] = prompts[b][done[b]:done[b] + n]
+            ws.append(w); keep.append(n); done[b] += n
+        g.verify(ws, want_logits=False)
+        g.commit(keep)
+    assert g.kv_len().tolist() == lens
+    r.prefill(prompts, 16)
+    compared, exempt, n_hist = 0, 0, []
+    for step, k in enumerate((4, 8, 16, 32, 8)):
+        ws, refs = [], []
+        for b in range(Bn):
+            s = r.seqs[b]
+            tmpw = [int(s.history()[-1])]
+            for _ in range(k - 1):     # drafts: mostly the oracle's own top-1
+                lg = s.verify_block(tmpw)
+                tmpw.append(int(lg[-1].argmax()) if rng.random() < 0.9 else int(rng.integers(0, V)))
+            w = np.array(tmpw, np.int32)
+            ws.append(w); refs.append(s.verify_block(w))
+        lg = g.verify(ws, temperature=T, seed=seed, step=50 + step)
+        n, emit, guide = g.accept(B.DBL_SAMPLE, None)
+        commits = g.ncommit
+        keep = []
+        for b in range(Bn):
+            err = np.abs(lg[b] - refs[b]).max()
+            assert err <= 8.0 * TOL[1], (k, b, err)     # sharpened LM head: 8 x the logit scale
+            n_ref, e_ref, gd_ref, am, gap = O.accept_sample(refs[b], ws[b], None, T, seed, 50 + step + commits, b)
+            if sample_margin_ok(refs[b], ws[b], None, T, am, gap, n_ref, err):
+                assert n[b] == n_ref, (k, b)
+                assert np.array_equal(emit[b], e_ref), (k, b)
+                compared += 1
+            else:
+                exempt += 1
+            n_hist.append(n_ref)
+            keep.append(n_ref + 1)
+            r.seqs[b].commit(n_ref + 1, e_ref[:n_ref + 1])
+        g.commit(keep)
+        for b in range(Bn):
+            B.dbl_history_set(g.ctx, b, r.seqs[b].history())
+        assert g.kv_len().tolist() == [len(r.seqs[b].history()) - 1 for b in range(Bn)]
+    assert compared >= 14, (compared, exempt)
+    assert len(set(n_hist)) >= 3, "accepted lengths should vary: %s" % sorted(set(n_hist))
+    g.close()
+
+
 # ----------------------------------------------------------------- retrieve
 
 def test_retrieval_parity():
