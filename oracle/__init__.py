@@ -72,6 +72,7 @@ def lib():
         L.orc_seq_vcache.argtypes = [C.c_void_p]
         L.orc_seq_reset.argtypes = [C.c_void_p]
         L.orc_seq_hist_set.argtypes = [C.c_void_p, i32p, C.c_int]
+        L.orc_seq_truncate.argtypes = [C.c_void_p, C.c_int, C.c_int]
         L.orc_rmsnorm.argtypes = [f64p, f32p, C.c_int, C.c_double, f64p]
         L.orc_rope.argtypes = [f64p, C.c_int, C.c_int, C.c_double]
         L.orc_verify_block.argtypes = [C.c_void_p, C.c_void_p, i32p, C.c_int, f64p, f64p]
@@ -186,6 +187,10 @@ class Seq:
 
     def reset(self):
         lib().orc_seq_reset(self.h)
+
+    def truncate(self, kv_len=-1, hist_len=-1):
+        if lib().orc_seq_truncate(self.h, int(kv_len), int(hist_len)) != 0:
+            raise ValueError("truncate beyond the current lengths")
 
     def hist_set(self, tokens):
         t = np.ascontiguousarray(tokens, dtype=np.int32)

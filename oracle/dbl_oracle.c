@@ -261,6 +261,15 @@ double *orc_seq_vcache(orc_seq *s) { return s->vc; }
 
 void orc_seq_reset(orc_seq *s) { s->kv_len = 0; s->hist_len = 0; }
 
+/* Rollback (Alg. 1 "rollback M_q", Alg. 2 "rollback both models"): forget the KV rows
+ * and the history tokens beyond the given lengths; -1 leaves a length as it is. */
+int orc_seq_truncate(orc_seq *s, int kv_len, int hist_len) {
+  if (kv_len > s->kv_len || hist_len > s->hist_len) return -1;
+  if (kv_len >= 0) s->kv_len = kv_len;
+  if (hist_len >= 0) s->hist_len = hist_len;
+  return 0;
+}
+
 int orc_seq_hist_set(orc_seq *s, const int32_t *tok, int n) {
   if (n < 0 || n > s->max_hist) return -1;
   memcpy(s->hist, tok, sizeof(int32_t) * (size_t)n);

@@ -192,8 +192,7 @@ void launch_gemm_t(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
   const dim3 grid(p.grid), block(p.NW * 64);
   constexpr bool is_bf = sizeof(T) == 2;
   constexpr int KS_BIG = is_bf ? 32 : 16, KS_SMALL = is_bf ? 16 : 8;
-  static const bool no_pack = std::getenv("DBL_NO_PACK") != nullptr;   // tuning aid
-  const bool pack = a.mrows <= 8 && !no_pack;   // two k-blocks of activations per register set
+  const bool pack = a.mrows <= 8;   // two k-blocks of activations per register set
   if (p.KS == KS_BIG && !CHUNK) {
     if (pack) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, true, false>), grid, block, 0, c->stream, a);
     else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, false, false>), grid, block, 0, c->stream, a);
