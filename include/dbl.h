@@ -114,6 +114,13 @@ int dbl_get_weights(dbl_ctx* ctx, int tensor_id, int layer, void* host, size_t b
  * `seq` (or every sequence when seq < 0) gets kv_len = hist_len = 0. */
 int dbl_reset(dbl_ctx* ctx, int seq);
 
+/* Rollback (Alg. 1 "rollback M_q", Alg. 2 "rollback both models"): sequence `seq`
+ * forgets the KV rows beyond kv_len and the history tokens beyond hist_len:
+ * kv_len[seq] = min(kv_len[seq], kv_len), hist_len[seq] = min(hist_len[seq], hist_len);
+ * a negative argument leaves that counter as it is.  Nothing is erased: the rows and
+ * tokens are overwritten by later calls.  Only enqueues on the context's stream. */
+int dbl_truncate(dbl_ctx* ctx, int seq, int32_t kv_len, int32_t hist_len);
+
 /* Replace the token history of sequence `seq` by `n` host tokens (the prompt).
  * The history is what dbl_retrieve searches; it normally ends with the pending
  * token, i.e. hist_len = kv_len + 1.  0 <= n <= max_hist. */

@@ -612,6 +612,18 @@ int dbl_reset(dbl_ctx* c, int seq) {
   return DBL_OK;
 }
 
+int dbl_truncate(dbl_ctx* c, int seq, int32_t kv_len, int32_t hist_len) {
+  if (!c) return DBL_EINVAL;
+  if (seq < 0 || seq >= c->cfg.max_batch) return fail(c, DBL_EINVAL, "seq out of range");
+  if (kv_len >= 0) c->kv_upper[seq] = std::min(c->kv_upper[seq], (int)kv_len);
+  if (hist_len >= 0) c->hist_upper[seq] = std::min(c->hist_upper[seq], (int)hist_len);
+  c->have_verify = c->have_accept = false;
+  if (c->dry) return DBL_ENODEV;
+  hipLaunchKernelGGL(truncate_kernel, dim3(1), dim3(64), 0, c->stream, c->kv_len, c->hist_len, seq, (int)kv_len, (int)hist_len);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
 int dbl_history_set(dbl_ctx* c, int seq, const int32_t* host_tokens, int n) {
   if (!c) return DBL_EINVAL;
   if (seq < 0 || seq >= c->cfg.max_batch) return fail(c, DBL_EINVAL, "seq out of range");

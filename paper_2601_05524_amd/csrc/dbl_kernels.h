@@ -272,6 +272,13 @@ __global__ void set_counters_kernel(int32_t* kv_len, int32_t* hist_len, int seq,
   if (b < B && (seq < 0 || b == seq)) { kv_len[b] = 0; hist_len[b] = 0; }
 }
 
+__global__ void truncate_kernel(int32_t* kv_len, int32_t* hist_len, int seq, int new_kv, int new_hist) {
+  if (threadIdx.x == 0) {
+    if (new_kv >= 0) kv_len[seq] = min(kv_len[seq], new_kv);
+    if (new_hist >= 0) hist_len[seq] = min(hist_len[seq], new_hist);
+  }
+}
+
 __global__ void fill_i32_kernel(int32_t* p, int32_t v, size_t n) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
