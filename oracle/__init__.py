@@ -80,6 +80,10 @@ def lib():
         L.orc_accept_sample.argtypes = [f64p, C.c_int, C.c_int, i32p, f32p, C.c_double, C.c_uint64,
                                         C.c_uint64, C.c_int, i32p, i32p, i32p, f64p, f64p]
         L.orc_retrieve.argtypes = [i32p, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p, i32p]
+        L.orc_retrieve_tiered.argtypes = [i32p, C.c_int, i32p, C.c_int, C.c_int, i32p, C.c_int, C.c_int, C.c_int,
+                                          C.c_int, i32p, i32p, i32p, i32p, i32p]
+        L.orc_rejected_append.argtypes = [i32p, C.c_int, C.c_int, i32p, C.c_int, i32p, C.c_int, C.c_int, C.c_int]
+        L.orc_rejected_append.restype = C.c_int
         L.orc_commit.argtypes = [C.c_void_p, C.c_int, i32p, C.c_int]
         _lib = L
     return _lib
@@ -269,3 +273,29 @@ def retrieve(hist, n_max, n_min, max_cont):
     lib().orc_retrieve(_p(h, C.c_int32), h.size, n_max, n_min, max_cont, _p(cont, C.c_int32),
                        C.byref(cl), C.byref(mn), C.byref(mp))
     return cont[:cl.value].copy(), cl.value, mn.value, mp.value
+
+
+def retrieve_tiered(prior, hist, prompt_len, rejected, n_max, n_min, max_cont):
+    """Alg. 3's priority search.  Returns (continuation, cont_len, match_n, match_pos, tier);
+    tier 0 prior, 1 dynamic, 2 rejected, 3 the sequence itself, -1 miss."""
+    pr = np.ascontiguousarray(prior, dtype=np.int32)
+    h = np.ascontiguousarray(hist, dtype=np.int32)
+    rj = np.ascontiguousarray(rejected, dtype=np.int32)
+    cont = np.full(max(max_cont, 1), -1, np.int32)
+    cl, mn, mp, mt = C.c_int32(0), C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    lib().orc_retrieve_tiered(_p(pr, C.c_int32), pr.size, _p(h, C.c_int32), h.size, int(prompt_len),
+                              _p(rj, C.c_int32), rj.size, n_max, n_min, max_cont, _p(cont, C.c_int32),
+                              C.byref(cl), C.byref(mn), C.byref(mp), C.byref(mt))
+    return cont[:cl.value].copy(), cl.value, mn.value, mp.value, mt.value
+
+
+def rejected_append(rejected, cap, hist, window, n_acc, n_draft, ctx_tokens=4):
+    """Alg. 3's cache update for the rejected tier; returns the tier's new contents."""
+    buf = np.full(cap, -1, np.int32)
+    r = np.ascontiguousarray(rejected, dtype=np.int32)
+    buf[:r.size] = r
+    h = np.ascontiguousarray(hist, dtype=np.int32)
+    w = np.ascontiguousarray(window, dtype=np.int32)
+    n = lib().orc_rejected_append(_p(buf, C.c_int32), r.size, cap, _p(h, C.c_int32), h.size, _p(w, C.c_int32),
+                                  int(n_acc), int(n_draft), int(ctx_tokens))
+    return buf[:n].copy()

@@ -573,6 +573,89 @@ void orc_retrieve(const int32_t *hist, int len, int n_max, int n_min, int max_co
 
 /* ----------------------------------------------------------------- commit */
 
+/* ------------------------------------------------- hierarchical datastore
+ *
+ * Alg. 3 (Retrieval Cache Mechanism) and Sec. 4.3.  Three token tiers are searched in a
+ * fixed priority for every n-gram length, longest first; only if no length hits in any
+ * tier does the search fall back to the plain search of the sequence in itself:
+ *   tier 0  C_prefix    a static token stream (the prior), shared by all sequences
+ *   tier 1  C_dynamic   the tokens generated in this session: hist[prompt_len .. len)
+ *   tier 2  C_rejected  the session's rejected draft chains
+ *   tier 3  fallback    the whole sequence (prompt + generated): orc_retrieve
+ * A tier is a token buffer; -1 separates segments (documents, rejected chains): an n-gram
+ * never contains a separator and a continuation stops in front of one.  Inside a tier the
+ * occurrence with the longest continuation (<= max_cont) wins, then the latest one -- the
+ * same rule as orc_retrieve.  The key is always the last n tokens of hist. */
+
+/* best occurrence of key[0..n) in buf[0..len) whose n-gram starts at or after lo and ends
+ * before hi_end (the key's own position must be excluded by the caller through hi_end) */
+static int tier_best(const int32_t *buf, int len, int lo, int hi_end, const int32_t *key, int n, int max_cont,
+                     int *best_c) {
+  int best_s = -1; *best_c = 0;
+  for (int s = lo; s + n <= hi_end; ++s) {
+    int eq = 1;
+    for (int i = 0; i < n; ++i) if (buf[s + i] != key[i]) { eq = 0; break; }
+    if (!eq) continue;
+    int c = 0;
+    while (c < max_cont && s + n + c < len && buf[s + n + c] >= 0) ++c;
+    if (c < 1) continue;
+    if (c > *best_c || (c == *best_c && s > best_s)) { *best_c = c; best_s = s; }
+  }
+  return best_s;
+}
+
+void orc_retrieve_tiered(const int32_t *prior, int prior_len, const int32_t *hist, int len, int prompt_len,
+                         const int32_t *rej, int rej_len, int n_max, int n_min, int max_cont,
+                         int32_t *cont, int32_t *cont_len, int32_t *match_n, int32_t *match_pos,
+                         int32_t *match_tier) {
+  *cont_len = 0; *match_n = 0; *match_pos = -1; *match_tier = -1;
+  if (n_min < 1) n_min = 1;
+  if (len < 1) return;
+  int n0 = n_max < len ? n_max : len;
+  for (int n = n0; n >= n_min; --n) {
+    const int32_t *key = hist + len - n;
+    for (int tier = 0; tier < 3; ++tier) {
+      const int32_t *buf; int blen, lo, hi_end;
+      if (tier == 0) { buf = prior; blen = prior_len; lo = 0; hi_end = prior_len; }
+      else if (tier == 1) { buf = hist; blen = len; lo = prompt_len; hi_end = len - 1; }   /* not the key itself */
+      else { buf = rej; blen = rej_len; lo = 0; hi_end = rej_len; }
+      if (!buf || blen <= 0) continue;
+      int c, s = tier_best(buf, blen, lo, hi_end, key, n, max_cont, &c);
+      if (s >= 0) {
+        for (int i = 0; i < c; ++i) cont[i] = buf[s + n + i];
+        *cont_len = c; *match_n = n; *match_pos = s; *match_tier = tier;
+        return;
+      }
+    }
+  }
+  orc_retrieve(hist, len, n_max, n_min, max_cont, cont, cont_len, match_n, match_pos);
+  if (*match_n > 0) *match_tier = 3;
+}
+
+/* Cache update of Alg. 3 for the rejected tier: after a window (pending token + drafts) was
+ * verified with n_acc drafts accepted, the drafts behind the first rejection,
+ * window[n_acc+1 .. n_draft], are appended as one segment: up to ctx_tokens tokens of the text
+ * in front of them (history followed by the accepted drafts), the rejected tokens, a
+ * separator.  Nothing is stored when no draft was rejected or the segment does not fit.
+ * hist is the history BEFORE the commit (it ends with the pending token = window[0]).
+ * Returns the new length of the tier. */
+int orc_rejected_append(int32_t *rej, int rej_len, int rej_cap, const int32_t *hist, int len,
+                        const int32_t *window, int n_acc, int n_draft, int ctx_tokens) {
+  int n_rej = n_draft - n_acc;
+  if (n_rej < 1) return rej_len;
+  /* text in front of the rejected tokens: hist[0..len) + window[1..n_acc] */
+  int avail = len + n_acc;
+  int nctx = ctx_tokens < avail ? ctx_tokens : avail;
+  if (rej_len + nctx + n_rej + 1 > rej_cap) return rej_len;
+  for (int i = 0; i < nctx; ++i) {
+    int p = avail - nctx + i;               /* position in hist + accepted */
+    rej[rej_len++] = p < len ? hist[p] : window[1 + (p - len)];
+  }
+  for (int i = 0; i < n_rej; ++i) rej[rej_len++] = window[n_acc + 1 + i];
+  rej[rej_len++] = -1;
+  return rej_len;
+}
+
 /* Keep the first n_keep window rows' KV (the pending token and the accepted
  * drafts), drop the rest (they are simply overwritten by the next window), and
  * append the n_emit emitted tokens to the history. */
