@@ -111,7 +111,8 @@ int dbl_set_weights(dbl_ctx* ctx, int tensor_id, int layer, const void* host, si
 int dbl_get_weights(dbl_ctx* ctx, int tensor_id, int layer, void* host, size_t bytes);
 
 /* Session flush (the paper's datastore is session-scoped, App. D.3): sequence
- * `seq` (or every sequence when seq < 0) gets kv_len = hist_len = 0. */
+ * `seq` (or every sequence when seq < 0) gets kv_len = hist_len = 0 and an empty
+ * rejected tier. */
 int dbl_reset(dbl_ctx* ctx, int seq);
 
 /* Rollback (Alg. 1 "rollback M_q", Alg. 2 "rollback both models"): sequence `seq`
@@ -142,6 +143,48 @@ int dbl_history_get(dbl_ctx* ctx, int seq, int32_t* host_out, int cap, int32_t* 
  */
 int dbl_retrieve(dbl_ctx* ctx, int B, int n_max, int n_min, int max_cont, int32_t* cont_dev,
                  int32_t* cont_len_dev, int32_t* match_n_dev, int32_t* match_pos_dev);
+
+/*
+ * Hierarchical datastore (Sec. 4.3, Alg. 3 "Retrieval Cache Mechanism").  Tiers, searched in
+ * this priority for every n-gram length, longest length first:
+ *   0  the prior: a static token stream shared by all sequences (dbl_prior_set);
+ *   1  the session's generated text: the history beyond what dbl_history_set put there;
+ *   2  the session's rejected draft chains (dbl_rejected_update);
+ * and only if no length hits in any of them
+ *   3  the plain search of the sequence in itself (what dbl_retrieve does).
+ * A tier is a token buffer in which -1 separates segments: an n-gram never contains a
+ * separator and a continuation stops in front of one.  Inside a tier: longest continuation
+ * (<= max_cont), then the latest occurrence.  Outputs as dbl_retrieve, plus match_tier[B]
+ * (-1 = miss); match_pos is the n-gram's start inside its tier's buffer.
+ */
+int dbl_retrieve_tiered(dbl_ctx* ctx, int B, int n_max, int n_min, int max_cont, int32_t* cont_dev,
+                        int32_t* cont_len_dev, int32_t* match_n_dev, int32_t* match_pos_dev,
+                        int32_t* match_tier_dev);
+
+/* Mark the first prompt_len tokens of sequence `seq`'s history as the prompt; what follows
+ * counts as the session's generated text (tier 1).  dbl_history_set marks all it sets as
+ * prompt; this call is for a caller that restores a running session.  0 <= prompt_len;
+ * clamped to the history length.  Synchronises. */
+int dbl_session_mark(dbl_ctx* ctx, int seq, int32_t prompt_len);
+
+/* Replace the prior tier by n host tokens (ids >= 0, or -1 as separator); n = 0 clears it.
+ * Allocates device memory and synchronises: a set-up call, not part of a step. */
+int dbl_prior_set(dbl_ctx* ctx, const int32_t* host_tokens, int n);
+
+/* Alg. 3's cache update for the rejected tier; call between dbl_accept and dbl_kv_commit.
+ * For every sequence of the last verified window (pending token + drafts), the drafts behind
+ * the first rejection, window[n_acc+1 .. n_draft[b]], are appended to its rejected tier as
+ * one segment: up to DBL_REJ_CTX tokens of the text in front of them (history, then the
+ * accepted drafts), the rejected tokens, a separator.  n_draft_dev (dev, [B]) = number of
+ * real drafts in the window (e.g. the cont_len a retrieval returned; clamped to 0..k-1);
+ * NULL = k-1.  A segment that does not fit (capacity max_hist tokens per sequence) is
+ * dropped.  dbl_reset empties the tier.  Only enqueues. */
+#define DBL_REJ_CTX 4
+int dbl_rejected_update(dbl_ctx* ctx, const int32_t* n_draft_dev);
+
+/* Copy the rejected tier of sequence `seq` to the host (min(length, cap) tokens), length
+ * into *n_out.  Synchronises. */
+int dbl_rejected_get(dbl_ctx* ctx, int seq, int32_t* host_out, int cap, int32_t* n_out);
 
 /* window[b][0] = last history token of b; window[b][1+i] = cont[b][i] for
  * i < min(cont_len[b], k-1), else pad_id.  cont rows have stride max_cont.

@@ -21,6 +21,7 @@ T_EMB, T_LM, T_GF = 0, 1, 2
 T_G1, T_WQ, T_WK, T_WV, T_GQ, T_GK, T_WO, T_G2, T_WG, T_WU, T_WD = range(10, 21)
 
 EXPORTS = ["dbl_create", "dbl_destroy", "dbl_last_error", "dbl_set_weights", "dbl_get_weights", "dbl_reset", "dbl_truncate",
+           "dbl_retrieve_tiered", "dbl_session_mark", "dbl_prior_set", "dbl_rejected_update", "dbl_rejected_get",
            "dbl_history_set", "dbl_history_get", "dbl_retrieve", "dbl_build_window", "dbl_verify_block", "dbl_accept",
            "dbl_kv_commit", "dbl_kv_len", "dbl_hist_len", "dbl_model_bytes", "dbl_debug_buffer",
            "dbl_bench_projection"]
@@ -60,6 +61,11 @@ def lib():
         L.dbl_get_weights.argtypes = [vp, i, i, vp, C.c_size_t]
         L.dbl_reset.argtypes = [vp, i]
         L.dbl_truncate.argtypes = [vp, i, C.c_int32, C.c_int32]
+        L.dbl_retrieve_tiered.argtypes = [vp, i, i, i, i, i32p, i32p, i32p, i32p, i32p]
+        L.dbl_prior_set.argtypes = [vp, i32p, i]
+        L.dbl_session_mark.argtypes = [vp, i, C.c_int32]
+        L.dbl_rejected_update.argtypes = [vp, i32p]
+        L.dbl_rejected_get.argtypes = [vp, i, i32p, i, C.POINTER(C.c_int32)]
         L.dbl_history_set.argtypes = [vp, i, vp, i]
         L.dbl_history_get.argtypes = [vp, i, vp, i, C.POINTER(C.c_int32)]
         L.dbl_retrieve.argtypes = [vp, i, i, i, i, i32p, i32p, i32p, i32p]
@@ -140,6 +146,29 @@ def dbl_history_get(ctx, seq, host_out):
 def dbl_retrieve(ctx, B, n_max, n_min, max_cont, cont, cont_len, match_n, match_pos):
     return _chk(ctx, lib().dbl_retrieve(ctx, B, n_max, n_min, max_cont, _ptr(cont), _ptr(cont_len),
                                         _ptr(match_n), _ptr(match_pos)))
+
+
+def dbl_retrieve_tiered(ctx, B, n_max, n_min, max_cont, cont, cont_len, match_n, match_pos, match_tier):
+    return _chk(ctx, lib().dbl_retrieve_tiered(ctx, B, n_max, n_min, max_cont, _ptr(cont), _ptr(cont_len),
+                                               _ptr(match_n), _ptr(match_pos), _ptr(match_tier)))
+
+
+def dbl_session_mark(ctx, seq, prompt_len):
+    return _chk(ctx, lib().dbl_session_mark(ctx, seq, int(prompt_len)))
+
+
+def dbl_prior_set(ctx, host_tokens):
+    return _chk(ctx, lib().dbl_prior_set(ctx, _ptr(host_tokens), int(host_tokens.size)))
+
+
+def dbl_rejected_update(ctx, n_draft=None):
+    return _chk(ctx, lib().dbl_rejected_update(ctx, _ptr(n_draft)))
+
+
+def dbl_rejected_get(ctx, seq, host_out):
+    n = C.c_int32(0)
+    _chk(ctx, lib().dbl_rejected_get(ctx, seq, _ptr(host_out), int(host_out.size), C.byref(n)))
+    return n.value
 
 
 def dbl_build_window(ctx, B, k, max_cont, cont, cont_len, pad_id, window):

@@ -100,6 +100,10 @@ struct dbl_ctx {
   void *kc = nullptr, *vt = nullptr;
   size_t kv_layer_elems = 0;
   int32_t *kv_len = nullptr, *hist_len = nullptr, *hist = nullptr, *status = nullptr;
+  int32_t *prompt_len = nullptr;     // [B] history length at the last dbl_history_set (start of the generated text)
+  int32_t *rej = nullptr, *rej_len = nullptr;   // rejected tier [B][max_hist], lengths [B]
+  int32_t *prior = nullptr;          // prior tier (allocated by dbl_prior_set)
+  int prior_len = 0;
   uint64_t* commits = nullptr;
   float *h = nullptr, *hg = nullptr, *ssq = nullptr;
   void* xn = nullptr;               // RMSNorm output of the current 16-row pass (windows of more than 8 rows)
@@ -443,7 +447,7 @@ int copy_tensor(dbl_ctx* c, const TensorLoc& t, int layer, void* host, bool to_d
 
 void free_all(dbl_ctx* c) {
   void* ptrs[] = {c->w_qkv, c->w_o, c->w_gu, c->w_d, c->w_lm, c->emb, c->g1, c->g2, c->gq, c->gk, c->gf, c->cosT,
-                  c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->status, c->commits, c->h, c->hg, c->xn, c->tile_ctr, c->qkv_part,
+                  c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->prompt_len, c->rej, c->rej_len, c->prior, c->status, c->commits, c->h, c->hg, c->xn, c->tile_ctr, c->qkv_part,
                   c->ssq, c->logits, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
                   c->n_acc_i, c->emit_i, c->win_i};
   for (void* p : ptrs) if (p) (void)hipFree(p);
@@ -510,6 +514,8 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(vt, L * c->kv_layer_elems * esz, true);
     ALLOC(kv_len, (size_t)g.max_batch * 4, true); ALLOC(hist_len, (size_t)g.max_batch * 4, true);
     ALLOC(hist, (size_t)g.max_batch * g.max_hist * 4, true);
+    ALLOC(prompt_len, (size_t)g.max_batch * 4, true);
+    ALLOC(rej, (size_t)g.max_batch * g.max_hist * 4, true); ALLOC(rej_len, (size_t)g.max_batch * 4, true);
     ALLOC(status, 4, true); ALLOC(commits, 8, true);
     ALLOC(h, (size_t)Mmax * c->ldh * 4, true);
     ALLOC(hg, (size_t)Mmax * c->ldh * 4, true);
@@ -607,7 +613,8 @@ int dbl_reset(dbl_ctx* c, int seq) {
     if (seq < 0 || b == seq) { c->kv_upper[b] = 0; c->hist_upper[b] = 0; }
   c->have_verify = c->have_accept = false;
   if (c->dry) return DBL_ENODEV;
-  hipLaunchKernelGGL(set_counters_kernel, dim3(1), dim3(128), 0, c->stream, c->kv_len, c->hist_len, seq, c->cfg.max_batch);
+  hipLaunchKernelGGL(set_counters_kernel, dim3(1), dim3(128), 0, c->stream, c->kv_len, c->hist_len, c->prompt_len, c->rej_len, seq,
+                     c->cfg.max_batch);
   HIPCHK(c, hipGetLastError());
   return DBL_OK;
 }
@@ -619,7 +626,8 @@ int dbl_truncate(dbl_ctx* c, int seq, int32_t kv_len, int32_t hist_len) {
   if (hist_len >= 0) c->hist_upper[seq] = std::min(c->hist_upper[seq], (int)hist_len);
   c->have_verify = c->have_accept = false;
   if (c->dry) return DBL_ENODEV;
-  hipLaunchKernelGGL(truncate_kernel, dim3(1), dim3(64), 0, c->stream, c->kv_len, c->hist_len, seq, (int)kv_len, (int)hist_len);
+  hipLaunchKernelGGL(truncate_kernel, dim3(1), dim3(64), 0, c->stream, c->kv_len, c->hist_len, c->prompt_len, seq, (int)kv_len,
+                     (int)hist_len);
   HIPCHK(c, hipGetLastError());
   return DBL_OK;
 }
@@ -634,6 +642,7 @@ int dbl_history_set(dbl_ctx* c, int seq, const int32_t* host_tokens, int n) {
   if (n > 0) HIPCHK(c, hipMemcpy(c->hist + (size_t)seq * c->cfg.max_hist, host_tokens, (size_t)n * 4, hipMemcpyHostToDevice));
   const int32_t nn = n;
   HIPCHK(c, hipMemcpy(c->hist_len + seq, &nn, 4, hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(c->prompt_len + seq, &nn, 4, hipMemcpyHostToDevice));
   return DBL_OK;
 }
 
@@ -663,6 +672,82 @@ int dbl_retrieve(dbl_ctx* c, int B, int n_max, int n_min, int max_cont, int32_t*
   hipLaunchKernelGGL(retrieve_kernel, dim3(B), dim3(1024), 0, c->stream, c->hist, c->hist_len, c->cfg.max_hist, n_max,
                      n_min, max_cont, cont, cont_len, match_n, match_pos);
   HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+int dbl_retrieve_tiered(dbl_ctx* c, int B, int n_max, int n_min, int max_cont, int32_t* cont, int32_t* cont_len,
+                        int32_t* match_n, int32_t* match_pos, int32_t* match_tier) {
+  if (!c) return DBL_EINVAL;
+  if (!cont || !cont_len || !match_n || !match_pos || !match_tier) return fail(c, DBL_EINVAL, "null output pointer");
+  if (B < 1 || B > c->cfg.max_batch) return fail(c, DBL_EINVAL, "B out of range");
+  if (n_min < 1 || n_max < n_min || n_max > 32) return fail(c, DBL_EINVAL, "need 1 <= n_min <= n_max <= 32");
+  if (max_cont < 1 || max_cont > 64) return fail(c, DBL_EINVAL, "need 1 <= max_cont <= 64");
+  if (c->dry) return DBL_ENODEV;
+  TierArgs a{};
+  a.prior = c->prior; a.prior_len = c->prior_len;
+  a.hist = c->hist; a.hist_len = c->hist_len; a.prompt_len = c->prompt_len; a.max_hist = c->cfg.max_hist;
+  a.rej = c->rej; a.rej_len = c->rej_len; a.rej_cap = c->cfg.max_hist;
+  a.n_max = n_max; a.n_min = n_min; a.max_cont = max_cont;
+  a.cont = cont; a.cont_len = cont_len; a.match_n = match_n; a.match_pos = match_pos; a.match_tier = match_tier;
+  hipLaunchKernelGGL(retrieve_tiered_kernel, dim3(B), dim3(1024), 0, c->stream, a);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+int dbl_session_mark(dbl_ctx* c, int seq, int32_t prompt_len) {
+  if (!c) return DBL_EINVAL;
+  if (seq < 0 || seq >= c->cfg.max_batch) return fail(c, DBL_EINVAL, "seq out of range");
+  if (prompt_len < 0) return fail(c, DBL_EINVAL, "prompt_len must not be negative");
+  if (c->dry) return DBL_ENODEV;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  int32_t hl = 0;
+  HIPCHK(c, hipMemcpy(&hl, c->hist_len + seq, 4, hipMemcpyDeviceToHost));
+  const int32_t v = std::min(prompt_len, hl);
+  HIPCHK(c, hipMemcpy(c->prompt_len + seq, &v, 4, hipMemcpyHostToDevice));
+  return DBL_OK;
+}
+
+int dbl_prior_set(dbl_ctx* c, const int32_t* host_tokens, int n) {
+  if (!c) return DBL_EINVAL;
+  if (n < 0 || (n > 0 && !host_tokens)) return fail(c, DBL_EINVAL, "bad prior length");
+  for (int i = 0; i < n; ++i)
+    if (host_tokens[i] < -1 || host_tokens[i] >= c->cfg.vocab) return fail(c, DBL_EINVAL, "prior token out of range");
+  if (c->dry) { c->prior_len = n; return DBL_ENODEV; }
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (c->prior) { (void)hipFree(c->prior); c->prior = nullptr; }
+  c->prior_len = 0;
+  if (n > 0) {
+    int rc = dmalloc(c, &c->prior, (size_t)n * 4, false);
+    if (rc != DBL_OK) return rc;
+    HIPCHK(c, hipMemcpy(c->prior, host_tokens, (size_t)n * 4, hipMemcpyHostToDevice));
+    c->prior_len = n;
+  }
+  return DBL_OK;
+}
+
+int dbl_rejected_update(dbl_ctx* c, const int32_t* n_draft) {
+  if (!c) return DBL_EINVAL;
+  if (!c->have_verify || !c->have_accept) return fail(c, DBL_ESTATE, "dbl_rejected_update needs dbl_verify_block and dbl_accept first");
+  if (c->dry) return DBL_ENODEV;
+  const int B = c->last_B, k = c->last_k;
+  hipLaunchKernelGGL(rejected_update_kernel, dim3(1), dim3(128), 0, c->stream, c->rej, c->rej_len, c->cfg.max_hist, c->hist,
+                     c->hist_len, c->cfg.max_hist, c->win_i, c->n_acc_i, n_draft, k, B, (int)DBL_REJ_CTX);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+int dbl_rejected_get(dbl_ctx* c, int seq, int32_t* host_out, int cap, int32_t* n_out) {
+  if (!c) return DBL_EINVAL;
+  if (seq < 0 || seq >= c->cfg.max_batch) return fail(c, DBL_EINVAL, "seq out of range");
+  if (!n_out || cap < 0 || (cap > 0 && !host_out)) return fail(c, DBL_EINVAL, "bad output buffer");
+  if (c->dry) return DBL_ENODEV;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  int32_t n = 0;
+  HIPCHK(c, hipMemcpy(&n, c->rej_len + seq, 4, hipMemcpyDeviceToHost));
+  n = std::min<int32_t>(n, c->cfg.max_hist);
+  *n_out = n;
+  const int m = std::min<int>(n, cap);
+  if (m > 0) HIPCHK(c, hipMemcpy(host_out, c->rej + (size_t)seq * c->cfg.max_hist, (size_t)m * 4, hipMemcpyDeviceToHost));
   return DBL_OK;
 }
 

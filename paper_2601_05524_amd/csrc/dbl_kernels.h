@@ -226,6 +226,121 @@ __global__ void __launch_bounds__(1024) retrieve_kernel(const int32_t* __restric
     cont[(size_t)b * max_cont + i] = (best && i < cl) ? h[e + i] : -1;
 }
 
+// Alg. 3's priority search over the prior, the generated text and the rejected chains, with the
+// plain search as fallback.  One workgroup per sequence; every thread walks end positions of
+// every buffer.  For an end position only its longest match matters (shorter lengths at the
+// same place lose to it), so one packed 64-bit maximum decides again:
+//   bit 63: found in a tier (beats any fallback hit) | n | 3 - tier | continuation | end.
+struct TierArgs {
+  const int32_t* prior; int prior_len;
+  const int32_t *hist, *hist_len, *prompt_len; int max_hist;
+  const int32_t *rej, *rej_len; int rej_cap;
+  int n_max, n_min, max_cont;
+  int32_t *cont, *cont_len, *match_n, *match_pos, *match_tier;
+};
+
+// tokens that follow position e in buf[0..len) up to a separator, at most max_cont
+__device__ __forceinline__ int cont_run(const int32_t* buf, int len, int e, int max_cont) {
+  int c = 0;
+  while (c < max_cont && e + c < len && buf[e + c] >= 0) ++c;
+  return c;
+}
+
+__global__ void __launch_bounds__(1024) retrieve_tiered_kernel(const TierArgs a) {
+  __shared__ unsigned long long wbest[16];
+  __shared__ int32_t suf[32];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int32_t* h = a.hist + (size_t)b * a.max_hist;
+  const int len = min(a.hist_len[b], a.max_hist);
+  const int plen = min(a.prompt_len[b], len);
+  const int32_t* rj = a.rej + (size_t)b * a.rej_cap;
+  const int rlen = min(a.rej_len[b], a.rej_cap);
+  const int cap_t = min(a.n_max, len);          // key length in a tier
+  if (tid < 32) suf[tid] = (tid < cap_t) ? h[len - 1 - tid] : -2;   // the key read backwards (-2 matches nothing)
+  __syncthreads();
+  unsigned long long best = 0ull;
+  auto offer = [&](int in_tier, int n, int tier, int cl, int e) {
+    if (n < a.n_min || cl < 1) return;
+    const unsigned long long key = ((unsigned long long)in_tier << 63) | ((unsigned long long)n << 56) |
+                                   ((unsigned long long)(3 - tier) << 54) | ((unsigned long long)cl << 32) | (unsigned)e;
+    best = key > best ? key : best;
+  };
+  // tiers 0 and 2: separate buffers
+  for (int pass = 0; pass < 2; ++pass) {
+    const int32_t* buf = pass == 0 ? a.prior : rj;
+    const int blen = pass == 0 ? a.prior_len : rlen;
+    for (int e = 1 + tid; e <= blen - 1; e += blockDim.x) {
+      int nm = 0;
+      const int cap = min(cap_t, e);
+      while (nm < cap && buf[e - 1 - nm] == suf[nm]) ++nm;
+      if (nm >= a.n_min) offer(1, nm, pass == 0 ? 0 : 2, cont_run(buf, blen, e, a.max_cont), e);
+    }
+  }
+  // the sequence itself: tier 1 where the n-gram lies in the generated part, and the fallback
+  for (int e = 1 + tid; e <= len - 1; e += blockDim.x) {
+    int nm = 0;
+    const int cap = min(min(a.n_max, len - 1), e);
+    while (nm < cap && h[e - 1 - nm] == suf[nm]) ++nm;
+    if (nm >= a.n_min) {
+      const int cl = min(a.max_cont, len - e);
+      offer(0, nm, 3, cl, e);
+      offer(1, min(nm, e - plen), 1, cl, e);
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const unsigned long long o = __shfl_xor(best, off);
+    best = o > best ? o : best;
+  }
+  if (lane == 0) wbest[wave] = best;
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < (int)(blockDim.x >> 6); ++w) best = wbest[w] > best ? wbest[w] : best;
+    wbest[0] = best;
+  }
+  __syncthreads();
+  best = wbest[0];
+  const int n = (int)((best >> 56) & 0x7f), cl = (int)((best >> 32) & 0xffff), e = (int)(best & 0xffffffffu);
+  const int tier = best ? ((best >> 63) ? 3 - (int)((best >> 54) & 3) : 3) : -1;
+  const int32_t* src = tier == 0 ? a.prior : tier == 2 ? rj : h;
+  if (tid == 0) {
+    a.cont_len[b] = best ? cl : 0;
+    a.match_n[b] = best ? n : 0;
+    a.match_pos[b] = best ? e - n : -1;
+    a.match_tier[b] = tier;
+  }
+  for (int i = tid; i < a.max_cont; i += blockDim.x)
+    a.cont[(size_t)b * a.max_cont + i] = (best && i < cl) ? src[e + i] : -1;
+}
+
+// Rejected tier update (one thread per sequence: a handful of tokens).
+__global__ void rejected_update_kernel(int32_t* __restrict__ rej, int32_t* __restrict__ rej_len, int rej_cap,
+                                       const int32_t* __restrict__ hist, const int32_t* __restrict__ hist_len, int max_hist,
+                                       const int32_t* __restrict__ window, const int32_t* __restrict__ n_acc,
+                                       const int32_t* __restrict__ n_draft, int k, int B, int ctx_tokens) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const int32_t* h = hist + (size_t)b * max_hist;
+  const int32_t* w = window + (size_t)b * k;
+  int32_t* r = rej + (size_t)b * rej_cap;
+  const int len = min(hist_len[b], max_hist);
+  const int na = max(0, min(n_acc[b], k - 1));
+  const int nd = n_draft ? max(0, min(n_draft[b], k - 1)) : k - 1;
+  const int n_rej = nd - na;
+  if (n_rej < 1) return;
+  const int avail = len + na;
+  const int nctx = min(ctx_tokens, avail);
+  int rl = min(rej_len[b], rej_cap);
+  if (rl + nctx + n_rej + 1 > rej_cap) return;
+  for (int i = 0; i < nctx; ++i) {
+    const int p = avail - nctx + i;
+    r[rl++] = p < len ? h[p] : w[1 + (p - len)];
+  }
+  for (int i = 0; i < n_rej; ++i) r[rl++] = w[na + 1 + i];
+  r[rl++] = -1;
+  rej_len[b] = rl;
+}
+
 // window[b][0] = last history token, then the continuation, then padding
 __global__ void build_window_kernel(const int32_t* __restrict__ hist, const int32_t* __restrict__ hist_len, int max_hist,
                                     const int32_t* __restrict__ cont, const int32_t* __restrict__ cont_len, int max_cont,
@@ -267,15 +382,15 @@ __global__ void commit_kernel(int32_t* __restrict__ kv_len, int32_t* __restrict_
   if (threadIdx.x == 0) *commits += 1;
 }
 
-__global__ void set_counters_kernel(int32_t* kv_len, int32_t* hist_len, int seq, int B) {
+__global__ void set_counters_kernel(int32_t* kv_len, int32_t* hist_len, int32_t* prompt_len, int32_t* rej_len, int seq, int B) {
   const int b = threadIdx.x;
-  if (b < B && (seq < 0 || b == seq)) { kv_len[b] = 0; hist_len[b] = 0; }
+  if (b < B && (seq < 0 || b == seq)) { kv_len[b] = 0; hist_len[b] = 0; prompt_len[b] = 0; rej_len[b] = 0; }
 }
 
-__global__ void truncate_kernel(int32_t* kv_len, int32_t* hist_len, int seq, int new_kv, int new_hist) {
+__global__ void truncate_kernel(int32_t* kv_len, int32_t* hist_len, int32_t* prompt_len, int seq, int new_kv, int new_hist) {
   if (threadIdx.x == 0) {
     if (new_kv >= 0) kv_len[seq] = min(kv_len[seq], new_kv);
-    if (new_hist >= 0) hist_len[seq] = min(hist_len[seq], new_hist);
+    if (new_hist >= 0) { hist_len[seq] = min(hist_len[seq], new_hist); prompt_len[seq] = min(prompt_len[seq], new_hist); }
   }
 }
 
