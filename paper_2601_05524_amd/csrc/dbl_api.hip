@@ -102,6 +102,7 @@ struct dbl_ctx {
   int32_t *kv_len = nullptr, *hist_len = nullptr, *hist = nullptr, *status = nullptr;
   int32_t *prompt_len = nullptr;     // [B] history length at the last dbl_history_set (start of the generated text)
   int32_t *rej = nullptr, *rej_len = nullptr;   // rejected tier [B][max_hist], lengths [B]
+  unsigned long long* tier_best = nullptr;   // [B] packed best key of a tiered retrieval, zero between calls
   int32_t *prior = nullptr;          // prior tier (allocated by dbl_prior_set)
   int prior_len = 0;
   uint64_t* commits = nullptr;
@@ -447,7 +448,7 @@ int copy_tensor(dbl_ctx* c, const TensorLoc& t, int layer, void* host, bool to_d
 
 void free_all(dbl_ctx* c) {
   void* ptrs[] = {c->w_qkv, c->w_o, c->w_gu, c->w_d, c->w_lm, c->emb, c->g1, c->g2, c->gq, c->gk, c->gf, c->cosT,
-                  c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->prompt_len, c->rej, c->rej_len, c->prior, c->status, c->commits, c->h, c->hg, c->xn, c->tile_ctr, c->qkv_part,
+                  c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->prompt_len, c->rej, c->rej_len, c->tier_best, c->prior, c->status, c->commits, c->h, c->hg, c->xn, c->tile_ctr, c->qkv_part,
                   c->ssq, c->logits, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
                   c->n_acc_i, c->emit_i, c->win_i};
   for (void* p : ptrs) if (p) (void)hipFree(p);
@@ -516,6 +517,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(hist, (size_t)g.max_batch * g.max_hist * 4, true);
     ALLOC(prompt_len, (size_t)g.max_batch * 4, true);
     ALLOC(rej, (size_t)g.max_batch * g.max_hist * 4, true); ALLOC(rej_len, (size_t)g.max_batch * 4, true);
+    ALLOC(tier_best, (size_t)g.max_batch * 8, true);
     ALLOC(status, 4, true); ALLOC(commits, 8, true);
     ALLOC(h, (size_t)Mmax * c->ldh * 4, true);
     ALLOC(hg, (size_t)Mmax * c->ldh * 4, true);
@@ -689,7 +691,10 @@ int dbl_retrieve_tiered(dbl_ctx* c, int B, int n_max, int n_min, int max_cont, i
   a.rej = c->rej; a.rej_len = c->rej_len; a.rej_cap = c->cfg.max_hist;
   a.n_max = n_max; a.n_min = n_min; a.max_cont = max_cont;
   a.cont = cont; a.cont_len = cont_len; a.match_n = match_n; a.match_pos = match_pos; a.match_tier = match_tier;
-  hipLaunchKernelGGL(retrieve_tiered_kernel, dim3(B), dim3(1024), 0, c->stream, a);
+  a.best = c->tier_best;
+  const int chunks = std::max(1, (c->prior_len + TIER_CHUNK - 1) / TIER_CHUNK);
+  hipLaunchKernelGGL(retrieve_tiered_scan_kernel, dim3(chunks, B), dim3(1024), 0, c->stream, a);
+  hipLaunchKernelGGL(retrieve_tiered_finish_kernel, dim3(B), dim3(64), 0, c->stream, a);
   HIPCHK(c, hipGetLastError());
   return DBL_OK;
 }

@@ -227,15 +227,22 @@ __global__ void __launch_bounds__(1024) retrieve_kernel(const int32_t* __restric
 }
 
 // Alg. 3's priority search over the prior, the generated text and the rejected chains, with the
-// plain search as fallback.  One workgroup per sequence; every thread walks end positions of
-// every buffer.  For an end position only its longest match matters (shorter lengths at the
-// same place lose to it), so one packed 64-bit maximum decides again:
+// plain search as fallback.  Every thread walks end positions of a buffer.  For an end position
+// only its longest match matters (shorter lengths at the same place lose to it), so one packed
+// 64-bit maximum decides again:
 //   bit 63: found in a tier (beats any fallback hit) | n | 3 - tier | continuation | end.
+// Two launches: the scan (workgroup (c, b) takes chunk c of the prior for sequence b; chunk 0
+// also the sequence itself and its rejected chains) folds its best key into best[b] with an
+// atomic maximum, which does not depend on the order of arrival; the finish kernel decodes
+// best[b], copies the continuation and clears best[b] for the next call.
+constexpr int TIER_CHUNK = 16384;   // prior tokens per scan workgroup
+
 struct TierArgs {
   const int32_t* prior; int prior_len;
   const int32_t *hist, *hist_len, *prompt_len; int max_hist;
   const int32_t *rej, *rej_len; int rej_cap;
   int n_max, n_min, max_cont;
+  unsigned long long* best;      // [B], zero between calls
   int32_t *cont, *cont_len, *match_n, *match_pos, *match_tier;
 };
 
@@ -246,10 +253,10 @@ __device__ __forceinline__ int cont_run(const int32_t* buf, int len, int e, int 
   return c;
 }
 
-__global__ void __launch_bounds__(1024) retrieve_tiered_kernel(const TierArgs a) {
+__global__ void __launch_bounds__(1024) retrieve_tiered_scan_kernel(const TierArgs a) {
   __shared__ unsigned long long wbest[16];
   __shared__ int32_t suf[32];
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int chunk = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t* h = a.hist + (size_t)b * a.max_hist;
   const int len = min(a.hist_len[b], a.max_hist);
   const int plen = min(a.prompt_len[b], len);
@@ -265,26 +272,27 @@ __global__ void __launch_bounds__(1024) retrieve_tiered_kernel(const TierArgs a)
                                    ((unsigned long long)(3 - tier) << 54) | ((unsigned long long)cl << 32) | (unsigned)e;
     best = key > best ? key : best;
   };
-  // tiers 0 and 2: separate buffers
-  for (int pass = 0; pass < 2; ++pass) {
-    const int32_t* buf = pass == 0 ? a.prior : rj;
-    const int blen = pass == 0 ? a.prior_len : rlen;
-    for (int e = 1 + tid; e <= blen - 1; e += blockDim.x) {
+  auto scan = [&](const int32_t* buf, int blen, int e_lo, int e_hi, int tier) {   // end positions e_lo .. e_hi-1
+    for (int e = e_lo + tid; e < e_hi; e += blockDim.x) {
       int nm = 0;
       const int cap = min(cap_t, e);
       while (nm < cap && buf[e - 1 - nm] == suf[nm]) ++nm;
-      if (nm >= a.n_min) offer(1, nm, pass == 0 ? 0 : 2, cont_run(buf, blen, e, a.max_cont), e);
+      if (nm >= a.n_min) offer(1, nm, tier, cont_run(buf, blen, e, a.max_cont), e);
     }
-  }
-  // the sequence itself: tier 1 where the n-gram lies in the generated part, and the fallback
-  for (int e = 1 + tid; e <= len - 1; e += blockDim.x) {
-    int nm = 0;
-    const int cap = min(min(a.n_max, len - 1), e);
-    while (nm < cap && h[e - 1 - nm] == suf[nm]) ++nm;
-    if (nm >= a.n_min) {
-      const int cl = min(a.max_cont, len - e);
-      offer(0, nm, 3, cl, e);
-      offer(1, min(nm, e - plen), 1, cl, e);
+  };
+  scan(a.prior, a.prior_len, max(1, chunk * TIER_CHUNK), min(a.prior_len, (chunk + 1) * TIER_CHUNK), 0);
+  if (chunk == 0) {
+    scan(rj, rlen, 1, rlen, 2);
+    // the sequence itself: tier 1 where the n-gram lies in the generated part, and the fallback
+    for (int e = 1 + tid; e <= len - 1; e += blockDim.x) {
+      int nm = 0;
+      const int cap = min(min(a.n_max, len - 1), e);
+      while (nm < cap && h[e - 1 - nm] == suf[nm]) ++nm;
+      if (nm >= a.n_min) {
+        const int cl = min(a.max_cont, len - e);
+        offer(0, nm, 3, cl, e);
+        offer(1, min(nm, e - plen), 1, cl, e);
+      }
     }
   }
 #pragma unroll
@@ -296,21 +304,26 @@ __global__ void __launch_bounds__(1024) retrieve_tiered_kernel(const TierArgs a)
   __syncthreads();
   if (tid == 0) {
     for (int w = 1; w < (int)(blockDim.x >> 6); ++w) best = wbest[w] > best ? wbest[w] : best;
-    wbest[0] = best;
+    if (best) atomicMax(a.best + b, best);
   }
-  __syncthreads();
-  best = wbest[0];
+}
+
+__global__ void __launch_bounds__(64) retrieve_tiered_finish_kernel(const TierArgs a) {
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const unsigned long long best = a.best[b];
   const int n = (int)((best >> 56) & 0x7f), cl = (int)((best >> 32) & 0xffff), e = (int)(best & 0xffffffffu);
   const int tier = best ? ((best >> 63) ? 3 - (int)((best >> 54) & 3) : 3) : -1;
-  const int32_t* src = tier == 0 ? a.prior : tier == 2 ? rj : h;
+  const int32_t* src = tier == 0 ? a.prior : tier == 2 ? a.rej + (size_t)b * a.rej_cap : a.hist + (size_t)b * a.max_hist;
+  for (int i = tid; i < a.max_cont; i += blockDim.x)
+    a.cont[(size_t)b * a.max_cont + i] = (best && i < cl) ? src[e + i] : -1;
+  __syncthreads();
   if (tid == 0) {
     a.cont_len[b] = best ? cl : 0;
     a.match_n[b] = best ? n : 0;
     a.match_pos[b] = best ? e - n : -1;
     a.match_tier[b] = tier;
+    a.best[b] = 0ull;
   }
-  for (int i = tid; i < a.max_cont; i += blockDim.x)
-    a.cont[(size_t)b * a.max_cont + i] = (best && i < cl) ? src[e + i] : -1;
 }
 
 // Rejected tier update (one thread per sequence: a handful of tokens).
