@@ -107,6 +107,48 @@ def test_validate_only_context_checks_arguments_and_order():
     assert B.dbl_destroy(ctx) == 0
 
 
+def test_validate_only_context_checks_the_datastore_and_rollback_calls():
+    ctx = B.dbl_create(cfg(), 1)
+    L = B.lib()
+    i32 = np.zeros(64, np.int32)
+    p = C.c_void_p(i32.ctypes.data)
+    ok = B.DBL_ENODEV
+    assert L.dbl_truncate(ctx, 0, 5, -1) == ok
+    assert L.dbl_truncate(ctx, 2, 5, -1) == B.DBL_EINVAL                       # seq out of range
+    assert L.dbl_retrieve_tiered(ctx, 2, 3, 1, 8, p, p, p, p, p) == ok
+    assert L.dbl_retrieve_tiered(ctx, 1, 3, 1, 8, p, p, p, p, None) == B.DBL_EINVAL
+    assert L.dbl_retrieve_tiered(ctx, 1, 33, 1, 8, p, p, p, p, p) == B.DBL_EINVAL
+    assert L.dbl_retrieve_tiered(ctx, 1, 3, 1, 65, p, p, p, p, p) == B.DBL_EINVAL
+    assert L.dbl_session_mark(ctx, 0, 3) == ok
+    assert L.dbl_session_mark(ctx, 0, -1) == B.DBL_EINVAL
+    assert L.dbl_session_mark(ctx, 9, 3) == B.DBL_EINVAL
+    prior = np.array([1, 2, -1, 2047], np.int32)
+    assert L.dbl_prior_set(ctx, C.c_void_p(prior.ctypes.data), 4) == ok
+    assert L.dbl_prior_set(ctx, None, 0) == ok
+    assert L.dbl_prior_set(ctx, None, 4) == B.DBL_EINVAL
+    bad = np.array([1, 2048], np.int32)                                        # id == vocab
+    assert L.dbl_prior_set(ctx, C.c_void_p(bad.ctypes.data), 2) == B.DBL_EINVAL
+    bad = np.array([1, -2], np.int32)
+    assert L.dbl_prior_set(ctx, C.c_void_p(bad.ctypes.data), 2) == B.DBL_EINVAL
+    # the rejected tier is updated between accept and commit
+    assert L.dbl_rejected_update(ctx, None) == B.DBL_ESTATE
+    assert L.dbl_verify_block(ctx, p, 1, 4, 0.0, 0, 0, None) == ok
+    assert L.dbl_rejected_update(ctx, None) == B.DBL_ESTATE                    # no accept yet
+    assert L.dbl_accept(ctx, B.DBL_GREEDY, None, p, p, p) == ok
+    assert L.dbl_rejected_update(ctx, p) == ok
+    assert L.dbl_kv_commit(ctx, None) == ok
+    assert L.dbl_rejected_update(ctx, None) == B.DBL_ESTATE                    # consumed by the commit
+    n = C.c_int32(0)
+    assert L.dbl_rejected_get(ctx, 0, p, 64, C.byref(n)) == ok
+    assert L.dbl_rejected_get(ctx, 0, p, 64, None) == B.DBL_EINVAL
+    assert L.dbl_rejected_get(ctx, 3, p, 64, C.byref(n)) == B.DBL_EINVAL
+    # a rollback invalidates a pending verify: commit afterwards is refused
+    assert L.dbl_verify_block(ctx, p, 1, 4, 0.0, 0, 0, None) == ok
+    assert L.dbl_truncate(ctx, 0, 0, 0) == ok
+    assert L.dbl_kv_commit(ctx, None) == B.DBL_ESTATE
+    assert B.dbl_destroy(ctx) == 0
+
+
 def test_null_context():
     L = B.lib()
     assert L.dbl_destroy(None) == B.DBL_EINVAL
