@@ -129,6 +129,15 @@ def bench_double(args):
     target.collect_history(); draft.collect_history()
 
     res = {}
+    # the iterative retrieval drafter alone (Eq. 5): gamma chained Retrieval Forwards of the draft
+    draft.sync_to(prompt)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    draft.retrieval_forwards(gamma, k_q, 3, 1, 10)
+    chain = draft.collect_history()
+    t_chain = time.perf_counter() - t0
+    res["draft_chain"] = {"forwards": gamma, "L_draft": len(chain), "AMT": round(len(chain) / gamma - 1.0, 3),
+                          "ms": round(t_chain * 1e3, 3), "ms_per_forward": round(t_chain / gamma * 1e3, 3)}
     # plain greedy decoding of the target, one token per forward
     t0 = time.perf_counter()
     ar = DR.autoregressive(target, prompt, min(n_new, 24))

@@ -208,6 +208,11 @@ int dbl_build_window(dbl_ctx* ctx, int B, int k, int max_cont, const int32_t* co
  * [B][k][vocab].  1 <= B <= max_batch, 1 <= k <= max_window, and for every b
  * kv_len[b] + k <= max_ctx (checked against the host's upper bound of kv_len).
  * temperature <= 0 means "greedy statistics only".
+ * The step's calls (retrieve, build_window, verify_block, accept, kv_commit) only enqueue
+ * kernels and one device-to-device copy, so they can be captured into a HIP graph and
+ * replayed; the Philox step word advances with the device-side commit counter.  Replays
+ * do not advance the host's upper bounds: the device clamps at max_ctx / max_hist and
+ * raises the status word that dbl_kv_len / dbl_hist_len report.
  */
 int dbl_verify_block(dbl_ctx* ctx, const int32_t* window_dev, int B, int k, float temperature,
                      uint64_t seed, uint64_t step, float* logits_opt_dev);
