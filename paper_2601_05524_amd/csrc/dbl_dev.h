@@ -17,7 +17,21 @@ constexpr int WAVE = 64;
 constexpr int TILE_N = 16;   // output features per MFMA tile
 constexpr int TILE_K = 32;   // contraction elements per tile block
 constexpr int BLOCK_ELEMS = TILE_N * TILE_K;  // 512 elements per weight block
-constexpr int VT_BLOCK = 64; // tokens per block of the transposed V cache
+
+// KV cache layout, per (sequence, kv head): max_ctx * head_dim elements each for K and V, both
+// stored in the order the attention kernel's MFMA operands want them, so that every wave-level
+// load is 1 KiB (bf16) of consecutive memory -- 8 full cache lines instead of 16 half-used ones.
+//   K: tiles of 16 tokens x 32 dims; inside a tile lane l = 16*(d%32/8) + t%16 owns its 8 dims.
+//   V: tiles of 32 tokens x 16 dims (V^T is the operand); lane l = 16*(t%16/4) + d%16 owns tokens
+//      {4q .. 4q+3} and {16+4q .. 16+4q+3} of the tile (q = t%16/4), in that order.
+// t = position in the sequence, d = dim, hd = head_dim; max_ctx is a multiple of 64.
+__host__ __device__ inline size_t kc_offset(int t, int d, int hd) {
+  return ((size_t)((t >> 4) * (hd >> 5) + (d >> 5)) * 64 + (((d & 31) >> 3) * 16 + (t & 15))) * 8 + (d & 7);
+}
+__host__ __device__ inline size_t vt_offset(int t, int d, int hd) {
+  const int tt = t & 31;
+  return ((size_t)((t >> 5) * (hd >> 4) + (d >> 4)) * 64 + (((tt & 15) >> 2) * 16 + (d & 15))) * 8 + ((tt >> 4) * 4 + (tt & 3));
+}
 
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
 

@@ -34,8 +34,8 @@ __device__ __forceinline__ float block_sum(float v, float* scratch) {
 // and the rotary embedding (pairs (i, i+hd/2); cos/sin from the fp32 table at the
 // row's position kv_len[b] + j), rounds to T, and writes
 //   q  -> qbuf[b][kvh][j*g + hg][hd]
-//   k  -> kc[layer][b][kvh][pos][hd]
-//   v  -> vt[layer][b][kvh][pos/64][hd][pos%64]      (transposed, 64-token blocks)
+//   k  -> kc[layer][b][kvh] at kc_offset(pos, dim)     (MFMA-tiled, see dbl_dev.h)
+//   v  -> vt[layer][b][kvh] at vt_offset(pos, dim)
 template <typename T>
 struct RopeArgs {
   const float* qkv; int nparts, Mtot, ldq;   // partials [nparts][Mtot][ldq]
@@ -69,9 +69,9 @@ __device__ __forceinline__ void rope_task(const RopeArgs<T>& a, int task) {
   if (!is_q && !is_k) {  // v head: no norm, no rotation
     if (act) {
       const int kvh = hh - a.H - a.Hkv;
-      T* dst = a.vt + ((size_t)(b * a.Hkv + kvh) * (a.max_ctx / VT_BLOCK) + pos / VT_BLOCK) * hd * VT_BLOCK + pos % VT_BLOCK;
-      st_round1(dst + (size_t)lane * VT_BLOCK, x0);
-      st_round1(dst + (size_t)(lane + half) * VT_BLOCK, x1);
+      T* dst = a.vt + (size_t)(b * a.Hkv + kvh) * a.max_ctx * hd;
+      st_round1(dst + vt_offset(pos, lane, hd), x0);
+      st_round1(dst + vt_offset(pos, lane + half, hd), x1);
     }
     return;
   }
@@ -84,16 +84,17 @@ __device__ __forceinline__ void rope_task(const RopeArgs<T>& a, int task) {
   if (act) {
     const float cs = a.cosT[(size_t)pos * half + lane], sn = a.sinT[(size_t)pos * half + lane];
     const float y0 = x0 * cs - x1 * sn, y1 = x0 * sn + x1 * cs;
-    T* dst;
     if (is_q) {
       const int g = a.H / a.Hkv, kvh = hh / g, hg = hh % g;
-      dst = a.qbuf + ((size_t)(b * a.Hkv + kvh) * a.qrows_pad + (j * g + hg)) * hd;
+      T* dst = a.qbuf + ((size_t)(b * a.Hkv + kvh) * a.qrows_pad + (j * g + hg)) * hd;
+      st_round1(dst + lane, y0);
+      st_round1(dst + lane + half, y1);
     } else {
       const int kvh = hh - a.H;
-      dst = a.kc + ((size_t)(b * a.Hkv + kvh) * a.max_ctx + pos) * hd;
+      T* dst = a.kc + (size_t)(b * a.Hkv + kvh) * a.max_ctx * hd;
+      st_round1(dst + kc_offset(pos, lane, hd), y0);
+      st_round1(dst + kc_offset(pos, lane + half, hd), y1);
     }
-    st_round1(dst + lane, y0);
-    st_round1(dst + lane + half, y1);
   }
 }
 
@@ -125,19 +126,6 @@ struct AttnArgs {
   int k, g, Hkv, hd, max_ctx, qrows_pad, nsplit, nqb;   // nqb = query blocks per (b, kv head)
   float scale;                      // log2(e) / sqrt(hd): scores and running maxima are kept in the log2 domain
 };
-
-__device__ __forceinline__ Frag<bf16_t> vt_frag(const bf16_t* v0, const bf16_t* v1) {
-  Frag<bf16_t> f;
-  const u32x2 a = *reinterpret_cast<const u32x2*>(v0), b = *reinterpret_cast<const u32x2*>(v1);
-  f.v = u32x4{a.x, a.y, b.x, b.y};
-  return f;
-}
-__device__ __forceinline__ Frag<float> vt_frag(const float* v0, const float* v1) {
-  Frag<float> f;
-  f.lo = *reinterpret_cast<const f32x4*>(v0);
-  f.hi = *reinterpret_cast<const f32x4*>(v1);
-  return f;
-}
 
 // Probabilities (fp32, in [0,1]) as MFMA B operands.  For bf16 models they are split
 // into a bf16 head and a bf16 tail (p = hi + lo up to 2^-17 relative), so the PV
@@ -172,22 +160,19 @@ template <typename T, int HD>
 struct KvFrags { Frag<T> kf[2][HD / 32]; Frag<T> vf[HD / 16]; };
 
 template <typename T, int HD>
-__device__ __forceinline__ void load_kv(KvFrags<T, HD>& f, const T* kbase, const T* vbase, int tb, int c, int g4) {
-  // K fragments (A operand) of the two 16-token tiles: token = tb + 16*h + c  (< max_ctx:
-  // tb + 31 < roundup32(len) <= max_ctx)
+__device__ __forceinline__ void load_kv(KvFrags<T, HD>& f, const T* kbase, const T* vbase, int tb, int lane) {
+  // tb is a multiple of 32 and tb + 31 < roundup32(len) <= max_ctx.  See kc_offset / vt_offset:
+  // K fragments (A operand) of the two 16-token tiles (token = tb + 16*h + lane%16, dims
+  // ks*32 + 8*(lane/16) ..), V^T fragments (dim = h*16 + lane%16, tokens tb + 4*(lane/16) + {0..3}
+  // and tb + 16 + 4*(lane/16) + {0..3}); each is the lane's 8 consecutive elements of a tile.
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const T* kp = kbase + (size_t)(tb + 16 * h + c) * HD + g4 * 8;
+  for (int h = 0; h < 2; ++h)
 #pragma unroll
-    for (int ks = 0; ks < HD / 32; ++ks) f.kf[h][ks] = frag_load_row(kp + ks * 32);
-  }
-  // V^T fragments: dim row = ht*16 + c; tokens tb + 4*g4 + {0..3} and tb + 16 + 4*g4 + {0..3}
-  const T* vp = vbase + (size_t)(tb / VT_BLOCK) * HD * VT_BLOCK + (tb % VT_BLOCK) + 4 * g4;
+    for (int ks = 0; ks < HD / 32; ++ks)
+      f.kf[h][ks] = frag_load_row(kbase + ((size_t)(((tb >> 4) + h) * (HD / 32) + ks) * 64 + lane) * 8);
 #pragma unroll
-  for (int h = 0; h < HD / 16; ++h) {
-    const T* r = vp + (size_t)(h * 16 + c) * VT_BLOCK;
-    f.vf[h] = vt_frag(r, r + 16);
-  }
+  for (int h = 0; h < HD / 16; ++h)
+    f.vf[h] = frag_load_row(vbase + ((size_t)((tb >> 5) * (HD / 16) + h) * 64 + lane) * 8);
 }
 
 // task = ((b * Hkv + kvh) * nsplit + sp) * nqb + qb.  The next step's K/V are fetched
@@ -223,19 +208,17 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
   for (int h = 0; h < HT; ++h) o[h] = f32x4{0.f, 0.f, 0.f, 0.f};
   float mrun = -INFINITY, lrun = 0.f;
   const T* kbase = a.kc + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
-  const T* vbase = a.vt + (size_t)(b * a.Hkv + kvh) * (a.max_ctx / VT_BLOCK) * HD * VT_BLOCK;
+  const T* vbase = a.vt + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
   const int lim = jrow < 0 ? -1 : min(P + jrow, t1 - 1);   // last slot this query row may see
 
-  KvFrags<T, HD> cur, nxt;
-  if (t0 < t1) load_kv<T, HD>(cur, kbase, vbase, t0, c, g4);
-  for (int tb = t0; tb < t1; tb += 32) {
-    if (tb + 32 < t1) load_kv<T, HD>(nxt, kbase, vbase, tb + 32, c, g4);
+  // One 32-token step: scores, online soft-max, O^T += V^T P^T.
+  auto step = [&](const KvFrags<T, HD>& f, int tb) {
     f32x4 s[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       s[h] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) s[h] = mma(cur.kf[h][ks], qf[ks], s[h]);
+      for (int ks = 0; ks < KSTEPS; ++ks) s[h] = mma(f.kf[h][ks], qf[ks], s[h]);
     }
     // lane holds scores of query row c for tokens tb + 16*h + 4*g4 + i
     float mx = -INFINITY;
@@ -264,8 +247,21 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
     lrun = lrun * alpha + psum;       // per-lane share; lane groups are summed at the end
 #pragma unroll
     for (int h = 0; h < HT; ++h) o[h] = o[h] * alpha;
-    pv_accumulate<HT>(o, cur.vf, s[0], s[1]);
-    cur = nxt;
+    pv_accumulate<HT>(o, f.vf, s[0], s[1]);
+  };
+  // The K/V of PRE steps (128 tokens) are requested together, before any of them is used:
+  // a step computes in a fraction of a memory round trip, so fetching only one step ahead
+  // costs one round trip per step.  A wave of this kernel has the CU's registers to itself
+  // (one workgroup of at most 4 waves per CU), which is what the PRE register sets need.
+  // Steps beyond the range re-read its first step (a valid address) and are skipped.
+  constexpr int PRE = sizeof(T) == 2 ? 4 : 2;   // fp32 fragments are twice as large
+  for (int tg = t0; tg < t1; tg += 32 * PRE) {
+    KvFrags<T, HD> f[PRE];
+#pragma unroll
+    for (int u = 0; u < PRE; ++u) load_kv<T, HD>(f[u], kbase, vbase, tg + 32 * u < t1 ? tg + 32 * u : t0, lane);
+#pragma unroll
+    for (int u = 0; u < PRE; ++u)
+      if (tg + 32 * u < t1) step(f[u], tg + 32 * u);
   }
   // write the partial
   float l = lrun;
