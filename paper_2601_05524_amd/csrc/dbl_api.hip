@@ -301,7 +301,15 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
 template <typename T, int HD>
 void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
   const int nblocks = B * s.attn.Hkv * s.attn.nsplit * s.nqg;
-  hipLaunchKernelGGL((attn_split_kernel<T, HD>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+  // four steps of K/V in flight per wave when every workgroup gets a CU of its own (bf16), else two
+  bool deep = false;
+  if constexpr (sizeof(T) == 2) deep = nblocks <= c->n_cu;
+  if (deep) {
+    if constexpr (sizeof(T) == 2)
+      hipLaunchKernelGGL((attn_split_kernel<T, HD, 4>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+  } else {
+    hipLaunchKernelGGL((attn_split_kernel<T, HD, 2>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+  }
   const int waves = M * H;
   hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3((waves + 3) / 4), dim3(256), 0, c->stream, s.comb);
 }

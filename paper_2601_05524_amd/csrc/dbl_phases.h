@@ -177,7 +177,7 @@ __device__ __forceinline__ void load_kv(KvFrags<T, HD>& f, const T* kbase, const
 
 // task = ((b * Hkv + kvh) * nsplit + sp) * nqb + qb.  The next step's K/V are fetched
 // into registers while the current one is computed.
-template <typename T, int HD>
+template <typename T, int HD, int PRE>
 __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
   constexpr int KSTEPS = HD / 32, HT = HD / 16;
   const int lane = threadIdx.x & 63, c = lane & 15, g4 = lane >> 4;
@@ -249,12 +249,12 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
     for (int h = 0; h < HT; ++h) o[h] = o[h] * alpha;
     pv_accumulate<HT>(o, f.vf, s[0], s[1]);
   };
-  // The K/V of PRE steps (128 tokens) are requested together, before any of them is used:
-  // a step computes in a fraction of a memory round trip, so fetching only one step ahead
-  // costs one round trip per step.  A wave of this kernel has the CU's registers to itself
-  // (one workgroup of at most 4 waves per CU), which is what the PRE register sets need.
+  // The K/V of PRE steps are requested together, before any of them is used: a step
+  // computes in a fraction of a memory round trip, so fetching only one step ahead costs one
+  // round trip per step.  PRE = 4 (128 tokens) needs the CU's registers for one workgroup
+  // (256 VGPRs + 114 AGPRs per lane): right when there is at most one workgroup per CU;
+  // with more workgroups than CUs PRE = 2 lets two of them share a CU.
   // Steps beyond the range re-read its first step (a valid address) and are skipped.
-  constexpr int PRE = sizeof(T) == 2 ? 4 : 2;   // fp32 fragments are twice as large
   for (int tg = t0; tg < t1; tg += 32 * PRE) {
     KvFrags<T, HD> f[PRE];
 #pragma unroll
@@ -275,13 +275,13 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
 // grid = B * Hkv * nsplit * ceil(nqb / wpg) workgroups of wpg waves; the waves of a
 // workgroup own consecutive query blocks of the same K/V range, so those reads are
 // shared through the CU's L1.
-template <typename T, int HD>
+template <typename T, int HD, int PRE>
 __global__ void __launch_bounds__(256) attn_split_kernel(const AttnArgs<T> a) {
   const int wpg = blockDim.x >> 6;
   const int nqg = (a.nqb + wpg - 1) / wpg;
   const int qb = (blockIdx.x % nqg) * wpg + (threadIdx.x >> 6);
   if (qb >= a.nqb) return;
-  attn_task<T, HD>(a, (blockIdx.x / nqg) * a.nqb + qb);
+  attn_task<T, HD, PRE>(a, (blockIdx.x / nqg) * a.nqb + qb);
 }
 
 // Merge the split partials of one (row m, query head): softmax-weighted sum,
