@@ -29,7 +29,7 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # rocprofv3 --pmc runs (FETCH_SIZE scaled by 2.000, the factor a plain 1 GiB copy gives on
 # this box, plus WRITE_SIZE); summary in profiles/gate_up_projection_llama70b_traffic.txt.
 # Counters cannot be read inside this process, so the figure is the recorded one.
-MEASURED_TRAFFIC = {"llama70b_ctx2048_k8_b1_greedy": 944_825_344}
+MEASURED_TRAFFIC = {"llama70b_ctx2048_k8_b1_greedy": 944_741_376}   # 922 599 KiB
 
 WORKLOADS = {
     # name: (shape key, context, k, batch, mode, temperature, repeat fraction, span lo, span hi)
