@@ -9,8 +9,12 @@ LLaMA-3.3-70B-shaped bf16 target (80 layers, d 8192, 64/8 heads, FFN 28672, voca
 real prefill of a Zipf(1.1) token stream with 20% repeated 16-grams, window k = 8,
 batch 1, greedy acceptance.
 
-Prints ONE JSON line (see the design doc for every field).  `--gpus N` with N > 1 is not
-supported: this build runs on one GPU.
+Prints ONE JSON line: metric/value/unit (verified window positions per second), ms_per_step,
+hbm_GBps_step (algorithmic bytes of a step / step time), breakdown_ms (per call, from events on
+the context's stream), projections (each projection kernel timed alone), roofline (the dominant
+kernel, fused gate/up: achieved GB/s from live HIP-event timing, recorded HBM traffic) and
+cpu_baseline (the CPU oracle timed on this host).  `--gpus N` with N > 1 is not supported: this
+build runs on one GPU.  `--double` measures the two-model Double round instead.
 """
 from __future__ import annotations
 
