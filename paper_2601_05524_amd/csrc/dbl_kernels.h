@@ -22,11 +22,11 @@ __global__ void __launch_bounds__(256) embed_kernel(const T* __restrict__ E, con
   tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
   const T* e = E + (size_t)tok * d;
   float s = 0.f;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) {
-    const float v = Elem<T>::to_f(e[i]);
-    h[(size_t)m * ldh + i] = v;
-    hg[(size_t)m * ldh + i] = v * gain[i];
-    s += v * v;
+  for (int i = 4 * threadIdx.x; i < d; i += 4 * blockDim.x) {      // d is a multiple of 16
+    const f32x4 v = {Elem<T>::to_f(e[i]), Elem<T>::to_f(e[i + 1]), Elem<T>::to_f(e[i + 2]), Elem<T>::to_f(e[i + 3])};
+    *reinterpret_cast<f32x4*>(h + (size_t)m * ldh + i) = v;
+    *reinterpret_cast<f32x4*>(hg + (size_t)m * ldh + i) = v * *reinterpret_cast<const f32x4*>(gain + i);
+    s += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
   }
   s = block_sum(s, scratch);
   for (int p = threadIdx.x; p < SSQ_PARTS; p += blockDim.x) ssq[(size_t)m * SSQ_PARTS + p] = p == 0 ? s : 0.f;
@@ -47,19 +47,21 @@ struct AcceptArgs {
   uint64_t seed, step;
 };
 
-// One workgroup per sequence.  Merges the LM-head statistics of its k rows, runs
-// the acceptance scan, and (dense q only) makes one pass over the rejected row to
+// One workgroup per sequence.  Merges the LM-head statistics of its k rows (one wave per
+// row), runs the acceptance scan, and (dense q only) makes one pass over the rejected row to
 // draw from max(0, p - q).
 __global__ void __launch_bounds__(256) accept_kernel(const AcceptArgs a) {
   __shared__ LmStat row[32];
-  __shared__ LmStat tmp[4];
   __shared__ int s_n, s_need_resid, s_tok;
   __shared__ float s_lse;
   __shared__ float rbest[4]; __shared__ int rbest_id[4];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint64_t stepv = a.step + *a.commits;
 
-  for (int j = 0; j < a.k; ++j) {
+  // one wave per window row (rows wave, wave + 4, ...): each lane merges its share of the
+  // per-workgroup statistics, then a butterfly inside the wave; lanes and shares are fixed, so
+  // the soft-max sums are always added in the same order
+  for (int j = wave; j < a.k; j += (int)(blockDim.x >> 6)) {
     const int m = b * a.k + j;
     LmStat s;
     s.best = -INFINITY; s.best_id = 0x7fffffff; s.smax = -INFINITY; s.ssum = 0.f; s.zdraft = -INFINITY;
@@ -75,8 +77,7 @@ __global__ void __launch_bounds__(256) accept_kernel(const AcceptArgs a) {
         x.p1 = y.p1; x.p1_id = y.p1_id;
       } else if (better(y.p1, y.p1_id, x.p2, x.p2_id)) { x.p2 = y.p1; x.p2_id = y.p1_id; }
     };
-    for (int i = tid; i < a.nstat; i += blockDim.x) merge(s, a.stats[(size_t)i * a.Mtot + m]);
-    // butterfly inside the wave, then across the 4 waves (fixed order)
+    for (int i = lane; i < a.nstat; i += 64) merge(s, a.stats[(size_t)i * a.Mtot + m]);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
       LmStat o;
@@ -86,15 +87,9 @@ __global__ void __launch_bounds__(256) accept_kernel(const AcceptArgs a) {
       o.p2 = __shfl_xor(s.p2, off); o.p2_id = __shfl_xor(s.p2_id, off);
       merge(s, o);
     }
-    if (lane == 0) tmp[wave] = s;
-    __syncthreads();
-    if (tid == 0) {
-      LmStat r = tmp[0];
-      for (int w = 1; w < (int)(blockDim.x >> 6); ++w) merge(r, tmp[w]);
-      row[j] = r;
-    }
-    __syncthreads();
+    if (lane == 0) row[j] = s;
   }
+  __syncthreads();
 
   const int32_t* win = a.window + (size_t)b * a.k;
   if (tid == 0) {
