@@ -115,6 +115,12 @@ int dbl_get_weights(dbl_ctx* ctx, int tensor_id, int layer, void* host, size_t b
  * rejected tier. */
 int dbl_reset(dbl_ctx* ctx, int seq);
 
+/* Measurement aid (bandwidth runs at contexts too long to prefill): pretend that the first
+ * n_tokens positions of sequence `seq` are committed.  Their K and V rows get seeded values of
+ * unit scale in every layer (not the model's own keys and values) and kv_len[seq] = n_tokens;
+ * the history is not touched.  0 <= n_tokens <= max_ctx - max_window.  Only enqueues. */
+int dbl_kv_fill(dbl_ctx* ctx, int seq, int32_t n_tokens, uint64_t seed);
+
 /* Rollback (Alg. 1 "rollback M_q", Alg. 2 "rollback both models"): sequence `seq`
  * forgets the KV rows beyond kv_len and the history tokens beyond hist_len:
  * kv_len[seq] = min(kv_len[seq], kv_len), hist_len[seq] = min(hist_len[seq], hist_len);

@@ -20,7 +20,7 @@ DBL_FLAG_VALIDATE_ONLY = 1
 T_EMB, T_LM, T_GF = 0, 1, 2
 T_G1, T_WQ, T_WK, T_WV, T_GQ, T_GK, T_WO, T_G2, T_WG, T_WU, T_WD = range(10, 21)
 
-EXPORTS = ["dbl_create", "dbl_destroy", "dbl_last_error", "dbl_set_weights", "dbl_get_weights", "dbl_reset", "dbl_truncate",
+EXPORTS = ["dbl_create", "dbl_destroy", "dbl_last_error", "dbl_set_weights", "dbl_get_weights", "dbl_reset", "dbl_truncate", "dbl_kv_fill",
            "dbl_retrieve_tiered", "dbl_session_mark", "dbl_prior_set", "dbl_rejected_update", "dbl_rejected_get",
            "dbl_history_set", "dbl_history_get", "dbl_retrieve", "dbl_build_window", "dbl_verify_block", "dbl_accept",
            "dbl_kv_commit", "dbl_kv_len", "dbl_hist_len", "dbl_model_bytes", "dbl_debug_buffer",
@@ -61,6 +61,7 @@ def lib():
         L.dbl_get_weights.argtypes = [vp, i, i, vp, C.c_size_t]
         L.dbl_reset.argtypes = [vp, i]
         L.dbl_truncate.argtypes = [vp, i, C.c_int32, C.c_int32]
+        L.dbl_kv_fill.argtypes = [vp, i, C.c_int32, C.c_uint64]
         L.dbl_retrieve_tiered.argtypes = [vp, i, i, i, i, i32p, i32p, i32p, i32p, i32p]
         L.dbl_prior_set.argtypes = [vp, i32p, i]
         L.dbl_session_mark.argtypes = [vp, i, C.c_int32]
@@ -127,6 +128,10 @@ def dbl_get_weights(ctx, tensor_id, layer, host_array):
 
 def dbl_reset(ctx, seq=-1):
     return _chk(ctx, lib().dbl_reset(ctx, seq))
+
+
+def dbl_kv_fill(ctx, seq, n_tokens, seed):
+    return _chk(ctx, lib().dbl_kv_fill(ctx, seq, int(n_tokens), int(seed)))
 
 
 def dbl_truncate(ctx, seq, kv_len=-1, hist_len=-1):

@@ -207,12 +207,38 @@ void launch_gemm_t(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
   }
 }
 
+// More than 16 rows (and not the LM head): passes of 16*R rows through gemm_rows_kernel.
+template <typename T, int R>
+void launch_gemm_rows(dbl_ctx* c, const GemmPlan& p, int epi, const GemmArgs<T>& a) {
+  constexpr int KSR = sizeof(T) == 2 ? 8 : 4;
+  GemmArgs<T> b = a;
+  b.NCH = p.NCH * (p.KS / KSR);     // the same k-blocks of a super slice, in chunks of NW * KSR
+  const dim3 grid(p.grid), block(p.NW * 64);
+  switch (epi) {
+    case EPI_PARTIAL: hipLaunchKernelGGL((gemm_rows_kernel<T, EPI_PARTIAL, KSR, R>), grid, block, 0, c->stream, b); break;
+    case EPI_RESIDUAL: hipLaunchKernelGGL((gemm_rows_kernel<T, EPI_RESIDUAL, KSR, R>), grid, block, 0, c->stream, b); break;
+    default: hipLaunchKernelGGL((gemm_rows_kernel<T, EPI_SWIGLU, KSR, R>), grid, block, 0, c->stream, b); break;
+  }
+}
+
 template <typename T>
 void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
   a.NT = p.NT; a.N = p.N; a.KBp = p.KBp; a.SS = p.SS; a.NCH = p.NCH; a.Mtot = M;
   a.d = (float)c->cfg.d_model; a.eps = c->cfg.rms_eps; a.ssq_in = c->ssq; a.ssq_out = c->ssq;
   a.tile_ctr = c->tile_ctr;
   static_assert(SSQ_PARTS == 256, "xn_kernel adds one partial per thread");
+  if (M > 16 && epi != EPI_LMHEAD) {
+    T* xn = reinterpret_cast<T*>(c->xn);
+    for (int m0 = 0; m0 < M; m0 += 64) {
+      a.m0 = m0; a.mrows = std::min(64, M - m0);
+      if (epi != EPI_RESIDUAL) {     // the RMSNorm output is stored first and read like any activation
+        hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, a.d, a.eps);
+        a.X = xn;
+      }
+      if (a.mrows > 32) launch_gemm_rows<T, 4>(c, p, epi, a); else launch_gemm_rows<T, 2>(c, p, epi, a);
+    }
+    return;
+  }
   for (int m0 = 0; m0 < M; m0 += 16) {
     a.m0 = m0; a.mrows = std::min(16, M - m0);
     if (epi != EPI_RESIDUAL && a.mrows > 8) {
@@ -625,6 +651,31 @@ int dbl_reset(dbl_ctx* c, int seq) {
   if (c->dry) return DBL_ENODEV;
   hipLaunchKernelGGL(set_counters_kernel, dim3(1), dim3(128), 0, c->stream, c->kv_len, c->hist_len, c->prompt_len, c->rej_len, seq,
                      c->cfg.max_batch);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+int dbl_kv_fill(dbl_ctx* c, int seq, int32_t n_tokens, uint64_t seed) {
+  if (!c) return DBL_EINVAL;
+  const dbl_model_cfg& g = c->cfg;
+  if (seq < 0 || seq >= g.max_batch) return fail(c, DBL_EINVAL, "seq out of range");
+  if (n_tokens < 0 || n_tokens > g.max_ctx - g.max_window) return fail(c, DBL_EINVAL, "n_tokens out of range");
+  c->kv_upper[seq] = n_tokens;
+  c->have_verify = c->have_accept = false;
+  if (c->dry) return DBL_ENODEV;
+  const size_t region = (size_t)g.max_ctx * g.head_dim;                       // one (sequence, kv head)
+  const size_t n = (size_t)((n_tokens + 31) / 32 * 32) * g.head_dim;          // whole tiles
+  if (n > 0 && g.n_layers > 0) {
+    const dim3 grid((unsigned)((n + 255) / 256), (unsigned)(g.n_layers * g.n_kv_heads));
+    const size_t seq_off = (size_t)seq * g.n_kv_heads * region;
+    if (c->bf16)
+      hipLaunchKernelGGL((fill_kv_kernel<bf16_t>), grid, dim3(256), 0, c->stream, reinterpret_cast<bf16_t*>(c->kc) + seq_off,
+                         reinterpret_cast<bf16_t*>(c->vt) + seq_off, region, c->kv_layer_elems, g.n_kv_heads, n, seed);
+    else
+      hipLaunchKernelGGL((fill_kv_kernel<float>), grid, dim3(256), 0, c->stream, reinterpret_cast<float*>(c->kc) + seq_off,
+                         reinterpret_cast<float*>(c->vt) + seq_off, region, c->kv_layer_elems, g.n_kv_heads, n, seed);
+  }
+  hipLaunchKernelGGL(set_kv_len_kernel, dim3(1), dim3(64), 0, c->stream, c->kv_len, seq, n_tokens);
   HIPCHK(c, hipGetLastError());
   return DBL_OK;
 }

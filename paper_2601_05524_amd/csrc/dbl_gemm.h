@@ -410,6 +410,137 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Windows of more than 16 rows: the same weight streaming, but every weight fragment is
+// multiplied with R row groups of 16 rows before the next one is fetched, so the weights are
+// read once per 16*R rows instead of once per 16.  The activation registers then hold R
+// groups, which leaves room for only KS k-blocks per wave and chunk (8 in bf16): every
+// projection walks K in chunks (NCH = k-blocks of a super slice / (NW*KS)), and the
+// activations of the next chunk are fetched when the current one is done (the ring drains once
+// per chunk; at 16*R rows per weight byte that is cheap).  Activations are always stored
+// tensors of type T (the host runs xn_kernel first for the normalising projections).
+// Epilogues as in gemm_stream_kernel, one row group at a time through one LDS buffer; tiles
+// are static; the LM head is not handled here (its per-row statistics stay on 16-row passes).
+template <typename T, int EPI, int KS, int R>
+__global__ void __launch_bounds__(512) gemm_rows_kernel(const GemmArgs<T> a) {
+  constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
+  constexpr int RING = KS;
+  static_assert(EPI != EPI_LMHEAD, "the LM head runs on 16-row passes");
+  __shared__ f32x4 red[8][NACC][WAVE];
+  const int wg = blockIdx.x, nwg = gridDim.x, nw = blockDim.x >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int ss = wg % a.SS, tstep = nwg / a.SS;
+  int t = wg / a.SS;
+  const int nch = a.NCH, seg = nw * KS;
+  const int kb0 = ss * nch * seg + wave * KS;
+  const T* wlane = a.W + (size_t)kb0 * BLOCK_ELEMS;
+  const size_t row_elems = (size_t)a.KBp * BLOCK_ELEMS, seg_elems = (size_t)seg * BLOCK_ELEMS;
+
+  Frag<T> ring[RING];
+  {
+    const int tf = t < a.NT ? t : 0;
+#pragma unroll
+    for (int j = 0; j < RING; ++j) ring[j] = frag_load_w(wlane + (size_t)tf * NACC * row_elems, j, lane);
+  }
+  Frag<T> breg[R][KS];
+  auto load_b = [&](int kblk) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const T* xp = a.X + (size_t)(a.m0 + min(16 * r + c, a.mrows - 1)) * a.ldx + (size_t)kblk * TILE_K + g * 8;
+#pragma unroll
+      for (int j = 0; j < KS; ++j) breg[r][j] = frag_load_row(xp + j * TILE_K);
+    }
+  };
+  load_b(kb0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): enter the loop with nothing but known loads in flight
+
+  f32x4 acc[R][NACC];
+  float sq[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    sq[r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NACC; ++s) acc[r][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  int ch = 0;
+  while (t < a.NT) {
+    const bool last = ch + 1 == nch;
+    const int tn = t + tstep, tnc = tn < a.NT ? tn : 0;
+    const T* wcur = wlane + (size_t)t * NACC * row_elems + (size_t)ch * seg_elems;
+    const T* wnext = last ? wlane + (size_t)tnc * NACC * row_elems : wcur + seg_elems;
+#pragma unroll
+    for (int s = 0; s < NACC; ++s) {
+#pragma unroll
+      for (int j = 0; j < KS; ++j) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[r][s] = mma(ring[j], breg[r][j], acc[r][s]);
+        if (s + 1 < NACC) ring[j] = frag_load_w(wcur + (s + 1) * row_elems, j, lane);
+        else ring[j] = frag_load_w(wnext, j, lane);
+        __builtin_amdgcn_sched_barrier(0x6);
+      }
+    }
+    // activations of the next chunk (chunk 0 of the next tile after the last one): one reload
+    // site, issued before the epilogue so that it overlaps it
+    load_b(kb0 + (last ? 0 : ch + 1) * seg);
+    if (!last) { ++ch; continue; }
+    // tile done: reduce and finish one row group at a time
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (wave != 0) {
+#pragma unroll
+        for (int s = 0; s < NACC; ++s) red[wave][s][lane] = acc[r][s];
+      }
+      __syncthreads();
+      if (wave == 0) {
+        for (int w = 1; w < nw; ++w) {
+#pragma unroll
+          for (int s = 0; s < NACC; ++s) acc[r][s] += red[w][s][lane];
+        }
+        const int mr = 16 * r + c;
+        if (mr < a.mrows) {
+          const int m = a.m0 + mr;
+          const int n = t * TILE_N + 4 * g;
+          if (EPI == EPI_PARTIAL) {
+            *reinterpret_cast<f32x4*>(a.out + ((size_t)ss * a.Mtot + m) * a.ldo + n) = acc[r][0];
+          } else if (EPI == EPI_RESIDUAL) {
+            f32x4* hp = reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n);
+            const f32x4 hv = *hp + acc[r][0];
+            *hp = hv;
+            *reinterpret_cast<f32x4*>(a.hg_out + (size_t)m * a.ldo + n) = hv * *reinterpret_cast<const f32x4*>(a.gain_out + n);
+            sq[r] += (hv.x * hv.x + hv.y * hv.y) + (hv.z * hv.z + hv.w * hv.w);
+          } else {   // EPI_SWIGLU
+            f32x4 v;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float gt = acc[r][0][i], up = acc[r][NACC - 1][i];
+              v[i] = (n + i < a.N) ? gt / (1.f + expf(-gt)) * up : 0.f;
+            }
+            st_round4(a.act + (size_t)m * a.ldact + n, v);
+          }
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int s = 0; s < NACC; ++s) acc[r][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    t = tn; ch = 0;
+  }
+
+  if (EPI == EPI_RESIDUAL && wave == 0) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      float v = sq[r];
+      v += __shfl_xor(v, 16); v += __shfl_xor(v, 32);
+      const int mr = 16 * r + c;
+      if (g == 0 && mr < a.mrows) {
+        float* dst = a.ssq_out + (size_t)(a.m0 + mr) * SSQ_PARTS;
+        for (int p = wg; p < SSQ_PARTS; p += nwg) dst[p] = p == wg ? v : 0.f;
+      }
+    }
+  }
+}
+
 // xn[row][:] = T(hg[row][:] * rsqrt(mean(h[row]^2) + eps)) for rows m0 + blockIdx.x: the
 // RMSNorm output as a stored tensor, for projection passes of more than 8 rows.
 // 256 threads; thread p adds slot p of the row's sum-of-squares partials.
