@@ -85,6 +85,16 @@ def test_llama70b_full_depth_properties():
     print("accepted lengths:", accepted)
     assert accepted[1] >= 2
 
+    # the first row of a k-row window sees exactly what a one-row window sees (same token, same
+    # cache); the two differ only in how the attention splits the context, i.e. in summation order
+    w8 = windows[-1]
+    row0_k8 = g.verify([w8])[0][0]
+    row0_k1 = g.verify([w8[:1]])[0][0]
+    d = np.abs(row0_k8.astype(np.float64) - row0_k1)
+    print("row 0 of a k=8 window vs a k=1 window: max-abs %.3g, rms %.3g (logit rms %.3g)" % (
+        d.max(), np.sqrt((d ** 2).mean()), row0_k8.std()))
+    assert np.sqrt((d ** 2).mean()) <= 0.05 * row0_k8.std()
+
     # run 2 from a reset context: identical bits
     g.prefill([prompt], 16)            # resets the context first
     for i in range(STEPS):
