@@ -263,7 +263,6 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
 template <typename T>
 struct LayerSteps {
   GemmArgs<T> qkv, o, gu, dn;
-  RopeArgs<T> rope;
   AttnArgs<T> attn;
   CombineArgs<T> comb;
   int wpg, nqg;     // attention: waves per workgroup, workgroups per (b, kv head, split)
@@ -275,7 +274,6 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
   const int M = B * k, d = g.d_model, hd = g.head_dim, H = g.n_q_heads, Hkv = g.n_kv_heads;
   T* attn = reinterpret_cast<T*>(c->attn);
   T* act = reinterpret_cast<T*>(c->act);
-  T* qbuf = reinterpret_cast<T*>(c->qbuf);
   T* kc = reinterpret_cast<T*>(c->kc) + (size_t)l * c->kv_layer_elems;
   T* vt = reinterpret_cast<T*>(c->vt) + (size_t)l * c->kv_layer_elems;
   LayerSteps<T> s{};
@@ -283,33 +281,33 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
   s.qkv.W = reinterpret_cast<const T*>(c->w_qkv) + (size_t)l * c->p_qkv.elems();
   s.qkv.HG = c->hg; s.qkv.ldx = c->ldh;
   s.qkv.out = c->qkv_part; s.qkv.ldo = c->p_qkv.ldo();
-  RopeArgs<T>& r = s.rope;
-  r.qkv = c->qkv_part; r.nparts = c->p_qkv.SS; r.Mtot = M; r.ldq = c->p_qkv.ldo();
-  r.gq = g.qk_norm ? c->gq + (size_t)l * hd : nullptr;
-  r.gk = g.qk_norm ? c->gk + (size_t)l * hd : nullptr;
-  r.cosT = c->cosT; r.sinT = c->sinT; r.kv_len = c->kv_len;
-  r.qbuf = qbuf; r.kc = kc; r.vt = vt;
-  r.k = k; r.H = H; r.Hkv = Hkv; r.hd = hd; r.max_ctx = g.max_ctx; r.max_batch = g.max_batch;
-  r.qrows_pad = c->qrows_pad; r.eps = g.rms_eps;
+  QkvSrc src{};
+  src.qkv = c->qkv_part; src.nparts = c->p_qkv.SS; src.Mtot = M; src.ldq = c->p_qkv.ldo();
+  src.gq = g.qk_norm ? c->gq + (size_t)l * hd : nullptr;
+  src.gk = g.qk_norm ? c->gk + (size_t)l * hd : nullptr;
+  src.cosT = c->cosT; src.sinT = c->sinT; src.H = H; src.Hkv = Hkv; src.eps = g.rms_eps;
   // attention geometry for this window size
   const int gq = H / Hkv, nq = gq * k, qblocks = (nq + 15) / 16;
   s.wpg = std::min(qblocks, 4);              // waves (query blocks) per workgroup
   s.nqg = (qblocks + s.wpg - 1) / s.wpg;
+  // splits: ncs over the cached tokens (none when every cache is empty) + 1 for the window rows
   int ctx_upper = 0;
-  for (int b = 0; b < B; ++b) ctx_upper = std::max(ctx_upper, c->kv_upper[b] + k);
-  int nsplit = (2 * c->n_cu + B * Hkv * s.nqg - 1) / (B * Hkv * s.nqg);
+  for (int b = 0; b < B; ++b) ctx_upper = std::max(ctx_upper, c->kv_upper[b]);
+  int ncs = (2 * c->n_cu + B * Hkv * s.nqg - 1) / (B * Hkv * s.nqg);
   // at least 128 tokens per split: the partials (m, l, O) are written and read back, so
   // finer splits cost more in traffic than they gain in parallelism
-  nsplit = std::max(1, std::min({nsplit, MAX_SPLITS, (ctx_upper + 127) / 128}));
+  ncs = std::min({ncs, MAX_SPLITS - 1, (ctx_upper + 127) / 128});
   if (const char* e = std::getenv("DBL_ATTN_SPLIT_TOKENS")) {   // tuning aid
     const int tok = std::max(32, std::atoi(e));
-    nsplit = std::max(1, std::min(MAX_SPLITS, (ctx_upper + tok - 1) / tok));
+    ncs = std::min(MAX_SPLITS - 1, (ctx_upper + tok - 1) / tok);
   }
+  const int nsplit = ncs + 1;
   AttnArgs<T>& at = s.attn;
-  at.qbuf = qbuf; at.kc = kc; at.vt = vt; at.kv_len = c->kv_len; at.pm = c->pm; at.pl = c->pl; at.po = c->po;
+  at.src = src; at.qbuf = reinterpret_cast<const T*>(c->qbuf); at.kc = kc; at.vt = vt; at.kv_len = c->kv_len; at.pm = c->pm; at.pl = c->pl; at.po = c->po;
   at.k = k; at.g = gq; at.Hkv = Hkv; at.hd = hd; at.max_ctx = g.max_ctx; at.qrows_pad = c->qrows_pad;
   at.nsplit = nsplit; at.nqb = qblocks; at.scale = (float)(1.4426950408889634 / std::sqrt((double)hd));
-  s.comb = CombineArgs<T>{c->pm, c->pl, c->po, attn, c->p_o.ldx(), M, k, H, Hkv, c->qrows_pad, nsplit};
+  s.comb = CombineArgs<T>{c->pm, c->pl, c->po, attn, c->p_o.ldx(), M, k, H, Hkv, c->qrows_pad, nsplit,
+                          src, c->kv_len, kc, vt, g.max_ctx};
   s.o.W = reinterpret_cast<const T*>(c->w_o) + (size_t)l * c->p_o.elems();
   s.o.X = attn; s.o.ldx = c->p_o.ldx(); s.o.out = c->h; s.o.ldo = c->ldh;      // h += attn Wo^T
   s.o.hg_out = c->hg; s.o.gain_out = c->g2 + (size_t)l * c->ldh;
@@ -327,16 +325,24 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
 template <typename T, int HD>
 void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
   const int nblocks = B * s.attn.Hkv * s.attn.nsplit * s.nqg;
-  // four steps of K/V in flight per wave when every workgroup gets a CU of its own (bf16), else two
+  // bf16: four steps of K/V in flight per wave and queries built in place when every workgroup
+  // gets a CU of its own (latency form), else two steps, two workgroups per CU and queries
+  // prepared once by a kernel of their own (throughput form)
   bool deep = false;
   if constexpr (sizeof(T) == 2) deep = nblocks <= c->n_cu;
   if (deep) {
     if constexpr (sizeof(T) == 2)
       hipLaunchKernelGGL((attn_split_kernel<T, HD, 4>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
   } else {
+    if constexpr (sizeof(T) == 2) {
+      RopeQArgs<T> q{s.attn.src, s.attn.kv_len, reinterpret_cast<T*>(c->qbuf), B, s.attn.k, s.attn.g, s.attn.qrows_pad,
+                     s.attn.max_ctx};
+      const int qwaves = (B * s.attn.Hkv * s.attn.g * s.attn.k + 15) / 16;
+      hipLaunchKernelGGL((rope_q_kernel<T, HD>), dim3((qwaves + 3) / 4), dim3(256), 0, c->stream, q);
+    }
     hipLaunchKernelGGL((attn_split_kernel<T, HD, 2>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
   }
-  const int waves = M * H;
+  const int waves = combine_waves<T>(M, H, s.attn.Hkv);   // merge tasks, then KV-append tasks
   hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3((waves + 3) / 4), dim3(256), 0, c->stream, s.comb);
 }
 
@@ -351,8 +357,6 @@ int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperatu
   for (int l = 0; l < g.n_layers; ++l) {
     const LayerSteps<T> s = layer_steps<T>(c, l, B, k);
     launch_gemm<T>(c, c->p_qkv, EPI_PARTIAL, s.qkv, M);
-    const int waves = M * (H + 2 * g.n_kv_heads);
-    hipLaunchKernelGGL((rope_kv_kernel<T>), dim3((waves + 3) / 4), dim3(256), 0, st, s.rope);
     if (hd == 128) launch_attn_hd<T, 128>(c, s, B, M, H); else launch_attn_hd<T, 64>(c, s, B, M, H);
     launch_gemm<T>(c, c->p_o, EPI_RESIDUAL, s.o, M);
     launch_gemm<T>(c, c->p_gu, EPI_SWIGLU, s.gu, M);
@@ -559,8 +563,8 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(ssq, (size_t)Mmax * SSQ_PARTS * 4, true);
     ALLOC(tile_ctr, (DYN_DONE + 1) * sizeof(unsigned), true);
     ALLOC(qkv_part, (size_t)c->p_qkv.SS * Mmax * c->p_qkv.ldo() * 4, true);
-    ALLOC(logits, (size_t)Mmax * c->p_lm.ldo() * 4, true);
     ALLOC(qbuf, (size_t)g.max_batch * g.n_kv_heads * c->qrows_pad * g.head_dim * esz, true);
+    ALLOC(logits, (size_t)Mmax * c->p_lm.ldo() * 4, true);
     ALLOC(attn, (size_t)Mmax * c->p_o.ldx() * esz, true);
     ALLOC(act, (size_t)Mmax * c->p_d.ldx() * esz, true);
     ALLOC(pm, part_rows * 4, true); ALLOC(pl, part_rows * 4, true); ALLOC(po, part_rows * g.head_dim * 4, true);

@@ -1,6 +1,7 @@
-// The per-layer steps between the projections: q/k-norm + RoPE + KV append, split-KV
-// GQA attention, combine.  Each is a device function over a "task" index (one wave per
-// task) with a thin kernel around it.
+// The per-layer steps between the projections: split-KV GQA attention (q/k-norm and RoPE
+// applied while it loads its operands) and the merge of its partials, which also appends
+// the window rows to the KV cache.  Each is a device function over a "task" index (one
+// wave per task) with a thin kernel around it.
 #pragma once
 #include "dbl_dev.h"
 
@@ -27,82 +28,135 @@ __device__ __forceinline__ float block_sum(float v, float* scratch) {
   return t;
 }
 
-// ---------------------------------------------- q/k norm + RoPE + KV append
+// ---------------------------------------------- q/k norm + RoPE on load, KV append
 
-// One wave per task = (row m, head hh) with hh in [0, H + 2*Hkv): q heads, then k
-// heads, then v heads.  Sums the QKV partials, applies the optional per-head RMSNorm
-// and the rotary embedding (pairs (i, i+hd/2); cos/sin from the fp32 table at the
-// row's position kv_len[b] + j), rounds to T, and writes
-//   q  -> qbuf[b][kvh][j*g + hg][hd]
-//   k  -> kc[layer][b][kvh] at kc_offset(pos, dim)     (MFMA-tiled, see dbl_dev.h)
-//   v  -> vt[layer][b][kvh] at vt_offset(pos, dim)
-template <typename T>
-struct RopeArgs {
+// Where the q/k/v projection left its result (nparts partial sums per element; columns: the
+// q heads, then the k heads, then the v heads) and what turns it into attention operands.
+// There is no kernel for this step: the attention builds its query and window-row operands
+// from here, and the kernel that merges the attention partials appends the window rows to
+// the KV cache.
+struct QkvSrc {
   const float* qkv; int nparts, Mtot, ldq;   // partials [nparts][Mtot][ldq]
-  const float *gq, *gk;                      // per-head gains (qk_norm) or nullptr
+  const float *gq, *gk;                      // per-head RMSNorm gains (qk_norm) or nullptr
   const float *cosT, *sinT;                  // [max_ctx][hd/2]
-  const int32_t* kv_len;                     // [B]
-  T *qbuf, *kc, *vt;                         // kc / vt already offset to the layer
-  int k, H, Hkv, hd, max_ctx, max_batch, qrows_pad;
+  int H, Hkv;
   float eps;
 };
 
-template <typename T>
-__device__ __forceinline__ void rope_task(const RopeArgs<T>& a, int task) {
-  const int lane = threadIdx.x & 63;
-  const int heads = a.H + 2 * a.Hkv;
-  const int m = task / heads, hh = task % heads;
-  const int b = m / a.k, j = m % a.k;
-  const int pos = a.kv_len[b] + j;
-  if (pos >= a.max_ctx) return;   // capacity guard; the host refuses such calls
-  const int hd = a.hd, half = hd >> 1;
-  // lane i < half holds the pair (i, i+half); hd = 128 -> 64 lanes, hd = 64 -> 32 lanes
-  const bool act = lane < half;
-  float x0 = 0.f, x1 = 0.f;
-  if (act) {
-    for (int p = 0; p < a.nparts; ++p) {
-      const float* src = a.qkv + ((size_t)p * a.Mtot + m) * a.ldq + (size_t)hh * hd;
-      x0 += *(src + lane); x1 += *(src + lane + half);
-    }
+__device__ __forceinline__ Frag<bf16_t> frag_round(const float (&x)[8], bf16_t) {
+  Frag<bf16_t> f;
+  f.v = u32x4{pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7])};
+  return f;
+}
+__device__ __forceinline__ Frag<float> frag_round(const float (&x)[8], float) {
+  Frag<float> f;
+  f.lo = f32x4{x[0], x[1], x[2], x[3]}; f.hi = f32x4{x[4], x[5], x[6], x[7]};
+  return f;
+}
+
+// Sum over the partials of 8 consecutive columns of row m, in partial order.
+__device__ __forceinline__ void qkv_sum8(const QkvSrc& s, int m, int col, float (&x)[8]) {
+  const size_t pstride = (size_t)s.Mtot * s.ldq;
+  const float* src = s.qkv + (size_t)m * s.ldq + col;
+  f32x4 a = *reinterpret_cast<const f32x4*>(src), b = *reinterpret_cast<const f32x4*>(src + 4);
+  if (s.nparts > 1) {   // the usual case, written out so that both partials are in flight together
+    a += *reinterpret_cast<const f32x4*>(src + pstride); b += *reinterpret_cast<const f32x4*>(src + pstride + 4);
   }
-  const bool is_q = hh < a.H, is_k = !is_q && hh < a.H + a.Hkv;
-  if (!is_q && !is_k) {  // v head: no norm, no rotation
-    if (act) {
-      const int kvh = hh - a.H - a.Hkv;
-      T* dst = a.vt + (size_t)(b * a.Hkv + kvh) * a.max_ctx * hd;
-      st_round1(dst + vt_offset(pos, lane, hd), x0);
-      st_round1(dst + vt_offset(pos, lane + half, hd), x1);
-    }
-    return;
+  for (int p = 2; p < s.nparts; ++p) {
+    a += *reinterpret_cast<const f32x4*>(src + p * pstride); b += *reinterpret_cast<const f32x4*>(src + p * pstride + 4);
   }
-  const float* gn = is_q ? a.gq : a.gk;
-  if (gn) {
-    float ss = wave_sum(act ? x0 * x0 + x1 * x1 : 0.f);
-    const float r = rsqrtf(ss / (float)hd + a.eps);
-    if (act) { x0 = x0 * r * gn[lane]; x1 = x1 * r * gn[lane + half]; }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { x[e] = a[e]; x[4 + e] = b[e]; }
+}
+
+// One q or k head vector of row m (columns col0 .. col0+HD-1 of the projection result) as MFMA
+// fragments: partial sums added, optional per-head RMSNorm (gain), rotary embedding at
+// position pos (pairs (i, i + HD/2), cos/sin from the fp32 table), rounded to T.  Lane group
+// g4 gets dims ks*32 + 8*g4 .. +7 in out[ks]; a dim and its rotation partner fall in the same
+// lane.  The four lanes l, l^16, l^32, l^48 must work on the same head (they share the
+// sum of squares); every user of a head vector goes through here, so the cache and the
+// in-flight window rows hold the same bits.
+// Two phases, so that a caller can request several heads (and other data) before it waits
+// for any: head_load only issues loads (no branch, no arithmetic), head_finish does the rest.
+template <int HD>
+struct HeadRaw {
+  f32x4 p0[HD / 32][2], p1[HD / 32][2];   // partials 0 and 1 (partial 0 again when there is only one)
+  f32x4 cs[HD / 64][2], sn[HD / 64][2];
+};
+
+template <int HD>
+__device__ __forceinline__ void head_load(const QkvSrc& s, int m, int col0, int pos, int g4, HeadRaw<HD>& r) {
+  constexpr int KSTEPS = HD / 32, HK = KSTEPS / 2, HALF = HD / 2;
+  const float* src = s.qkv + (size_t)m * s.ldq + col0 + 8 * g4;
+  const float* src1 = src + (s.nparts > 1 ? (size_t)s.Mtot * s.ldq : 0);
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks) {
+    r.p0[ks][0] = *reinterpret_cast<const f32x4*>(src + ks * 32); r.p0[ks][1] = *reinterpret_cast<const f32x4*>(src + ks * 32 + 4);
+    r.p1[ks][0] = *reinterpret_cast<const f32x4*>(src1 + ks * 32); r.p1[ks][1] = *reinterpret_cast<const f32x4*>(src1 + ks * 32 + 4);
   }
-  if (act) {
-    const float cs = a.cosT[(size_t)pos * half + lane], sn = a.sinT[(size_t)pos * half + lane];
-    const float y0 = x0 * cs - x1 * sn, y1 = x0 * sn + x1 * cs;
-    if (is_q) {
-      const int g = a.H / a.Hkv, kvh = hh / g, hg = hh % g;
-      T* dst = a.qbuf + ((size_t)(b * a.Hkv + kvh) * a.qrows_pad + (j * g + hg)) * hd;
-      st_round1(dst + lane, y0);
-      st_round1(dst + lane + half, y1);
-    } else {
-      const int kvh = hh - a.H;
-      T* dst = a.kc + (size_t)(b * a.Hkv + kvh) * a.max_ctx * hd;
-      st_round1(dst + kc_offset(pos, lane, hd), y0);
-      st_round1(dst + kc_offset(pos, lane + half, hd), y1);
-    }
+#pragma unroll
+  for (int ks = 0; ks < HK; ++ks) {
+    const size_t o = (size_t)pos * HALF + ks * 32 + 8 * g4;
+    r.cs[ks][0] = *reinterpret_cast<const f32x4*>(s.cosT + o); r.cs[ks][1] = *reinterpret_cast<const f32x4*>(s.cosT + o + 4);
+    r.sn[ks][0] = *reinterpret_cast<const f32x4*>(s.sinT + o); r.sn[ks][1] = *reinterpret_cast<const f32x4*>(s.sinT + o + 4);
   }
 }
 
-template <typename T>
-__global__ void __launch_bounds__(256) rope_kv_kernel(const RopeArgs<T> a) {
-  const int task = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (task >= a.Mtot * (a.H + 2 * a.Hkv)) return;
-  rope_task<T>(a, task);
+template <typename T, int HD>
+__device__ __forceinline__ void head_finish(const QkvSrc& s, const HeadRaw<HD>& r, int m, int col0, const float* gain,
+                                            int g4, Frag<T> (&out)[HD / 32]) {
+  constexpr int KSTEPS = HD / 32, HK = KSTEPS / 2;
+  const float w1 = s.nparts > 1 ? 1.f : 0.f;   // p0 + 1*p1 is p0 + p1 exactly; p0 + 0*p0 is p0
+  float x[KSTEPS][8];
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[ks][e] = r.p0[ks][e >> 2][e & 3] + w1 * r.p1[ks][e >> 2][e & 3];
+  for (int p = 2; p < s.nparts; ++p) {         // further partials (unusual shapes), in order
+    const float* src = s.qkv + ((size_t)p * s.Mtot + m) * s.ldq + col0 + 8 * g4;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      const f32x4 u0 = *reinterpret_cast<const f32x4*>(src + ks * 32), u1 = *reinterpret_cast<const f32x4*>(src + ks * 32 + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { x[ks][e] += u0[e]; x[ks][4 + e] += u1[e]; }
+    }
+  }
+  if (gain) {
+    float ss = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += x[ks][e] * x[ks][e];
+    ss += __shfl_xor(ss, 16); ss += __shfl_xor(ss, 32);
+    const float rn = rsqrtf(ss / (float)HD + s.eps);
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      const f32x4 g0 = *reinterpret_cast<const f32x4*>(gain + ks * 32 + 8 * g4);
+      const f32x4 g1 = *reinterpret_cast<const f32x4*>(gain + ks * 32 + 8 * g4 + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { x[ks][e] = x[ks][e] * rn * g0[e]; x[ks][4 + e] = x[ks][4 + e] * rn * g1[e]; }
+    }
+  }
+#pragma unroll
+  for (int ks = 0; ks < HK; ++ks) {
+    float y0[8], y1[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float c = r.cs[ks][e >> 2][e & 3], sv = r.sn[ks][e >> 2][e & 3];
+      const float x0 = x[ks][e], x1 = x[ks + HK][e];
+      y0[e] = x0 * c - x1 * sv; y1[e] = x0 * sv + x1 * c;
+    }
+    out[ks] = frag_round(y0, T());
+    out[ks + HK] = frag_round(y1, T());
+  }
+}
+
+template <typename T, int HD>
+__device__ __forceinline__ void rope_head(const QkvSrc& s, int m, int col0, const float* gain, int pos, int g4,
+                                          Frag<T> (&out)[HD / 32]) {
+  HeadRaw<HD> r;
+  head_load<HD>(s, m, col0, pos, g4, r);
+  head_finish<T, HD>(s, r, m, col0, gain, g4, out);
 }
 
 // ------------------------------------------------------------ GQA attention
@@ -120,7 +174,9 @@ __global__ void __launch_bounds__(256) rope_kv_kernel(const RopeArgs<T> a) {
 // Output: unnormalised partial (m, l, O) per split; combine_task merges.
 template <typename T>
 struct AttnArgs {
-  const T *qbuf, *kc, *vt;          // kc / vt offset to the layer
+  QkvSrc src;                       // the window rows' q / k / v as the projection left them
+  const T* qbuf;                    // throughput form only: the queries, already normed / rotated / rounded
+  const T *kc, *vt;                 // KV cache, offset to the layer: the tokens before the window
   const int32_t* kv_len;
   float *pm, *pl, *po;              // [B][Hkv][nsplit][qrows_pad] / ...[hd]
   int k, g, Hkv, hd, max_ctx, qrows_pad, nsplit, nqb;   // nqb = query blocks per (b, kv head)
@@ -175,44 +231,43 @@ __device__ __forceinline__ void load_kv(KvFrags<T, HD>& f, const T* kbase, const
     f.vf[h] = frag_load_row(vbase + ((size_t)((tb >> 5) * (HD / 16) + h) * 64 + lane) * 8);
 }
 
-// task = ((b * Hkv + kvh) * nsplit + sp) * nqb + qb.  The next step's K/V are fetched
-// into registers while the current one is computed.
+// task = ((b * Hkv + kvh) * nsplit + sp) * nqb + qb.  The P = kv_len[b] cached tokens are cut
+// into nsplit - 1 ranges; the last split takes the k window rows themselves, whose keys and
+// values are not in the cache yet: it builds them from the projection result (one 32-token
+// step, row j sees window rows 0..j).  With nsplit = 1 the one split does both.
 template <typename T, int HD, int PRE>
 __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
   constexpr int KSTEPS = HD / 32, HT = HD / 16;
+  constexpr bool HALF_REGS = PRE == 2 && sizeof(T) == 2;   // see attn_split_kernel
   const int lane = threadIdx.x & 63, c = lane & 15, g4 = lane >> 4;
   int id = task;
   const int qb = id % a.nqb; id /= a.nqb;
   const int sp = id % a.nsplit; id /= a.nsplit;
   const int kvh = id % a.Hkv; const int b = id / a.Hkv;
-  const int P = a.kv_len[b];
-  const int len = min(P + a.k, a.max_ctx);          // slots visible to the last row
-  int per = (len + a.nsplit - 1) / a.nsplit;
-  per = (per + 31) & ~31;                            // token ranges start on 32-token steps
-  const int t0 = sp * per, t1 = min(len, t0 + per);
+  const int P = min(a.kv_len[b], a.max_ctx - a.k);   // (the host refuses windows that do not fit)
+  const int ncs = a.nsplit - 1;                      // splits over the cached tokens; the last split is the window
+  const bool win = sp == ncs;
+  int t0 = 0, t1 = P;
+  if (ncs > 0) {
+    int per = (P + ncs - 1) / ncs;
+    per = (per + 31) & ~31;                          // token ranges start on 32-token steps
+    t0 = min(P, sp * per); t1 = win ? t0 : min(P, t0 + per);
+  }
   const int nq = a.g * a.k;
   const int row = qb * 16 + c;
-
-  // query fragments (B operand): dims ks*32 + 8*g4 ..
-  Frag<T> qf[KSTEPS];
   const int jrow = row < nq ? row / a.g : -1;
-  {
-    const T* qp = a.qbuf + ((size_t)(b * a.Hkv + kvh) * a.qrows_pad + row) * HD + g4 * 8;
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      if (row < nq) qf[ks] = frag_load_row(qp + ks * 32); else frag_zero(qf[ks]);
-    }
-  }
+  const T* kbase = a.kc + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
+  const T* vbase = a.vt + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
+
   f32x4 o[HT];
 #pragma unroll
   for (int h = 0; h < HT; ++h) o[h] = f32x4{0.f, 0.f, 0.f, 0.f};
   float mrun = -INFINITY, lrun = 0.f;
-  const T* kbase = a.kc + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
-  const T* vbase = a.vt + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
-  const int lim = jrow < 0 ? -1 : min(P + jrow, t1 - 1);   // last slot this query row may see
+  Frag<T> qf[KSTEPS];   // query fragments (B operand): dims ks*32 + 8*g4 .. of query row `row` = (window row, head in group)
 
-  // One 32-token step: scores, online soft-max, O^T += V^T P^T.
-  auto step = [&](const KvFrags<T, HD>& f, int tb) {
+  // One 32-token step: scores, online soft-max, O^T += V^T P^T.  Token tb + i is visible to
+  // this lane's query row iff tb + i <= lim.
+  auto step = [&](const KvFrags<T, HD>& f, int tb, int lim) {
     f32x4 s[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -249,19 +304,126 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
     for (int h = 0; h < HT; ++h) o[h] = o[h] * alpha;
     pv_accumulate<HT>(o, f.vf, s[0], s[1]);
   };
-  // The K/V of PRE steps are requested together, before any of them is used: a step
-  // computes in a fraction of a memory round trip, so fetching only one step ahead costs one
-  // round trip per step.  PRE = 4 (128 tokens) needs the CU's registers for one workgroup
-  // (256 VGPRs + 114 AGPRs per lane): right when there is at most one workgroup per CU;
-  // with more workgroups than CUs PRE = 2 lets two of them share a CU.
-  // Steps beyond the range re-read its first step (a valid address) and are skipped.
-  for (int tg = t0; tg < t1; tg += 32 * PRE) {
+
+  const int qr = min(row, nq - 1), qj = qr / a.g, qm = b * a.k + qj, qcol = (kvh * a.g + qr % a.g) * HD;
+  // throughput form: a wave handles many steps and a (b, kv head, query block) has many splits,
+  // so the queries are prepared once by rope_q_kernel instead of by every wave
+  auto load_q = [&]() {
+    const T* qp = a.qbuf + ((size_t)(b * a.Hkv + kvh) * a.qrows_pad + qr) * HD + g4 * 8;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) qf[ks] = frag_load_row(qp + ks * 32);
+  };
+  const int kcol = (a.src.H + kvh) * HD, vcol = (a.src.H + a.src.Hkv + kvh) * HD;
+  const size_t pstride = (size_t)a.src.Mtot * a.src.ldq;
+  const int w1 = a.src.nparts > 1 ? 1 : 0;
+
+  // The window rows as virtual tokens 0..k-1, sixteen at a time (one round in a decoding
+  // window, two in a prefill-sized one), in the operand layouts of load_kv with the second
+  // 16-token tile left empty.  Key fragment: token r0 + c, dims of lane group g4.  V^T
+  // fragment: lane (dim h*16 + c) needs tokens r0 + 4*g4 + {0..3}.  Loads and arithmetic are
+  // separate so that the caller can have everything in flight before it waits.
+  struct WinRaw { HeadRaw<HD> k; float v0[HT][4], v1[HT][4]; };
+  auto win_load_k = [&](WinRaw& w, int r0) {
+    const int v = min(r0 + c, a.k - 1);
+    head_load<HD>(a.src, b * a.k + v, kcol, P + v, g4, w.k);
+  };
+  auto win_load_v = [&](WinRaw& w, int r0) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float* q = a.src.qkv + (size_t)(b * a.k + min(r0 + 4 * g4 + e, a.k - 1)) * a.src.ldq + vcol + c;
+#pragma unroll
+      for (int h = 0; h < HT; ++h) { w.v0[h][e] = *(q + h * 16); w.v1[h][e] = *(q + w1 * pstride + h * 16); }
+    }
+  };
+  auto win_step = [&](WinRaw& w, KvFrags<T, HD>& fw, int r0) {
+    head_finish<T, HD>(a.src, w.k, b * a.k + min(r0 + c, a.k - 1), kcol, a.src.gk, g4, fw.kf[0]);
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) frag_zero(fw.kf[1][ks]);
+    if constexpr (HALF_REGS) win_load_v(w, r0);   // (the registers do not hold both sets of loads at once)
+#pragma unroll
+    for (int h = 0; h < HT; ++h) {
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { x[e] = 0.f + w.v0[h][e] + (float)w1 * w.v1[h][e]; x[4 + e] = 0.f; }
+      for (int p = 2; p < a.src.nparts; ++p) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          x[e] += *(a.src.qkv + p * pstride + (size_t)(b * a.k + min(r0 + 4 * g4 + e, a.k - 1)) * a.src.ldq + vcol + c + h * 16);
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (r0 + 4 * g4 + e >= a.k) x[e] = 0.f;
+      fw.vf[h] = frag_round(x, T());
+    }
+    step(fw, r0, min(jrow, r0 + 15));
+  };
+
+  if (win && ncs > 0) {
+    // the window split proper: query and window rows arrive in one round trip (two in the
+    // throughput form, whose registers do not hold all of it at once)
+    WinRaw w;
+    if constexpr (!HALF_REGS) {
+      HeadRaw<HD> qraw;
+      head_load<HD>(a.src, qm, qcol, P + qj, g4, qraw);
+      win_load_k(w, 0); win_load_v(w, 0);
+      head_finish<T, HD>(a.src, qraw, qm, qcol, a.src.gq, g4, qf);
+    } else {
+      load_q();
+      win_load_k(w, 0);
+    }
+    KvFrags<T, HD> fw;
+    win_step(w, fw, 0);
+    if (a.k > 16) {
+      win_load_k(w, 16);
+      if constexpr (!HALF_REGS) win_load_v(w, 16);
+      win_step(w, fw, 16);
+    }
+  } else {
+    // The K/V of PRE steps are requested together, before any of them is used: a step
+    // computes in a fraction of a memory round trip, so fetching only one step ahead costs one
+    // round trip per step.  PRE = 4 (128 tokens) needs the CU's registers for one workgroup:
+    // right when there is at most one workgroup per CU; with more workgroups than CUs PRE = 2
+    // lets two of them share a CU.  The first group is requested before the query is built, so
+    // that both arrive in the same round trip.
+    // Steps beyond the range re-read its first step (a valid address) and are skipped.
     KvFrags<T, HD> f[PRE];
+    auto load_group = [&](int tg, int fallback) {
 #pragma unroll
-    for (int u = 0; u < PRE; ++u) load_kv<T, HD>(f[u], kbase, vbase, tg + 32 * u < t1 ? tg + 32 * u : t0, lane);
+      for (int u = 0; u < PRE; ++u) load_kv<T, HD>(f[u], kbase, vbase, tg + 32 * u < t1 ? tg + 32 * u : fallback, lane);
+    };
+    const int lim_c = jrow < 0 ? -1 : t1 - 1;          // every cached token is visible to every window row
+    auto run_group = [&](int tg) {
 #pragma unroll
-    for (int u = 0; u < PRE; ++u)
-      if (tg + 32 * u < t1) step(f[u], tg + 32 * u);
+      for (int u = 0; u < PRE; ++u)
+        if (tg + 32 * u < t1) step(f[u], tg + 32 * u, lim_c);
+    };
+    if constexpr (!HALF_REGS) {
+      // latency form (a group or two per wave): the first group is requested before the query
+      load_group(t0, t0 < t1 ? t0 : 0);
+      rope_head<T, HD>(a.src, qm, qcol, a.src.gq, P + qj, g4, qf);
+      for (int tg = t0; tg < t1;) {
+        run_group(tg);
+        tg += 32 * PRE;
+        if (tg < t1) load_group(tg, t0);
+      }
+    } else {
+      // throughput form (many groups per wave, two waves per SIMD): loads unconditional and
+      // first in the loop body, so that the steps wait for their own fragments only and step u
+      // runs while the fragments of step u+1 are still arriving
+      load_q();
+      for (int tg = t0; tg < t1; tg += 32 * PRE) {
+        load_group(tg, t0);
+        run_group(tg);
+      }
+    }
+    if (win) {   // a single split does everything (empty or very short caches)
+      WinRaw w;
+      for (int r0 = 0; r0 < a.k; r0 += 16) {
+        win_load_k(w, r0);
+        if constexpr (!HALF_REGS) win_load_v(w, r0);
+        win_step(w, f[0], r0);
+      }
+    }
   }
   // write the partial
   float l = lrun;
@@ -274,14 +436,52 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
 
 // grid = B * Hkv * nsplit * ceil(nqb / wpg) workgroups of wpg waves; the waves of a
 // workgroup own consecutive query blocks of the same K/V range, so those reads are
-// shared through the CU's L1.
+// shared through the CU's L1.  The workgroups of the cached ranges come first, the (short)
+// window splits last: when the grid is larger than the chip holds at once, the ones that
+// wait for a free slot are short.
+// (PRE = 2 in bf16 is the form for more workgroups than CUs: held to two waves per SIMD.)
 template <typename T, int HD, int PRE>
-__global__ void __launch_bounds__(256) attn_split_kernel(const AttnArgs<T> a) {
+__global__ void __launch_bounds__(256, (PRE == 2 && sizeof(T) == 2) ? 2 : 1) attn_split_kernel(const AttnArgs<T> a) {
   const int wpg = blockDim.x >> 6;
   const int nqg = (a.nqb + wpg - 1) / wpg;
-  const int qb = (blockIdx.x % nqg) * wpg + (threadIdx.x >> 6);
+  const int ncs = a.nsplit - 1;
+  const int ncache = (int)(gridDim.x / a.nsplit) * ncs;   // gridDim.x = (B * Hkv * nqg) * nsplit
+  int blk = blockIdx.x, sp, bh, qg;
+  if (blk < ncache) { qg = blk % nqg; sp = (blk / nqg) % ncs; bh = blk / (nqg * ncs); }
+  else { blk -= ncache; qg = blk % nqg; sp = ncs; bh = blk / nqg; }
+  const int qb = qg * wpg + (threadIdx.x >> 6);
   if (qb >= a.nqb) return;
-  attn_task<T, HD, PRE>(a, (blockIdx.x / nqg) * a.nqb + qb);
+  attn_task<T, HD, PRE>(a, (bh * a.nsplit + sp) * a.nqb + qb);
+}
+
+// Queries for the throughput form of the attention: wave w handles 16 query rows of the
+// (b, kv head, row) list, four lanes (one per dim group) each -> qbuf[b][kvh][row][HD].
+template <typename T>
+struct RopeQArgs {
+  QkvSrc src;
+  const int32_t* kv_len;
+  T* qbuf;
+  int B, k, g, qrows_pad, max_ctx;
+};
+
+template <typename T, int HD>
+__global__ void __launch_bounds__(256) rope_q_kernel(const RopeQArgs<T> a) {
+  constexpr int KSTEPS = HD / 32;
+  const int w = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, c = lane & 15, g4 = lane >> 4;
+  const int nq = a.g * a.k, nitems = a.B * a.src.Hkv * nq;
+  if (w * 16 >= nitems) return;
+  const int item = w * 16 + c, it = min(item, nitems - 1);
+  const int row = it % nq, kvh = (it / nq) % a.src.Hkv, b = it / (nq * a.src.Hkv);
+  const int j = row / a.g, hh = kvh * a.g + row % a.g;
+  const int P = min(a.kv_len[b], a.max_ctx - a.k);
+  Frag<T> qf[KSTEPS];
+  rope_head<T, HD>(a.src, b * a.k + j, hh * HD, a.src.gq, P + j, g4, qf);
+  if (item < nitems) {
+    T* dst = a.qbuf + ((size_t)(b * a.src.Hkv + kvh) * a.qrows_pad + row) * HD + g4 * 8;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) *reinterpret_cast<Frag<T>*>(dst + ks * 32) = qf[ks];
+  }
 }
 
 // Merge the split partials of one (row m, query head): softmax-weighted sum,
@@ -293,7 +493,56 @@ struct CombineArgs {
   const float *pm, *pl, *po;
   T* attn; int ldat;
   int Mtot, k, H, Hkv, qrows_pad, nsplit;
+  // KV append (the same launch, further waves): the window rows' keys and values go to
+  // cache positions kv_len[b] + j
+  QkvSrc src;
+  const int32_t* kv_len;
+  T *kc, *vt;                       // offset to the layer
+  int max_ctx;
 };
+
+// Key append: wave w handles 16 (row, kv head) items, four lanes (one per dim group) each:
+// item = m * Hkv + kvh -> norm, rotary embedding, one 8-element store per fragment.
+// Nobody reads these cache rows before the next kernel starts (the attention of this layer
+// took the window rows from the projection result).
+template <typename T, int HD>
+__device__ __forceinline__ void append_k_task(const CombineArgs<T>& a, int w) {
+  constexpr int KSTEPS = HD / 32;
+  const int lane = threadIdx.x & 63, c = lane & 15, g4 = lane >> 4;
+  const int nitems = a.Mtot * a.Hkv;
+  const int item = w * 16 + c, it = min(item, nitems - 1);
+  const int m = it / a.Hkv, kvh = it % a.Hkv;
+  const int b = m / a.k, j = m % a.k;
+  const int pos = a.kv_len[b] + j;
+  const bool live = item < nitems && pos < a.max_ctx;   // capacity guard; the host refuses such calls
+  Frag<T> kf[KSTEPS];
+  rope_head<T, HD>(a.src, m, (a.src.H + kvh) * HD, a.src.gk, min(pos, a.max_ctx - 1), g4, kf);
+  if (live) {
+    T* dst = a.kc + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) *reinterpret_cast<Frag<T>*>(dst + kc_offset(pos, ks * 32 + 8 * g4, HD)) = kf[ks];
+  }
+}
+
+// Value append: one wave per (row m, kv head), lane = dim (and dim + 64): the transposed
+// cache takes single elements, so the stores are spread over as many lanes as possible.
+template <typename T, int HD>
+__device__ __forceinline__ void append_v_task(const CombineArgs<T>& a, int w) {
+  const int lane = threadIdx.x & 63;
+  const int m = w / a.Hkv, kvh = w % a.Hkv;
+  const int b = m / a.k, j = m % a.k;
+  const int pos = a.kv_len[b] + j;
+  if (pos >= a.max_ctx) return;
+  const size_t pstride = (size_t)a.src.Mtot * a.src.ldq;
+  const float* src = a.src.qkv + (size_t)m * a.src.ldq + (size_t)(a.src.H + a.src.Hkv + kvh) * HD;
+  T* dst = a.vt + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
+#pragma unroll
+  for (int d = lane; d < HD; d += 64) {
+    float x = src[d];
+    for (int p = 1; p < a.src.nparts; ++p) x += src[d + p * pstride];
+    st_round1(dst + vt_offset(pos, d, HD), x);
+  }
+}
 
 template <typename T, int HD>
 __device__ __forceinline__ void combine_task(const CombineArgs<T>& a, int task) {
@@ -351,11 +600,20 @@ __device__ __forceinline__ void combine_task(const CombineArgs<T>& a, int task) 
   }
 }
 
+// waves 0 .. Mtot*H-1 merge; then ceil(Mtot*Hkv / 16) key-append waves; then Mtot*Hkv
+// value-append waves
+template <typename T>
+__host__ __device__ inline int combine_waves(int Mtot, int H, int Hkv) { return Mtot * H + (Mtot * Hkv + 15) / 16 + Mtot * Hkv; }
+
 template <typename T, int HD>
 __global__ void __launch_bounds__(256) attn_combine_kernel(const CombineArgs<T> a) {
-  const int task = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (task >= a.Mtot * a.H) return;
-  combine_task<T, HD>(a, task);
+  int task = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int nmerge = a.Mtot * a.H, nk = (a.Mtot * a.Hkv + 15) / 16, nv = a.Mtot * a.Hkv;
+  if (task < nmerge) { combine_task<T, HD>(a, task); return; }
+  task -= nmerge;
+  if (task < nk) { append_k_task<T, HD>(a, task); return; }
+  task -= nk;
+  if (task < nv) append_v_task<T, HD>(a, task);
 }
 
 }  // namespace dbl
