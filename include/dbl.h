@@ -267,8 +267,8 @@ int dbl_model_bytes(const dbl_ctx* ctx, uint64_t* weight_bytes, uint64_t* kv_byt
 
 /* Measurement: launch one projection kernel `iters` times (layer = launch index
  * mod n_layers, so consecutive launches stream different weights, as in a real
- * step) for M <= 16 rows on the context's stream between two HIP events, with the
- * launch configuration dbl_verify_block uses.  which: 0 = fused q/k/v, 1 = output
+ * step) for M <= max_batch*max_window rows on the context's stream between two HIP
+ * events, with the launch configuration dbl_verify_block uses for that many rows.  which: 0 = fused q/k/v, 1 = output
  * projection, 2 = fused gate/up + SwiGLU, 3 = down projection, 4 = LM head + row
  * statistics.  *ms_out = mean milliseconds per launch; *bytes_out = logical weight
  * bytes one launch must read.  Activations are whatever the scratch buffers hold;
@@ -280,7 +280,10 @@ int dbl_bench_projection(dbl_ctx* ctx, int which, int M, int iters, float* ms_ou
  * the last layer [rows][ld] f32; 1 = last layer's attention output [rows][ld] in
  * the model dtype; 2 = last layer's silu(gate)*up [rows][ld] in the model dtype.
  * *ld_out receives the row stride in elements; `bytes` is the capacity of `host`
- * and must cover max_batch*max_window rows. */
+ * and must cover max_batch*max_window rows.  Buffers 1 and 2 are row-major only
+ * after a call with at most 16 rows (B*k <= 16); larger calls keep them in blocks
+ * of 16 rows x 32 columns, element (m, c) at
+ * ((m/16 * ld/32 + c/32) * 64 + (c%32/8) * 16 + m%16) * 8 + c%8. */
 int dbl_debug_buffer(dbl_ctx* ctx, int which, void* host, size_t bytes, int32_t* ld_out);
 
 #ifdef __cplusplus

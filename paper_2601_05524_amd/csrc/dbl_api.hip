@@ -207,18 +207,51 @@ void launch_gemm_t(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
   }
 }
 
-// More than 16 rows (and not the LM head): passes of 16*R rows through gemm_rows_kernel.
+// More than 16 rows (and not the LM head): passes of 16*R rows through gemm_rows_kernel, in
+// units of Q tile rows.  Larger units re-read the activations less often but leave fewer of
+// them to share out: Q is the one with the least modelled time (units per workgroup, counted
+// half as whole rounds and half as the exact ratio, times tile rows per unit, with the activation
+// traffic, R/Q of the weight traffic, at a quarter of its cost; fitted to measured launches).
+template <typename T, int EPI, int R>
+void launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
+  constexpr int NACC = EPI == EPI_SWIGLU ? 2 : 1;
+  int bestq = 0, bestg = 0; double best = 1e30;
+  for (int q : {4, 2}) {
+    if (q < NACC) continue;
+    const int units = (p.NT + q / NACC - 1) / (q / NACC) * p.SS;
+    int g = std::min(units, std::min(c->n_cu, SSQ_PARTS));
+    g = std::max(p.SS, g / p.SS * p.SS);
+    const double rounds = 0.5 * ((units + g - 1) / g) + 0.5 * (double)units / g;
+    const double cost = rounds * q * (1.0 + 0.25 * R / q);
+    if (cost < best) { best = cost; bestq = q; bestg = g; }
+  }
+  const dim3 grid(bestg), block(256);
+  if (bestq == 4) hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4>), grid, block, 0, c->stream, a);
+  else hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 2>), grid, block, 0, c->stream, a);
+}
+
 template <typename T, int R>
 void launch_gemm_rows(dbl_ctx* c, const GemmPlan& p, int epi, const GemmArgs<T>& a) {
-  constexpr int KSR = sizeof(T) == 2 ? 8 : 4;
-  GemmArgs<T> b = a;
-  b.NCH = p.NCH * (p.KS / KSR);     // the same k-blocks of a super slice, in chunks of NW * KSR
-  const dim3 grid(p.grid), block(p.NW * 64);
   switch (epi) {
-    case EPI_PARTIAL: hipLaunchKernelGGL((gemm_rows_kernel<T, EPI_PARTIAL, KSR, R>), grid, block, 0, c->stream, b); break;
-    case EPI_RESIDUAL: hipLaunchKernelGGL((gemm_rows_kernel<T, EPI_RESIDUAL, KSR, R>), grid, block, 0, c->stream, b); break;
-    default: hipLaunchKernelGGL((gemm_rows_kernel<T, EPI_SWIGLU, KSR, R>), grid, block, 0, c->stream, b); break;
+    case EPI_PARTIAL: launch_gemm_rows_q<T, EPI_PARTIAL, R>(c, p, a); break;
+    case EPI_RESIDUAL: launch_gemm_rows_q<T, EPI_RESIDUAL, R>(c, p, a); break;
+    default: launch_gemm_rows_q<T, EPI_SWIGLU, R>(c, p, a); break;
   }
+}
+
+// Which kernel runs a projection of M rows.  The LM head always takes 16-row passes of
+// gemm_stream_kernel (its row statistics live there).  Windows of more than 8 rows take
+// gemm_rows_kernel.  At 8 rows or fewer, measured inside a running layer at three widths:
+// the gate/up projection is faster through gemm_rows_kernel everywhere (70B width 8 us per
+// layer, 1B width 4 us), output and down projection where their tile pairs fill the chip
+// (70B width 3 + 4 us, 32B width 2 + 10 us; at the 1B width, 64 units for 256 CUs, slower by
+// 3 + 5 us), the q/k/v projection nowhere (it would need a stored RMSNorm output of its own).
+static bool rows_kernel_for(const dbl_ctx* c, const GemmPlan& p, int epi, int M) {
+  if (epi == EPI_LMHEAD) return false;
+  if (M > 8) return true;
+  if (epi == EPI_SWIGLU) return true;
+  if (epi == EPI_RESIDUAL) return p.NT >= c->n_cu;
+  return false;
 }
 
 template <typename T>
@@ -227,15 +260,19 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
   a.d = (float)c->cfg.d_model; a.eps = c->cfg.rms_eps; a.ssq_in = c->ssq; a.ssq_out = c->ssq;
   a.tile_ctr = c->tile_ctr;
   static_assert(SSQ_PARTS == 256, "xn_kernel adds one partial per thread");
-  if (M > 16 && epi != EPI_LMHEAD) {
+  const bool rows = rows_kernel_for(c, p, epi, M);
+  if (rows) {
     T* xn = reinterpret_cast<T*>(c->xn);
+    a.act_tiled = rows_kernel_for(c, c->p_d, EPI_RESIDUAL, M) ? 1 : 0;
     for (int m0 = 0; m0 < M; m0 += 64) {
       a.m0 = m0; a.mrows = std::min(64, M - m0);
       if (epi != EPI_RESIDUAL) {     // the RMSNorm output is stored first and read like any activation
-        hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, a.d, a.eps);
+        hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, a.d, a.eps, 1);
         a.X = xn;
       }
-      if (a.mrows > 32) launch_gemm_rows<T, 4>(c, p, epi, a); else launch_gemm_rows<T, 2>(c, p, epi, a);
+      if (a.mrows > 32) launch_gemm_rows<T, 4>(c, p, epi, a);
+      else if (a.mrows > 16) launch_gemm_rows<T, 2>(c, p, epi, a);
+      else launch_gemm_rows<T, 1>(c, p, epi, a);
     }
     return;
   }
@@ -244,7 +281,7 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
     if (epi != EPI_RESIDUAL && a.mrows > 8) {
       // more than 8 rows: the RMSNorm output is stored first and read like any activation
       T* xn = reinterpret_cast<T*>(c->xn);
-      hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, a.d, a.eps);
+      hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, a.d, a.eps, 0);
       a.X = xn;
     }
     switch (epi) {
@@ -306,7 +343,7 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
   at.src = src; at.qbuf = reinterpret_cast<const T*>(c->qbuf); at.kc = kc; at.vt = vt; at.kv_len = c->kv_len; at.pm = c->pm; at.pl = c->pl; at.po = c->po;
   at.k = k; at.g = gq; at.Hkv = Hkv; at.hd = hd; at.max_ctx = g.max_ctx; at.qrows_pad = c->qrows_pad;
   at.nsplit = nsplit; at.nqb = qblocks; at.scale = (float)(1.4426950408889634 / std::sqrt((double)hd));
-  s.comb = CombineArgs<T>{c->pm, c->pl, c->po, attn, c->p_o.ldx(), M, k, H, Hkv, c->qrows_pad, nsplit,
+  s.comb = CombineArgs<T>{c->pm, c->pl, c->po, attn, c->p_o.ldx(), rows_kernel_for(c, c->p_o, EPI_RESIDUAL, M) ? 1 : 0, M, k, H, Hkv, c->qrows_pad, nsplit,
                           src, c->kv_len, kc, vt, g.max_ctx};
   s.o.W = reinterpret_cast<const T*>(c->w_o) + (size_t)l * c->p_o.elems();
   s.o.X = attn; s.o.ldx = c->p_o.ldx(); s.o.out = c->h; s.o.ldo = c->ldh;      // h += attn Wo^T
@@ -559,14 +596,15 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(status, 4, true); ALLOC(commits, 8, true);
     ALLOC(h, (size_t)Mmax * c->ldh * 4, true);
     ALLOC(hg, (size_t)Mmax * c->ldh * 4, true);
-    ALLOC(xn, (size_t)Mmax * c->ldh * esz, true);
+    const size_t M16 = (size_t)(Mmax + 15) / 16 * 16;   // the fragment-tiled activation layout holds whole groups of 16 rows
+    ALLOC(xn, M16 * c->ldh * esz, true);
     ALLOC(ssq, (size_t)Mmax * SSQ_PARTS * 4, true);
     ALLOC(tile_ctr, (DYN_DONE + 1) * sizeof(unsigned), true);
     ALLOC(qkv_part, (size_t)c->p_qkv.SS * Mmax * c->p_qkv.ldo() * 4, true);
     ALLOC(qbuf, (size_t)g.max_batch * g.n_kv_heads * c->qrows_pad * g.head_dim * esz, true);
     ALLOC(logits, (size_t)Mmax * c->p_lm.ldo() * 4, true);
-    ALLOC(attn, (size_t)Mmax * c->p_o.ldx() * esz, true);
-    ALLOC(act, (size_t)Mmax * c->p_d.ldx() * esz, true);
+    ALLOC(attn, M16 * c->p_o.ldx() * esz, true);
+    ALLOC(act, M16 * c->p_d.ldx() * esz, true);
     ALLOC(pm, part_rows * 4, true); ALLOC(pl, part_rows * 4, true); ALLOC(po, part_rows * g.head_dim * 4, true);
     ALLOC(stats, (size_t)c->p_lm.grid * Mmax * sizeof(LmStat), true);
     ALLOC(n_acc_i, (size_t)g.max_batch * 4, true); ALLOC(emit_i, (size_t)Mmax * 4, true);
@@ -939,7 +977,7 @@ int dbl_bench_projection(dbl_ctx* c, int which, int M, int iters, float* ms_out,
   if (!c) return DBL_EINVAL;
   if (!ms_out || !bytes_out) return fail(c, DBL_EINVAL, "null output pointer");
   if (which < 0 || which > 4 || iters < 1 || iters > 100000) return fail(c, DBL_EINVAL, "bad which / iters");
-  if (M < 1 || M > 16 || M > c->cfg.max_batch * c->cfg.max_window) return fail(c, DBL_EINVAL, "M out of range");
+  if (M < 1 || M > c->cfg.max_batch * c->cfg.max_window) return fail(c, DBL_EINVAL, "M out of range");
   if (which < 4 && c->cfg.n_layers < 1) return fail(c, DBL_EINVAL, "model has no layers");
   const dbl_model_cfg& g = c->cfg;
   const uint64_t elems[5] = {(uint64_t)c->n_qkv * g.d_model, (uint64_t)g.d_model * c->hq, 2ull * g.d_ffn * g.d_model,

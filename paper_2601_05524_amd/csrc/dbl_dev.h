@@ -33,6 +33,14 @@ __host__ __device__ inline size_t vt_offset(int t, int d, int hd) {
   return ((size_t)((t >> 5) * (hd >> 4) + (d >> 4)) * 64 + (((tt & 15) >> 2) * 16 + (d & 15))) * 8 + ((tt >> 4) * 4 + (tt & 3));
 }
 
+// Activations of passes with more than 16 rows (inputs of gemm_rows_kernel) are stored as the
+// MFMA B fragments that kernel loads: blocks of 16 rows x 32 inputs, lane l = 16*(k%32/8) + m%16
+// owns its 8 inputs, block (m/16, k/32) at ((m/16) * (ld/32) + k/32) * 512.  ld = row length in
+// elements (a multiple of 32); the buffer holds a multiple of 16 rows.
+__host__ __device__ inline size_t xt_offset(int m, int k, int ld) {
+  return ((size_t)((m >> 4) * (ld >> 5) + (k >> 5)) * 64 + (((k & 31) >> 3) * 16 + (m & 15))) * 8 + (k & 7);
+}
+
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
 // round-to-nearest-even float -> bfloat16

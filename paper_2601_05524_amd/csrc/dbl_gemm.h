@@ -82,6 +82,7 @@ struct GemmArgs {
   const float* gain_out;   // RESIDUAL: [>= NT*16] gain of the next RMSNorm
   T* act;              // SWIGLU: [Mtot][ldact]
   int ldact;
+  int act_tiled;       // SWIGLU in gemm_rows_kernel: act in the fragment-tiled layout (its reader is gemm_rows_kernel too)
   LmArgs lm;
 };
 
@@ -413,127 +414,185 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
 // ---------------------------------------------------------------------------
 // Windows of more than 16 rows: the same weight streaming, but every weight fragment is
 // multiplied with R row groups of 16 rows before the next one is fetched, so the weights are
-// read once per 16*R rows instead of once per 16.  The activation registers then hold R
-// groups, which leaves room for only KS k-blocks per wave and chunk (8 in bf16): every
-// projection walks K in chunks (NCH = k-blocks of a super slice / (NW*KS)), and the
-// activations of the next chunk are fetched when the current one is done (the ring drains once
-// per chunk; at 16*R rows per weight byte that is cheap).  Activations are always stored
-// tensors of type T (the host runs xn_kernel first for the normalising projections).
-// Epilogues as in gemm_stream_kernel, one row group at a time through one LDS buffer; tiles
-// are static; the LM head is not handled here (its per-row statistics stay on 16-row passes).
-template <typename T, int EPI, int KS, int R>
-__global__ void __launch_bounds__(512) gemm_rows_kernel(const GemmArgs<T> a) {
+// read once per 16*R rows instead of once per 16.
+//   * Four waves per workgroup (one per SIMD, the whole register file each) split the k-blocks
+//     of a chunk: KS blocks per wave, 4*KS per chunk.  A wave keeps the activations of its
+//     slice for all R groups in registers (R*KS fragments) and fetches the next chunk's while
+//     it multiplies the current one.  (Eight waves with half the registers each and no second
+//     set were measured 10-15 % slower.)
+//   * A workgroup works on a unit of Q tile rows at a time (Q/NACC output tiles): per chunk a
+//     wave streams Q*KS weight fragments against R*KS activation fragments, so the activation
+//     traffic through L1 (from L2) is R/Q of the weight traffic.  The ring is 2*KS fragments
+//     deep and runs across chunks and units.
+//   * At the end of a unit the four partial sums of every (tile, row group) pair are added in
+//     wave order through LDS; the pairs are shared out over the waves for the epilogue.
+//   * A slice whose length is not a multiple of 4*KS ends with waves that have no k-blocks left:
+//     they multiply zeros (their loads are redirected to the start of the slice).
+// Activations are always stored tensors of type T in the fragment-tiled layout of xt_offset
+// (the host runs xn_kernel first for the normalising projections; the attention merge and
+// the SwiGLU epilogue below write that layout directly).  Epilogues as in gemm_stream_kernel; tiles are static; the LM head is
+// not handled here (its per-row statistics stay on 16-row passes).
+template <typename T, int EPI, int R, int Q>
+__global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
   constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
-  constexpr int RING = KS;
+  constexpr int TT = Q / NACC;                  // output tiles per unit
+  constexpr int NWV = 4;                        // waves: one per SIMD, the whole register file each
+  constexpr int KS = sizeof(T) == 2 ? 8 : 4;    // k-blocks per wave and chunk
+  constexpr int NF = Q * KS;                    // weight fragments per wave and chunk
+  constexpr int RING = GemmCfg<T>::RING;
+  constexpr int P = TT * R;                     // (tile, row group) pairs per unit
+  constexpr int PH = P > 8 ? 8 : P;             // pairs per reduction round
   static_assert(EPI != EPI_LMHEAD, "the LM head runs on 16-row passes");
-  __shared__ f32x4 red[8][NACC][WAVE];
-  const int wg = blockIdx.x, nwg = gridDim.x, nw = blockDim.x >> 6;
+  static_assert(Q % NACC == 0 && NF % RING == 0 && P % PH == 0, "unit shape");
+  __shared__ f32x4 red[NWV][PH][NACC][WAVE];
+  __shared__ float wsq[NWV][R][16];
+  const int wg = blockIdx.x, nwg = gridDim.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 15, g = lane >> 4;
-  const int ss = wg % a.SS, tstep = nwg / a.SS;
-  int t = wg / a.SS;
-  const int nch = a.NCH, seg = nw * KS;
-  const int kb0 = ss * nch * seg + wave * KS;
-  const T* wlane = a.W + (size_t)kb0 * BLOCK_ELEMS;
-  const size_t row_elems = (size_t)a.KBp * BLOCK_ELEMS, seg_elems = (size_t)seg * BLOCK_ELEMS;
-
-  Frag<T> ring[RING];
-  {
-    const int tf = t < a.NT ? t : 0;
-#pragma unroll
-    for (int j = 0; j < RING; ++j) ring[j] = frag_load_w(wlane + (size_t)tf * NACC * row_elems, j, lane);
-  }
-  Frag<T> breg[R][KS];
-  auto load_b = [&](int kblk) {
+  const int ss = wg % a.SS, ustep = nwg / a.SS;
+  const int KBs = a.KBp / a.SS;                 // k-blocks of a super slice
+  const int nch = (KBs + NWV * KS - 1) / (NWV * KS);
+  const int NU = (a.NT + TT - 1) / TT;
+  const size_t row_elems = (size_t)a.KBp * BLOCK_ELEMS;
+  const T* wbase = a.W + (size_t)(ss * KBs) * BLOCK_ELEMS;
+  // this wave's first k-block of chunk ch inside the slice (0 if it has none), and whether it has one
+  auto kofs = [&](int ch) { const int o = (ch * NWV + wave) * KS; return o < KBs ? o : 0; };
+  auto kval = [&](int ch) { return (ch * NWV + wave) * KS < KBs; };
+  // tile row q of unit u (tiles beyond the last one re-read it; their results are dropped)
+  auto wptr = [&](int u, int q, int ch) {
+    const int t = min(u * TT + q / NACC, a.NT - 1);
+    return wbase + (size_t)(t * NACC + q % NACC) * row_elems + (size_t)kofs(ch) * BLOCK_ELEMS;
+  };
+  // activations in the fragment-tiled layout (xt_offset): every load is 1 KiB of consecutive memory
+  // (building them from the fp32 residual rows on load, as gemm_stream_kernel does for 8 rows,
+  // was measured slower than a stored copy at every width: those loads are 16 separate rows)
+  auto load_b = [&](Frag<T> (&dst)[R][KS], int ch) {
+    const int kb = ss * KBs + kofs(ch), KBx = a.ldx >> 5, glast = (a.mrows - 1) >> 4;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const T* xp = a.X + (size_t)(a.m0 + min(16 * r + c, a.mrows - 1)) * a.ldx + (size_t)kblk * TILE_K + g * 8;
+      const T* xp = a.X + ((size_t)((a.m0 >> 4) + min(r, glast)) * KBx + kb) * BLOCK_ELEMS + lane * 8;
 #pragma unroll
-      for (int j = 0; j < KS; ++j) breg[r][j] = frag_load_row(xp + j * TILE_K);
+      for (int j = 0; j < KS; ++j) dst[r][j] = frag_load_row(xp + j * BLOCK_ELEMS);
     }
   };
-  load_b(kb0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): enter the loop with nothing but known loads in flight
+  auto take_b = [&](Frag<T> (&dst)[R][KS], const Frag<T> (&src)[R][KS], bool valid) {
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int j = 0; j < KS; ++j) {
+        dst[r][j] = src[r][j];
+        if (!valid) frag_zero(dst[r][j]);
+      }
+  };
 
-  f32x4 acc[R][NACC];
+  int u = wg / a.SS, ch = 0;
+  Frag<T> ring[RING];
+  {
+    const int uf = u < NU ? u : 0;
+#pragma unroll
+    for (int i = 0; i < RING; ++i) ring[i] = frag_load_w(wptr(uf, i / KS, 0), i % KS, lane);
+  }
+  Frag<T> breg[R][KS], bnext[R][KS];
+  load_b(bnext, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): enter the loop with nothing but known loads in flight
+  take_b(breg, bnext, kval(0));
+
+  f32x4 acc[Q][R];
   float sq[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     sq[r] = 0.f;
 #pragma unroll
-    for (int s = 0; s < NACC; ++s) acc[r][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < Q; ++q) acc[q][r] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  int ch = 0;
-  while (t < a.NT) {
+  while (u < NU) {
     const bool last = ch + 1 == nch;
-    const int tn = t + tstep, tnc = tn < a.NT ? tn : 0;
-    const T* wcur = wlane + (size_t)t * NACC * row_elems + (size_t)ch * seg_elems;
-    const T* wnext = last ? wlane + (size_t)tnc * NACC * row_elems : wcur + seg_elems;
+    const int un = last ? u + ustep : u, chn = last ? 0 : ch + 1;
+    const int unc = un < NU ? un : 0;   // after the last unit the refill loads go on, harmlessly, into unit 0
+    const T *wc[Q], *wn[Q];
 #pragma unroll
-    for (int s = 0; s < NACC; ++s) {
+    for (int q = 0; q < Q; ++q) { wc[q] = wptr(u, q, ch); wn[q] = wptr(unc, q, chn); }
 #pragma unroll
-      for (int j = 0; j < KS; ++j) {
+    for (int i = 0; i < NF; ++i) {
+      const int q = i / KS, j = i % KS;
 #pragma unroll
-        for (int r = 0; r < R; ++r) acc[r][s] = mma(ring[j], breg[r][j], acc[r][s]);
-        if (s + 1 < NACC) ring[j] = frag_load_w(wcur + (s + 1) * row_elems, j, lane);
-        else ring[j] = frag_load_w(wnext, j, lane);
-        __builtin_amdgcn_sched_barrier(0x6);
-      }
+      for (int r = 0; r < R; ++r) acc[q][r] = mma(ring[i % RING], breg[r][j], acc[q][r]);
+      const int in = i + RING;
+      if (in < NF) ring[i % RING] = frag_load_w(wc[in / KS], in % KS, lane);
+      else ring[i % RING] = frag_load_w(wn[(in - NF) / KS], (in - NF) % KS, lane);
+      if (i == 0) load_b(bnext, chn);   // (after the first product, so that the loop starts with the oldest weight load)
+      __builtin_amdgcn_sched_barrier(0x6);
     }
-    // activations of the next chunk (chunk 0 of the next tile after the last one): one reload
-    // site, issued before the epilogue so that it overlaps it
-    load_b(kb0 + (last ? 0 : ch + 1) * seg);
+    take_b(breg, bnext, kval(chn));
     if (!last) { ++ch; continue; }
-    // tile done: reduce and finish one row group at a time
+    // unit done: add the four partial sums of every pair, PH pairs per round
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      if (wave != 0) {
+    for (int h = 0; h < P / PH; ++h) {
 #pragma unroll
-        for (int s = 0; s < NACC; ++s) red[wave][s][lane] = acc[r][s];
+      for (int pp = 0; pp < PH; ++pp) {
+        const int p = h * PH + pp, tt = p / R, r = p % R;
+#pragma unroll
+        for (int s = 0; s < NACC; ++s) red[wave][pp][s][lane] = acc[tt * NACC + s][r];
       }
       __syncthreads();
-      if (wave == 0) {
-        for (int w = 1; w < nw; ++w) {
+      for (int pp = wave; pp < PH; pp += NWV) {
+        const int p = h * PH + pp, tt = p / R, r = p % R;
+        f32x4 v[NACC];
 #pragma unroll
-          for (int s = 0; s < NACC; ++s) acc[r][s] += red[w][s][lane];
+        for (int s = 0; s < NACC; ++s) {
+          v[s] = red[0][pp][s][lane];
+#pragma unroll
+          for (int w = 1; w < NWV; ++w) v[s] += red[w][pp][s][lane];
         }
-        const int mr = 16 * r + c;
-        if (mr < a.mrows) {
+        const int t = u * TT + tt, mr = 16 * r + c;
+        if (t < a.NT && mr < a.mrows) {
           const int m = a.m0 + mr;
           const int n = t * TILE_N + 4 * g;
           if (EPI == EPI_PARTIAL) {
-            *reinterpret_cast<f32x4*>(a.out + ((size_t)ss * a.Mtot + m) * a.ldo + n) = acc[r][0];
+            *reinterpret_cast<f32x4*>(a.out + ((size_t)ss * a.Mtot + m) * a.ldo + n) = v[0];
           } else if (EPI == EPI_RESIDUAL) {
             f32x4* hp = reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n);
-            const f32x4 hv = *hp + acc[r][0];
+            const f32x4 hv = *hp + v[0];
             *hp = hv;
             *reinterpret_cast<f32x4*>(a.hg_out + (size_t)m * a.ldo + n) = hv * *reinterpret_cast<const f32x4*>(a.gain_out + n);
-            sq[r] += (hv.x * hv.x + hv.y * hv.y) + (hv.z * hv.z + hv.w * hv.w);
+            const float e = (hv.x * hv.x + hv.y * hv.y) + (hv.z * hv.z + hv.w * hv.w);
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr) sq[rr] += rr == r ? e : 0.f;
           } else {   // EPI_SWIGLU
-            f32x4 v;
+            f32x4 o;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              const float gt = acc[r][0][i], up = acc[r][NACC - 1][i];
-              v[i] = (n + i < a.N) ? gt / (1.f + expf(-gt)) * up : 0.f;
+              const float gt = v[0][i], up = v[NACC - 1][i];
+              o[i] = (n + i < a.N) ? gt / (1.f + expf(-gt)) * up : 0.f;
             }
-            st_round4(a.act + (size_t)m * a.ldact + n, v);
+            st_round4(a.act_tiled ? a.act + xt_offset(m, n, a.ldact) : a.act + (size_t)m * a.ldact + n, o);
           }
         }
       }
       __syncthreads();
-#pragma unroll
-      for (int s = 0; s < NACC; ++s) acc[r][s] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    t = tn; ch = 0;
+#pragma unroll
+    for (int q = 0; q < Q; ++q)
+#pragma unroll
+      for (int r = 0; r < R; ++r) acc[q][r] = f32x4{0.f, 0.f, 0.f, 0.f};
+    u = un; ch = 0;
   }
 
-  if (EPI == EPI_RESIDUAL && wave == 0) {
+  if (EPI == EPI_RESIDUAL) {
+    // this workgroup's partial sum of squares per row: lane groups, then waves in order
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       float v = sq[r];
       v += __shfl_xor(v, 16); v += __shfl_xor(v, 32);
-      const int mr = 16 * r + c;
-      if (g == 0 && mr < a.mrows) {
+      if (g == 0) wsq[wave][r][c] = v;
+    }
+    __syncthreads();
+    if (wave == 0 && g < R) {   // lane group g takes row group g
+      const int mr = 16 * g + c;
+      if (mr < a.mrows) {
+        float v = wsq[0][g][c];
+#pragma unroll
+        for (int w = 1; w < NWV; ++w) v += wsq[w][g][c];
         float* dst = a.ssq_out + (size_t)(a.m0 + mr) * SSQ_PARTS;
         for (int p = wg; p < SSQ_PARTS; p += nwg) dst[p] = p == wg ? v : 0.f;
       }
@@ -542,11 +601,12 @@ __global__ void __launch_bounds__(512) gemm_rows_kernel(const GemmArgs<T> a) {
 }
 
 // xn[row][:] = T(hg[row][:] * rsqrt(mean(h[row]^2) + eps)) for rows m0 + blockIdx.x: the
-// RMSNorm output as a stored tensor, for projection passes of more than 8 rows.
+// RMSNorm output as a stored tensor, for projection passes of more than 8 rows (row-major for
+// 9..16 rows, fragment-tiled for the passes of gemm_rows_kernel).
 // 256 threads; thread p adds slot p of the row's sum-of-squares partials.
 template <typename T>
 __global__ void __launch_bounds__(256) xn_kernel(const float* __restrict__ hg, const float* __restrict__ ssq,
-                                                 T* __restrict__ xn, int ld, int m0, float d, float eps) {
+                                                 T* __restrict__ xn, int ld, int m0, float d, float eps, int tiled) {
   __shared__ float part[4];
   const int row = m0 + blockIdx.x;
   float s = ssq[(size_t)row * SSQ_PARTS + threadIdx.x];
@@ -556,8 +616,10 @@ __global__ void __launch_bounds__(256) xn_kernel(const float* __restrict__ hg, c
   __syncthreads();
   const float r = rsqrtf(((part[0] + part[1]) + (part[2] + part[3])) / d + eps);
   const float* src = hg + (size_t)row * ld;
-  T* dst = xn + (size_t)row * ld;
-  for (int i = 4 * threadIdx.x; i < ld; i += 4 * 256) st_round4(dst + i, *reinterpret_cast<const f32x4*>(src + i) * r);
+  for (int i = 4 * threadIdx.x; i < ld; i += 4 * 256) {
+    T* dst = tiled ? xn + xt_offset(row, i, ld) : xn + (size_t)row * ld + i;
+    st_round4(dst, *reinterpret_cast<const f32x4*>(src + i) * r);
+  }
 }
 
 }  // namespace dbl

@@ -492,6 +492,7 @@ template <typename T>
 struct CombineArgs {
   const float *pm, *pl, *po;
   T* attn; int ldat;
+  int tiled;                        // attn in the fragment-tiled layout (more than 16 rows) or row-major
   int Mtot, k, H, Hkv, qrows_pad, nsplit;
   // KV append (the same launch, further waves): the window rows' keys and values go to
   // cache positions kv_len[b] + j
@@ -591,7 +592,8 @@ __device__ __forceinline__ void combine_task(const CombineArgs<T>& a, int task) 
     for (int i = 0; i < DPL; ++i) acc[i] += v[i] * wu;
   }
   const float inv = L > 0.f ? 1.f / L : 0.f;
-  T* dst = a.attn + (size_t)m * a.ldat + (size_t)hh * HD + lane * DPL;
+  T* dst = a.tiled ? a.attn + xt_offset(m, hh * HD + lane * DPL, a.ldat)
+                   : a.attn + (size_t)m * a.ldat + (size_t)hh * HD + lane * DPL;
   if (DPL == 2 && sizeof(T) == 2) {
     *reinterpret_cast<uint32_t*>(dst) = (pack_bf16(acc[0] * inv, acc[DPL - 1] * inv));
   } else {
