@@ -29,11 +29,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
-# HBM bytes one launch of the dominant kernel (fused gate/up projection) moves, from two
-# rocprofv3 --pmc runs (FETCH_SIZE scaled by 2.000, the factor a plain 1 GiB copy gives on
-# this box, plus WRITE_SIZE); summary in profiles/gate_up_projection_llama70b_traffic.txt.
+# HBM bytes one launch of the dominant kernel (fused gate/up projection: gemm_rows_kernel plus
+# the xn_kernel that stores its normalised input) moves, from two rocprofv3 --pmc runs
+# (FETCH_SIZE scaled by 2.000, the factor a plain 1 GiB copy gives on this machine, plus
+# WRITE_SIZE); summary in profiles/gate_up_projection_llama70b_traffic.txt.
 # Counters cannot be read inside this process, so the figure is the recorded one.
-MEASURED_TRAFFIC = {"llama70b_ctx2048_k8_b1_greedy": 944_741_376}   # 922 599 KiB
+MEASURED_TRAFFIC = {"llama70b_ctx2048_k8_b1_greedy": 944_398_336}   # 921 208 + 1 056 KiB
 
 WORKLOADS = {
     # name: (shape key, context, k, batch, mode, temperature, repeat fraction, span lo, span hi)
@@ -311,7 +312,7 @@ def main():
     breakdown = {n: round(v, 4) for n, v in zip(names, acc)}
 
     # dominant kernel: the fused gate/up + SwiGLU projection (55% of the bytes at 70B shape)
-    M = min(16, Bn * k)
+    M = min(64, Bn * k)    # rows of one projection pass
     proj = {}
     for which, name in enumerate(["qkv", "o_proj", "gate_up_swiglu", "down_proj", "lm_head_stats"]):
         if which < 4 and shape["n_layers"] < 1:
@@ -319,7 +320,7 @@ def main():
         ms, nbytes = B.dbl_bench_projection(ctx, which, M, args.kernel_iters if which != 4 else max(4, args.kernel_iters // 4))
         proj[name] = {"ms": round(ms, 5), "GB/s": round(nbytes / ms / 1e6, 1), "bytes": nbytes}
     dom = proj.get("gate_up_swiglu") or proj["lm_head_stats"]
-    roofline = {"bound": "hbm", "kernel": "gemm_stream_kernel<bf16, EPI_SWIGLU> (fused gate/up projection)",
+    roofline = {"bound": "hbm", "kernel": "gemm_rows_kernel<EPI_SWIGLU> after xn_kernel (fused gate/up projection of one layer)",
                 "achieved": dom["GB/s"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(dom["GB/s"] / HBM_PEAK_GBPS, 4), "traffic": None,
                 "bytes_per_launch": dom["bytes"], "ms_per_launch": dom["ms"]}

@@ -14,9 +14,7 @@ HEADERS = ["dbl_dev.h", "dbl_gemm.h", "dbl_kernels.h", "dbl_phases.h", os.path.j
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",
          # packed fp32 arithmetic is kept off for every kernel of this library
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         # one-lane atomics stay one-lane atomics: the optimizer's read-first-lane would wait for the answer at once
-         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
 def stale() -> bool:

@@ -110,7 +110,6 @@ struct dbl_ctx {
   void* xn = nullptr;               // RMSNorm output of the current 16-row pass (windows of more than 8 rows)
   float *qkv_part = nullptr, *logits = nullptr;
   void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
-  unsigned* tile_ctr = nullptr;     // dynamic tile scheduling: counters, zero between launches
   int ldh = 0;                      // row stride of h and layer stride of g1 / g2 / gf (>= every consumer's K padding)
   float *pm = nullptr, *pl = nullptr, *po = nullptr;
   LmStat* stats = nullptr;
@@ -258,7 +257,6 @@ template <typename T>
 void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
   a.NT = p.NT; a.N = p.N; a.KBp = p.KBp; a.SS = p.SS; a.NCH = p.NCH; a.Mtot = M;
   a.d = (float)c->cfg.d_model; a.eps = c->cfg.rms_eps; a.ssq_in = c->ssq; a.ssq_out = c->ssq;
-  a.tile_ctr = c->tile_ctr;
   static_assert(SSQ_PARTS == 256, "xn_kernel adds one partial per thread");
   const bool rows = rows_kernel_for(c, p, epi, M);
   if (rows) {
@@ -290,7 +288,6 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
         if (p.NCH > 1) launch_gemm_t<T, EPI_RESIDUAL, true>(c, p, a);
         else launch_gemm_t<T, EPI_RESIDUAL, false>(c, p, a);
         break;
-      case EPI_SWIGLU: launch_gemm_t<T, EPI_SWIGLU, false>(c, p, a); break;
       default: launch_gemm_t<T, EPI_LMHEAD, false>(c, p, a); break;
     }
   }
@@ -523,7 +520,7 @@ int copy_tensor(dbl_ctx* c, const TensorLoc& t, int layer, void* host, bool to_d
 
 void free_all(dbl_ctx* c) {
   void* ptrs[] = {c->w_qkv, c->w_o, c->w_gu, c->w_d, c->w_lm, c->emb, c->g1, c->g2, c->gq, c->gk, c->gf, c->cosT,
-                  c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->prompt_len, c->rej, c->rej_len, c->tier_best, c->prior, c->status, c->commits, c->h, c->hg, c->xn, c->tile_ctr, c->qkv_part,
+                  c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->prompt_len, c->rej, c->rej_len, c->tier_best, c->prior, c->status, c->commits, c->h, c->hg, c->xn, c->qkv_part,
                   c->ssq, c->logits, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
                   c->n_acc_i, c->emit_i, c->win_i};
   for (void* p : ptrs) if (p) (void)hipFree(p);
@@ -599,7 +596,6 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     const size_t M16 = (size_t)(Mmax + 15) / 16 * 16;   // the fragment-tiled activation layout holds whole groups of 16 rows
     ALLOC(xn, M16 * c->ldh * esz, true);
     ALLOC(ssq, (size_t)Mmax * SSQ_PARTS * 4, true);
-    ALLOC(tile_ctr, (DYN_DONE + 1) * sizeof(unsigned), true);
     ALLOC(qkv_part, (size_t)c->p_qkv.SS * Mmax * c->p_qkv.ldo() * 4, true);
     ALLOC(qbuf, (size_t)g.max_batch * g.n_kv_heads * c->qrows_pad * g.head_dim * esz, true);
     ALLOC(logits, (size_t)Mmax * c->p_lm.ldo() * 4, true);

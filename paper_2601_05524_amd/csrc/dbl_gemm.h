@@ -1,33 +1,33 @@
-// Weight-streaming small-M projection kernels (M = batch * window rows <= 16 per pass).
+// Weight-streaming projection kernels.
 //
-// The verify step reads every weight once and reuses it for M <= 16 rows, so it is
-// bound by HBM bandwidth (arithmetic intensity M flop/byte against a ridge of ~300).
-// Design:
-//   * weights are the MFMA A operand (16 output features x 32 inputs per block) in
-//     the tiled layout of dbl_dev.h, so every wave-level load is 1 KiB contiguous;
-//   * the activations (the B operand, 32 inputs x 16 rows) of a wave's K slice live
-//     in registers: a wave owns KS k-blocks of every output tile its workgroup
-//     visits, so activations are fetched once per wave (once per K chunk in the
-//     chunked form below);
-//   * the NW waves of a workgroup own NW consecutive K slices of the same output
-//     tile; their partial tiles are summed through LDS in a fixed order
-//     (deterministic, no atomics) and wave 0 applies the epilogue;
-//   * loads run RING blocks ahead of the MFMAs and the ring runs across output
-//     tiles, so the memory pipe never drains inside a kernel;
-//   * a workgroup starts at output tile wg/SS and then either steps by nwg/SS or draws
-//     further tiles from a device counter (see the kernel);
-//   * K longer than NW*KS blocks is covered either by SS workgroup "super slices",
-//     each writing its own partial result that the consumer sums (q/k/v projection),
-//     or by NCH sequential K chunks inside the workgroup with the accumulator kept
-//     in registers (CHUNK form: output and down projection, which add straight into
-//     the residual stream).
+// The verify step reads every weight once and reuses it for the M = batch * window rows, so it
+// is bound by HBM bandwidth (arithmetic intensity M flop/byte against a ridge of ~300).  Weights
+// are the MFMA A operand (16 output features x 32 inputs per block) in the tiled layout of
+// dbl_dev.h, so every wave-level load is 1 KiB contiguous and non-temporal; activations (the B
+// operand, 32 inputs x 16 rows) live in registers; loads run a ring of blocks ahead of the
+// MFMAs and the ring never drains inside a kernel; partial sums of the waves that split K are
+// added through LDS in a fixed order (deterministic, no atomics).  Two kernels:
+//
+// gemm_stream_kernel (at most 16 rows per pass: q/k/v at up to 8 rows, the LM head always,
+// output/down at narrow widths):
+//   * a wave owns KS k-blocks of every output tile its workgroup visits, so activations are
+//     fetched once per wave (once per K chunk in the chunked form);
+//   * the NW <= 8 waves of a workgroup own consecutive K slices of the same output tile; wave 0
+//     applies the epilogue;
+//   * a workgroup starts at output tile wg/SS and steps by nwg/SS;
+//   * K longer than NW*KS blocks is covered either by SS workgroup "super slices", each writing
+//     its own partial result that the consumer sums (q/k/v projection), or by NCH sequential K
+//     chunks inside the workgroup with the accumulator kept in registers (CHUNK form).
+//
+// gemm_rows_kernel (any number of rows in passes of up to 64; the gate/up projection always):
+// see its own comment.
 //
 // RMSNorm is not a kernel of its own.  Whichever kernel wrote the residual stream h last
 // (embedding, output projection, down projection) also stores hg = h * gain of the next
 // norm, and each of its workgroups leaves one partial sum of squares per row in
-// ssq[row][workgroup] (SSQ_PARTS slots per row, unused ones zero).  The projections that
-// consume a normalised input (q/k/v, gate/up, LM head) add the partials in a fixed order
-// and build bf16(hg * rsqrt(mean(h^2) + eps)) while loading their activation registers.
+// ssq[row][workgroup] (SSQ_PARTS slots per row, unused ones zero).  gemm_stream_kernel adds the
+// partials in a fixed order and builds bf16(hg * rsqrt(mean(h^2) + eps)) while loading its
+// activation registers (at most 8 rows); xn_kernel stores that tensor for everything else.
 #pragma once
 #include "dbl_dev.h"
 
@@ -35,7 +35,6 @@ namespace dbl {
 
 enum GemmEpi { EPI_PARTIAL = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3 };
 
-constexpr int DYN_DONE = 8;       // tile_ctr[0..7]: tiles drawn per super slice; tile_ctr[DYN_DONE]: workgroups that left
 constexpr int SSQ_PARTS = 256;    // sum-of-squares partials per row; a producer launches at most this many workgroups
 
 // Per-workgroup, per-row statistics left by the LM-head epilogue.
@@ -74,7 +73,6 @@ struct GemmArgs {
   int KBp;             // k-blocks per tile row = SS * NCH * NW * KS
   int SS;              // super slices; number of workgroups % SS == 0
   int NCH;             // K chunks walked by one workgroup (1 unless the CHUNK form runs)
-  unsigned* tile_ctr;  // SWIGLU: [DYN_DONE + 1] tile counters per super slice + departures, all zero between launches
   float* out;          // PARTIAL: [SS][Mtot][ldo] ; RESIDUAL: h[Mtot][ldo] (+=) ; LMHEAD: logits[Mtot][ldo]
   int ldo;
   float* ssq_out;      // RESIDUAL: [Mtot][SSQ_PARTS] partial sums of squares of the updated rows
@@ -164,11 +162,8 @@ __device__ __forceinline__ void load_acts(const GemmArgs<T>& a, int kblk, float 
 // activations of the next chunk are fetched while the current one is multiplied.
 template <typename T, int EPI, int KS, bool PACK, bool CHUNK>
 __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
-  // Tiles are drawn dynamically where the epilogue keeps no state across tiles and a tile
-  // lasts much longer than a round trip to the counter: the gate/up projection (~19 us per
-  // tile; the q/k/v projection's ~5 us tiles lose more to the counter than they gain).
-  constexpr bool DYN = EPI == EPI_SWIGLU;
-  constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
+  static_assert(EPI != EPI_SWIGLU, "the gate/up projection runs in gemm_rows_kernel");
+  constexpr int NACC = 1;
   constexpr int RING = GemmCfg<T>::RING;
   constexpr int NB = PACK ? KS / 2 : KS;       // activation register sets
   // Normalise-on-load only in the packed form (at most 8 rows): for 9..16 rows the fp32
@@ -185,18 +180,7 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
   const int c = lane & 15, g = lane >> 4;
   const int ss = wg % a.SS;
   const int tstep = nwg / a.SS;
-  // Tile order.  The first tile of a workgroup is wg/SS.  Static form: then +tstep each
-  // round.  DYN form: the second tile too, every further one is taken from a device counter
-  // (one per super slice), so workgroups that stream faster take more tiles.  Under a saturating read the
-  // odd-numbered XCDs of an MI355X get 7-10% less bandwidth than the even ones; with
-  // equal shares the even half of the chip idles at the end of every long kernel.
-  // A tile's result does not depend on who computes it (same K split, same reduction
-  // order), so the result stays deterministic as long as the epilogue keeps no state
-  // across tiles.
-  // The id of the tile after the current one must be known when the current one starts
-  // (the weight ring runs across the boundary), so ids are drawn two tiles ahead by
-  // thread 0 and handed to the other waves at the barrier that ends each tile.
-  __shared__ int s_next[2];
+  // Tile order: a workgroup starts at tile wg/SS and steps by nwg/SS.
   int t = wg / a.SS;
   int tn = t + tstep;
   const int nch = CHUNK ? a.NCH : 1;
@@ -250,14 +234,6 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
   for (int s = 0; s < NACC; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int it = 0; t < a.NT;) {
     const bool last = !CHUNK || ch + 1 == nch;
-    // DYN, thread 0 only: the tile after the next one.  Left without a value in the other
-    // threads on purpose: a defined value there would make the compiler wait for the
-    // counter's answer (and with it for every weight load in flight) right here.
-    int drawn;
-    if constexpr (DYN) {
-      if (threadIdx.x == 0)
-        drawn = (int)__hip_atomic_fetch_add(a.tile_ctr + ss, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
     // after the last tile the refill loads go on, harmlessly, into tile 0 (an L2 hit)
     const int tnc = tn < a.NT ? tn : 0;
     const T* wcur = wlane + (size_t)t * NACC * row_elems + (size_t)ch * seg_elems;
@@ -296,9 +272,6 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
       if (!last) { ++ch; continue; }
     }
     const int buf = it & 1;
-    if constexpr (DYN) {
-      if (threadIdx.x == 0) s_next[(it + 1) & 1] = drawn + 2 * tstep;   // first use of the counter's answer
-    }
     if (wave != 0) {
 #pragma unroll
       for (int s = 0; s < NACC; ++s) red[buf][wave][s][lane] = acc[s];
@@ -319,14 +292,6 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
           *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = hv;
           *reinterpret_cast<f32x4*>(a.hg_out + (size_t)m * a.ldo + n) = hv * gout;
           sq += (hv.x * hv.x + hv.y * hv.y) + (hv.z * hv.z + hv.w * hv.w);
-        } else if (EPI == EPI_SWIGLU) {
-          f32x4 v;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float gt = acc[0][i], up = acc[1][i];
-            v[i] = (n + i < a.N) ? gt / (1.f + expf(-gt)) * up : 0.f;
-          }
-          st_round4(a.act + (size_t)m * a.ldact + n, v);
         } else {  // EPI_LMHEAD
           *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = acc[0];
           Philox4 rnd{0, 0, 0, 0};
@@ -355,21 +320,10 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
       }
     }
     t = tn;
-    tn = DYN ? s_next[(it + 1) & 1] : tn + tstep;
+    tn += tstep;
     ++it; ch = 0;
 #pragma unroll
     for (int s = 0; s < NACC; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-
-  if constexpr (DYN) {
-    // the last workgroup to leave rewinds the counters for the next launch that uses them
-    if (threadIdx.x == 0) {
-      const unsigned left = __hip_atomic_fetch_add(a.tile_ctr + DYN_DONE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (left == (unsigned)nwg - 1) {
-        for (int i = 0; i < a.SS; ++i) __hip_atomic_store(a.tile_ctr + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(a.tile_ctr + DYN_DONE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-    }
   }
 
   if (EPI == EPI_RESIDUAL && wave == 0) {
