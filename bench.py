@@ -42,6 +42,9 @@ WORKLOADS = {
     "llama1b_ctx1024_k8_b1_greedy": ("llama1b", 1024, 8, 1, "greedy", 0.0, 0.15, 16, 16),
     "qwen32b_ctx8192_k16_b1_sample": ("qwen32b", 8192, 16, 1, "sample", 0.7, 0.20, 16, 16),
     "tiny_ctx256_k4_b1_greedy": ("tiny", 256, 4, 1, "greedy", 0.0, 0.25, 8, 8),
+    # higher concurrency (App. D.1's regime): 64 and 128 window rows per step at the headline context
+    "llama70b_ctx2048_k8_b8_greedy": ("llama70b", 2048, 8, 8, "greedy", 0.0, 0.20, 16, 16),
+    "llama70b_ctx2048_k8_b16_greedy": ("llama70b", 2048, 8, 16, "greedy", 0.0, 0.20, 16, 16),
     # long-context stress: the KV cache is a seeded fill (dbl_kv_fill), not a prefill: bandwidth runs
     "llama70b_ctx32768_k4_b4_sample": ("llama70b", 32768, 4, 4, "sample", 1.0, 0.30, 8, 64),
     "llama70b_ctx32768_k8_b4_sample": ("llama70b", 32768, 8, 4, "sample", 1.0, 0.30, 8, 64),
@@ -225,7 +228,7 @@ def main():
     idx = list(synth.CONFIGS).index(shape_key)
     seed = synth.BASE_SEED + idx
     steps, warm = args.steps, args.warmup
-    chunk = 16
+    chunk = min(16, 128 // Bn)      # rows of one prefill call stay within the library's 128
     if P > 8192:
         steps, warm = min(steps, 6), min(warm, 1)       # a 128-row window streams the weights 8 times
     max_ctx = ((P + (steps + warm + 6) * k + 63) // 64 + 1) * 64

@@ -224,6 +224,21 @@ int dbl_verify_block(dbl_ctx* ctx, const int32_t* window_dev, int B, int k, floa
                      uint64_t seed, uint64_t step, float* logits_opt_dev);
 
 /*
+ * The same forward for windows of different lengths in one batch (the higher-concurrency
+ * regime of App. D.1: sequences with different numbers of drafts, or none, share a step).
+ * win_len_dev[b] (device, int32, clamped to 0..k) is the number of real rows of sequence b:
+ * its pending token and win_len[b]-1 drafts.  Rows beyond it are computed (all B*k rows run,
+ * the projections are bound by the weights, not by the rows) but count as "no draft":
+ * dbl_accept accepts at most win_len[b]-1 drafts and emits at most win_len[b] tokens, and
+ * their logits are meaningless.  win_len[b] = 0 leaves sequence b untouched by the step:
+ * dbl_accept reports n_acc[b] = -1 and emits nothing, dbl_kv_commit keeps nothing.
+ * Every sequence still needs room for k rows (kv_len[b] + k <= max_ctx).  Everything else
+ * as dbl_verify_block, including ownership, capture and error behaviour.
+ */
+int dbl_verify_block_ragged(dbl_ctx* ctx, const int32_t* window_dev, const int32_t* win_len_dev, int B, int k,
+                            float temperature, uint64_t seed, uint64_t step, float* logits_opt_dev);
+
+/*
  * Acceptance on the rows of the last dbl_verify_block (same B, k, window).
  * mode DBL_GREEDY (App. D.2): y_j = argmax of row j (lowest id on ties); n_acc =
  * number of leading drafts with window[j+1] == y_j; emit = those drafts then

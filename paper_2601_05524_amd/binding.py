@@ -22,7 +22,7 @@ T_G1, T_WQ, T_WK, T_WV, T_GQ, T_GK, T_WO, T_G2, T_WG, T_WU, T_WD = range(10, 21)
 
 EXPORTS = ["dbl_create", "dbl_destroy", "dbl_last_error", "dbl_set_weights", "dbl_get_weights", "dbl_reset", "dbl_truncate", "dbl_kv_fill",
            "dbl_retrieve_tiered", "dbl_session_mark", "dbl_prior_set", "dbl_rejected_update", "dbl_rejected_get",
-           "dbl_history_set", "dbl_history_get", "dbl_retrieve", "dbl_build_window", "dbl_verify_block", "dbl_accept",
+           "dbl_history_set", "dbl_history_get", "dbl_retrieve", "dbl_build_window", "dbl_verify_block", "dbl_verify_block_ragged", "dbl_accept",
            "dbl_kv_commit", "dbl_kv_len", "dbl_hist_len", "dbl_model_bytes", "dbl_debug_buffer",
            "dbl_bench_projection"]
 
@@ -72,6 +72,7 @@ def lib():
         L.dbl_retrieve.argtypes = [vp, i, i, i, i, i32p, i32p, i32p, i32p]
         L.dbl_build_window.argtypes = [vp, i, i, i, i32p, i32p, C.c_int32, i32p]
         L.dbl_verify_block.argtypes = [vp, i32p, i, i, C.c_float, C.c_uint64, C.c_uint64, vp]
+        L.dbl_verify_block_ragged.argtypes = [vp, i32p, i32p, i, i, C.c_float, C.c_uint64, C.c_uint64, vp]
         L.dbl_accept.argtypes = [vp, i, vp, i32p, i32p, i32p]
         L.dbl_kv_commit.argtypes = [vp, i32p]
         L.dbl_kv_len.argtypes = [vp, vp]
@@ -182,6 +183,11 @@ def dbl_build_window(ctx, B, k, max_cont, cont, cont_len, pad_id, window):
 
 def dbl_verify_block(ctx, window, B, k, temperature=0.0, seed=0, step=0, logits_opt=None):
     return _chk(ctx, lib().dbl_verify_block(ctx, _ptr(window), B, k, temperature, seed, step, _ptr(logits_opt)))
+
+
+def dbl_verify_block_ragged(ctx, window, win_len, B, k, temperature=0.0, seed=0, step=0, logits_opt=None):
+    return _chk(ctx, lib().dbl_verify_block_ragged(ctx, _ptr(window), _ptr(win_len), B, k, temperature, seed, step,
+                                                   _ptr(logits_opt)))
 
 
 def dbl_accept(ctx, mode, q_probs, n_acc, emit, guide):

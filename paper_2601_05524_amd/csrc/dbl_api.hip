@@ -868,9 +868,8 @@ int dbl_build_window(dbl_ctx* c, int B, int k, int max_cont, const int32_t* cont
   return DBL_OK;
 }
 
-int dbl_verify_block(dbl_ctx* c, const int32_t* window, int B, int k, float temperature, uint64_t seed, uint64_t step,
-                     float* logits_opt) {
-  if (!c) return DBL_EINVAL;
+static int verify_common(dbl_ctx* c, const int32_t* window, const int32_t* win_len, int B, int k, float temperature,
+                         uint64_t seed, uint64_t step, float* logits_opt) {
   if (!window) return fail(c, DBL_EINVAL, "null window");
   if (B < 1 || B > c->cfg.max_batch) return fail(c, DBL_EINVAL, "B out of range");
   if (k < 1 || k > c->cfg.max_window) return fail(c, DBL_EINVAL, "k out of range");
@@ -879,8 +878,13 @@ int dbl_verify_block(dbl_ctx* c, const int32_t* window, int B, int k, float temp
     if (c->kv_upper[b] + k > c->cfg.max_ctx) return fail(c, DBL_EINVAL, "kv_len + k would exceed max_ctx");
   c->have_verify = false; c->have_accept = false;
   if (c->dry) { c->have_verify = true; c->last_B = B; c->last_k = k; c->verify_sampling = temperature > 0.f; return DBL_ENODEV; }
-  // keep the window for accept (the caller's buffer is not retained)
-  HIPCHK(c, hipMemcpyAsync(c->win_i, window, (size_t)B * k * 4, hipMemcpyDeviceToDevice, c->stream));
+  // keep the window for accept (the caller's buffer is not retained); ragged: rows beyond a
+  // sequence's own length are marked "no token"
+  if (win_len) {
+    hipLaunchKernelGGL(mask_window_kernel, dim3((B * k + 127) / 128), dim3(128), 0, c->stream, window, win_len, B, k, c->win_i);
+  } else {
+    HIPCHK(c, hipMemcpyAsync(c->win_i, window, (size_t)B * k * 4, hipMemcpyDeviceToDevice, c->stream));
+  }
   int rc = c->bf16 ? verify_impl<bf16_t>(c, c->win_i, B, k, temperature, seed, step)
                    : verify_impl<float>(c, c->win_i, B, k, temperature, seed, step);
   if (rc != DBL_OK) return rc;
@@ -891,6 +895,19 @@ int dbl_verify_block(dbl_ctx* c, const int32_t* window, int B, int k, float temp
   c->have_verify = true; c->last_B = B; c->last_k = k; c->verify_sampling = temperature > 0.f;
   c->last_T = temperature; c->last_seed = seed; c->last_step = step;
   return DBL_OK;
+}
+
+int dbl_verify_block(dbl_ctx* c, const int32_t* window, int B, int k, float temperature, uint64_t seed, uint64_t step,
+                     float* logits_opt) {
+  if (!c) return DBL_EINVAL;
+  return verify_common(c, window, nullptr, B, k, temperature, seed, step, logits_opt);
+}
+
+int dbl_verify_block_ragged(dbl_ctx* c, const int32_t* window, const int32_t* win_len, int B, int k, float temperature,
+                            uint64_t seed, uint64_t step, float* logits_opt) {
+  if (!c) return DBL_EINVAL;
+  if (!win_len) return fail(c, DBL_EINVAL, "null win_len");
+  return verify_common(c, window, win_len, B, k, temperature, seed, step, logits_opt);
 }
 
 int dbl_accept(dbl_ctx* c, int mode, const float* q_probs, int32_t* n_acc, int32_t* emit, int32_t* guide) {

@@ -32,6 +32,14 @@ __global__ void __launch_bounds__(256) embed_kernel(const T* __restrict__ E, con
   for (int p = threadIdx.x; p < SSQ_PARTS; p += blockDim.x) ssq[(size_t)m * SSQ_PARTS + p] = p == 0 ? s : 0.f;
 }
 
+// win[b][j] = j < win_len[b] ? window[b][j] : -1 (no token): the window kept for the LM head's
+// draft look-up and for acceptance, with rows beyond a sequence's own length marked.
+__global__ void mask_window_kernel(const int32_t* __restrict__ window, const int32_t* __restrict__ win_len, int B, int k,
+                                   int32_t* __restrict__ win) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < B * k) win[i] = (i % k) < win_len[i / k] ? window[i] : -1;
+}
+
 // ------------------------------------------------------------------- accept
 
 struct AcceptArgs {
@@ -93,8 +101,13 @@ __global__ void __launch_bounds__(256) accept_kernel(const AcceptArgs a) {
 
   const int32_t* win = a.window + (size_t)b * a.k;
   if (tid == 0) {
+    // A negative id marks a row beyond the sequence's own window (ragged batches): no draft
+    // there, and a sequence whose first row is marked takes no part in the step (n = -1).
     int n = a.k - 1, need = 0, tok = -1;
-    if (a.mode == 0) {
+    if (win[0] < 0) {
+      n = -1;
+      for (int j = 0; j < a.k; ++j) a.guide[(size_t)b * a.k + j] = -1;
+    } else if (a.mode == 0) {
       n = 0;
       while (n < a.k - 1 && win[n + 1] == row[n].best_id) ++n;
       tok = row[n].best_id;
@@ -102,6 +115,7 @@ __global__ void __launch_bounds__(256) accept_kernel(const AcceptArgs a) {
     } else {
       for (int j = 0; j < a.k - 1; ++j) {
         const int x = win[j + 1];
+        if (x < 0) { n = j; break; }
         const float lse = row[j].smax + logf(row[j].ssum);
         const float px = expf(row[j].zdraft * a.inv_T - lse);
         const Philox4 r = philox4x32_10((uint32_t)stepv, (uint32_t)b, (uint32_t)j, 0u, (uint32_t)a.seed,
@@ -110,7 +124,7 @@ __global__ void __launch_bounds__(256) accept_kernel(const AcceptArgs a) {
         const float qx = a.q ? a.q[((size_t)b * (a.k - 1) + j) * a.V + x] : 1.f;
         if (!(u * qx < px)) { n = j; break; }
       }
-      if (n < a.k - 1) {
+      if (n < a.k - 1 && win[n + 1] >= 0) {
         if (a.q) { need = 1; tok = row[n].p1_id; /* fallback if the residual is empty */ }
         else { const int x = win[n + 1]; tok = row[n].p1_id != x ? row[n].p1_id : row[n].p2_id; }
       } else {
@@ -119,7 +133,7 @@ __global__ void __launch_bounds__(256) accept_kernel(const AcceptArgs a) {
       for (int j = 0; j < a.k; ++j) a.guide[(size_t)b * a.k + j] = j <= n ? row[j].p1_id : -1;
     }
     s_n = n; s_need_resid = need; s_tok = tok;
-    s_lse = a.mode ? row[n].smax + logf(row[n].ssum) : 0.f;
+    s_lse = (a.mode && n >= 0) ? row[n].smax + logf(row[n].ssum) : 0.f;
   }
   __syncthreads();
   const int n = s_n;
@@ -332,8 +346,10 @@ __global__ void rejected_update_kernel(int32_t* __restrict__ rej, int32_t* __res
   const int32_t* w = window + (size_t)b * k;
   int32_t* r = rej + (size_t)b * rej_cap;
   const int len = min(hist_len[b], max_hist);
+  if (w[0] < 0 || n_acc[b] < 0) return;   // the sequence took no part in the step
   const int na = max(0, min(n_acc[b], k - 1));
-  const int nd = n_draft ? max(0, min(n_draft[b], k - 1)) : k - 1;
+  int nd = n_draft ? max(0, min(n_draft[b], k - 1)) : k - 1;
+  while (nd > na && w[nd] < 0) --nd;      // rows beyond the sequence's own window hold no draft
   const int n_rej = nd - na;
   if (n_rej < 1) return;
   const int avail = len + na;

@@ -82,11 +82,15 @@ class Gpu:
                 "wk": Hkv * hd * d, "wv": Hkv * hd * d, "wo": d * H * hd, "wg": F * d, "wu": F * d, "wd": d * F}[name]
 
     # -- one call each, returning host arrays (synchronising) -------------
-    def verify(self, windows, temperature=0.0, seed=0, step=0, want_logits=True):
+    def verify(self, windows, temperature=0.0, seed=0, step=0, want_logits=True, win_len=None):
         w = torch.as_tensor(np.asarray(windows, dtype=np.int32), device=DEV)
         Bn, k = w.shape
         lg = torch.empty((Bn, k, self.V), dtype=torch.float32, device=DEV) if want_logits else None
-        B.dbl_verify_block(self.ctx, w, Bn, k, temperature, seed, step, lg)
+        if win_len is None:
+            B.dbl_verify_block(self.ctx, w, Bn, k, temperature, seed, step, lg)
+        else:
+            wl = torch.as_tensor(np.asarray(win_len, dtype=np.int32), device=DEV)
+            B.dbl_verify_block_ragged(self.ctx, w, wl, Bn, k, temperature, seed, step, lg)
         self._bk = (Bn, k)
         torch.cuda.synchronize()
         return lg.cpu().numpy() if want_logits else None

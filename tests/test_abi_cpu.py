@@ -76,6 +76,10 @@ def test_validate_only_context_checks_arguments_and_order():
     assert L.dbl_verify_block(ctx, p, 1, 9, 0.0, 0, 0, None) == B.DBL_EINVAL
     assert L.dbl_verify_block(ctx, p, 0, 4, 0.0, 0, 0, None) == B.DBL_EINVAL
     assert L.dbl_verify_block(ctx, p, 1, 4, float("nan"), 0, 0, None) == B.DBL_EINVAL
+    assert L.dbl_verify_block_ragged(ctx, p, None, 1, 4, 0.0, 0, 0, None) == B.DBL_EINVAL   # lengths are required
+    assert L.dbl_verify_block_ragged(ctx, None, p, 1, 4, 0.0, 0, 0, None) == B.DBL_EINVAL
+    assert L.dbl_verify_block_ragged(ctx, p, p, 1, 9, 0.0, 0, 0, None) == B.DBL_EINVAL
+    assert L.dbl_verify_block_ragged(ctx, p, p, 1, 4, 0.0, 0, 0, None) == ok
     assert L.dbl_verify_block(ctx, p, 1, 4, 0.0, 0, 0, None) == ok
     assert L.dbl_kv_commit(ctx, None) == B.DBL_ESTATE                        # no accept yet
     assert L.dbl_accept(ctx, B.DBL_SAMPLE, None, p, p, p) == B.DBL_ESTATE    # verify was greedy

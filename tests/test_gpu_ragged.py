@@ -1,0 +1,166 @@
+"""GPU parity of dbl_verify_block_ragged: sequences with windows of different lengths (and
+sequences that sit a step out) in one batch, against the oracle run sequence by sequence on
+each sequence's own, unpadded window (paper App. D.1: the higher-concurrency regime).
+
+What a padded row holds must not matter: the padding here is random tokens."""
+import numpy as np
+import pytest
+
+import oracle as O
+from paper_2601_05524_amd import binding as B
+from paper_2601_05524_amd import synth
+from tests.gpu_util import Gpu, Ref
+from tests.test_gpu_parity import SMALL_BF16, TINY, TOL, pair, sample_margin_ok, sharpen
+
+pytestmark = pytest.mark.gpu
+
+K, BN = 8, 4
+LENGTHS = [[8, 3, 1, 0], [0, 8, 5, 2], [1, 1, 8, 8], [4, 0, 0, 7], [8, 8, 8, 8], [2, 6, 0, 1]]
+
+
+def own_window(s, L, V, step, b, alpha=0.7):
+    """pending token + L-1 drafts: the oracle's own greedy continuation, corrupted at random places"""
+    pending = int(s.history()[-1])
+    tmpw, cont = [pending], []
+    for _ in range(L - 1):
+        lg = s.verify_block(tmpw)
+        cont.append(int(lg[-1].argmax()))
+        tmpw.append(cont[-1])
+    drafts = synth.corrupt_drafts(5000 + 16 * step + b, np.array(cont, np.int32), V, alpha=alpha) if L > 1 else []
+    return np.concatenate([[pending], drafts]).astype(np.int32)
+
+
+def padded(ws, V, rng):
+    out = rng.integers(0, V, (len(ws), K)).astype(np.int32)      # padding: random tokens
+    for b, w in enumerate(ws):
+        out[b, :len(w)] = w
+    return out
+
+
+def test_ragged_greedy_steps_match_per_sequence_oracle():
+    shape = SMALL_BF16
+    g, r = pair(shape, 21, max_batch=BN, max_ctx=512, max_window=K, max_hist=1024)
+    sharpen(g, r, 8.0)
+    V = shape["vocab"]
+    tol = 8.0 * TOL[1]
+    rng = np.random.default_rng(11)
+    prompts = [synth.uniform_history(300 + b, length=64, vocab=V, span=8, every=24, tail=4) for b in range(BN)]
+    g.prefill(prompts, 8)
+    r.prefill(prompts, 8)
+    compared = exempt = 0
+    for step, lens in enumerate(LENGTHS * 2):
+        ws = [own_window(r.seqs[b], L, V, step, b) if L > 0 else np.zeros(0, np.int32) for b, L in enumerate(lens)]
+        lg = g.verify(padded(ws, V, rng), win_len=lens)
+        n, emit, guide = g.accept(B.DBL_GREEDY)
+        keep = []
+        for b, L in enumerate(lens):
+            s = r.seqs[b]
+            if L == 0:
+                assert n[b] == -1 and (emit[b] == -1).all() and (guide[b] == -1).all()
+                keep.append(0)
+                continue
+            lg_ref = s.verify_block(ws[b])
+            err = np.abs(lg[b][:L] - lg_ref).max()
+            assert err <= tol, (step, b, err)
+            n_ref, emit_ref, guide_ref, margin = O.accept_greedy(lg_ref, ws[b])
+            ex = margin < max(4 * err, 1e-5)
+            assert n[b] <= L - 1
+            assert np.array_equal(guide[b][:L][~ex], guide_ref[~ex])
+            if not ex[:n_ref + 1].any():
+                assert n[b] == n_ref, (step, b)
+                assert np.array_equal(emit[b][:n_ref + 1], emit_ref[:n_ref + 1])
+                assert (emit[b][n_ref + 1:] == -1).all()
+                compared += 1
+            else:
+                exempt += 1
+            keep.append(n_ref + 1)
+            s.commit(n_ref + 1, emit_ref[:n_ref + 1])
+        g.commit(keep)                      # teacher forcing: both sides continue from the oracle's decisions
+        for b in range(BN):
+            B.dbl_history_set(g.ctx, b, r.seqs[b].history())
+        assert list(g.kv_len()[:BN]) == [r.seqs[b].kv_len for b in range(BN)]
+    assert compared >= 18, (compared, exempt)     # (rows whose top-2 gap is below 4x the logit error are not compared)
+    g.close()
+
+
+def test_ragged_free_running_commit_on_the_device():
+    """fp32 tiny model: decisions are exact, so the device keeps its own counts (dbl_kv_commit
+    without host counts) and must stay in step with four independent oracle sequences."""
+    shape = TINY
+    g, r = pair(shape, 51, max_batch=BN, max_ctx=512, max_window=K, max_hist=1024)   # a seed whose top-2 gaps stay above 5e-3
+    V = shape["vocab"]
+    rng = np.random.default_rng(3)
+    prompts = [synth.uniform_history(700 + b, length=48, vocab=V, span=8, every=16, tail=4) for b in range(BN)]
+    g.prefill(prompts, 8)
+    r.prefill(prompts, 8)
+    for step, lens in enumerate(LENGTHS * 3):
+        ws = [own_window(r.seqs[b], L, V, step, b, alpha=0.5) if L > 0 else np.zeros(0, np.int32) for b, L in enumerate(lens)]
+        g.verify(padded(ws, V, rng), win_len=lens, want_logits=False)
+        n, emit, _ = g.accept(B.DBL_GREEDY)
+        g.commit()
+        for b, L in enumerate(lens):
+            if L == 0:
+                assert n[b] == -1
+                continue
+            s = r.seqs[b]
+            n_ref, emit_ref, _, margin = O.accept_greedy(s.verify_block(ws[b]), ws[b])
+            assert margin[:n_ref + 1].min() > 1e-3, "seeded scenario has a near-tie: pick another seed"
+            assert n[b] == n_ref and np.array_equal(emit[b][:n_ref + 1], emit_ref[:n_ref + 1]), (step, b)
+            s.commit(n_ref + 1, emit_ref[:n_ref + 1])
+        assert list(g.kv_len()[:BN]) == [r.seqs[b].kv_len for b in range(BN)]
+        for b in range(BN):
+            assert np.array_equal(g.history(b), r.seqs[b].history())
+    g.close()
+
+
+@pytest.mark.parametrize("dense", [False, True], ids=["one_hot_q", "dense_q"])
+def test_ragged_sampling_accept(dense):
+    shape = SMALL_BF16
+    g, r = pair(shape, 14, max_batch=BN, max_ctx=512, max_window=K)
+    sharpen(g, r, 8.0)
+    V, T, seed = shape["vocab"], 0.7, 0x5EED0123
+    rng = np.random.default_rng(8)
+    prompts = [synth.zipf_history(40 + b, 40, V) for b in range(BN)]
+    g.prefill(prompts, 8)
+    r.prefill(prompts, 8)
+    compared = exempt = 0
+    for step, lens in enumerate(LENGTHS * 2):
+        ws, qs, refs = [], [], []
+        for b, L in enumerate(lens):
+            s = r.seqs[b]
+            w = own_window(s, L, V, step, b, alpha=0.85) if L > 0 else np.zeros(0, np.int32)
+            lg_ref = s.verify_block(w) if L > 0 else None
+            q = synth.dense_q(900 + 8 * step + b, L - 1, V, T, mix_logits=lg_ref[:L - 1] * 1.5) if (dense and L > 1) else None
+            ws.append(w); qs.append(q); refs.append(lg_ref)
+        qd = None
+        if dense:
+            qd = np.full((BN, K - 1, V), 1.0 / V, np.float32)      # rows without a draft: anything
+            for b, q in enumerate(qs):
+                if q is not None:
+                    qd[b, :len(q)] = q
+        lg = g.verify(padded(ws, V, rng), temperature=T, seed=seed, step=500 + step, win_len=lens)
+        n, emit, guide = g.accept(B.DBL_SAMPLE, qd)
+        commits = g.ncommit
+        keep = []
+        for b, L in enumerate(lens):
+            if L == 0:
+                assert n[b] == -1 and (emit[b] == -1).all()
+                keep.append(0)
+                continue
+            err = np.abs(lg[b][:L] - refs[b]).max()
+            assert err <= 8.0 * TOL[1]
+            q_ref = qs[b] if (dense and L > 1) else None
+            n_ref, e_ref, gd_ref, am, gap = O.accept_sample(refs[b], ws[b], q_ref, T, seed, 500 + step + commits, b)
+            if sample_margin_ok(refs[b], ws[b], q_ref, T, am, gap, n_ref, err):
+                assert n[b] == n_ref, (step, b, L)
+                assert np.array_equal(emit[b][:n_ref + 1], e_ref[:n_ref + 1]), (step, b, L)
+                compared += 1
+            else:
+                exempt += 1
+            keep.append(n_ref + 1)
+            r.seqs[b].commit(n_ref + 1, e_ref[:n_ref + 1])
+        g.commit(keep)
+        for b in range(BN):
+            B.dbl_history_set(g.ctx, b, r.seqs[b].history())
+    assert compared >= 16, (compared, exempt)     # (decisions inside the measured logit error are not compared)
+    g.close()
