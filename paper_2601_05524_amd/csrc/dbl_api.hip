@@ -110,6 +110,7 @@ struct dbl_ctx {
   void* xn = nullptr;               // RMSNorm output of the current 16-row pass (windows of more than 8 rows)
   float *qkv_part = nullptr, *logits = nullptr;
   void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
+  int lm_nstat = 0;                 // workgroups of the last LM-head launch (row-statistics entries per row)
   int ldh = 0;                      // row stride of h and layer stride of g1 / g2 / gf (>= every consumer's K padding)
   float *pm = nullptr, *pl = nullptr, *po = nullptr;
   LmStat* stats = nullptr;
@@ -196,27 +197,22 @@ void launch_gemm_t(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
   const dim3 grid(p.grid), block(p.NW * 64);
   constexpr bool is_bf = sizeof(T) == 2;
   constexpr int KS_BIG = is_bf ? 32 : 16, KS_SMALL = is_bf ? 16 : 8;
-  const bool pack = a.mrows <= 8;   // two k-blocks of activations per register set
-  if (p.KS == KS_BIG && !CHUNK) {
-    if (pack) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, true, false>), grid, block, 0, c->stream, a);
-    else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, false, false>), grid, block, 0, c->stream, a);
-  } else {
-    if (pack) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL, true, CHUNK>), grid, block, 0, c->stream, a);
-    else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL, false, CHUNK>), grid, block, 0, c->stream, a);
-  }
+  if (p.KS == KS_BIG && !CHUNK) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, false>), grid, block, 0, c->stream, a);
+  else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL, CHUNK>), grid, block, 0, c->stream, a);
 }
 
-// More than 16 rows (and not the LM head): passes of 16*R rows through gemm_rows_kernel, in
+// gemm_rows_kernel: passes of 16*R rows, in
 // units of Q tile rows.  Larger units re-read the activations less often but leave fewer of
 // them to share out: Q is the one with the least modelled time (units per workgroup, counted
 // half as whole rounds and half as the exact ratio, times tile rows per unit, with the activation
 // traffic, R/Q of the weight traffic, at a quarter of its cost; fitted to measured launches).
 template <typename T, int EPI, int R>
-void launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
+int launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
   constexpr int NACC = EPI == EPI_SWIGLU ? 2 : 1;
   int bestq = 0, bestg = 0; double best = 1e30;
   for (int q : {4, 2}) {
     if (q < NACC) continue;
+    if (EPI == EPI_LMHEAD && R == 4 && q == 4) continue;   // (the row statistics of four groups leave no room for 16 accumulators)
     const int units = (p.NT + q / NACC - 1) / (q / NACC) * p.SS;
     int g = std::min(units, std::min(c->n_cu, SSQ_PARTS));
     g = std::max(p.SS, g / p.SS * p.SS);
@@ -227,6 +223,7 @@ void launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
   const dim3 grid(bestg), block(256);
   if (bestq == 4) hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4>), grid, block, 0, c->stream, a);
   else hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 2>), grid, block, 0, c->stream, a);
+  return bestg;
 }
 
 template <typename T, int R>
@@ -234,21 +231,20 @@ void launch_gemm_rows(dbl_ctx* c, const GemmPlan& p, int epi, const GemmArgs<T>&
   switch (epi) {
     case EPI_PARTIAL: launch_gemm_rows_q<T, EPI_PARTIAL, R>(c, p, a); break;
     case EPI_RESIDUAL: launch_gemm_rows_q<T, EPI_RESIDUAL, R>(c, p, a); break;
-    default: launch_gemm_rows_q<T, EPI_SWIGLU, R>(c, p, a); break;
+    case EPI_SWIGLU: launch_gemm_rows_q<T, EPI_SWIGLU, R>(c, p, a); break;
+    default: c->lm_nstat = launch_gemm_rows_q<T, EPI_LMHEAD, R>(c, p, a); break;
   }
 }
 
-// Which kernel runs a projection of M rows.  The LM head always takes 16-row passes of
-// gemm_stream_kernel (its row statistics live there).  Windows of more than 8 rows take
-// gemm_rows_kernel.  At 8 rows or fewer, measured inside a running layer at three widths:
-// the gate/up projection is faster through gemm_rows_kernel everywhere (70B width 8 us per
-// layer, 1B width 4 us), output and down projection where their tile pairs fill the chip
-// (70B width 3 + 4 us, 32B width 2 + 10 us; at the 1B width, 64 units for 256 CUs, slower by
-// 3 + 5 us), the q/k/v projection nowhere (it would need a stored RMSNorm output of its own).
+// Which kernel runs a projection of M rows.  Windows of more than 8 rows: gemm_rows_kernel.
+// At 8 rows or fewer, measured inside a running layer at three widths: the gate/up projection
+// and the LM head are faster through gemm_rows_kernel everywhere (70B width: 8 us per layer and
+// 45 us per step; 1B width: 4 us per layer), output and down projection where their tile pairs
+// fill the chip (70B width 3 + 4 us, 32B width 2 + 10 us; at the 1B width, 64 units for 256
+// CUs, slower by 3 + 5 us), the q/k/v projection nowhere (it would need a stored RMSNorm
+// output of its own).
 static bool rows_kernel_for(const dbl_ctx* c, const GemmPlan& p, int epi, int M) {
-  if (epi == EPI_LMHEAD) return false;
-  if (M > 8) return true;
-  if (epi == EPI_SWIGLU) return true;
+  if (M > 8 || epi == EPI_SWIGLU || epi == EPI_LMHEAD) return true;
   if (epi == EPI_RESIDUAL) return p.NT >= c->n_cu;
   return false;
 }
@@ -265,7 +261,7 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
     for (int m0 = 0; m0 < M; m0 += 64) {
       a.m0 = m0; a.mrows = std::min(64, M - m0);
       if (epi != EPI_RESIDUAL) {     // the RMSNorm output is stored first and read like any activation
-        hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, a.d, a.eps, 1);
+        hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, a.d, a.eps);
         a.X = xn;
       }
       if (a.mrows > 32) launch_gemm_rows<T, 4>(c, p, epi, a);
@@ -274,23 +270,11 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
     }
     return;
   }
-  for (int m0 = 0; m0 < M; m0 += 16) {
-    a.m0 = m0; a.mrows = std::min(16, M - m0);
-    if (epi != EPI_RESIDUAL && a.mrows > 8) {
-      // more than 8 rows: the RMSNorm output is stored first and read like any activation
-      T* xn = reinterpret_cast<T*>(c->xn);
-      hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, a.d, a.eps, 0);
-      a.X = xn;
-    }
-    switch (epi) {
-      case EPI_PARTIAL: launch_gemm_t<T, EPI_PARTIAL, false>(c, p, a); break;
-      case EPI_RESIDUAL:
-        if (p.NCH > 1) launch_gemm_t<T, EPI_RESIDUAL, true>(c, p, a);
-        else launch_gemm_t<T, EPI_RESIDUAL, false>(c, p, a);
-        break;
-      default: launch_gemm_t<T, EPI_LMHEAD, false>(c, p, a); break;
-    }
-  }
+  // at most 8 rows, q/k/v or a narrow output / down projection
+  a.m0 = 0; a.mrows = M;
+  if (epi == EPI_PARTIAL) launch_gemm_t<T, EPI_PARTIAL, false>(c, p, a);
+  else if (p.NCH > 1) launch_gemm_t<T, EPI_RESIDUAL, true>(c, p, a);
+  else launch_gemm_t<T, EPI_RESIDUAL, false>(c, p, a);
 }
 
 // Arguments of every per-layer step, for layer `l`, window (B, k).
@@ -602,7 +586,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(attn, M16 * c->p_o.ldx() * esz, true);
     ALLOC(act, M16 * c->p_d.ldx() * esz, true);
     ALLOC(pm, part_rows * 4, true); ALLOC(pl, part_rows * 4, true); ALLOC(po, part_rows * g.head_dim * 4, true);
-    ALLOC(stats, (size_t)c->p_lm.grid * Mmax * sizeof(LmStat), true);
+    ALLOC(stats, (size_t)std::max(c->p_lm.grid, c->n_cu) * Mmax * sizeof(LmStat), true);
     ALLOC(n_acc_i, (size_t)g.max_batch * 4, true); ALLOC(emit_i, (size_t)Mmax * 4, true);
     ALLOC(win_i, (size_t)Mmax * 4, true);
   } while (0);
@@ -919,7 +903,7 @@ int dbl_accept(dbl_ctx* c, int mode, const float* q_probs, int32_t* n_acc, int32
   if (mode == DBL_GREEDY && q_probs) return fail(c, DBL_EINVAL, "q_probs given in greedy mode");
   if (c->dry) { c->have_accept = true; return DBL_ENODEV; }
   AcceptArgs a{};
-  a.stats = c->stats; a.nstat = c->p_lm.grid; a.Mtot = c->last_B * c->last_k;
+  a.stats = c->stats; a.nstat = c->lm_nstat; a.Mtot = c->last_B * c->last_k;
   a.logits = c->logits; a.ldl = c->p_lm.ldo(); a.window = c->win_i; a.q = q_probs; a.commits = c->commits;
   a.n_acc = n_acc; a.emit = emit; a.guide = guide; a.n_acc_i = c->n_acc_i; a.emit_i = c->emit_i;
   a.k = c->last_k; a.V = c->cfg.vocab; a.mode = mode;

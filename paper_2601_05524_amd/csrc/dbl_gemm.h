@@ -8,10 +8,10 @@
 // MFMAs and the ring never drains inside a kernel; partial sums of the waves that split K are
 // added through LDS in a fixed order (deterministic, no atomics).  Two kernels:
 //
-// gemm_stream_kernel (at most 16 rows per pass: q/k/v at up to 8 rows, the LM head always,
-// output/down at narrow widths):
+// gemm_stream_kernel (at most 8 rows: the q/k/v projection, and output/down at narrow widths):
 //   * a wave owns KS k-blocks of every output tile its workgroup visits, so activations are
-//     fetched once per wave (once per K chunk in the chunked form);
+//     fetched once per wave (once per K chunk in the chunked form), two k-blocks per register
+//     set, and RMSNorm is applied while they are loaded;
 //   * the NW <= 8 waves of a workgroup own consecutive K slices of the same output tile; wave 0
 //     applies the epilogue;
 //   * a workgroup starts at output tile wg/SS and steps by nwg/SS;
@@ -19,7 +19,7 @@
 //     its own partial result that the consumer sums (q/k/v projection), or by NCH sequential K
 //     chunks inside the workgroup with the accumulator kept in registers (CHUNK form).
 //
-// gemm_rows_kernel (any number of rows in passes of up to 64; the gate/up projection always):
+// gemm_rows_kernel (any number of rows in passes of up to 64; gate/up and the LM head always):
 // see its own comment.
 //
 // RMSNorm is not a kernel of its own.  Whichever kernel wrote the residual stream h last
@@ -27,7 +27,7 @@
 // norm, and each of its workgroups leaves one partial sum of squares per row in
 // ssq[row][workgroup] (SSQ_PARTS slots per row, unused ones zero).  gemm_stream_kernel adds the
 // partials in a fixed order and builds bf16(hg * rsqrt(mean(h^2) + eps)) while loading its
-// activation registers (at most 8 rows); xn_kernel stores that tensor for everything else.
+// activation registers; xn_kernel stores that tensor for gemm_rows_kernel.
 #pragma once
 #include "dbl_dev.h"
 
@@ -54,6 +54,58 @@ struct LmArgs {
   float inv_T;                    // 0 => greedy statistics only
   uint64_t seed, step;
 };
+
+// Row statistics of the LM head: empty state, merge of two states (any order of merges
+// gives the same arg-max / top-2; the soft-max sums are added in whatever order the caller
+// fixes), and the update with four consecutive logits n..n+3 of one row.
+__device__ __forceinline__ void lm_init(LmStat& s) {
+  s.best = -INFINITY; s.best_id = 0x7fffffff; s.smax = -INFINITY; s.ssum = 0.f; s.zdraft = -INFINITY;
+  s.p1 = -INFINITY; s.p1_id = 0x7fffffff; s.p2 = -INFINITY; s.p2_id = 0x7fffffff;
+}
+__device__ __forceinline__ void lm_merge(LmStat& x, const LmStat& y) {
+  if (better(y.best, y.best_id, x.best, x.best_id)) { x.best = y.best; x.best_id = y.best_id; }
+  x.zdraft = fmaxf(x.zdraft, y.zdraft);
+  const float nm = fmaxf(x.smax, y.smax);
+  if (nm > -INFINITY) x.ssum = x.ssum * expf(x.smax - nm) + y.ssum * expf(y.smax - nm);
+  x.smax = nm;
+  if (better(y.p1, y.p1_id, x.p1, x.p1_id)) {
+    if (better(x.p1, x.p1_id, y.p2, y.p2_id)) { x.p2 = x.p1; x.p2_id = x.p1_id; } else { x.p2 = y.p2; x.p2_id = y.p2_id; }
+    x.p1 = y.p1; x.p1_id = y.p1_id;
+  } else if (better(y.p1, y.p1_id, x.p2, x.p2_id)) { x.p2 = y.p1; x.p2_id = y.p1_id; }
+}
+__device__ __forceinline__ LmStat lm_shfl_xor(const LmStat& s, int off) {
+  LmStat o;
+  o.best = __shfl_xor(s.best, off); o.best_id = __shfl_xor(s.best_id, off);
+  o.smax = __shfl_xor(s.smax, off); o.ssum = __shfl_xor(s.ssum, off); o.zdraft = __shfl_xor(s.zdraft, off);
+  o.p1 = __shfl_xor(s.p1, off); o.p1_id = __shfl_xor(s.p1_id, off);
+  o.p2 = __shfl_xor(s.p2, off); o.p2_id = __shfl_xor(s.p2_id, off);
+  return o;
+}
+// (pb, pj) = (sequence, window row) of the logits' row, draft = that row's draft token or -1
+__device__ __forceinline__ void lm_update(LmStat& s, const f32x4& z4, int n, int N, int draft, uint32_t pb, uint32_t pj,
+                                          uint64_t stepv, const LmArgs& lm) {
+  Philox4 rnd{0, 0, 0, 0};
+  const bool sampling = lm.inv_T > 0.f;
+  if (sampling)
+    rnd = philox4x32_10((uint32_t)stepv, pb, pj, 1u + (uint32_t)(n >> 2), (uint32_t)lm.seed, (uint32_t)(lm.seed >> 32));
+  const uint32_t rw[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int v = n + i;
+    if (v >= N) continue;
+    const float z = z4[i];
+    if (better(z, v, s.best, s.best_id)) { s.best = z; s.best_id = v; }
+    if (v == draft) s.zdraft = z;
+    if (sampling) {
+      const float zs = z * lm.inv_T;
+      if (zs > s.smax) { s.ssum = s.ssum * expf(s.smax - zs) + 1.f; s.smax = zs; }
+      else s.ssum += expf(zs - s.smax);
+      const float sc = zs + gumbel(rw[i]);
+      if (better(sc, v, s.p1, s.p1_id)) { s.p2 = s.p1; s.p2_id = s.p1_id; s.p1 = sc; s.p1_id = v; }
+      else if (better(sc, v, s.p2, s.p2_id)) { s.p2 = sc; s.p2_id = v; }
+    }
+  }
+}
 
 template <typename T>
 struct GemmArgs {
@@ -88,31 +140,23 @@ template <typename T> struct GemmCfg;
 template <> struct GemmCfg<bf16_t> { static constexpr int RING = 16; };
 template <> struct GemmCfg<float> { static constexpr int RING = 8; };
 
-typedef f32x4 GemmRed[8][2][WAVE];   // one LDS reduction buffer: [wave][accumulator][lane]
+typedef f32x4 GemmRed[8][WAVE];   // one LDS reduction buffer: [wave][lane]
 
-// 1 / rms of the row a lane works on: row (lane & 7) [PACK] or (lane & 15), clamped to
-// the valid rows.  Eight lanes add the 256 partials of one row (32 each, then a
-// butterfly); the result is fetched from that group's first lane.
-template <bool PACK>
+// 1 / rms of the row a lane of gemm_stream_kernel works on: row (lane & 7), clamped to the
+// valid rows.  Eight lanes add the 256 partials of one row (32 each, then a butterfly); the
+// result is fetched from that group's first lane.
 __device__ __forceinline__ float row_scale(const float* ssq, int m0, int mrows, float d, float eps, int lane) {
-  const int c = lane & 15, want = PACK ? (c & 7) : c;
-  float out = 0.f;
+  const int rr = min(lane >> 3, mrows - 1);
+  const f32x4* p = reinterpret_cast<const f32x4*>(ssq + (size_t)(m0 + rr) * SSQ_PARTS) + (lane & 7) * 8;
+  f32x4 v[8];
 #pragma unroll
-  for (int half = 0; half < (PACK ? 1 : 2); ++half) {
-    const int rr = min(half * 8 + (lane >> 3), mrows - 1);
-    const f32x4* p = reinterpret_cast<const f32x4*>(ssq + (size_t)(m0 + rr) * SSQ_PARTS) + (lane & 7) * 8;
-    f32x4 v[8];
+  for (int u = 0; u < 8; ++u) v[u] = p[u];
+  float s = 0.f;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = p[u];
-    float s = 0.f;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) s += (v[u].x + v[u].y) + (v[u].z + v[u].w);
-    s += __shfl_xor(s, 1); s += __shfl_xor(s, 2); s += __shfl_xor(s, 4);
-    const float r = rsqrtf(s / d + eps);
-    const float got = __shfl(r, (want & 7) * 8);
-    if (PACK || (want >> 3) == half) out = got;
-  }
-  return out;
+  for (int u = 0; u < 8; ++u) s += (v[u].x + v[u].y) + (v[u].z + v[u].w);
+  s += __shfl_xor(s, 1); s += __shfl_xor(s, 2); s += __shfl_xor(s, 4);
+  const float r = rsqrtf(s / d + eps);
+  return __shfl(r, (lane & 7) * 8);
 }
 
 // Eight activations of one row as an MFMA fragment: T((h * gain) * r), the RMSNorm output
@@ -132,45 +176,41 @@ __device__ __forceinline__ Frag<float> norm_frag(const float* hg, float r, float
   return f;
 }
 
-// Activation registers of the KS k-blocks starting at block kblk.
-// PACK (at most 8 rows): the B operand has 16 columns but only 8 rows to put in them,
-// so one register set holds TWO k-blocks: lanes c < 8 carry block 2i (row c), lanes
-// c >= 8 carry block 2i+1 (row c-8).  Block 2i is used as it is (columns 8..15 of the
-// product are never read); for block 2i+1 the halves are swapped with a DPP rotate by
-// 8 inside each 16-lane row.  This halves the registers the activations take.
-// Output column j of a tile depends only on activation row j, so lanes of unused rows
-// re-read the last valid row: all loads are unconditional and stay in flight together.
-template <typename T, bool NORM, bool PACK, int KS>
-__device__ __forceinline__ void load_acts(const GemmArgs<T>& a, int kblk, float r, int lane,
-                                          Frag<T> (&b)[PACK ? KS / 2 : KS]) {
+// Activation registers of the KS k-blocks starting at block kblk, for at most 8 rows: the B
+// operand has 16 columns but only 8 rows to put in them, so one register set holds TWO
+// k-blocks: lanes c < 8 carry block 2i (row c), lanes c >= 8 carry block 2i+1 (row c-8).
+// Block 2i is used as it is (columns 8..15 of the product are never read); for block 2i+1
+// the halves are swapped with a DPP rotate by 8 inside each 16-lane row.  This halves the
+// registers the activations take.  Output column j of a tile depends only on activation row
+// j, so lanes of unused rows re-read the last valid row: all loads are unconditional and stay
+// in flight together.
+template <typename T, bool NORM, int KS>
+__device__ __forceinline__ void load_acts(const GemmArgs<T>& a, int kblk, float r, int lane, Frag<T> (&b)[KS / 2]) {
   const int c = lane & 15, g = lane >> 4;
-  const int row = a.m0 + min(PACK ? (c & 7) : c, a.mrows - 1);
-  const size_t k0 = (size_t)(kblk + (PACK ? (c >> 3) : 0)) * TILE_K + g * 8;
-  constexpr int STEP = (PACK ? 2 : 1) * TILE_K;
+  const int row = a.m0 + min(c & 7, a.mrows - 1);
+  const size_t k0 = (size_t)(kblk + (c >> 3)) * TILE_K + g * 8;
   if (NORM) {
     const float* hp = a.HG + (size_t)row * a.ldx + k0;
 #pragma unroll
-    for (int j = 0; j < (PACK ? KS / 2 : KS); ++j) b[j] = norm_frag(hp + j * STEP, r, T());
+    for (int j = 0; j < KS / 2; ++j) b[j] = norm_frag(hp + j * 2 * TILE_K, r, T());
   } else {
     const T* xp = a.X + (size_t)row * a.ldx + k0;
 #pragma unroll
-    for (int j = 0; j < (PACK ? KS / 2 : KS); ++j) b[j] = frag_load_row(xp + j * STEP);
+    for (int j = 0; j < KS / 2; ++j) b[j] = frag_load_row(xp + j * 2 * TILE_K);
   }
 }
 
-// CHUNK: the workgroup walks NCH K chunks per output tile (EPI_RESIDUAL only); the
+// At most 8 rows; EPI_PARTIAL (q/k/v: RMSNorm applied on load, partial store per super slice)
+// or EPI_RESIDUAL (output / down projection at widths whose tiles do not fill the chip in
+// pairs).  CHUNK: the workgroup walks NCH K chunks per output tile (EPI_RESIDUAL only); the
 // activations of the next chunk are fetched while the current one is multiplied.
-template <typename T, int EPI, int KS, bool PACK, bool CHUNK>
+template <typename T, int EPI, int KS, bool CHUNK>
 __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
-  static_assert(EPI != EPI_SWIGLU, "the gate/up projection runs in gemm_rows_kernel");
-  constexpr int NACC = 1;
+  static_assert(EPI == EPI_PARTIAL || EPI == EPI_RESIDUAL, "the other epilogues live in gemm_rows_kernel");
   constexpr int RING = GemmCfg<T>::RING;
-  constexpr int NB = PACK ? KS / 2 : KS;       // activation register sets
-  // Normalise-on-load only in the packed form (at most 8 rows): for 9..16 rows the fp32
-  // loads it needs do not fit beside 16 rows of activation registers, and the host runs
-  // xn_kernel first and passes its output as X.
-  constexpr bool NORM = PACK && EPI != EPI_RESIDUAL;
-  static_assert(!PACK || KS % 2 == 0, "packed activations pair k-blocks");
+  constexpr int NB = KS / 2;                   // activation register sets
+  constexpr bool NORM = EPI != EPI_RESIDUAL;
+  static_assert(KS % 2 == 0, "packed activations pair k-blocks");
   static_assert(KS % RING == 0, "slice must be a whole number of rings");
   static_assert(!CHUNK || EPI == EPI_RESIDUAL, "only the residual projections walk K chunks");
 
@@ -200,23 +240,12 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
   {
     const int tf = t < a.NT ? t : 0;
 #pragma unroll
-    for (int j = 0; j < RING; ++j) ring[j] = frag_load_w(wlane + (size_t)tf * NACC * row_elems, j, lane);
+    for (int j = 0; j < RING; ++j) ring[j] = frag_load_w(wlane + (size_t)tf * row_elems, j, lane);
   }
   float r = 1.f;
-  if (NORM) r = row_scale<PACK>(a.ssq_in, a.m0, a.mrows, a.d, a.eps, lane);
+  if (NORM) r = row_scale(a.ssq_in, a.m0, a.mrows, a.d, a.eps, lane);
   Frag<T> breg[NB];
-  load_acts<T, NORM, PACK, KS>(a, kb0, r, lane, breg);
-
-  // LM-head running statistics (wave 0 only)
-  float best = -INFINITY, smax = -INFINITY, ssum = 0.f, zdraft = -INFINITY, p1 = -INFINITY, p2 = -INFINITY;
-  int best_id = 0x7fffffff, p1_id = 0x7fffffff, p2_id = 0x7fffffff;
-  int draft = -1; uint32_t pb = 0, pj = 0; uint64_t stepv = 0;
-  if (EPI == EPI_LMHEAD && wave == 0 && c < a.mrows) {
-    const int m = a.m0 + c;
-    pb = m / a.lm.k; pj = m % a.lm.k;
-    if ((int)pj + 1 < a.lm.k) draft = a.lm.window[m + 1];
-    stepv = a.lm.step + *a.lm.commits;
-  }
+  load_acts<T, NORM, KS>(a, kb0, r, lane, breg);
   float sq = 0.f;   // RESIDUAL: this lane's share of the rows' sums of squares
 
   // Everything requested so far has to be there before the first product anyway (the
@@ -229,42 +258,34 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
   // flat loop, so that the loads in flight (weight ring, next chunk's activations) are
   // carried by one loop only and the compiler keeps exact counts of them.
   int ch = 0;
-  f32x4 acc[NACC];
-#pragma unroll
-  for (int s = 0; s < NACC; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int it = 0; t < a.NT;) {
     const bool last = !CHUNK || ch + 1 == nch;
     // after the last tile the refill loads go on, harmlessly, into tile 0 (an L2 hit)
     const int tnc = tn < a.NT ? tn : 0;
-    const T* wcur = wlane + (size_t)t * NACC * row_elems + (size_t)ch * seg_elems;
-    const T* wnext = last ? wlane + (size_t)tnc * NACC * row_elems : wcur + seg_elems;
+    const T* wcur = wlane + (size_t)t * row_elems + (size_t)ch * seg_elems;
+    const T* wnext = last ? wlane + (size_t)tnc * row_elems : wcur + seg_elems;
     Frag<T> bnext[NB];
     f32x4 hold, gout;
 #pragma unroll
-    for (int s = 0; s < NACC; ++s) {
-#pragma unroll
-      for (int j = 0; j < KS; ++j) {
-        if (PACK) acc[s] = mma(ring[j % RING], (j & 1) ? frag_swap_halves(breg[j / 2]) : breg[j / 2], acc[s]);
-        else acc[s] = mma(ring[j % RING], breg[j], acc[s]);
-        const int jn = j + RING;
-        if (jn < KS) ring[j % RING] = frag_load_w(wcur + s * row_elems, jn, lane);
-        else if (s + 1 < NACC) ring[j % RING] = frag_load_w(wcur + (s + 1) * row_elems, jn - KS, lane);
-        else ring[j % RING] = frag_load_w(wnext, jn - KS, lane);
-        if (s == 0 && j == 0) {
-          // (after the first product, so that the loop starts with the oldest weight load)
-          if constexpr (CHUNK) load_acts<T, NORM, PACK, KS>(a, kb0 + (last ? 0 : ch + 1) * seg, r, lane, bnext);
-          // RESIDUAL: this lane's old h values and gains, fetched ahead of the epilogue (every
-          // chunk, unconditionally; only this workgroup writes them, and only after the last chunk)
-          if constexpr (EPI == EPI_RESIDUAL) {
-            const int n = t * TILE_N + 4 * g;
-            hold = *reinterpret_cast<const f32x4*>(a.out + (size_t)(a.m0 + min(c, a.mrows - 1)) * a.ldo + n);
-            gout = *reinterpret_cast<const f32x4*>(a.gain_out + n);
-          }
+    for (int j = 0; j < KS; ++j) {
+      acc = mma(ring[j % RING], (j & 1) ? frag_swap_halves(breg[j / 2]) : breg[j / 2], acc);
+      const int jn = j + RING;
+      if (jn < KS) ring[j % RING] = frag_load_w(wcur, jn, lane);
+      else ring[j % RING] = frag_load_w(wnext, jn - KS, lane);
+      if (j == 0) {
+        // (after the first product, so that the loop starts with the oldest weight load)
+        if constexpr (CHUNK) load_acts<T, NORM, KS>(a, kb0 + (last ? 0 : ch + 1) * seg, r, lane, bnext);
+        // RESIDUAL: this lane's old h values and gains, fetched ahead of the epilogue (every
+        // chunk, unconditionally; only this workgroup writes them, and only after the last chunk)
+        if constexpr (EPI == EPI_RESIDUAL) {
+          const int n = t * TILE_N + 4 * g;
+          hold = *reinterpret_cast<const f32x4*>(a.out + (size_t)(a.m0 + min(c, a.mrows - 1)) * a.ldo + n);
+          gout = *reinterpret_cast<const f32x4*>(a.gain_out + n);
         }
-        // keep program order: the scheduler would otherwise start the next accumulator's
-        // products early, which makes it wait for loads issued only a few slots before
-        __builtin_amdgcn_sched_barrier(0x6);   // scalar and vector ALU work may cross, products and loads may not
       }
+      // keep program order: products and loads stay where they are, scalar and vector ALU work may cross
+      __builtin_amdgcn_sched_barrier(0x6);
     }
     if constexpr (CHUNK) {
 #pragma unroll
@@ -272,58 +293,27 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
       if (!last) { ++ch; continue; }
     }
     const int buf = it & 1;
-    if (wave != 0) {
-#pragma unroll
-      for (int s = 0; s < NACC; ++s) red[buf][wave][s][lane] = acc[s];
-    }
+    if (wave != 0) red[buf][wave][lane] = acc;
     __syncthreads();
     if (wave == 0) {
-      for (int w = 1; w < nw; ++w) {
-#pragma unroll
-        for (int s = 0; s < NACC; ++s) acc[s] += red[buf][w][s][lane];
-      }
+      for (int w = 1; w < nw; ++w) acc += red[buf][w][lane];
       if (c < a.mrows) {
         const int m = a.m0 + c;
         const int n = t * TILE_N + 4 * g;   // first of this lane's 4 output features
         if (EPI == EPI_PARTIAL) {
-          *reinterpret_cast<f32x4*>(a.out + ((size_t)ss * a.Mtot + m) * a.ldo + n) = acc[0];
-        } else if (EPI == EPI_RESIDUAL) {
-          const f32x4 hv = hold + acc[0];
+          *reinterpret_cast<f32x4*>(a.out + ((size_t)ss * a.Mtot + m) * a.ldo + n) = acc;
+        } else {
+          const f32x4 hv = hold + acc;
           *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = hv;
           *reinterpret_cast<f32x4*>(a.hg_out + (size_t)m * a.ldo + n) = hv * gout;
           sq += (hv.x * hv.x + hv.y * hv.y) + (hv.z * hv.z + hv.w * hv.w);
-        } else {  // EPI_LMHEAD
-          *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = acc[0];
-          Philox4 rnd{0, 0, 0, 0};
-          const bool sampling = a.lm.inv_T > 0.f;
-          if (sampling)
-            rnd = philox4x32_10((uint32_t)stepv, pb, pj, 1u + (uint32_t)(n >> 2), (uint32_t)a.lm.seed,
-                                (uint32_t)(a.lm.seed >> 32));
-          const uint32_t rw[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int v = n + i;
-            if (v >= a.N) continue;
-            const float z = acc[0][i];
-            if (better(z, v, best, best_id)) { best = z; best_id = v; }
-            if (v == draft) zdraft = z;
-            if (sampling) {
-              const float zs = z * a.lm.inv_T;
-              if (zs > smax) { ssum = ssum * expf(smax - zs) + 1.f; smax = zs; }
-              else ssum += expf(zs - smax);
-              const float sc = zs + gumbel(rw[i]);
-              if (better(sc, v, p1, p1_id)) { p2 = p1; p2_id = p1_id; p1 = sc; p1_id = v; }
-              else if (better(sc, v, p2, p2_id)) { p2 = sc; p2_id = v; }
-            }
-          }
         }
       }
     }
     t = tn;
     tn += tstep;
     ++it; ch = 0;
-#pragma unroll
-    for (int s = 0; s < NACC; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    acc = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
   if (EPI == EPI_RESIDUAL && wave == 0) {
@@ -333,34 +323,6 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
     if (g == 0 && c < a.mrows) {
       float* dst = a.ssq_out + (size_t)(a.m0 + c) * SSQ_PARTS;
       for (int p = wg; p < SSQ_PARTS; p += nwg) dst[p] = p == wg ? sq : 0.f;
-    }
-  }
-
-  if (EPI == EPI_LMHEAD && wave == 0) {
-    // merge the four lane groups that share a row
-#pragma unroll
-    for (int off = 16; off <= 32; off <<= 1) {
-      const float ob = __shfl_xor(best, off); const int obi = __shfl_xor(best_id, off);
-      if (better(ob, obi, best, best_id)) { best = ob; best_id = obi; }
-      const float oz = __shfl_xor(zdraft, off);
-      zdraft = fmaxf(zdraft, oz);
-      const float om = __shfl_xor(smax, off), os = __shfl_xor(ssum, off);
-      const float nm = fmaxf(smax, om);
-      if (nm > -INFINITY) ssum = ssum * expf(smax - nm) + os * expf(om - nm);
-      smax = nm;
-      const float o1 = __shfl_xor(p1, off), o2 = __shfl_xor(p2, off);
-      const int o1i = __shfl_xor(p1_id, off), o2i = __shfl_xor(p2_id, off);
-      // merge two sorted pairs
-      if (better(o1, o1i, p1, p1_id)) {
-        if (better(p1, p1_id, o2, o2i)) { p2 = p1; p2_id = p1_id; } else { p2 = o2; p2_id = o2i; }
-        p1 = o1; p1_id = o1i;
-      } else if (better(o1, o1i, p2, p2_id)) { p2 = o1; p2_id = o1i; }
-    }
-    if (g == 0 && c < a.mrows) {
-      LmStat s;
-      s.best = best; s.best_id = best_id; s.smax = smax; s.ssum = ssum; s.zdraft = zdraft;
-      s.p1 = p1; s.p1_id = p1_id; s.p2 = p2; s.p2_id = p2_id;
-      a.lm.stats[(size_t)wg * a.Mtot + a.m0 + c] = s;
     }
   }
 }
@@ -384,8 +346,9 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
 //     they multiply zeros (their loads are redirected to the start of the slice).
 // Activations are always stored tensors of type T in the fragment-tiled layout of xt_offset
 // (the host runs xn_kernel first for the normalising projections; the attention merge and
-// the SwiGLU epilogue below write that layout directly).  Epilogues as in gemm_stream_kernel; tiles are static; the LM head is
-// not handled here (its per-row statistics stay on 16-row passes).
+// the SwiGLU epilogue below write that layout directly).  Epilogues: partial store, residual
+// add + hg + sum-of-squares partial, SwiGLU, LM head (logits + the row statistics of every row
+// group, kept per lane and merged over lane groups and waves at the end).  Units are static.
 template <typename T, int EPI, int R, int Q>
 __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
   constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
@@ -396,10 +359,10 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
   constexpr int RING = GemmCfg<T>::RING;
   constexpr int P = TT * R;                     // (tile, row group) pairs per unit
   constexpr int PH = P > 8 ? 8 : P;             // pairs per reduction round
-  static_assert(EPI != EPI_LMHEAD, "the LM head runs on 16-row passes");
   static_assert(Q % NACC == 0 && NF % RING == 0 && P % PH == 0, "unit shape");
   __shared__ f32x4 red[NWV][PH][NACC][WAVE];
   __shared__ float wsq[NWV][R][16];
+  __shared__ LmStat lmred[EPI == EPI_LMHEAD ? NWV : 1][R][16];
   const int wg = blockIdx.x, nwg = gridDim.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 15, g = lane >> 4;
@@ -453,6 +416,19 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
 
   f32x4 acc[Q][R];
   float sq[R];
+  // LM head: running statistics of this lane's row in every row group
+  LmStat st[EPI == EPI_LMHEAD ? R : 1];
+  int draft[R]; uint32_t pb[R], pj[R]; uint64_t stepv = 0;
+  if constexpr (EPI == EPI_LMHEAD) {
+    stepv = a.lm.step + *a.lm.commits;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      lm_init(st[r]);
+      const int m = a.m0 + min(16 * r + c, a.mrows - 1);
+      pb[r] = m / a.lm.k; pj[r] = m % a.lm.k;
+      draft[r] = ((int)pj[r] + 1 < a.lm.k) ? a.lm.window[m + 1] : -1;
+    }
+  }
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     sq[r] = 0.f;
@@ -512,6 +488,11 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
             const float e = (hv.x * hv.x + hv.y * hv.y) + (hv.z * hv.z + hv.w * hv.w);
 #pragma unroll
             for (int rr = 0; rr < R; ++rr) sq[rr] += rr == r ? e : 0.f;
+          } else if (EPI == EPI_LMHEAD) {
+            *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = v[0];
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr)
+              if (rr == r) lm_update(st[EPI == EPI_LMHEAD ? rr : 0], v[0], n, a.N, draft[rr], pb[rr], pj[rr], stepv, a.lm);
           } else {   // EPI_SWIGLU
             f32x4 o;
 #pragma unroll
@@ -530,6 +511,25 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
 #pragma unroll
       for (int r = 0; r < R; ++r) acc[q][r] = f32x4{0.f, 0.f, 0.f, 0.f};
     u = un; ch = 0;
+  }
+
+  if constexpr (EPI == EPI_LMHEAD) {
+    // this workgroup's statistics per row: the four lane groups of a row, then the waves in order
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      lm_merge(st[r], lm_shfl_xor(st[r], 16));
+      lm_merge(st[r], lm_shfl_xor(st[r], 32));
+      if (g == 0) lmred[wave][r][c] = st[r];
+    }
+    __syncthreads();
+    if (wave == 0 && g < R) {
+      const int mr = 16 * g + c;
+      if (mr < a.mrows) {
+        LmStat s = lmred[0][g][c];
+        for (int w = 1; w < NWV; ++w) lm_merge(s, lmred[w][g][c]);
+        a.lm.stats[(size_t)wg * a.Mtot + a.m0 + mr] = s;
+      }
+    }
   }
 
   if (EPI == EPI_RESIDUAL) {
@@ -555,12 +555,11 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
 }
 
 // xn[row][:] = T(hg[row][:] * rsqrt(mean(h[row]^2) + eps)) for rows m0 + blockIdx.x: the
-// RMSNorm output as a stored tensor, for projection passes of more than 8 rows (row-major for
-// 9..16 rows, fragment-tiled for the passes of gemm_rows_kernel).
+// RMSNorm output as a stored tensor in the fragment-tiled layout, for gemm_rows_kernel.
 // 256 threads; thread p adds slot p of the row's sum-of-squares partials.
 template <typename T>
 __global__ void __launch_bounds__(256) xn_kernel(const float* __restrict__ hg, const float* __restrict__ ssq,
-                                                 T* __restrict__ xn, int ld, int m0, float d, float eps, int tiled) {
+                                                 T* __restrict__ xn, int ld, int m0, float d, float eps) {
   __shared__ float part[4];
   const int row = m0 + blockIdx.x;
   float s = ssq[(size_t)row * SSQ_PARTS + threadIdx.x];
@@ -571,8 +570,7 @@ __global__ void __launch_bounds__(256) xn_kernel(const float* __restrict__ hg, c
   const float r = rsqrtf(((part[0] + part[1]) + (part[2] + part[3])) / d + eps);
   const float* src = hg + (size_t)row * ld;
   for (int i = 4 * threadIdx.x; i < ld; i += 4 * 256) {
-    T* dst = tiled ? xn + xt_offset(row, i, ld) : xn + (size_t)row * ld + i;
-    st_round4(dst, *reinterpret_cast<const f32x4*>(src + i) * r);
+    st_round4(xn + xt_offset(row, i, ld), *reinterpret_cast<const f32x4*>(src + i) * r);
   }
 }
 
