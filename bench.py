@@ -204,6 +204,7 @@ def main():
     ap.add_argument("--kernel-iters", type=int, default=40, help="launches per projection for the roofline line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 --pmc byte counters)")
+    ap.add_argument("--paged-kv", action="store_true", help="KV cache as a pool of 256-token pages (default: contiguous)")
     ap.add_argument("--double", action="store_true",
                     help="measure the full Double round (draft + target on two streams) instead of the headline step")
     ap.add_argument("--double-tokens", type=int, default=64)
@@ -232,11 +233,14 @@ def main():
     if P > 8192:
         steps, warm = min(steps, 6), min(warm, 1)       # a 128-row window streams the weights 8 times
     max_ctx = ((P + (steps + warm + 6) * k + 63) // 64 + 1) * 64
+    if args.paged_kv:
+        max_ctx = (max_ctx + 255) // 256 * 256
     max_hist = P + 1 + (steps + warm + 6) * k + 64
     torch.cuda.set_device(0)
     dev = "cuda:0"
     t0 = time.perf_counter()
-    cfg = B.make_cfg(**shape, max_batch=Bn, max_ctx=max_ctx, max_window=max(chunk, k), max_hist=max_hist)
+    cfg = B.make_cfg(**shape, max_batch=Bn, max_ctx=max_ctx, max_window=max(chunk, k), max_hist=max_hist,
+                     flags=B.DBL_FLAG_PAGED_KV if args.paged_kv else 0)
     ctx = B.dbl_create(cfg, seed, torch.cuda.current_stream().cuda_stream)
     wbytes, kv_per_tok = B.dbl_model_bytes(ctx)
     log("[bench] context created in %.1fs: %.2f GB of weights streamed per step" % (time.perf_counter() - t0, wbytes / 1e9))
@@ -346,7 +350,7 @@ def main():
         "dtype": "bf16" if shape["dtype"] == 1 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "layers": shape["n_layers"], "ctx": P, "k": k, "batch": Bn,
                    "accept": mode, "weights": "random N(0,0.02) from seed %d" % seed,
-                   "kv_cache": "seeded fill" if filled else "prefill of the history"},
+                   "kv_cache": ("seeded fill" if filled else "prefill of the history") + (", paged" if args.paged_kv else "")},
         "hbm_GBps_step": round(step_gbps, 1), "hbm_frac_step": round(step_gbps / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": int(step_bytes), "emitted_tokens_per_s": round(emitted / dt, 2),
         "breakdown_ms": breakdown, "projections": proj, "roofline": roofline,

@@ -53,7 +53,10 @@ typedef enum {
 
 enum { DBL_F32 = 0, DBL_BF16 = 1 };
 enum { DBL_GREEDY = 0, DBL_SAMPLE = 1 };
-enum { DBL_FLAG_VALIDATE_ONLY = 1 }; /* dbl_model_cfg.flags: no GPU is touched     */
+enum {
+  DBL_FLAG_VALIDATE_ONLY = 1, /* dbl_model_cfg.flags: no GPU is touched                */
+  DBL_FLAG_PAGED_KV = 2       /* KV cache as a pool of 256-token pages, see dbl_create  */
+};
 
 /* Tensor ids for dbl_set_weights / dbl_get_weights.  Matrices are logical
  * row-major [out_features][in_features]. */
@@ -96,6 +99,15 @@ typedef struct {
  * borrowed: all later work of this context is enqueued on it.
  * Limits: head_dim in {64, 128}; n_q_heads % n_kv_heads == 0;
  * 1 <= max_window; max_batch*max_window <= 128; max_ctx % 64 == 0.
+ * KV cache: by default one region of max_ctx positions per sequence.  With
+ * DBL_FLAG_PAGED_KV (higher concurrency, App. D.1: many sequences of very different
+ * lengths) it is a pool of pages of 256 positions shared by all sequences; flags >> 8 is the
+ * number of pages (0: max_batch * max_ctx / 256, i.e. no saving), max_ctx % 256 == 0 is
+ * required and max_ctx only bounds one sequence.  The library hands a sequence its pages when a
+ * call needs them (dbl_verify_block, dbl_kv_fill: DBL_ENOMEM "KV page pool exhausted" when none
+ * is left, nothing is enqueued then) and takes them back in dbl_reset and dbl_truncate; results do
+ * not depend on the cache form.  Page hand-outs enqueue one small kernel each, so a captured
+ * graph must not contain a call that crosses a page boundary for the first time.
  */
 int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream, dbl_ctx** out);
 int dbl_destroy(dbl_ctx* ctx);

@@ -17,6 +17,8 @@ DBL_OK, DBL_EINVAL, DBL_ESTATE, DBL_ENOMEM, DBL_EHIP, DBL_ENODEV = 0, -1, -2, -3
 DBL_F32, DBL_BF16 = 0, 1
 DBL_GREEDY, DBL_SAMPLE = 0, 1
 DBL_FLAG_VALIDATE_ONLY = 1
+DBL_FLAG_PAGED_KV = 2
+KV_PAGE = 256
 T_EMB, T_LM, T_GF = 0, 1, 2
 T_G1, T_WQ, T_WK, T_WV, T_GQ, T_GK, T_WO, T_G2, T_WG, T_WU, T_WD = range(10, 21)
 

@@ -111,6 +111,12 @@ struct dbl_ctx {
   float *qkv_part = nullptr, *logits = nullptr;
   void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
   int lm_nstat = 0;                 // workgroups of the last LM-head launch (row-statistics entries per row)
+  // paged KV cache (DBL_FLAG_PAGED_KV): pool of pages shared by the sequences, table kept by the host
+  bool paged = false;
+  int pool_pages = 0, pps = 0;      // pages in the pool; table entries per sequence (max_ctx / KV_PAGE)
+  int32_t* page_table = nullptr;    // device [max_batch][pps]
+  std::vector<int32_t> free_pages;  // host free list (stack)
+  std::vector<std::vector<int32_t>> seq_pages;   // pages each sequence holds, in position order
   int ldh = 0;                      // row stride of h and layer stride of g1 / g2 / gf (>= every consumer's K padding)
   float *pm = nullptr, *pl = nullptr, *po = nullptr;
   LmStat* stats = nullptr;
@@ -167,6 +173,8 @@ int validate_cfg(const dbl_model_cfg* g, std::string& why) {
   if ((int64_t)g->max_batch * g->max_window > MAX_ROWS) return bad("max_batch * max_window exceeds 128 rows");
   if (g->max_ctx < 64 || g->max_ctx % 64) return bad("max_ctx must be a positive multiple of 64");
   if (g->max_hist < 1) return bad("max_hist must be positive");
+  if ((g->flags & DBL_FLAG_PAGED_KV) && g->max_ctx % KV_PAGE) return bad("a paged KV cache needs max_ctx to be a multiple of 256");
+  if (!(g->flags & DBL_FLAG_PAGED_KV) && (g->flags >> 8)) return bad("a pool size without DBL_FLAG_PAGED_KV");
   return DBL_OK;
 }
 
@@ -321,11 +329,12 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
   }
   const int nsplit = ncs + 1;
   AttnArgs<T>& at = s.attn;
+  at.page_table = c->page_table; at.pps = c->pps;
   at.src = src; at.qbuf = reinterpret_cast<const T*>(c->qbuf); at.kc = kc; at.vt = vt; at.kv_len = c->kv_len; at.pm = c->pm; at.pl = c->pl; at.po = c->po;
   at.k = k; at.g = gq; at.Hkv = Hkv; at.hd = hd; at.max_ctx = g.max_ctx; at.qrows_pad = c->qrows_pad;
   at.nsplit = nsplit; at.nqb = qblocks; at.scale = (float)(1.4426950408889634 / std::sqrt((double)hd));
   s.comb = CombineArgs<T>{c->pm, c->pl, c->po, attn, c->p_o.ldx(), rows_kernel_for(c, c->p_o, EPI_RESIDUAL, M) ? 1 : 0, M, k, H, Hkv, c->qrows_pad, nsplit,
-                          src, c->kv_len, kc, vt, g.max_ctx};
+                          src, c->kv_len, kc, vt, g.max_ctx, c->page_table, c->pps};
   s.o.W = reinterpret_cast<const T*>(c->w_o) + (size_t)l * c->p_o.elems();
   s.o.X = attn; s.o.ldx = c->p_o.ldx(); s.o.out = c->h; s.o.ldo = c->ldh;      // h += attn Wo^T
   s.o.hg_out = c->hg; s.o.gain_out = c->g2 + (size_t)l * c->ldh;
@@ -350,7 +359,8 @@ void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
   if constexpr (sizeof(T) == 2) deep = nblocks <= c->n_cu;
   if (deep) {
     if constexpr (sizeof(T) == 2)
-      hipLaunchKernelGGL((attn_split_kernel<T, HD, 4>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+      if (c->paged) hipLaunchKernelGGL((attn_split_kernel<T, HD, 4, true>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+      else hipLaunchKernelGGL((attn_split_kernel<T, HD, 4, false>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
   } else {
     if constexpr (sizeof(T) == 2) {
       RopeQArgs<T> q{s.attn.src, s.attn.kv_len, reinterpret_cast<T*>(c->qbuf), B, s.attn.k, s.attn.g, s.attn.qrows_pad,
@@ -358,7 +368,8 @@ void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
       const int qwaves = (B * s.attn.Hkv * s.attn.g * s.attn.k + 15) / 16;
       hipLaunchKernelGGL((rope_q_kernel<T, HD>), dim3((qwaves + 3) / 4), dim3(256), 0, c->stream, q);
     }
-    hipLaunchKernelGGL((attn_split_kernel<T, HD, 2>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+    if (c->paged) hipLaunchKernelGGL((attn_split_kernel<T, HD, 2, true>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+    else hipLaunchKernelGGL((attn_split_kernel<T, HD, 2, false>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
   }
   const int waves = combine_waves<T>(M, H, s.attn.Hkv);   // merge tasks, then KV-append tasks
   hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3((waves + 3) / 4), dim3(256), 0, c->stream, s.comb);
@@ -502,9 +513,32 @@ int copy_tensor(dbl_ctx* c, const TensorLoc& t, int layer, void* host, bool to_d
   return DBL_OK;
 }
 
+// Paged cache: sequence `seq` gets pages for positions [0, n_tokens) (no-op when it has them).
+static int ensure_pages(dbl_ctx* c, int seq, int n_tokens) {
+  if (!c->paged) return DBL_OK;
+  const int need = (n_tokens + KV_PAGE - 1) / KV_PAGE;
+  std::vector<int32_t>& mine = c->seq_pages[seq];
+  if ((int)mine.size() >= need) return DBL_OK;
+  if (need - (int)mine.size() > (int)c->free_pages.size()) return fail(c, DBL_ENOMEM, "KV page pool exhausted");
+  while ((int)mine.size() < need) {
+    const int32_t page = c->free_pages.back(); c->free_pages.pop_back();
+    hipLaunchKernelGGL(set_page_kernel, dim3(1), dim3(64), 0, c->stream, c->page_table, seq * c->pps + (int)mine.size(), page);
+    mine.push_back(page);
+  }
+  return DBL_OK;
+}
+// ... and gives back the pages beyond position n_tokens (work already enqueued still sees them;
+// whoever gets them next is enqueued later)
+static void release_pages(dbl_ctx* c, int seq, int n_tokens) {
+  if (!c->paged) return;
+  const int keep = (n_tokens + KV_PAGE - 1) / KV_PAGE;
+  std::vector<int32_t>& mine = c->seq_pages[seq];
+  while ((int)mine.size() > keep) { c->free_pages.push_back(mine.back()); mine.pop_back(); }
+}
+
 void free_all(dbl_ctx* c) {
   void* ptrs[] = {c->w_qkv, c->w_o, c->w_gu, c->w_d, c->w_lm, c->emb, c->g1, c->g2, c->gq, c->gk, c->gf, c->cosT,
-                  c->sinT, c->kc, c->vt, c->kv_len, c->hist_len, c->hist, c->prompt_len, c->rej, c->rej_len, c->tier_best, c->prior, c->status, c->commits, c->h, c->hg, c->xn, c->qkv_part,
+                  c->sinT, c->kc, c->vt, c->page_table, c->kv_len, c->hist_len, c->hist, c->prompt_len, c->rej, c->rej_len, c->tier_best, c->prior, c->status, c->commits, c->h, c->hg, c->xn, c->qkv_part,
                   c->ssq, c->logits, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
                   c->n_acc_i, c->emit_i, c->win_i};
   for (void* p : ptrs) if (p) (void)hipFree(p);
@@ -552,6 +586,14 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
   const int gq = g.n_q_heads / g.n_kv_heads;
   c->qrows_pad = ((gq * g.max_window + 63) / 64) * 64;
   c->kv_layer_elems = (size_t)g.max_batch * g.n_kv_heads * g.max_ctx * g.head_dim;
+  c->paged = (g.flags & DBL_FLAG_PAGED_KV) != 0;
+  if (c->paged) {
+    c->pps = g.max_ctx / KV_PAGE;
+    c->pool_pages = (g.flags >> 8) ? (g.flags >> 8) : g.max_batch * c->pps;
+    c->kv_layer_elems = (size_t)c->pool_pages * g.n_kv_heads * KV_PAGE * g.head_dim;
+    c->seq_pages.assign(g.max_batch, {});
+    for (int i = c->pool_pages - 1; i >= 0; --i) c->free_pages.push_back(i);   // page 0 is handed out first
+  }
   const size_t part_rows = (size_t)g.max_batch * g.n_kv_heads * MAX_SPLITS * c->qrows_pad;
 
 #define ALLOC(ptr, bytes, zero) if ((rc = dmalloc(c, &c->ptr, (bytes), (zero))) != DBL_OK) break
@@ -569,6 +611,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(sinT, (size_t)g.max_ctx * (g.head_dim / 2) * 4, false);
     ALLOC(kc, L * c->kv_layer_elems * esz, true);
     ALLOC(vt, L * c->kv_layer_elems * esz, true);
+    if (c->paged) ALLOC(page_table, (size_t)g.max_batch * c->pps * 4, true);
     ALLOC(kv_len, (size_t)g.max_batch * 4, true); ALLOC(hist_len, (size_t)g.max_batch * 4, true);
     ALLOC(hist, (size_t)g.max_batch * g.max_hist * 4, true);
     ALLOC(prompt_len, (size_t)g.max_batch * 4, true);
@@ -671,6 +714,8 @@ int dbl_reset(dbl_ctx* c, int seq) {
     if (seq < 0 || b == seq) { c->kv_upper[b] = 0; c->hist_upper[b] = 0; }
   c->have_verify = c->have_accept = false;
   if (c->dry) return DBL_ENODEV;
+  for (int b = 0; b < c->cfg.max_batch; ++b)
+    if (seq < 0 || b == seq) release_pages(c, b, 0);
   hipLaunchKernelGGL(set_counters_kernel, dim3(1), dim3(128), 0, c->stream, c->kv_len, c->hist_len, c->prompt_len, c->rej_len, seq,
                      c->cfg.max_batch);
   HIPCHK(c, hipGetLastError());
@@ -687,15 +732,21 @@ int dbl_kv_fill(dbl_ctx* c, int seq, int32_t n_tokens, uint64_t seed) {
   if (c->dry) return DBL_ENODEV;
   const size_t region = (size_t)g.max_ctx * g.head_dim;                       // one (sequence, kv head)
   const size_t n = (size_t)((n_tokens + 31) / 32 * 32) * g.head_dim;          // whole tiles
+  {
+    const int rc_pages = ensure_pages(c, seq, n_tokens);
+    if (rc_pages != DBL_OK) return rc_pages;
+  }
   if (n > 0 && g.n_layers > 0) {
     const dim3 grid((unsigned)((n + 255) / 256), (unsigned)(g.n_layers * g.n_kv_heads));
-    const size_t seq_off = (size_t)seq * g.n_kv_heads * region;
+    const size_t seq_off = c->paged ? 0 : (size_t)seq * g.n_kv_heads * region;
+    const int32_t* pages = c->paged ? c->page_table + (size_t)seq * c->pps : nullptr;
+    const size_t page_elems = (size_t)KV_PAGE * g.head_dim;
     if (c->bf16)
       hipLaunchKernelGGL((fill_kv_kernel<bf16_t>), grid, dim3(256), 0, c->stream, reinterpret_cast<bf16_t*>(c->kc) + seq_off,
-                         reinterpret_cast<bf16_t*>(c->vt) + seq_off, region, c->kv_layer_elems, g.n_kv_heads, n, seed);
+                         reinterpret_cast<bf16_t*>(c->vt) + seq_off, region, c->kv_layer_elems, g.n_kv_heads, n, seed, pages, page_elems);
     else
       hipLaunchKernelGGL((fill_kv_kernel<float>), grid, dim3(256), 0, c->stream, reinterpret_cast<float*>(c->kc) + seq_off,
-                         reinterpret_cast<float*>(c->vt) + seq_off, region, c->kv_layer_elems, g.n_kv_heads, n, seed);
+                         reinterpret_cast<float*>(c->vt) + seq_off, region, c->kv_layer_elems, g.n_kv_heads, n, seed, pages, page_elems);
   }
   hipLaunchKernelGGL(set_kv_len_kernel, dim3(1), dim3(64), 0, c->stream, c->kv_len, seq, n_tokens);
   HIPCHK(c, hipGetLastError());
@@ -709,6 +760,7 @@ int dbl_truncate(dbl_ctx* c, int seq, int32_t kv_len, int32_t hist_len) {
   if (hist_len >= 0) c->hist_upper[seq] = std::min(c->hist_upper[seq], (int)hist_len);
   c->have_verify = c->have_accept = false;
   if (c->dry) return DBL_ENODEV;
+  if (kv_len >= 0) release_pages(c, seq, c->kv_upper[seq]);
   hipLaunchKernelGGL(truncate_kernel, dim3(1), dim3(64), 0, c->stream, c->kv_len, c->hist_len, c->prompt_len, seq, (int)kv_len,
                      (int)hist_len);
   HIPCHK(c, hipGetLastError());
@@ -862,6 +914,10 @@ static int verify_common(dbl_ctx* c, const int32_t* window, const int32_t* win_l
     if (c->kv_upper[b] + k > c->cfg.max_ctx) return fail(c, DBL_EINVAL, "kv_len + k would exceed max_ctx");
   c->have_verify = false; c->have_accept = false;
   if (c->dry) { c->have_verify = true; c->last_B = B; c->last_k = k; c->verify_sampling = temperature > 0.f; return DBL_ENODEV; }
+  for (int b = 0; b < B; ++b) {
+    const int rc_pages = ensure_pages(c, b, c->kv_upper[b] + k);
+    if (rc_pages != DBL_OK) return rc_pages;
+  }
   // keep the window for accept (the caller's buffer is not retained); ragged: rows beyond a
   // sequence's own length are marked "no token"
   if (win_len) {
@@ -943,6 +999,9 @@ static int read_counters(dbl_ctx* c, int32_t* host_out, bool kv) {
   HIPCHK(c, hipMemcpy(a.data(), c->kv_len, (size_t)n * 4, hipMemcpyDeviceToHost));
   HIPCHK(c, hipMemcpy(b.data(), c->hist_len, (size_t)n * 4, hipMemcpyDeviceToHost));
   for (int i = 0; i < n; ++i) { c->kv_upper[i] = a[i]; c->hist_upper[i] = b[i]; }
+  // paged cache: pages handed out against the host's (looser) upper bound go back to the pool,
+  // except the ones a window that is verified but not committed yet may still need
+  for (int i = 0; i < n; ++i) release_pages(c, i, a[i] + c->cfg.max_window);
   std::memcpy(host_out, kv ? a.data() : b.data(), (size_t)n * 4);
   return check_status(c);
 }

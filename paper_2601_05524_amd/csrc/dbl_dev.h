@@ -25,6 +25,10 @@ constexpr int BLOCK_ELEMS = TILE_N * TILE_K;  // 512 elements per weight block
 //   V: tiles of 32 tokens x 16 dims (V^T is the operand); lane l = 16*(t%16/4) + d%16 owns tokens
 //      {4q .. 4q+3} and {16+4q .. 16+4q+3} of the tile (q = t%16/4), in that order.
 // t = position in the sequence, d = dim, hd = head_dim; max_ctx is a multiple of 64.
+// Paged cache: a page holds KV_PAGE consecutive positions of every kv head in the same tiled
+// order (t = position inside the page); KV_PAGE is a multiple of both tile lengths, so a
+// 32-token attention step never straddles two pages.
+constexpr int KV_PAGE = 256;
 __host__ __device__ inline size_t kc_offset(int t, int d, int hd) {
   return ((size_t)((t >> 4) * (hd >> 5) + (d >> 5)) * 64 + (((d & 31) >> 3) * 16 + (t & 15))) * 8 + (d & 7);
 }

@@ -478,16 +478,21 @@ __global__ void fill_rowmajor_kernel(T* __restrict__ W, size_t n, int tensor_id,
 
 // Seeded stand-in KV rows (measurement aid): elements [0, n) of every (layer, kv head) region
 // of one sequence; any bit pattern is a valid entry of the tiled cache layout.
+// The value of element i of a (layer, kv head) region is the same in both cache forms.
 template <typename T>
 __global__ void fill_kv_kernel(T* __restrict__ kc, T* __restrict__ vt, size_t region, size_t layer_stride, int n_regions_per_layer,
-                               size_t n, uint64_t seed) {
+                               size_t n, uint64_t seed, const int32_t* __restrict__ pages, size_t page_elems) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   const int r = blockIdx.y % n_regions_per_layer, l = blockIdx.y / n_regions_per_layer;
-  const size_t off = (size_t)l * layer_stride + (size_t)r * region + i;
+  size_t off;
+  if (pages) off = (size_t)l * layer_stride + ((size_t)pages[i / page_elems] * n_regions_per_layer + r) * page_elems + i % page_elems;
+  else off = (size_t)l * layer_stride + (size_t)r * region + i;
   kc[off] = Elem<T>::from_f(32.f * weight_value(seed, 30, (int)blockIdx.y, i));
   vt[off] = Elem<T>::from_f(32.f * weight_value(seed, 31, (int)blockIdx.y, i));
 }
+
+__global__ void set_page_kernel(int32_t* table, int idx, int32_t page) { if (threadIdx.x == 0) table[idx] = page; }
 
 __global__ void set_kv_len_kernel(int32_t* kv_len, int seq, int32_t v) { if (threadIdx.x == 0) kv_len[seq] = v; }
 

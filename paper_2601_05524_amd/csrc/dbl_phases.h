@@ -178,6 +178,8 @@ struct AttnArgs {
   const T* qbuf;                    // throughput form only: the queries, already normed / rotated / rounded
   const T *kc, *vt;                 // KV cache, offset to the layer: the tokens before the window
   const int32_t* kv_len;
+  const int32_t* page_table;        // paged cache: [max_batch][pps] page ids (page = KV_PAGE tokens of every kv head)
+  int pps;                          //   pages per sequence
   float *pm, *pl, *po;              // [B][Hkv][nsplit][qrows_pad] / ...[hd]
   int k, g, Hkv, hd, max_ctx, qrows_pad, nsplit, nqb;   // nqb = query blocks per (b, kv head)
   float scale;                      // log2(e) / sqrt(hd): scores and running maxima are kept in the log2 domain
@@ -235,7 +237,7 @@ __device__ __forceinline__ void load_kv(KvFrags<T, HD>& f, const T* kbase, const
 // into nsplit - 1 ranges; the last split takes the k window rows themselves, whose keys and
 // values are not in the cache yet: it builds them from the projection result (one 32-token
 // step, row j sees window rows 0..j).  With nsplit = 1 the one split does both.
-template <typename T, int HD, int PRE>
+template <typename T, int HD, int PRE, bool PAGED>
 __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
   constexpr int KSTEPS = HD / 32, HT = HD / 16;
   constexpr bool HALF_REGS = PRE == 2 && sizeof(T) == 2;   // see attn_split_kernel
@@ -387,9 +389,18 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
     // that both arrive in the same round trip.
     // Steps beyond the range re-read its first step (a valid address) and are skipped.
     KvFrags<T, HD> f[PRE];
+    // (paged cache: a 32-token step lies inside one page; the page of every step is looked up)
     auto load_group = [&](int tg, int fallback) {
 #pragma unroll
-      for (int u = 0; u < PRE; ++u) load_kv<T, HD>(f[u], kbase, vbase, tg + 32 * u < t1 ? tg + 32 * u : fallback, lane);
+      for (int u = 0; u < PRE; ++u) {
+        const int tb = tg + 32 * u < t1 ? tg + 32 * u : fallback;
+        if constexpr (PAGED) {
+          const size_t po = ((size_t)a.page_table[b * a.pps + tb / KV_PAGE] * a.Hkv + kvh) * KV_PAGE * HD;
+          load_kv<T, HD>(f[u], a.kc + po, a.vt + po, tb % KV_PAGE, lane);
+        } else {
+          load_kv<T, HD>(f[u], kbase, vbase, tb, lane);
+        }
+      }
     };
     const int lim_c = jrow < 0 ? -1 : t1 - 1;          // every cached token is visible to every window row
     auto run_group = [&](int tg) {
@@ -440,7 +451,7 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
 // window splits last: when the grid is larger than the chip holds at once, the ones that
 // wait for a free slot are short.
 // (PRE = 2 in bf16 is the form for more workgroups than CUs: held to two waves per SIMD.)
-template <typename T, int HD, int PRE>
+template <typename T, int HD, int PRE, bool PAGED>
 __global__ void __launch_bounds__(256, (PRE == 2 && sizeof(T) == 2) ? 2 : 1) attn_split_kernel(const AttnArgs<T> a) {
   const int wpg = blockDim.x >> 6;
   const int nqg = (a.nqb + wpg - 1) / wpg;
@@ -451,7 +462,7 @@ __global__ void __launch_bounds__(256, (PRE == 2 && sizeof(T) == 2) ? 2 : 1) att
   else { blk -= ncache; qg = blk % nqg; sp = ncs; bh = blk / nqg; }
   const int qb = qg * wpg + (threadIdx.x >> 6);
   if (qb >= a.nqb) return;
-  attn_task<T, HD, PRE>(a, (bh * a.nsplit + sp) * a.nqb + qb);
+  attn_task<T, HD, PRE, PAGED>(a, (bh * a.nsplit + sp) * a.nqb + qb);
 }
 
 // Queries for the throughput form of the attention: wave w handles 16 query rows of the
@@ -500,7 +511,21 @@ struct CombineArgs {
   const int32_t* kv_len;
   T *kc, *vt;                       // offset to the layer
   int max_ctx;
+  const int32_t* page_table;        // paged cache (else nullptr): [max_batch][pps]
+  int pps;
 };
+
+// element offset of (sequence b, kv head, position pos) in a layer's cache, up to the
+// position-inside-the-tiles part that kc_offset / vt_offset add (pos_local)
+template <typename T>
+__device__ __forceinline__ size_t cache_base(const CombineArgs<T>& a, int b, int kvh, int pos, int hd, int& pos_local) {
+  if (a.page_table) {
+    pos_local = pos % KV_PAGE;
+    return ((size_t)a.page_table[b * a.pps + pos / KV_PAGE] * a.Hkv + kvh) * KV_PAGE * hd;
+  }
+  pos_local = pos;
+  return (size_t)(b * a.Hkv + kvh) * a.max_ctx * hd;
+}
 
 // Key append: wave w handles 16 (row, kv head) items, four lanes (one per dim group) each:
 // item = m * Hkv + kvh -> norm, rotary embedding, one 8-element store per fragment.
@@ -519,9 +544,10 @@ __device__ __forceinline__ void append_k_task(const CombineArgs<T>& a, int w) {
   Frag<T> kf[KSTEPS];
   rope_head<T, HD>(a.src, m, (a.src.H + kvh) * HD, a.src.gk, min(pos, a.max_ctx - 1), g4, kf);
   if (live) {
-    T* dst = a.kc + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
+    int pl;
+    T* dst = a.kc + cache_base(a, b, kvh, pos, HD, pl);
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) *reinterpret_cast<Frag<T>*>(dst + kc_offset(pos, ks * 32 + 8 * g4, HD)) = kf[ks];
+    for (int ks = 0; ks < KSTEPS; ++ks) *reinterpret_cast<Frag<T>*>(dst + kc_offset(pl, ks * 32 + 8 * g4, HD)) = kf[ks];
   }
 }
 
@@ -536,12 +562,13 @@ __device__ __forceinline__ void append_v_task(const CombineArgs<T>& a, int w) {
   if (pos >= a.max_ctx) return;
   const size_t pstride = (size_t)a.src.Mtot * a.src.ldq;
   const float* src = a.src.qkv + (size_t)m * a.src.ldq + (size_t)(a.src.H + a.src.Hkv + kvh) * HD;
-  T* dst = a.vt + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
+  int pl;
+  T* dst = a.vt + cache_base(a, b, kvh, pos, HD, pl);
 #pragma unroll
   for (int d = lane; d < HD; d += 64) {
     float x = src[d];
     for (int p = 1; p < a.src.nparts; ++p) x += src[d + p * pstride];
-    st_round1(dst + vt_offset(pos, d, HD), x);
+    st_round1(dst + vt_offset(pl, d, HD), x);
   }
 }
 

@@ -30,10 +30,13 @@ GAINS = ("gf", "g1", "g2", "gq", "gk")
 class Gpu:
     """libdbl context + the device buffers a caller needs."""
 
-    def __init__(self, shape, *, seed, max_batch=1, max_ctx=512, max_window=8, max_hist=1024):
+    def __init__(self, shape, *, seed, max_batch=1, max_ctx=512, max_window=8, max_hist=1024, kv_pages=None):
+        """kv_pages: None = one contiguous cache region per sequence; n >= 0 = paged cache with a
+        pool of n pages (0: the default pool size)."""
         self.shape = dict(shape)
+        flags = 0 if kv_pages is None else (B.DBL_FLAG_PAGED_KV | (kv_pages << 8))
         self.cfg = B.make_cfg(**shape, max_batch=max_batch, max_ctx=max_ctx, max_window=max_window,
-                              max_hist=max_hist)
+                              max_hist=max_hist, flags=flags)
         torch.cuda.set_device(0)
         self.stream = torch.cuda.current_stream()
         self.ctx = B.dbl_create(self.cfg, seed, self.stream.cuda_stream)

@@ -36,7 +36,9 @@ def cfg(**kw):
 
 @pytest.mark.parametrize("bad", [dict(head_dim=48), dict(n_q_heads=3), dict(max_ctx=100), dict(dtype=7),
                                  dict(max_window=64), dict(max_batch=8, max_window=32), dict(d_model=8200 * 2),
-                                 dict(vocab=1), dict(rms_eps=0.0), dict(max_hist=0), dict(d_model=250)])
+                                 dict(vocab=1), dict(rms_eps=0.0), dict(max_hist=0), dict(d_model=250),
+                                 dict(max_ctx=320, flags=B.DBL_FLAG_VALIDATE_ONLY | B.DBL_FLAG_PAGED_KV),   # paged: 256-token pages
+                                 dict(flags=B.DBL_FLAG_VALIDATE_ONLY | (5 << 8))])                      # pool size without paging
 def test_create_rejects_bad_configs(bad):
     with pytest.raises(B.DblError) as e:
         B.dbl_create(cfg(**bad), 1)
