@@ -8,6 +8,7 @@
  *     dbl_retrieve      d candidate tokens by n-gram match            (Alg. 3)
  *     dbl_build_window  pending token + candidates -> k window rows
  *     dbl_verify_block  one target forward over the k rows            (Sec. 2.1)
+ *                       (dbl_verify_block_ragged: windows of different lengths in one batch)
  *     dbl_accept        s matched tokens + 1 correction               (Sec. 2.1, App. D.2)
  *     dbl_kv_commit     keep the accepted rows' KV, extend the history (Alg. 1, Alg. 2)
  *
@@ -17,7 +18,8 @@
  *     never frees caller memory and does not keep caller pointers after the
  *     stream work of the call that received them has finished.
  *   - The context owns weights, KV cache, token history, per-sequence counters
- *     and all scratch.  B sequences (0 <= b < B <= max_batch) advance in lockstep.
+ *     and all scratch.  B sequences (0 <= b < B <= max_batch) advance in lockstep
+ *     (with dbl_verify_block_ragged a sequence may bring a shorter window or sit a step out).
  *   - The hot calls (retrieve, build_window, verify_block, accept, kv_commit) only
  *     enqueue work on the context's stream and return; results are valid once the
  *     caller has synchronised that stream.  Counters (kv_len, hist_len, n_acc) stay
