@@ -221,6 +221,7 @@ int launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
   for (int q : {4, 2}) {
     if (q < NACC) continue;
     if (EPI == EPI_LMHEAD && R == 4 && q == 4) continue;   // (the row statistics of four groups leave no room for 16 accumulators)
+    if (R == 8 && q != 4) continue;                         // (eight row groups: half the k-blocks per chunk, so 4 tile rows fill the ring)
     const int units = (p.NT + q / NACC - 1) / (q / NACC) * p.SS;
     int g = std::min(units, std::min(c->n_cu, SSQ_PARTS));
     g = std::max(p.SS, g / p.SS * p.SS);
@@ -229,8 +230,12 @@ int launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
     if (cost < best) { best = cost; bestq = q; bestg = g; }
   }
   const dim3 grid(bestg), block(256);
-  if (bestq == 4) hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4>), grid, block, 0, c->stream, a);
-  else hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 2>), grid, block, 0, c->stream, a);
+  if constexpr (R == 8) {
+    hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4>), grid, block, 0, c->stream, a);
+  } else {
+    if (bestq == 4) hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4>), grid, block, 0, c->stream, a);
+    else hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 2>), grid, block, 0, c->stream, a);
+  }
   return bestg;
 }
 
@@ -240,7 +245,9 @@ void launch_gemm_rows(dbl_ctx* c, const GemmPlan& p, int epi, const GemmArgs<T>&
     case EPI_PARTIAL: launch_gemm_rows_q<T, EPI_PARTIAL, R>(c, p, a); break;
     case EPI_RESIDUAL: launch_gemm_rows_q<T, EPI_RESIDUAL, R>(c, p, a); break;
     case EPI_SWIGLU: launch_gemm_rows_q<T, EPI_SWIGLU, R>(c, p, a); break;
-    default: c->lm_nstat = launch_gemm_rows_q<T, EPI_LMHEAD, R>(c, p, a); break;
+    default:
+      if constexpr (R <= 4) c->lm_nstat = launch_gemm_rows_q<T, EPI_LMHEAD, R>(c, p, a);
+      break;
   }
 }
 
@@ -266,13 +273,17 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
   if (rows) {
     T* xn = reinterpret_cast<T*>(c->xn);
     a.act_tiled = rows_kernel_for(c, c->p_d, EPI_RESIDUAL, M) ? 1 : 0;
-    for (int m0 = 0; m0 < M; m0 += 64) {
-      a.m0 = m0; a.mrows = std::min(64, M - m0);
+    // rows per pass: 128 (eight row groups; measured at the 70B width against two 64-row passes:
+    // q/k/v 66 / 98 us, output 58 / 68, gate/up 222 / 335, down 167 / 189), 64 for the LM head
+    const int pass = epi == EPI_LMHEAD ? 64 : 128;
+    for (int m0 = 0; m0 < M; m0 += pass) {
+      a.m0 = m0; a.mrows = std::min(pass, M - m0);
       if (epi != EPI_RESIDUAL) {     // the RMSNorm output is stored first and read like any activation
         hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, a.d, a.eps);
         a.X = xn;
       }
-      if (a.mrows > 32) launch_gemm_rows<T, 4>(c, p, epi, a);
+      if (a.mrows > 64) launch_gemm_rows<T, 8>(c, p, epi, a);
+      else if (a.mrows > 32) launch_gemm_rows<T, 4>(c, p, epi, a);
       else if (a.mrows > 16) launch_gemm_rows<T, 2>(c, p, epi, a);
       else launch_gemm_rows<T, 1>(c, p, epi, a);
     }

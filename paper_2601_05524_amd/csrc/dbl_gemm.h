@@ -328,9 +328,9 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
 }
 
 // ---------------------------------------------------------------------------
-// Windows of more than 16 rows: the same weight streaming, but every weight fragment is
-// multiplied with R row groups of 16 rows before the next one is fetched, so the weights are
-// read once per 16*R rows instead of once per 16.
+// Any number of rows, in passes of R = 1, 2, 4 or 8 row groups of 16 rows: every weight fragment
+// is multiplied with all R groups before the next one is fetched, so the weights are read once
+// per 16*R rows.
 //   * Four waves per workgroup (one per SIMD, the whole register file each) split the k-blocks
 //     of a chunk: KS blocks per wave, 4*KS per chunk.  A wave keeps the activations of its
 //     slice for all R groups in registers (R*KS fragments) and fetches the next chunk's while
@@ -354,12 +354,13 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
   constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
   constexpr int TT = Q / NACC;                  // output tiles per unit
   constexpr int NWV = 4;                        // waves: one per SIMD, the whole register file each
-  constexpr int KS = sizeof(T) == 2 ? 8 : 4;    // k-blocks per wave and chunk
+  constexpr int KS = (sizeof(T) == 2 ? 8 : 4) / (R > 4 ? 2 : 1);   // k-blocks per wave and chunk (halved for 8 row groups: registers)
   constexpr int NF = Q * KS;                    // weight fragments per wave and chunk
   constexpr int RING = GemmCfg<T>::RING;
   constexpr int P = TT * R;                     // (tile, row group) pairs per unit
   constexpr int PH = P > 8 ? 8 : P;             // pairs per reduction round
   static_assert(Q % NACC == 0 && NF % RING == 0 && P % PH == 0, "unit shape");
+  static_assert(R <= 4 || EPI != EPI_LMHEAD, "the LM head's row statistics fit for at most four row groups");
   __shared__ f32x4 red[NWV][PH][NACC][WAVE];
   __shared__ float wsq[NWV][R][16];
   __shared__ LmStat lmred[EPI == EPI_LMHEAD ? NWV : 1][R][16];
@@ -522,7 +523,7 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
       if (g == 0) lmred[wave][r][c] = st[r];
     }
     __syncthreads();
-    if (wave == 0 && g < R) {
+    if (wave == 0 && g < R) {   // lane group g takes row group g (R <= 4 here)
       const int mr = 16 * g + c;
       if (mr < a.mrows) {
         LmStat s = lmred[0][g][c];
@@ -541,14 +542,16 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
       if (g == 0) wsq[wave][r][c] = v;
     }
     __syncthreads();
-    if (wave == 0 && g < R) {   // lane group g takes row group g
-      const int mr = 16 * g + c;
-      if (mr < a.mrows) {
-        float v = wsq[0][g][c];
+    if (wave == 0) {
+      for (int rg = g; rg < R; rg += 4) {   // lane group g takes row groups g, g + 4
+        const int mr = 16 * rg + c;
+        if (mr < a.mrows) {
+          float v = wsq[0][rg][c];
 #pragma unroll
-        for (int w = 1; w < NWV; ++w) v += wsq[w][g][c];
-        float* dst = a.ssq_out + (size_t)(a.m0 + mr) * SSQ_PARTS;
-        for (int p = wg; p < SSQ_PARTS; p += nwg) dst[p] = p == wg ? v : 0.f;
+          for (int w = 1; w < NWV; ++w) v += wsq[w][rg][c];
+          float* dst = a.ssq_out + (size_t)(a.m0 + mr) * SSQ_PARTS;
+          for (int p = wg; p < SSQ_PARTS; p += nwg) dst[p] = p == wg ? v : 0.f;
+        }
       }
     }
   }

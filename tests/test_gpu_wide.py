@@ -43,7 +43,7 @@ def reference(name, seed):
     key = (name, seed)
     if key not in _REF:
         _REF.clear()                # one wide model at a time: they are several GB each
-        r = Ref(slice_of(name), seed=seed, max_batch=2, max_ctx=512)
+        r = Ref(slice_of(name), seed=seed, max_batch=4, max_ctx=512)
         saved = {(t, l): r.get_tensor(t, l) for t in ("wo", "wd") for l in (0, 1)}
         _REF[key] = (r, saved)
     return _REF[key]
@@ -127,27 +127,28 @@ def test_llama70b_width_two_layers_16_row_chunks():
     composite("llama70b", 12, 16, 35)
 
 
-def test_llama70b_width_two_layers_64_row_window():
-    """Two sequences with 32-row windows: 64 rows go through the multi-row-group projection
-    kernel (four row groups per weight fragment, K walked in chunks) at the full 70B width."""
+@pytest.mark.parametrize("nseq", [2, 4], ids=["64_rows", "128_rows"])
+def test_llama70b_width_two_layers_many_row_window(nseq):
+    """Two / four sequences with 32-row windows: 64 / 128 rows go through the projection kernel
+    with four / eight row groups per weight fragment at the full 70B width."""
     shape = slice_of("llama70b")
     r, saved = reference("llama70b", 31)
     for (t, l), v in saved.items():
         r.set_tensor(t, l, v)
-    g = Gpu(shape, seed=31, max_batch=2, max_ctx=512, max_window=32)
+    g = Gpu(shape, seed=31, max_batch=nseq, max_ctx=512, max_window=32)
     V = shape["vocab"]
-    prompts = [synth.zipf_history(31 + b, 33, V) for b in range(2)]
+    prompts = [synth.zipf_history(31 + b, 33, V) for b in range(nseq)]
     g.prefill(prompts, 32)
     r.prefill(prompts, 16)
     rng = np.random.default_rng(9)
     ws = [np.concatenate([[p[-1]], rng.integers(0, V, 31)]).astype(np.int32) for p in prompts]
     got = g.verify(ws)
     refs = r.verify(ws)
-    for b in range(2):
+    for b in range(nseq):
         ref = refs[b]
         d = got[b].astype(np.float64) - ref
         rel = np.sqrt((d ** 2).mean()) / np.sqrt((ref ** 2).mean())
-        print("64-row window, sequence %d: rms error / rms logits %.3g, max-abs %.3g" % (b, rel, np.abs(d).max()))
+        print("%d-row window, sequence %d: rms error / rms logits %.3g, max-abs %.3g" % (32 * nseq, b, rel, np.abs(d).max()))
         assert np.isfinite(got[b]).all()
         assert rel <= COMPOSITE_REL
         assert np.abs(d).max() <= COMPOSITE_MAX
