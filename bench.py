@@ -319,7 +319,7 @@ def main():
     breakdown = {n: round(v, 4) for n, v in zip(names, acc)}
 
     # dominant kernel: the fused gate/up + SwiGLU projection (55% of the bytes at 70B shape)
-    M = min(64, Bn * k)    # rows of one projection pass
+    M = min(128, Bn * k)   # rows of one projection pass (the LM head splits it into passes of 64)
     proj = {}
     for which, name in enumerate(["qkv", "o_proj", "gate_up_swiglu", "down_proj", "lm_head_stats"]):
         if which < 4 and shape["n_layers"] < 1:
