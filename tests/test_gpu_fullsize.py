@@ -7,11 +7,11 @@ any two implementations anyway (the two-layer full-width slices in test_gpu_wide
 element-wise check).  What is checked here holds at any size:
   * the logits are finite and not degenerate;
   * the acceptance results agree, bit for bit, with the greedy rule re-evaluated in numpy on
-    the logits the same call returned (the fused LM-head statistics over 256 workgroups and
+    the logits the same call returned (the fused LM-head statistics over 256 workgroups x 4 waves and
     the acceptance kernel against a plain arg-max over 128 256 logits per row);
   * the device counters move by exactly the accepted length + 1;
-  * a second run from a reset context reproduces every logit bit for bit, although the
-    gate/up projection hands out its tiles dynamically.
+  * a second run from a reset context reproduces every logit bit for bit (every sum over
+    waves, workgroups and attention splits is taken in a fixed order).
 """
 import numpy as np
 import pytest
