@@ -312,8 +312,8 @@ def test_sampling_accept_parity(dense):
 
 def test_stress_shape_batch4_ragged_contexts_windows_4_to_32():
     """The long-context stress workload's structure at a width the oracle can follow: batch 4
-    with different context lengths, verify windows k = 4, 8, 16, 32 (up to 128 rows = eight
-    16-row passes over the weights), speculative sampling at temperature 1.0."""
+    with different context lengths, verify windows k = 4, 8, 16, 32 (16, 32, 64, 128 rows: one
+    pass over the weights with 1, 2, 4, 8 row groups), speculative sampling at temperature 1.0."""
     shape = SMALL_BF16
     Bn, T, seed = 4, 1.0, 0x5EED5EED
     g, r = pair(shape, 15, max_batch=Bn, max_ctx=1280, max_window=32, max_hist=2048)

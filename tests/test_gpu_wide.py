@@ -123,7 +123,7 @@ def test_llama70b_width_two_layers():
 
 
 def test_llama70b_width_two_layers_16_row_chunks():
-    """Windows of more than 8 rows take the unpacked activation layout."""
+    """Windows of 9..16 rows: one row group of the row-group projection kernel for every projection."""
     composite("llama70b", 12, 16, 35)
 
 
