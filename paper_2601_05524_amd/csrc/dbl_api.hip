@@ -369,9 +369,13 @@ void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
   bool deep = false;
   if constexpr (sizeof(T) == 2) deep = nblocks <= c->n_cu;
   if (deep) {
-    if constexpr (sizeof(T) == 2)
-      if (c->paged) hipLaunchKernelGGL((attn_split_kernel<T, HD, 4, true>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
-      else hipLaunchKernelGGL((attn_split_kernel<T, HD, 4, false>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+    if constexpr (sizeof(T) == 2) {
+      if (c->paged) {
+        hipLaunchKernelGGL((attn_split_kernel<T, HD, 4, true>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+      } else {
+        hipLaunchKernelGGL((attn_split_kernel<T, HD, 4, false>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+      }
+    }
   } else {
     if constexpr (sizeof(T) == 2) {
       RopeQArgs<T> q{s.attn.src, s.attn.kv_len, reinterpret_cast<T*>(c->qbuf), B, s.attn.k, s.attn.g, s.attn.qrows_pad,
@@ -379,8 +383,11 @@ void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
       const int qwaves = (B * s.attn.Hkv * s.attn.g * s.attn.k + 15) / 16;
       hipLaunchKernelGGL((rope_q_kernel<T, HD>), dim3((qwaves + 3) / 4), dim3(256), 0, c->stream, q);
     }
-    if (c->paged) hipLaunchKernelGGL((attn_split_kernel<T, HD, 2, true>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
-    else hipLaunchKernelGGL((attn_split_kernel<T, HD, 2, false>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+    if (c->paged) {
+      hipLaunchKernelGGL((attn_split_kernel<T, HD, 2, true>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+    } else {
+      hipLaunchKernelGGL((attn_split_kernel<T, HD, 2, false>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+    }
   }
   const int waves = combine_waves<T>(M, H, s.attn.Hkv);   // merge tasks, then KV-append tasks
   hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3((waves + 3) / 4), dim3(256), 0, c->stream, s.comb);
