@@ -18,6 +18,8 @@ COMPOSITE_MAX (max-abs).
 import numpy as np
 import pytest
 
+import oracle as O
+from paper_2601_05524_amd import binding as B
 from paper_2601_05524_amd import synth
 from tests.gpu_util import Gpu, Ref
 
@@ -106,6 +108,51 @@ def one_path(name, k, chunk, path):
 @pytest.mark.parametrize("path", list(PATHS))
 def test_llama70b_width_one_path_at_a_time(path):
     one_path("llama70b", 8, 8, path)
+
+
+def test_llama70b_width_lm_head_sampling_statistics():
+    """The fused LM-head statistics over the full vocabulary (8016 tiles, 256 workgroups x 4 waves) in
+    sampling mode: accepted lengths and emitted tokens against the oracle's acceptance on the
+    oracle's own logits, for windows whose decisions lie outside the measured logit error."""
+    from tests.test_gpu_parity import sample_margin_ok
+    shape = slice_of("llama70b")
+    r, saved = reference("llama70b", 31)
+    g = Gpu(shape, seed=31, max_ctx=512, max_window=8)
+    for (t, l), v in saved.items():        # embedding -> final norm -> LM head on both sides
+        z = np.zeros_like(v)
+        r.set_tensor(t, l, z); g.set_tensor(t, l, z)
+    V, T, seed = shape["vocab"], 0.25, 0x70B5A3
+    prompt = synth.zipf_history(31, 17, V)
+    g.prefill([prompt], 8)
+    r.prefill([prompt], 8)
+    rng = np.random.default_rng(5)
+    compared, lengths = 0, []
+    for step in range(6):
+        s = r.seqs[0]
+        pending = int(s.history()[-1]) if step == 0 else int(rng.integers(0, V))
+        # drafts: the oracle's own most likely continuation for the first rows, random afterwards
+        w = [pending]
+        for j in range(7):
+            lg = s.verify_block(w)
+            w.append(int(lg[-1].argmax()) if j < 2 + step % 4 else int(rng.integers(0, V)))
+        w = np.array(w, np.int32)
+        ref = s.verify_block(w)
+        got = g.verify([w], temperature=T, seed=seed, step=100 + step)[0]
+        err = np.abs(got - ref).max()
+        assert err <= TOL_BF16
+        n, emit, guide = g.accept(B.DBL_SAMPLE)
+        n_ref, e_ref, gd_ref, am, gap = O.accept_sample(ref, w, None, T, seed, 100 + step + g.ncommit, 0)
+        if sample_margin_ok(ref, w, None, T, am, gap, n_ref, err):
+            assert n[0] == n_ref, step
+            assert np.array_equal(emit[0], e_ref), step
+            compared += 1
+        lengths.append(n_ref)
+        g.commit([1]); s.commit(1, [])
+    print("compared %d of 6 windows, accepted lengths %s" % (compared, lengths))
+    assert compared >= 3
+    for (t, l), v in saved.items():
+        r.set_tensor(t, l, v)
+    g.close()
 
 
 def composite(name, k, chunk, ctx_tokens):
