@@ -11,7 +11,8 @@ element-wise check).  What is checked here holds at any size:
     the acceptance kernel against a plain arg-max over 128 256 logits per row);
   * the device counters move by exactly the accepted length + 1;
   * a second run from a reset context reproduces every logit bit for bit (every sum over
-    waves, workgroups and attention splits is taken in a fixed order).
+    waves, workgroups and attention splits is taken in a fixed order), and so does a third run
+    with the paged KV cache.
 """
 import numpy as np
 import pytest
@@ -102,4 +103,14 @@ def test_llama70b_full_depth_properties():
         g.accept(B.DBL_GREEDY)
         g.commit()
         assert np.array_equal(logits, res[i]), "step %d differs between two runs" % i
+    g.close()
+
+    # run 3 with the KV cache as a pool of pages: other addresses, the same arithmetic, identical bits
+    g = Gpu(shape, seed=seed, max_ctx=CTX + 256, max_window=16, max_hist=CTX + 256, kv_pages=0)
+    g.prefill([prompt], 16)
+    for i in range(STEPS):
+        logits = g.verify([windows[i]])[0]
+        g.accept(B.DBL_GREEDY)
+        g.commit()
+        assert np.array_equal(logits, res[i]), "step %d differs between the paged and the contiguous cache" % i
     g.close()
