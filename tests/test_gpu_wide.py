@@ -209,3 +209,67 @@ def test_qwen32b_width_one_path_at_a_time(path):
 
 def test_qwen32b_width_two_layers():
     composite("qwen32b", 6, 16, 37)
+
+
+# ---- the 1B-shaped draft model: its projections take the 8-row streaming kernels ----------
+@pytest.mark.parametrize("path", list(PATHS))
+def test_llama1b_width_one_path_at_a_time(path):
+    one_path("llama1b", 8, 8, path)
+
+
+def test_llama1b_width_two_layers():
+    composite("llama1b", 8, 8, 40)
+
+
+FULL_DEPTH_REL = 2e-2    # rms error / rms logits after 16 layers of bf16 rounding noise
+
+
+def test_llama1b_full_depth_greedy_steps():
+    """All 16 layers of the 1B-shaped model: greedy steps (verify, accept, commit), teacher-forced
+    from the oracle's decisions.  Logits are held to the compounded-noise bar; the target's top-1
+    per row, the accepted length and the emitted tokens must be equal wherever the oracle's top-2
+    margins exceed the measured error."""
+    shape = dict(synth.CONFIGS["llama1b"])
+    _REF.clear()
+    r = Ref(shape, seed=47, max_batch=1, max_ctx=512)
+    g = Gpu(shape, seed=47, max_ctx=512, max_window=8)
+    V, k = shape["vocab"], 8
+    prompt = synth.zipf_history(47, 121, V, 1.1, 0.15, 16, 16)
+    g.prefill([prompt], 8)
+    r.prefill([prompt], 8)
+    rng = np.random.default_rng(47)
+    compared, rows_decided = 0, 0
+    for step in range(6):
+        s = r.seqs[0]
+        pending = int(s.history()[-1])
+        # drafts: the oracle's own greedy continuation for the first rows, random afterwards
+        w = [pending]
+        for j in range(k - 1):
+            lg = s.verify_block(w)
+            w.append(int(lg[-1].argmax()) if j < 1 + step % 4 else int(rng.integers(0, V)))
+        w = np.array(w, np.int32)
+        ref = s.verify_block(w)
+        got = g.verify([w])[0]
+        d = got.astype(np.float64) - ref
+        rel = np.sqrt((d ** 2).mean()) / np.sqrt((ref ** 2).mean())
+        err = np.abs(d).max()
+        print("step %d: rms error / rms logits %.3g, max-abs %.3g" % (step, rel, err))
+        assert np.isfinite(got).all() and rel <= FULL_DEPTH_REL
+        n, emit, guide = g.accept(B.DBL_GREEDY)
+        n_ref, e_ref, gd_ref, margin = O.accept_greedy(ref, w)
+        err_row = np.abs(d).max(axis=1)
+        ex = margin < 2 * err_row           # rows whose top-2 gap the row's measured error could flip
+        assert np.array_equal(guide[0][~ex], gd_ref[~ex])
+        rows_decided += int((~ex).sum())
+        for j in np.nonzero(ex)[0]:         # there, any token within the error of the maximum is a valid top-1
+            assert ref[j, guide[0, j]] >= ref[j].max() - 2 * err_row[j], (step, j)
+        if not ex[:n_ref + 1].any():
+            assert n[0] == n_ref and np.array_equal(emit[0], e_ref), step
+            compared += 1
+        # teacher forcing: both sides continue from the oracle's decision
+        g.commit([n_ref + 1])
+        s.commit(n_ref + 1, e_ref[:n_ref + 1])
+        B.dbl_history_set(g.ctx, 0, s.history())
+    print("compared %d of 6 steps, %d of 48 rows decided" % (compared, rows_decided))
+    assert compared >= 1 and rows_decided >= 24
+    g.close()
