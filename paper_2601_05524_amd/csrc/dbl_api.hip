@@ -108,6 +108,9 @@ struct dbl_ctx {
   uint64_t* commits = nullptr;
   float *h = nullptr, *hg = nullptr, *ssq = nullptr;
   void* xn = nullptr;               // RMSNorm output of the current 16-row pass (windows of more than 8 rows)
+  float* sk_part = nullptr;         // gemm_rows_kernel's split units: two slots of partial sums per workgroup
+  int* sk_cnt = nullptr;            //   arrivals per unit (zero between launches)
+  int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never (DBL_STREAMK at create)
   float *qkv_part = nullptr, *logits = nullptr;
   void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
   int lm_nstat = 0;                 // workgroups of the last LM-head launch (row-statistics entries per row)
@@ -209,34 +212,74 @@ void launch_gemm_t(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
   else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL, CHUNK>), grid, block, 0, c->stream, a);
 }
 
-// gemm_rows_kernel: passes of 16*R rows, in
-// units of Q tile rows.  Larger units re-read the activations less often but leave fewer of
-// them to share out: Q is the one with the least modelled time (units per workgroup, counted
-// half as whole rounds and half as the exact ratio, times tile rows per unit, with the activation
-// traffic, R/Q of the weight traffic, at a quarter of its cost; fitted to measured launches).
-template <typename T, int EPI, int R>
-int launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
-  constexpr int NACC = EPI == EPI_SWIGLU ? 2 : 1;
-  int bestq = 0, bestg = 0; double best = 1e30;
+// gemm_rows_kernel: passes of 16*R rows, in units of Q tile rows.  Larger units re-read the
+// activations less often but leave fewer of them to share out: Q is the one with the least
+// modelled time (units per workgroup, counted half as whole rounds and half as the exact ratio,
+// times tile rows per unit, with the activation traffic, R/Q of the weight traffic, at a quarter
+// of its cost; fitted to measured launches).  Whole units per workgroup are kept where they fill
+// the chip to at least 90 %; otherwise the (unit, chunk) items are cut into equal ranges
+// (the kernel's SK form: every workgroup streams the same number of bytes, units that straddle
+// ranges are finished by their last workgroup; it ignores the plan's super slices and leaves one
+// result, see qkv_parts).
+struct RowsChoice { int q = 0, grid = 0; bool sk = false; };
+
+RowsChoice rows_choice(const dbl_ctx* c, const GemmPlan& p, int epi, int R) {
+  const int nacc = epi == EPI_SWIGLU ? 2 : 1;
+  const int kchunk = 4 * ((c->bf16 ? 8 : 4) / (R > 4 ? 2 : 1));      // k-blocks per chunk (the kernel's NWV * KS)
+  const int nch_slice = (p.KBp / p.SS + kchunk - 1) / kchunk, nch_all = (p.KBp + kchunk - 1) / kchunk;
+  RowsChoice best, best_sk; double best_cost = 1e30, best_cost_sk = 1e30;
   for (int q : {4, 2}) {
-    if (q < NACC) continue;
-    if (EPI == EPI_LMHEAD && R == 4 && q == 4) continue;   // (the row statistics of four groups leave no room for 16 accumulators)
+    if (q < nacc) continue;
+    if (epi == EPI_LMHEAD && R == 4 && q == 4) continue;   // (the row statistics of four groups leave no room for 16 accumulators)
     if (R == 8 && q != 4) continue;                         // (eight row groups: half the k-blocks per chunk, so 4 tile rows fill the ring)
-    const int units = (p.NT + q / NACC - 1) / (q / NACC) * p.SS;
+    const int nu = (p.NT + q / nacc - 1) / (q / nacc);
+    const int units = nu * p.SS;
     int g = std::min(units, std::min(c->n_cu, SSQ_PARTS));
     g = std::max(p.SS, g / p.SS * p.SS);
-    const double rounds = 0.5 * ((units + g - 1) / g) + 0.5 * (double)units / g;
-    const double cost = rounds * q * (1.0 + 0.25 * R / q);
-    if (cost < best) { best = cost; bestq = q; bestg = g; }
+    // modelled time in chunks of one workgroup, times the cost of a chunk
+    const double per_chunk = q * (1.0 + 0.25 * R / q);
+    const double cost = (0.5 * ((units + g - 1) / g) + 0.5 * (double)units / g) * nch_slice * per_chunk;
+    if (cost < best_cost) { best_cost = cost; best = RowsChoice{q, g, false}; }
+    // split units: equal ranges of items, plus what publishing and adding the parts costs.  Only where
+    // whole units leave more than a quarter of the chip without work: 160 of 256 CUs already draw 6.4 TB/s,
+    // so the gain is small (32B-shaped output + down projection 74 -> 69 us) and at better fill there is none
+    const long items = (long)nu * nch_all;
+    const bool poor_fill = (double)units / ((double)((units + g - 1) / g) * std::min(c->n_cu, SSQ_PARTS)) < 0.75;
+    // (a residual projection leaves one sum-of-squares slot per unit)
+    if (epi != EPI_LMHEAD && c->sk_part && c->sk_mode >= 0 && (poor_fill || c->sk_mode == 1) && items * SSQ_PARTS < (1L << 31) &&
+        (epi != EPI_RESIDUAL || nu <= SSQ_PARTS)) {
+      const int gs = (int)std::min<long>(items, std::min(c->n_cu, SSQ_PARTS));
+      const double cost_sk = ((double)((items + gs - 1) / gs) + 1.5) * per_chunk;
+      if (cost_sk < best_cost_sk) { best_cost_sk = cost_sk; best_sk = RowsChoice{q, gs, true}; }
+    }
   }
-  const dim3 grid(bestg), block(256);
+  if (best_sk.q && (c->sk_mode == 1 || best_cost_sk < best_cost)) return best_sk;
+  return best;
+}
+
+template <typename T, int EPI, int R>
+int launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, GemmArgs<T> a) {
+  const RowsChoice ch = rows_choice(c, p, EPI, R);
+  const dim3 grid(ch.grid), block(256);
+  a.sk_part = c->sk_part; a.sk_cnt = c->sk_cnt;
+  if constexpr (EPI != EPI_LMHEAD) {
+    if (ch.sk) {
+      if constexpr (R == 8) {
+        hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4, true>), grid, block, 0, c->stream, a);
+      } else {
+        if (ch.q == 4) hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4, true>), grid, block, 0, c->stream, a);
+        else hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 2, true>), grid, block, 0, c->stream, a);
+      }
+      return ch.grid;
+    }
+  }
   if constexpr (R == 8) {
-    hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4>), grid, block, 0, c->stream, a);
+    hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4, false>), grid, block, 0, c->stream, a);
   } else {
-    if (bestq == 4) hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4>), grid, block, 0, c->stream, a);
-    else hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 2>), grid, block, 0, c->stream, a);
+    if (ch.q == 4) hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4, false>), grid, block, 0, c->stream, a);
+    else hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 2, false>), grid, block, 0, c->stream, a);
   }
-  return bestg;
+  return ch.grid;
 }
 
 template <typename T, int R>
@@ -256,12 +299,22 @@ void launch_gemm_rows(dbl_ctx* c, const GemmPlan& p, int epi, const GemmArgs<T>&
 // and the LM head are faster through gemm_rows_kernel everywhere (70B width: 8 us per layer and
 // 45 us per step; 1B width: 4 us per layer), output and down projection where their tile pairs
 // fill the chip (70B width 3 + 4 us, 32B width 2 + 10 us; at the 1B width, 64 units for 256
-// CUs, slower by 3 + 5 us), the q/k/v projection nowhere (it would need a stored RMSNorm
-// output of its own).
+// CUs, slower by 3 + 5 us), the q/k/v projection nowhere (it needs a stored RMSNorm output of its
+// own: 70B width 35.3 us with whole units, 32.8 us with split units, against 30.4 us).
 static bool rows_kernel_for(const dbl_ctx* c, const GemmPlan& p, int epi, int M) {
   if (M > 8 || epi == EPI_SWIGLU || epi == EPI_LMHEAD) return true;
   if (epi == EPI_RESIDUAL) return p.NT >= c->n_cu;
   return false;
+}
+
+// Row groups of a pass of mrows rows.
+static int pass_groups(int mrows) { return mrows > 64 ? 8 : mrows > 32 ? 4 : mrows > 16 ? 2 : 1; }
+
+// Partial results the q/k/v projection of an M-row window leaves for its readers to add: one per
+// super slice of its plan, except that gemm_rows_kernel's SK form leaves a single, complete one.
+static int qkv_parts(const dbl_ctx* c, int M) {
+  if (rows_kernel_for(c, c->p_qkv, EPI_PARTIAL, M) && rows_choice(c, c->p_qkv, EPI_PARTIAL, pass_groups(std::min(M, 128))).sk) return 1;
+  return c->p_qkv.SS;
 }
 
 template <typename T>
@@ -279,7 +332,9 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
     for (int m0 = 0; m0 < M; m0 += pass) {
       a.m0 = m0; a.mrows = std::min(pass, M - m0);
       if (epi != EPI_RESIDUAL) {     // the RMSNorm output is stored first and read like any activation
-        hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, a.d, a.eps);
+        // (a row's columns over several workgroups while the rows alone would leave most of the chip idle)
+        const int nsl = std::max(1, std::min((c->ldh + 1023) / 1024, 64 / a.mrows));
+        hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows * nsl), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, nsl, a.d, a.eps);
         a.X = xn;
       }
       if (a.mrows > 64) launch_gemm_rows<T, 8>(c, p, epi, a);
@@ -319,7 +374,7 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
   s.qkv.HG = c->hg; s.qkv.ldx = c->ldh;
   s.qkv.out = c->qkv_part; s.qkv.ldo = c->p_qkv.ldo();
   QkvSrc src{};
-  src.qkv = c->qkv_part; src.nparts = c->p_qkv.SS; src.Mtot = M; src.ldq = c->p_qkv.ldo();
+  src.qkv = c->qkv_part; src.nparts = qkv_parts(c, M); src.Mtot = M; src.ldq = c->p_qkv.ldo();
   src.gq = g.qk_norm ? c->gq + (size_t)l * hd : nullptr;
   src.gk = g.qk_norm ? c->gk + (size_t)l * hd : nullptr;
   src.cosT = c->cosT; src.sinT = c->sinT; src.H = H; src.Hkv = Hkv; src.eps = g.rms_eps;
@@ -556,7 +611,7 @@ static void release_pages(dbl_ctx* c, int seq, int n_tokens) {
 
 void free_all(dbl_ctx* c) {
   void* ptrs[] = {c->w_qkv, c->w_o, c->w_gu, c->w_d, c->w_lm, c->emb, c->g1, c->g2, c->gq, c->gk, c->gf, c->cosT,
-                  c->sinT, c->kc, c->vt, c->page_table, c->kv_len, c->hist_len, c->hist, c->prompt_len, c->rej, c->rej_len, c->tier_best, c->prior, c->status, c->commits, c->h, c->hg, c->xn, c->qkv_part,
+                  c->sinT, c->kc, c->vt, c->page_table, c->kv_len, c->hist_len, c->hist, c->prompt_len, c->rej, c->rej_len, c->tier_best, c->prior, c->status, c->commits, c->h, c->hg, c->xn, c->sk_part, c->sk_cnt, c->qkv_part,
                   c->ssq, c->logits, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
                   c->n_acc_i, c->emit_i, c->win_i};
   for (void* p : ptrs) if (p) (void)hipFree(p);
@@ -584,6 +639,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
   if (!c) return DBL_ENOMEM;
   c->cfg = *cfg; c->bf16 = cfg->dtype == DBL_BF16; c->esz = c->bf16 ? 2 : 4;
   c->dry = (cfg->flags & DBL_FLAG_VALIDATE_ONLY) != 0;
+  if (const char* e = std::getenv("DBL_STREAMK")) c->sk_mode = std::atoi(e) > 0 ? 1 : -1;   // testing / tuning aid
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
   c->seed = weight_seed;
   c->kv_upper.assign(cfg->max_batch, 0); c->hist_upper.assign(cfg->max_batch, 0);
@@ -641,6 +697,13 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     const size_t M16 = (size_t)(Mmax + 15) / 16 * 16;   // the fragment-tiled activation layout holds whole groups of 16 rows
     ALLOC(xn, M16 * c->ldh * esz, true);
     ALLOC(ssq, (size_t)Mmax * SSQ_PARTS * 4, true);
+    {
+      // split units of gemm_rows_kernel: two slots per workgroup of (up to 4 tile rows) x (row groups of
+      // the largest pass) x 1 KiB, and one arrival counter per unit
+      const size_t rg = Mmax > 64 ? 8 : Mmax > 32 ? 4 : Mmax > 16 ? 2 : 1;
+      ALLOC(sk_part, (size_t)2 * SSQ_PARTS * 4 * rg * 1024, false);
+      ALLOC(sk_cnt, (size_t)std::max({c->p_qkv.NT, c->p_o.NT, c->p_gu.NT, c->p_d.NT}) * 4, true);
+    }
     ALLOC(qkv_part, (size_t)c->p_qkv.SS * Mmax * c->p_qkv.ldo() * 4, true);
     ALLOC(qbuf, (size_t)g.max_batch * g.n_kv_heads * c->qrows_pad * g.head_dim * esz, true);
     ALLOC(logits, (size_t)Mmax * c->p_lm.ldo() * 4, true);

@@ -133,8 +133,27 @@ struct GemmArgs {
   T* act;              // SWIGLU: [Mtot][ldact]
   int ldact;
   int act_tiled;       // SWIGLU in gemm_rows_kernel: act in the fragment-tiled layout (its reader is gemm_rows_kernel too)
+  float* sk_part;      // gemm_rows_kernel, split units: partial sums, two slots per workgroup
+  int* sk_cnt;         //   arrivals per unit, zero between launches
   LmArgs lm;
 };
+
+// 16 bytes to / from memory that other workgroups of the launch read / wrote: device-scope relaxed
+// atomics (two 8-byte ones), which go past the L2 of the XCD
+__device__ __forceinline__ void st_device(float* p, const f32x4& v) {
+  unsigned long long* q = reinterpret_cast<unsigned long long*>(p);
+  const unsigned long long lo = (unsigned long long)__float_as_uint(v.x) | ((unsigned long long)__float_as_uint(v.y) << 32);
+  const unsigned long long hi = (unsigned long long)__float_as_uint(v.z) | ((unsigned long long)__float_as_uint(v.w) << 32);
+  __hip_atomic_store(q, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(q + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ f32x4 ld_device(const float* p) {
+  const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
+  const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return f32x4{__uint_as_float((uint32_t)lo), __uint_as_float((uint32_t)(lo >> 32)), __uint_as_float((uint32_t)hi),
+               __uint_as_float((uint32_t)(hi >> 32))};
+}
 
 template <typename T> struct GemmCfg;
 template <> struct GemmCfg<bf16_t> { static constexpr int RING = 16; };
@@ -348,8 +367,22 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
 // (the host runs xn_kernel first for the normalising projections; the attention merge and
 // the SwiGLU epilogue below write that layout directly).  Epilogues: partial store, residual
 // add + hg + sum-of-squares partial, SwiGLU, LM head (logits + the row statistics of every row
-// group, kept per lane and merged over lane groups and waves at the end).  Units are static.
-template <typename T, int EPI, int R, int Q>
+// group, kept per lane and merged over lane groups and waves at the end).
+// Work is shared out statically, in one of two ways:
+//   * SK = false: whole units, workgroup w takes units w, w + grid, ... (K cut into SS super slices
+//     with one partial result each, if the plan has them).  Right when the units fill the chip evenly.
+//   * SK = true ("stream-K"): the (unit, chunk) items of the launch form one sequence that is cut
+//     into gridDim.x equal ranges, so every workgroup streams the same number of bytes whatever the
+//     number of units (320 tile rows over 256 CUs would otherwise cost two rounds for 1.25 rounds
+//     of work).  A unit that straddles ranges is finished by whichever of its workgroups arrives
+//     last: each stores the sum of its chunks (slot 2*wg + 1 if its part starts the unit, else
+//     2*wg) and counts itself in; the one that completes the count adds the parts in workgroup
+//     order -- a fixed order, so results do not depend on who came last -- applies the epilogue
+//     and clears the counter.  Nobody waits for anybody.  The parts travel as device-scope
+//     relaxed atomic stores and loads (they pass the per-XCD L2s), ordered against the counter
+//     by a wait for the stores' completion: a device-scope fence would write back and
+//     invalidate the whole L2 of the XCD each time, which more than doubled the kernel's time.
+template <typename T, int EPI, int R, int Q, bool SK>
 __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
   constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
   constexpr int TT = Q / NACC;                  // output tiles per unit
@@ -361,14 +394,17 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
   constexpr int PH = P > 8 ? 8 : P;             // pairs per reduction round
   static_assert(Q % NACC == 0 && NF % RING == 0 && P % PH == 0, "unit shape");
   static_assert(R <= 4 || EPI != EPI_LMHEAD, "the LM head's row statistics fit for at most four row groups");
+  static_assert(!SK || EPI != EPI_LMHEAD, "the LM head runs whole units");
+  constexpr int SLOT = P * NACC * WAVE * 4;     // floats per slot of sk_part
+  __shared__ int sk_last;
   __shared__ f32x4 red[NWV][PH][NACC][WAVE];
   __shared__ float wsq[NWV][R][16];
   __shared__ LmStat lmred[EPI == EPI_LMHEAD ? NWV : 1][R][16];
   const int wg = blockIdx.x, nwg = gridDim.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 15, g = lane >> 4;
-  const int ss = wg % a.SS, ustep = nwg / a.SS;
-  const int KBs = a.KBp / a.SS;                 // k-blocks of a super slice
+  const int ss = SK ? 0 : wg % a.SS, ustep = SK ? 1 : nwg / a.SS;
+  const int KBs = SK ? a.KBp : a.KBp / a.SS;    // k-blocks of a super slice
   const int nch = (KBs + NWV * KS - 1) / (NWV * KS);
   const int NU = (a.NT + TT - 1) / TT;
   const size_t row_elems = (size_t)a.KBp * BLOCK_ELEMS;
@@ -403,17 +439,25 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
       }
   };
 
-  int u = wg / a.SS, ch = 0;
+  // SK: items it .. it1-1 of the sequence (unit 0 chunk 0, unit 0 chunk 1, ...) are this workgroup's;
+  // ch0 = the chunk at which its part of the current unit starts
+  const int IT = NU * nch;
+  int u = wg / a.SS, ch = 0, it = 0, it1 = 0, ch0 = 0;
+  if constexpr (SK) {
+    it = (int)((long)IT * wg / nwg); it1 = (int)((long)IT * (wg + 1) / nwg);
+    u = it / nch; ch = it % nch; ch0 = ch;
+  }
+  auto more = [&]() { return SK ? it < it1 : u < NU; };
   Frag<T> ring[RING];
   {
-    const int uf = u < NU ? u : 0;
+    const int uf = more() ? u : 0, cf = more() ? ch : 0;
 #pragma unroll
-    for (int i = 0; i < RING; ++i) ring[i] = frag_load_w(wptr(uf, i / KS, 0), i % KS, lane);
+    for (int i = 0; i < RING; ++i) ring[i] = frag_load_w(wptr(uf, i / KS, cf), i % KS, lane);
   }
   Frag<T> breg[R][KS], bnext[R][KS];
-  load_b(bnext, 0);
+  load_b(bnext, ch);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): enter the loop with nothing but known loads in flight
-  take_b(breg, bnext, kval(0));
+  take_b(breg, bnext, kval(ch));
 
   f32x4 acc[Q][R];
   float sq[R];
@@ -436,9 +480,74 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
 #pragma unroll
     for (int q = 0; q < Q; ++q) acc[q][r] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  while (u < NU) {
-    const bool last = ch + 1 == nch;
-    const int un = last ? u + ustep : u, chn = last ? 0 : ch + 1;
+  // epilogue of pair p = (tile tt of unit u, row group r) with the complete sums v
+  auto epilogue = [&](int p, const f32x4 (&v)[NACC]) {
+    const int tt = p / R, r = p % R;
+    const int t = u * TT + tt, mr = 16 * r + c;
+    if (t < a.NT && mr < a.mrows) {
+      const int m = a.m0 + mr;
+      const int n = t * TILE_N + 4 * g;
+      if (EPI == EPI_PARTIAL) {
+        *reinterpret_cast<f32x4*>(a.out + ((size_t)ss * a.Mtot + m) * a.ldo + n) = v[0];
+      } else if (EPI == EPI_RESIDUAL) {
+        f32x4* hp = reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n);
+        const f32x4 hv = *hp + v[0];
+        *hp = hv;
+        *reinterpret_cast<f32x4*>(a.hg_out + (size_t)m * a.ldo + n) = hv * *reinterpret_cast<const f32x4*>(a.gain_out + n);
+        const float e = (hv.x * hv.x + hv.y * hv.y) + (hv.z * hv.z + hv.w * hv.w);
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) sq[rr] += rr == r ? e : 0.f;
+      } else if (EPI == EPI_LMHEAD) {
+        *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = v[0];
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr)
+          if (rr == r) lm_update(st[EPI == EPI_LMHEAD ? rr : 0], v[0], n, a.N, draft[rr], pb[rr], pj[rr], stepv, a.lm);
+      } else {   // EPI_SWIGLU
+        f32x4 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float gt = v[0][i], up = v[NACC - 1][i];
+          o[i] = (n + i < a.N) ? gt / (1.f + expf(-gt)) * up : 0.f;
+        }
+        st_round4(a.act_tiled ? a.act + xt_offset(m, n, a.ldact) : a.act + (size_t)m * a.ldact + n, o);
+      }
+    }
+  };
+  // SK, residual projections: the finished unit's sums of squares go to slot `unit` of the rows'
+  // partials (a unit is finished by whichever workgroup arrives last, so a slot per workgroup
+  // would make the order of the consumer's sum, and its last bit, depend on the timing)
+  auto flush_sq = [&](int unit) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      float v = sq[r];
+      v += __shfl_xor(v, 16); v += __shfl_xor(v, 32);
+      if (g == 0) wsq[wave][r][c] = v;
+      sq[r] = 0.f;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      for (int rg = g; rg < R; rg += 4) {
+        const int mr = 16 * rg + c;
+        if (mr < a.mrows) {
+          float v = wsq[0][rg][c];
+#pragma unroll
+          for (int w = 1; w < NWV; ++w) v += wsq[w][rg][c];
+          a.ssq_out[(size_t)(a.m0 + mr) * SSQ_PARTS + unit] = v;
+        }
+      }
+    }
+    __syncthreads();
+  };
+  while (more()) {
+    const bool uend = ch + 1 == nch;                            // last chunk of the unit
+    const bool last = SK ? (uend || it + 1 == it1) : uend;      // ... of this workgroup's part of it
+    int un, chn;
+    if constexpr (SK) {
+      const bool fin = it + 1 == it1;                           // (the refill loads then go on into unit 0)
+      un = fin ? 0 : (uend ? u + 1 : u); chn = (fin || uend) ? 0 : ch + 1;
+    } else {
+      un = last ? u + ustep : u; chn = last ? 0 : ch + 1;
+    }
     const int unc = un < NU ? un : 0;   // after the last unit the refill loads go on, harmlessly, into unit 0
     const T *wc[Q], *wn[Q];
 #pragma unroll
@@ -455,8 +564,12 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
       __builtin_amdgcn_sched_barrier(0x6);
     }
     take_b(breg, bnext, kval(chn));
-    if (!last) { ++ch; continue; }
-    // unit done: add the four partial sums of every pair, PH pairs per round
+    if (!last) { ++ch; if constexpr (SK) ++it; continue; }
+    // this workgroup's part of the unit is done: add the four partial sums of every pair, PH pairs
+    // per round; a whole unit goes through the epilogue, a part of one into this workgroup's slot
+    const bool whole = !SK || (ch0 == 0 && uend);
+    float* slot = nullptr;
+    if constexpr (SK) slot = a.sk_part + (size_t)(2 * wg + (ch0 == 0 ? 1 : 0)) * SLOT + lane * 4;
 #pragma unroll
     for (int h = 0; h < P / PH; ++h) {
 #pragma unroll
@@ -467,7 +580,7 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
       }
       __syncthreads();
       for (int pp = wave; pp < PH; pp += NWV) {
-        const int p = h * PH + pp, tt = p / R, r = p % R;
+        const int p = h * PH + pp;
         f32x4 v[NACC];
 #pragma unroll
         for (int s = 0; s < NACC; ++s) {
@@ -475,43 +588,58 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
 #pragma unroll
           for (int w = 1; w < NWV; ++w) v[s] += red[w][pp][s][lane];
         }
-        const int t = u * TT + tt, mr = 16 * r + c;
-        if (t < a.NT && mr < a.mrows) {
-          const int m = a.m0 + mr;
-          const int n = t * TILE_N + 4 * g;
-          if (EPI == EPI_PARTIAL) {
-            *reinterpret_cast<f32x4*>(a.out + ((size_t)ss * a.Mtot + m) * a.ldo + n) = v[0];
-          } else if (EPI == EPI_RESIDUAL) {
-            f32x4* hp = reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n);
-            const f32x4 hv = *hp + v[0];
-            *hp = hv;
-            *reinterpret_cast<f32x4*>(a.hg_out + (size_t)m * a.ldo + n) = hv * *reinterpret_cast<const f32x4*>(a.gain_out + n);
-            const float e = (hv.x * hv.x + hv.y * hv.y) + (hv.z * hv.z + hv.w * hv.w);
+        if (whole) {
+          epilogue(p, v);
+        } else {
 #pragma unroll
-            for (int rr = 0; rr < R; ++rr) sq[rr] += rr == r ? e : 0.f;
-          } else if (EPI == EPI_LMHEAD) {
-            *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = v[0];
-#pragma unroll
-            for (int rr = 0; rr < R; ++rr)
-              if (rr == r) lm_update(st[EPI == EPI_LMHEAD ? rr : 0], v[0], n, a.N, draft[rr], pb[rr], pj[rr], stepv, a.lm);
-          } else {   // EPI_SWIGLU
-            f32x4 o;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const float gt = v[0][i], up = v[NACC - 1][i];
-              o[i] = (n + i < a.N) ? gt / (1.f + expf(-gt)) * up : 0.f;
-            }
-            st_round4(a.act_tiled ? a.act + xt_offset(m, n, a.ldact) : a.act + (size_t)m * a.ldact + n, o);
-          }
+          for (int s = 0; s < NACC; ++s) st_device(slot + (p * NACC + s) * (WAVE * 4), v[s]);
         }
       }
       __syncthreads();
+    }
+    if constexpr (SK && EPI == EPI_RESIDUAL) {
+      if (whole) flush_sq(u);
+    }
+    if constexpr (SK) {
+      if (!whole) {
+        // first and last workgroup with items of unit u: those whose ranges hold its first and last item
+        const int fw = (int)((((long)u * nch + 1) * nwg - 1) / IT), lw = (int)(((long)(u + 1) * nch * nwg - 1) / IT);
+        // this workgroup's part is in device memory before it is counted: every wave waits for its stores
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (threadIdx.x == 0) {
+          const int arrived = atomicAdd(a.sk_cnt + u, 1);
+          sk_last = arrived == lw - fw;
+          if (arrived == lw - fw) atomicExch(a.sk_cnt + u, 0);   // (for the next launch)
+        }
+        __syncthreads();
+        if (sk_last) {
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+          for (int p = wave; p < P; p += NWV) {
+            f32x4 v[NACC];
+            for (int w = fw; w <= lw; ++w) {
+              // workgroup w's part starts the unit iff its range starts at or before the unit's first item
+              const int w0 = (int)((long)IT * w / nwg);
+              const float* src = a.sk_part + (size_t)(2 * w + (w0 <= u * nch ? 1 : 0)) * SLOT + lane * 4;
+#pragma unroll
+              for (int s = 0; s < NACC; ++s) {
+                const f32x4 x = ld_device(src + (p * NACC + s) * (WAVE * 4));
+                v[s] = w == fw ? x : v[s] + x;
+              }
+            }
+            epilogue(p, v);
+          }
+          if constexpr (EPI == EPI_RESIDUAL) flush_sq(u);
+        }
+      }
+      ch0 = 0; ++it;
     }
 #pragma unroll
     for (int q = 0; q < Q; ++q)
 #pragma unroll
       for (int r = 0; r < R; ++r) acc[q][r] = f32x4{0.f, 0.f, 0.f, 0.f};
-    u = un; ch = 0;
+    u = SK ? (uend ? u + 1 : u) : un; ch = 0;
   }
 
   if constexpr (EPI == EPI_LMHEAD) {
@@ -533,7 +661,12 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
     }
   }
 
-  if (EPI == EPI_RESIDUAL) {
+  if constexpr (SK && EPI == EPI_RESIDUAL) {
+    // one slot per unit was filled above; the slots beyond the units are zeroed
+    static_assert(R * 16 <= 256, "one thread per row");
+    if ((int)threadIdx.x < a.mrows)
+      for (int p = NU + wg; p < SSQ_PARTS; p += nwg) a.ssq_out[(size_t)(a.m0 + threadIdx.x) * SSQ_PARTS + p] = 0.f;
+  } else if (EPI == EPI_RESIDUAL) {
     // this workgroup's partial sum of squares per row: lane groups, then waves in order
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -557,14 +690,15 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
   }
 }
 
-// xn[row][:] = T(hg[row][:] * rsqrt(mean(h[row]^2) + eps)) for rows m0 + blockIdx.x: the
+// xn[row][:] = T(hg[row][:] * rsqrt(mean(h[row]^2) + eps)) for rows m0 + blockIdx.x / nsl: the
 // RMSNorm output as a stored tensor in the fragment-tiled layout, for gemm_rows_kernel.
-// 256 threads; thread p adds slot p of the row's sum-of-squares partials.
+// 256 threads; thread p adds slot p of the row's sum-of-squares partials; the nsl workgroups
+// of a row (each adds the partials for itself) take every nsl-th group of 1024 columns.
 template <typename T>
 __global__ void __launch_bounds__(256) xn_kernel(const float* __restrict__ hg, const float* __restrict__ ssq,
-                                                 T* __restrict__ xn, int ld, int m0, float d, float eps) {
+                                                 T* __restrict__ xn, int ld, int m0, int nsl, float d, float eps) {
   __shared__ float part[4];
-  const int row = m0 + blockIdx.x;
+  const int row = m0 + blockIdx.x / nsl, sl = blockIdx.x % nsl;
   float s = ssq[(size_t)row * SSQ_PARTS + threadIdx.x];
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
@@ -572,7 +706,7 @@ __global__ void __launch_bounds__(256) xn_kernel(const float* __restrict__ hg, c
   __syncthreads();
   const float r = rsqrtf(((part[0] + part[1]) + (part[2] + part[3])) / d + eps);
   const float* src = hg + (size_t)row * ld;
-  for (int i = 4 * threadIdx.x; i < ld; i += 4 * 256) {
+  for (int i = 4 * (threadIdx.x + 256 * sl); i < ld; i += 4 * 256 * nsl) {
     st_round4(xn + xt_offset(row, i, ld), *reinterpret_cast<const f32x4*>(src + i) * r);
   }
 }

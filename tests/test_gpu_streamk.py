@@ -1,0 +1,122 @@
+"""GPU parity of the projection kernel's split-unit form (equal ranges of (unit, chunk) items per
+workgroup, units that straddle ranges finished by their last workgroup).
+
+The library picks that form by itself only where whole units would fill the chip badly (large
+widths that are not a multiple of 256 tile rows); DBL_STREAMK=1 at context creation makes it
+the form of every projection that can take it, so that small models reach every path of it:
+units cut into one chunk per workgroup, ranges that hold whole units and parts of units, every
+epilogue, every pass size.  Bars as in the other parity tests (logits 2e-2 bf16 / 1e-4 fp32
+against the oracle), plus bit-identical results from run to run (the parts of a unit are added in
+workgroup order, whoever arrives last).
+"""
+import numpy as np
+import pytest
+
+from paper_2601_05524_amd import synth
+from tests.gpu_util import Gpu, Ref
+from tests.test_gpu_parity import SMALL_BF16, SMALL_QWEN, SMALL_F32_128, TOL, jitter_gains
+
+pytestmark = pytest.mark.gpu
+
+# (one layer: at this width two bf16 layers already put the largest of 64 x 5000 logit errors at the 2e-2 bar,
+# whatever the form of the projections)
+# gate/up: 375 tile pairs x 2 chunks = 750 items over 256 workgroups (ranges of 2-3 items: whole units
+# and parts); down: 48 units x 6 chunks; output: 48 units x 2 chunks; q/k/v 80 units x 2 chunks
+MID_BF16 = dict(n_layers=1, d_model=1536, n_q_heads=12, n_kv_heads=4, head_dim=128, d_ffn=6000, vocab=5000,
+                qk_norm=1, dtype=1, rms_eps=1e-6, rope_base=1e6)
+MID_F32 = dict(n_layers=1, d_model=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ffn=4200, vocab=1500,
+               qk_norm=0, dtype=0, rms_eps=1e-5, rope_base=1e4)
+
+
+@pytest.fixture
+def forced(monkeypatch):
+    monkeypatch.setenv("DBL_STREAMK", "1")
+
+
+def max_err(got, ref):
+    assert np.isfinite(got).all()
+    return float(np.abs(got.astype(np.float64) - ref).max())
+
+
+@pytest.mark.parametrize("shape,seed", [(SMALL_BF16, 16), (SMALL_QWEN, 17), (SMALL_F32_128, 18), (MID_BF16, 19), (MID_F32, 20)],
+                         ids=["small_bf16", "small_qwen", "f32_hd128", "mid_bf16", "mid_f32"])
+def test_split_units_forward_parity(forced, shape, seed):
+    g, r = Gpu(shape, seed=seed, max_ctx=256, max_window=16), Ref(shape, seed=seed, max_ctx=256)
+    jitter_gains(g, r, shape)
+    rng = np.random.default_rng(seed)
+    toks = rng.integers(0, shape["vocab"], 120).astype(np.int32)
+    i = 0
+    for k in [16, 1, 7, 16, 3, 16, 9, 16, 8, 12]:
+        w = toks[i:i + k]
+        err = max_err(g.verify([w])[0], r.verify([w])[0])
+        assert err <= TOL[shape["dtype"]], (k, err)
+        keep = k if k != 7 else 4
+        g.commit([keep])
+        r.seqs[0].commit(keep, [])
+        i += keep
+    assert g.kv_len()[0] == r.seqs[0].kv_len == i
+    g.close()
+
+
+@pytest.mark.parametrize("Bn,k", [(2, 16), (4, 16), (8, 16), (5, 11)], ids=["32_rows", "64_rows", "128_rows", "55_rows"])
+def test_split_units_many_row_passes(forced, Bn, k):
+    shape = MID_BF16
+    g, r = Gpu(shape, seed=31, max_batch=Bn, max_ctx=128, max_window=16), Ref(shape, seed=31, max_batch=Bn, max_ctx=128)
+    rng = np.random.default_rng(Bn * 100 + k)
+    for step in range(2):
+        ws = [rng.integers(0, shape["vocab"], k).astype(np.int32) for _ in range(Bn)]
+        err = max_err(g.verify(ws), r.verify(ws))
+        assert err <= TOL[1], (step, err)
+        keep = [int(x) for x in rng.integers(1, k + 1, Bn)]
+        g.commit(keep)
+        for b in range(Bn):
+            r.seqs[b].commit(keep[b], [])
+    g.close()
+
+
+def test_split_units_are_reproducible_and_close_to_whole_units(monkeypatch):
+    shape = MID_BF16
+    rng = np.random.default_rng(5)
+    ws = [[rng.integers(0, shape["vocab"], 16).astype(np.int32) for _ in range(2)] for _ in range(3)]
+
+    def run():
+        g = Gpu(shape, seed=41, max_batch=2, max_ctx=128, max_window=16)
+        out = []
+        for w in ws:
+            out.append(g.verify(w))
+            g.commit([16, 9])
+        g.close()
+        return np.stack(out)
+
+    monkeypatch.setenv("DBL_STREAMK", "1")
+    a, b = run(), run()
+    assert np.array_equal(a, b)
+    # the same window again and again on one context (nothing committed in between): which workgroup
+    # finishes a unit changes from launch to launch, the result must not
+    g = Gpu(shape, seed=41, max_batch=2, max_ctx=128, max_window=16)
+    first = g.verify(ws[0])
+    for _ in range(20):
+        assert np.array_equal(g.verify(ws[0]), first)
+    g.close()
+    monkeypatch.setenv("DBL_STREAMK", "0")
+    c = run()
+    # same arithmetic up to the order of fp32 additions; a value that lands on the other side of a bf16
+    # rounding boundary moves a logit by up to 1e-2 at this width, so the bar is the parity bar itself
+    diff = float(np.abs(a - c).max())
+    rms = float(np.sqrt(np.mean((a - c) ** 2)))
+    assert diff <= TOL[1] and rms <= 2e-3, (diff, rms)
+
+
+def test_split_units_are_chosen_at_the_qwen_width():
+    """Without the switch: a 5120-wide model (320 tile rows for 256 CUs) takes the split form for its
+    output and down projections by itself and still matches the oracle (one layer, 16 rows)."""
+    shape = dict(synth.CONFIGS["qwen32b"], n_layers=1, vocab=4096)
+    g, r = Gpu(shape, seed=51, max_ctx=128, max_window=16), Ref(shape, seed=51, max_ctx=128)
+    rng = np.random.default_rng(6)
+    for k in (16, 16):
+        w = rng.integers(0, shape["vocab"], k).astype(np.int32)
+        err = max_err(g.verify([w])[0], r.verify([w])[0])
+        assert err <= TOL[1], err
+        g.commit([k])
+        r.seqs[0].commit(k, [])
+    g.close()
