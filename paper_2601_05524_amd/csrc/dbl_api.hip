@@ -298,12 +298,14 @@ void launch_gemm_rows(dbl_ctx* c, const GemmPlan& p, int epi, const GemmArgs<T>&
 // At 8 rows or fewer, measured inside a running layer at three widths: the gate/up projection
 // and the LM head are faster through gemm_rows_kernel everywhere (70B width: 8 us per layer and
 // 45 us per step; 1B width: 4 us per layer), output and down projection where their tile pairs
-// fill the chip (70B width 3 + 4 us, 32B width 2 + 10 us; at the 1B width, 64 units for 256
-// CUs, slower by 3 + 5 us), the q/k/v projection nowhere (it needs a stored RMSNorm output of its
-// own: 70B width 35.3 us with whole units, 32.8 us with split units, against 30.4 us).
+// fill the chip (70B width 3 + 4 us, 32B width 2 + 10 us; at the 1B width, 64 whole units for 256
+// CUs, slower by 3 + 5 us) or where the split-unit form is the choice (1B width, down projection:
+// 2.3 us per layer faster inside a running step), the q/k/v projection nowhere (it needs a stored
+// RMSNorm output of its own: 70B width 35.3 us with whole units, 32.8 us with split units,
+// against 30.4 us).
 static bool rows_kernel_for(const dbl_ctx* c, const GemmPlan& p, int epi, int M) {
   if (M > 8 || epi == EPI_SWIGLU || epi == EPI_LMHEAD) return true;
-  if (epi == EPI_RESIDUAL) return p.NT >= c->n_cu;
+  if (epi == EPI_RESIDUAL) return p.NT >= c->n_cu || rows_choice(c, p, epi, 1).sk;
   return false;
 }
 
