@@ -110,6 +110,11 @@ typedef struct {
  * is left, nothing is enqueued then) and takes them back in dbl_reset and dbl_truncate; results do
  * not depend on the cache form.  Page hand-outs enqueue one small kernel each, so a captured
  * graph must not contain a call that crosses a page boundary for the first time.
+ *
+ * Environment read here (testing and tuning aids, results stay within the same bars):
+ * DBL_STREAMK = 1 makes the projection kernel's split-unit form the form of every projection that
+ * can take it, 0 switches it off, unset lets the library choose per launch; DBL_VERBOSE prints the
+ * projection plans to stderr.
  */
 int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream, dbl_ctx** out);
 int dbl_destroy(dbl_ctx* ctx);
