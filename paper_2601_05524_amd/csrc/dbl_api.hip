@@ -110,6 +110,7 @@ struct dbl_ctx {
   void* xn = nullptr;               // RMSNorm output of the current 16-row pass (windows of more than 8 rows)
   float* sk_part = nullptr;         // gemm_rows_kernel's split units: two slots of partial sums per workgroup
   int* sk_cnt = nullptr;            //   arrivals per unit (zero between launches)
+  int attn_nb = 2;                  // query blocks per wave of the attention where it pays; DBL_ATTN_NB at create: 1 never, 3 wherever possible
   int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never (DBL_STREAMK at create)
   float *qkv_part = nullptr, *logits = nullptr;
   void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
@@ -360,6 +361,8 @@ struct LayerSteps {
   AttnArgs<T> attn;
   CombineArgs<T> comb;
   int wpg, nqg;     // attention: waves per workgroup, workgroups per (b, kv head, split)
+  int nb;           //   query blocks per wave
+  bool deep;        //   latency form
 };
 
 template <typename T>
@@ -382,18 +385,38 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
   src.cosT = c->cosT; src.sinT = c->sinT; src.H = H; src.Hkv = Hkv; src.eps = g.rms_eps;
   // attention geometry for this window size
   const int gq = H / Hkv, nq = gq * k, qblocks = (nq + 15) / 16;
-  s.wpg = std::min(qblocks, 4);              // waves (query blocks) per workgroup
-  s.nqg = (qblocks + s.wpg - 1) / s.wpg;
   // splits: ncs over the cached tokens (none when every cache is empty) + 1 for the window rows
   int ctx_upper = 0;
   for (int b = 0; b < B; ++b) ctx_upper = std::max(ctx_upper, c->kv_upper[b]);
-  int ncs = (2 * c->n_cu + B * Hkv * s.nqg - 1) / (B * Hkv * s.nqg);
-  // at least 128 tokens per split: the partials (m, l, O) are written and read back, so
-  // finer splits cost more in traffic than they gain in parallelism
-  ncs = std::min({ncs, MAX_SPLITS - 1, (ctx_upper + 127) / 128});
-  if (const char* e = std::getenv("DBL_ATTN_SPLIT_TOKENS")) {   // tuning aid
-    const int tok = std::max(32, std::atoi(e));
-    ncs = std::min(MAX_SPLITS - 1, (ctx_upper + tok - 1) / tok);
+  int ncs = 0;
+  // nb query blocks per wave, workgroups for `slots` workgroups per CU
+  auto geometry = [&](int nb, int slots) {
+    const int nqw = (qblocks + nb - 1) / nb;
+    s.nb = nb;
+    s.wpg = std::min(nqw, 4);                // waves per workgroup
+    s.nqg = (nqw + s.wpg - 1) / s.wpg;
+    ncs = (slots * c->n_cu + B * Hkv * s.nqg - 1) / (B * Hkv * s.nqg);
+    // at least 128 tokens per split: the partials (m, l, O) are written and read back, so
+    // finer splits cost more in traffic than they gain in parallelism
+    ncs = std::min({ncs, MAX_SPLITS - 1, (ctx_upper + 127) / 128});
+    if (const char* e = std::getenv("DBL_ATTN_SPLIT_TOKENS")) {   // tuning aid
+      const int tok = std::max(32, std::atoi(e));
+      ncs = std::min(MAX_SPLITS - 1, (ctx_upper + tok - 1) / tok);
+    }
+  };
+  geometry(1, 2);
+  // bf16: four steps of K/V in flight per wave and queries built in place when every workgroup
+  // gets a CU of its own (latency form); else queries prepared once by a kernel of their own and
+  // either two steps in flight and two workgroups per CU (throughput form) or, from 8 query blocks
+  // per kv head on, two query blocks per wave on one set of K/V fragments and one workgroup per CU
+  s.deep = c->bf16 && B * Hkv * (ncs + 1) * s.nqg <= c->n_cu;
+  if (c->bf16 && ((!s.deep && qblocks >= 8 && c->attn_nb > 1) || (c->attn_nb > 2 && qblocks >= 2))) {
+    const bool was_deep = s.deep;
+    geometry(2, 1);
+    s.deep = false;
+    // (ranges of less than 1024 tokens: two workgroups per CU hide the loads of a range's start better; 32B-shaped
+    // step at 8192 tokens and 8 query blocks 14.4 against 14.8 ms)
+    if (c->attn_nb < 3 && ncs > 0 && ctx_upper / ncs < 1024) { geometry(1, 2); s.deep = was_deep; }
   }
   const int nsplit = ncs + 1;
   AttnArgs<T>& at = s.attn;
@@ -420,18 +443,11 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
 template <typename T, int HD>
 void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
   const int nblocks = B * s.attn.Hkv * s.attn.nsplit * s.nqg;
-  // bf16: four steps of K/V in flight per wave and queries built in place when every workgroup
-  // gets a CU of its own (latency form), else two steps, two workgroups per CU and queries
-  // prepared once by a kernel of their own (throughput form)
-  bool deep = false;
-  if constexpr (sizeof(T) == 2) deep = nblocks <= c->n_cu;
-  if (deep) {
+  const dim3 grid(nblocks), block(64 * s.wpg);
+  if (s.deep) {
     if constexpr (sizeof(T) == 2) {
-      if (c->paged) {
-        hipLaunchKernelGGL((attn_split_kernel<T, HD, 4, true>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
-      } else {
-        hipLaunchKernelGGL((attn_split_kernel<T, HD, 4, false>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
-      }
+      if (c->paged) hipLaunchKernelGGL((attn_split_kernel<T, HD, 4, true>), grid, block, 0, c->stream, s.attn);
+      else hipLaunchKernelGGL((attn_split_kernel<T, HD, 4, false>), grid, block, 0, c->stream, s.attn);
     }
   } else {
     if constexpr (sizeof(T) == 2) {
@@ -439,11 +455,14 @@ void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
                      s.attn.max_ctx};
       const int qwaves = (B * s.attn.Hkv * s.attn.g * s.attn.k + 15) / 16;
       hipLaunchKernelGGL((rope_q_kernel<T, HD>), dim3((qwaves + 3) / 4), dim3(256), 0, c->stream, q);
+      if (s.nb == 2) {
+        if (c->paged) hipLaunchKernelGGL((attn_split_kernel<T, HD, 2, true, 2>), grid, block, 0, c->stream, s.attn);
+        else hipLaunchKernelGGL((attn_split_kernel<T, HD, 2, false, 2>), grid, block, 0, c->stream, s.attn);
+      }
     }
-    if (c->paged) {
-      hipLaunchKernelGGL((attn_split_kernel<T, HD, 2, true>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
-    } else {
-      hipLaunchKernelGGL((attn_split_kernel<T, HD, 2, false>), dim3(nblocks), dim3(64 * s.wpg), 0, c->stream, s.attn);
+    if (s.nb == 1) {
+      if (c->paged) hipLaunchKernelGGL((attn_split_kernel<T, HD, 2, true>), grid, block, 0, c->stream, s.attn);
+      else hipLaunchKernelGGL((attn_split_kernel<T, HD, 2, false>), grid, block, 0, c->stream, s.attn);
     }
   }
   const int waves = combine_waves<T>(M, H, s.attn.Hkv);   // merge tasks, then KV-append tasks
@@ -641,6 +660,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
   if (!c) return DBL_ENOMEM;
   c->cfg = *cfg; c->bf16 = cfg->dtype == DBL_BF16; c->esz = c->bf16 ? 2 : 4;
   c->dry = (cfg->flags & DBL_FLAG_VALIDATE_ONLY) != 0;
+  if (const char* e = std::getenv("DBL_ATTN_NB")) c->attn_nb = std::atoi(e);
   if (const char* e = std::getenv("DBL_STREAMK")) c->sk_mode = std::atoi(e) > 0 ? 1 : -1;   // testing / tuning aid
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
   c->seed = weight_seed;

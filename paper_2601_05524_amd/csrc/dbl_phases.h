@@ -233,19 +233,22 @@ __device__ __forceinline__ void load_kv(KvFrags<T, HD>& f, const T* kbase, const
     f.vf[h] = frag_load_row(vbase + ((size_t)((tb >> 5) * (HD / 16) + h) * 64 + lane) * 8);
 }
 
-// task = ((b * Hkv + kvh) * nsplit + sp) * nqb + qb.  The P = kv_len[b] cached tokens are cut
-// into nsplit - 1 ranges; the last split takes the k window rows themselves, whose keys and
-// values are not in the cache yet: it builds them from the projection result (one 32-token
-// step, row j sees window rows 0..j).  With nsplit = 1 the one split does both.
-template <typename T, int HD, int PRE, bool PAGED>
-__device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
+// One wave: NB consecutive 16-row query blocks (from block qb0) of (b, kv head) = bh against split sp.
+// The P = kv_len[b] cached tokens are cut into nsplit - 1 ranges; the last split takes the k window
+// rows themselves, whose keys and values are not in the cache yet: it builds them from the
+// projection result (one 32-token step, row j sees window rows 0..j).  With nsplit = 1 the one
+// split does both.
+// NB > 1 keeps the K/V fragments of a step in registers for NB query blocks: at long contexts and
+// many query rows the kernel is bound by the bytes the four waves of a CU pull through its L1
+// (every wave 16 KiB per 32-token step, about 1000 cycles for the four), not by its arithmetic, and
+// a second block per wave halves those bytes per query row.
+template <typename T, int HD, int PRE, bool PAGED, int NB>
+__device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int bh, int sp, int qb0) {
   constexpr int KSTEPS = HD / 32, HT = HD / 16;
-  constexpr bool HALF_REGS = PRE == 2 && sizeof(T) == 2;   // see attn_split_kernel
+  constexpr bool HALF_REGS = PRE == 2 && sizeof(T) == 2 && NB == 1;   // see attn_split_kernel
+  constexpr bool QBUF = HALF_REGS || NB > 1;                          // queries prepared by rope_q_kernel
   const int lane = threadIdx.x & 63, c = lane & 15, g4 = lane >> 4;
-  int id = task;
-  const int qb = id % a.nqb; id /= a.nqb;
-  const int sp = id % a.nsplit; id /= a.nsplit;
-  const int kvh = id % a.Hkv; const int b = id / a.Hkv;
+  const int kvh = bh % a.Hkv; const int b = bh / a.Hkv;
   const int P = min(a.kv_len[b], a.max_ctx - a.k);   // (the host refuses windows that do not fit)
   const int ncs = a.nsplit - 1;                      // splits over the cached tokens; the last split is the window
   const bool win = sp == ncs;
@@ -256,64 +259,98 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
     t0 = min(P, sp * per); t1 = win ? t0 : min(P, t0 + per);
   }
   const int nq = a.g * a.k;
-  const int row = qb * 16 + c;
-  const int jrow = row < nq ? row / a.g : -1;
+  int row[NB], jrow[NB];
+#pragma unroll
+  for (int n = 0; n < NB; ++n) {
+    row[n] = (qb0 + n) * 16 + c;
+    jrow[n] = row[n] < nq ? row[n] / a.g : -1;
+  }
   const T* kbase = a.kc + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
   const T* vbase = a.vt + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
 
-  f32x4 o[HT];
+  f32x4 o[NB][HT];
+  float mrun[NB], lrun[NB];
+  Frag<T> qf[NB][KSTEPS];   // query fragments (B operand): dims ks*32 + 8*g4 .. of query row `row` = (window row, head in group)
 #pragma unroll
-  for (int h = 0; h < HT; ++h) o[h] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float mrun = -INFINITY, lrun = 0.f;
-  Frag<T> qf[KSTEPS];   // query fragments (B operand): dims ks*32 + 8*g4 .. of query row `row` = (window row, head in group)
+  for (int n = 0; n < NB; ++n) {
+    mrun[n] = -INFINITY; lrun[n] = 0.f;
+#pragma unroll
+    for (int h = 0; h < HT; ++h) o[n][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
 
-  // One 32-token step: scores, online soft-max, O^T += V^T P^T.  Token tb + i is visible to
-  // this lane's query row iff tb + i <= lim.
-  auto step = [&](const KvFrags<T, HD>& f, int tb, int lim) {
-    f32x4 s[2];
+  // One 32-token step: scores, online soft-max, O^T += V^T P^T for every block of the wave.  Token
+  // tb + i is visible to this lane's query row of block n iff tb + i <= lim[n]; `open` (the same for
+  // the whole wave) says that all 32 tokens are visible to every row, so that nothing is compared
+  // (rows beyond the last query row then work on the last row's query: finite values that nobody
+  // reads).  The running sums are rescaled only when some lane's maximum grew: for the others the
+  // factor is exactly 1.
+  auto step = [&](const KvFrags<T, HD>& f, int tb, const int (&lim)[NB], bool open) {
+    f32x4 s[NB][2];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      s[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int n = 0; n < NB; ++n)
 #pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) s[h] = mma(f.kf[h][ks], qf[ks], s[h]);
-    }
-    // lane holds scores of query row c for tokens tb + 16*h + 4*g4 + i
-    float mx = -INFINITY;
+      for (int h = 0; h < 2; ++h) {
+        s[n][h] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int tok = tb + 16 * h + 4 * g4 + i;
-        const float v = tok <= lim ? s[h][i] * a.scale : -INFINITY;
-        s[h][i] = v; mx = fmaxf(mx, v);
+        for (int ks = 0; ks < KSTEPS; ++ks) s[n][h] = mma(f.kf[h][ks], qf[n][ks], s[n][h]);
       }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float mnew = fmaxf(mrun, mx);
-    float alpha = 1.f, psum = 0.f;
-    if (mnew > -INFINITY) {
-      alpha = fast_exp2(mrun - mnew);   // 2^(-inf) = 0 on the first visible step
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
+    for (int n = 0; n < NB; ++n) {
+      // lane holds scores of query row c for tokens tb + 16*h + 4*g4 + i
+      float mx = -INFINITY;
+      if (open) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { const float p = fast_exp2(s[h][i] - mnew); s[h][i] = p; psum += p; }
-    } else {
-      s[0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[1] = s[0];
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { const float v = s[n][h][i] * a.scale; s[n][h][i] = v; mx = fmaxf(mx, v); }
+      } else {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int tok = tb + 16 * h + 4 * g4 + i;
+            const float v = tok <= lim[n] ? s[n][h][i] * a.scale : -INFINITY;
+            s[n][h][i] = v; mx = fmaxf(mx, v);
+          }
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float mnew = fmaxf(mrun[n], mx);
+      float psum = 0.f;
+      if (mnew > -INFINITY) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { const float p = fast_exp2(s[n][h][i] - mnew); s[n][h][i] = p; psum += p; }
+      } else {
+        s[n][0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[n][1] = s[n][0];
+      }
+      if (__builtin_amdgcn_ballot_w64(mnew > mrun[n]) != 0) {
+        const float alpha = mnew > mrun[n] ? fast_exp2(mrun[n] - mnew) : 1.f;   // 2^(-inf) = 0 on the first visible step
+        lrun[n] *= alpha;               // per-lane share; lane groups are summed at the end
+#pragma unroll
+        for (int h = 0; h < HT; ++h) o[n][h] = o[n][h] * alpha;
+      }
+      mrun[n] = mnew;
+      lrun[n] += psum;
+      pv_accumulate<HT>(o[n], f.vf, s[n][0], s[n][1]);
     }
-    mrun = mnew;
-    lrun = lrun * alpha + psum;       // per-lane share; lane groups are summed at the end
-#pragma unroll
-    for (int h = 0; h < HT; ++h) o[h] = o[h] * alpha;
-    pv_accumulate<HT>(o, f.vf, s[0], s[1]);
   };
 
-  const int qr = min(row, nq - 1), qj = qr / a.g, qm = b * a.k + qj, qcol = (kvh * a.g + qr % a.g) * HD;
+  int qr[NB], qj[NB], qm[NB], qcol[NB];
+#pragma unroll
+  for (int n = 0; n < NB; ++n) {
+    qr[n] = min(row[n], nq - 1); qj[n] = qr[n] / a.g; qm[n] = b * a.k + qj[n]; qcol[n] = (kvh * a.g + qr[n] % a.g) * HD;
+  }
   // throughput form: a wave handles many steps and a (b, kv head, query block) has many splits,
   // so the queries are prepared once by rope_q_kernel instead of by every wave
   auto load_q = [&]() {
-    const T* qp = a.qbuf + ((size_t)(b * a.Hkv + kvh) * a.qrows_pad + qr) * HD + g4 * 8;
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) qf[ks] = frag_load_row(qp + ks * 32);
+    for (int n = 0; n < NB; ++n) {
+      const T* qp = a.qbuf + ((size_t)(b * a.Hkv + kvh) * a.qrows_pad + qr[n]) * HD + g4 * 8;
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) qf[n][ks] = frag_load_row(qp + ks * 32);
+    }
   };
   const int kcol = (a.src.H + kvh) * HD, vcol = (a.src.H + a.src.Hkv + kvh) * HD;
   const size_t pstride = (size_t)a.src.Mtot * a.src.ldq;
@@ -357,21 +394,25 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
         if (r0 + 4 * g4 + e >= a.k) x[e] = 0.f;
       fw.vf[h] = frag_round(x, T());
     }
-    step(fw, r0, min(jrow, r0 + 15));
+    int lim[NB];
+#pragma unroll
+    for (int n = 0; n < NB; ++n) lim[n] = min(jrow[n], r0 + 15);
+    step(fw, r0, lim, false);
   };
 
   if (win && ncs > 0) {
     // the window split proper: query and window rows arrive in one round trip (two in the
     // throughput form, whose registers do not hold all of it at once)
     WinRaw w;
-    if constexpr (!HALF_REGS) {
+    if constexpr (!QBUF) {
       HeadRaw<HD> qraw;
-      head_load<HD>(a.src, qm, qcol, P + qj, g4, qraw);
+      head_load<HD>(a.src, qm[0], qcol[0], P + qj[0], g4, qraw);
       win_load_k(w, 0); win_load_v(w, 0);
-      head_finish<T, HD>(a.src, qraw, qm, qcol, a.src.gq, g4, qf);
+      head_finish<T, HD>(a.src, qraw, qm[0], qcol[0], a.src.gq, g4, qf[0]);
     } else {
       load_q();
       win_load_k(w, 0);
+      if constexpr (!HALF_REGS) win_load_v(w, 0);
     }
     KvFrags<T, HD> fw;
     win_step(w, fw, 0);
@@ -390,32 +431,47 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
     // Steps beyond the range re-read its first step (a valid address) and are skipped.
     KvFrags<T, HD> f[PRE];
     // (paged cache: a 32-token step lies inside one page; the page of every step is looked up)
-    auto load_group = [&](int tg, int fallback) {
+    auto load_group = [&](KvFrags<T, HD> (&fb)[PRE], int tg, int fallback) {
 #pragma unroll
       for (int u = 0; u < PRE; ++u) {
         const int tb = tg + 32 * u < t1 ? tg + 32 * u : fallback;
         if constexpr (PAGED) {
           const size_t po = ((size_t)a.page_table[b * a.pps + tb / KV_PAGE] * a.Hkv + kvh) * KV_PAGE * HD;
-          load_kv<T, HD>(f[u], a.kc + po, a.vt + po, tb % KV_PAGE, lane);
+          load_kv<T, HD>(fb[u], a.kc + po, a.vt + po, tb % KV_PAGE, lane);
         } else {
-          load_kv<T, HD>(f[u], kbase, vbase, tb, lane);
+          load_kv<T, HD>(fb[u], kbase, vbase, tb, lane);
         }
       }
     };
-    const int lim_c = jrow < 0 ? -1 : t1 - 1;          // every cached token is visible to every window row
-    auto run_group = [&](int tg) {
+    int lim_c[NB];                                       // every cached token is visible to every window row
+#pragma unroll
+    for (int n = 0; n < NB; ++n) lim_c[n] = jrow[n] < 0 ? -1 : t1 - 1;
+    auto run_group = [&](const KvFrags<T, HD> (&fb)[PRE], int tg) {
 #pragma unroll
       for (int u = 0; u < PRE; ++u)
-        if (tg + 32 * u < t1) step(f[u], tg + 32 * u, lim_c);
+        if (tg + 32 * u < t1) step(fb[u], tg + 32 * u, lim_c, tg + 32 * u + 32 <= t1);
     };
-    if constexpr (!HALF_REGS) {
+    if constexpr (!QBUF) {
       // latency form (a group or two per wave): the first group is requested before the query
-      load_group(t0, t0 < t1 ? t0 : 0);
-      rope_head<T, HD>(a.src, qm, qcol, a.src.gq, P + qj, g4, qf);
+      load_group(f, t0, t0 < t1 ? t0 : 0);
+      rope_head<T, HD>(a.src, qm[0], qcol[0], a.src.gq, P + qj[0], g4, qf[0]);
       for (int tg = t0; tg < t1;) {
-        run_group(tg);
+        run_group(f, tg);
         tg += 32 * PRE;
-        if (tg < t1) load_group(tg, t0);
+        if (tg < t1) load_group(f, tg, t0);
+      }
+    } else if constexpr (NB > 1) {
+      // several blocks per wave, one wave per SIMD, nobody else to hide the loads behind: two sets of
+      // fragments, the next group requested (unconditionally: beyond the range it re-reads the
+      // range's first step) before the current one is worked on
+      KvFrags<T, HD> f2[PRE];
+      load_q();
+      load_group(f, t0, t0 < t1 ? t0 : 0);
+      for (int tg = t0; tg < t1; tg += 64 * PRE) {
+        load_group(f2, tg + 32 * PRE, t0 < t1 ? t0 : 0);
+        run_group(f, tg);
+        load_group(f, tg + 64 * PRE, t0 < t1 ? t0 : 0);
+        run_group(f2, tg + 32 * PRE);
       }
     } else {
       // throughput form (many groups per wave, two waves per SIMD): loads unconditional and
@@ -423,8 +479,8 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
       // runs while the fragments of step u+1 are still arriving
       load_q();
       for (int tg = t0; tg < t1; tg += 32 * PRE) {
-        load_group(tg, t0);
-        run_group(tg);
+        load_group(f, tg, t0);
+        run_group(f, tg);
       }
     }
     if (win) {   // a single split does everything (empty or very short caches)
@@ -436,33 +492,39 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int task) {
       }
     }
   }
-  // write the partial
-  float l = lrun;
-  l += __shfl_xor(l, 16); l += __shfl_xor(l, 32);
-  const size_t pidx = ((size_t)(b * a.Hkv + kvh) * a.nsplit + sp) * a.qrows_pad + row;
-  if (g4 == 0) { a.pm[pidx] = mrun; a.pl[pidx] = l; }
+  // write the partials (blocks beyond the last one fall inside the padded rows and are never read)
 #pragma unroll
-  for (int h = 0; h < HT; ++h) *reinterpret_cast<f32x4*>(a.po + pidx * HD + h * 16 + 4 * g4) = o[h];
+  for (int n = 0; n < NB; ++n) {
+    float l = lrun[n];
+    l += __shfl_xor(l, 16); l += __shfl_xor(l, 32);
+    const size_t pidx = ((size_t)(b * a.Hkv + kvh) * a.nsplit + sp) * a.qrows_pad + row[n];
+    if (row[n] < a.qrows_pad) {
+      if (g4 == 0) { a.pm[pidx] = mrun[n]; a.pl[pidx] = l; }
+#pragma unroll
+      for (int h = 0; h < HT; ++h) *reinterpret_cast<f32x4*>(a.po + pidx * HD + h * 16 + 4 * g4) = o[n][h];
+    }
+  }
 }
 
-// grid = B * Hkv * nsplit * ceil(nqb / wpg) workgroups of wpg waves; the waves of a
-// workgroup own consecutive query blocks of the same K/V range, so those reads are
-// shared through the CU's L1.  The workgroups of the cached ranges come first, the (short)
-// window splits last: when the grid is larger than the chip holds at once, the ones that
-// wait for a free slot are short.
-// (PRE = 2 in bf16 is the form for more workgroups than CUs: held to two waves per SIMD.)
-template <typename T, int HD, int PRE, bool PAGED>
-__global__ void __launch_bounds__(256, (PRE == 2 && sizeof(T) == 2) ? 2 : 1) attn_split_kernel(const AttnArgs<T> a) {
+// grid = B * Hkv * nsplit * ceil(nqw / wpg) workgroups of wpg waves, nqw = ceil(nqb / NB) waves'
+// worth of query blocks; the waves of a workgroup own consecutive query blocks of the same K/V
+// range, so those reads are shared through the CU's L1.  The workgroups of the cached ranges come
+// first, the (short) window splits last: when the grid is larger than the chip holds at once, the
+// ones that wait for a free slot are short.
+// (PRE = 2 with one block per wave in bf16 is the form for more workgroups than CUs: held to two waves per SIMD.)
+template <typename T, int HD, int PRE, bool PAGED, int NB = 1>
+__global__ void __launch_bounds__(256, (PRE == 2 && sizeof(T) == 2 && NB == 1) ? 2 : 1) attn_split_kernel(const AttnArgs<T> a) {
   const int wpg = blockDim.x >> 6;
-  const int nqg = (a.nqb + wpg - 1) / wpg;
+  const int nqw = (a.nqb + NB - 1) / NB;
+  const int nqg = (nqw + wpg - 1) / wpg;
   const int ncs = a.nsplit - 1;
   const int ncache = (int)(gridDim.x / a.nsplit) * ncs;   // gridDim.x = (B * Hkv * nqg) * nsplit
   int blk = blockIdx.x, sp, bh, qg;
   if (blk < ncache) { qg = blk % nqg; sp = (blk / nqg) % ncs; bh = blk / (nqg * ncs); }
   else { blk -= ncache; qg = blk % nqg; sp = ncs; bh = blk / nqg; }
-  const int qb = qg * wpg + (threadIdx.x >> 6);
-  if (qb >= a.nqb) return;
-  attn_task<T, HD, PRE, PAGED>(a, (bh * a.nsplit + sp) * a.nqb + qb);
+  const int qw = qg * wpg + (threadIdx.x >> 6);
+  if (qw >= nqw) return;
+  attn_task<T, HD, PRE, PAGED, NB>(a, bh, sp, qw * NB);
 }
 
 // Queries for the throughput form of the attention: wave w handles 16 query rows of the
