@@ -407,12 +407,13 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
   geometry(1, 2);
   // bf16: four steps of K/V in flight per wave and queries built in place when every workgroup
   // gets a CU of its own (latency form); else queries prepared once by a kernel of their own and
-  // either two steps in flight and two workgroups per CU (throughput form) or, from 8 query blocks
-  // per kv head on, two query blocks per wave on one set of K/V fragments and one workgroup per CU
+  // either two steps in flight and two workgroups per CU (throughput form) or, from 4 query blocks
+  // per kv head on, two query blocks per wave on one set of K/V fragments and one wave per SIMD
   s.deep = c->bf16 && B * Hkv * (ncs + 1) * s.nqg <= c->n_cu;
-  if (c->bf16 && ((!s.deep && qblocks >= 8 && c->attn_nb > 1) || (c->attn_nb > 2 && qblocks >= 2))) {
+  if (c->bf16 && ((!s.deep && qblocks >= 4 && c->attn_nb > 1) || (c->attn_nb > 2 && qblocks >= 2))) {
     const bool was_deep = s.deep;
-    geometry(2, 1);
+    // (one wave per SIMD: workgroups of fewer than four waves share a CU)
+    geometry(2, 4 / std::min((qblocks + 1) / 2, 4));
     s.deep = false;
     // (ranges of less than 1024 tokens: two workgroups per CU hide the loads of a range's start better; 32B-shaped
     // step at 8192 tokens and 8 query blocks 14.4 against 14.8 ms)
