@@ -110,7 +110,9 @@ struct dbl_ctx {
   void* xn = nullptr;               // RMSNorm output of the current 16-row pass (windows of more than 8 rows)
   float* sk_part = nullptr;         // gemm_rows_kernel's split units: two slots of partial sums per workgroup
   int* sk_cnt = nullptr;            //   arrivals per unit (zero between launches)
+  int attn_lds = 1;                 // attention's shared (LDS-staged) form: 1 where it pays, 0 never, 2 wherever a kv head has two query blocks and a cached split exists (DBL_ATTN_LDS at create)
   int attn_nb = 2;                  // query blocks per wave of the attention where it pays; DBL_ATTN_NB at create: 1 never, 3 wherever possible
+  int rows_q = 4;                   // units of 8 tile rows in passes of more than 32 rows: 0 where the model says they pay; 8 wherever possible; 4 never (DBL_ROWS_Q at create)
   int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never (DBL_STREAMK at create)
   float *qkv_part = nullptr, *logits = nullptr;
   void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
@@ -226,19 +228,22 @@ struct RowsChoice { int q = 0, grid = 0; bool sk = false; };
 
 RowsChoice rows_choice(const dbl_ctx* c, const GemmPlan& p, int epi, int R) {
   const int nacc = epi == EPI_SWIGLU ? 2 : 1;
-  const int kchunk = 4 * ((c->bf16 ? 8 : 4) / (R > 4 ? 2 : 1));      // k-blocks per chunk (the kernel's NWV * KS)
-  const int nch_slice = (p.KBp / p.SS + kchunk - 1) / kchunk, nch_all = (p.KBp + kchunk - 1) / kchunk;
   RowsChoice best, best_sk; double best_cost = 1e30, best_cost_sk = 1e30;
-  for (int q : {4, 2}) {
+  const bool can8 = R >= 4 && epi != EPI_LMHEAD && c->rows_q != 4;   // units of 8 tile rows: passes of more than 32 rows
+  for (int q : {8, 4, 2}) {
     if (q < nacc) continue;
+    if (q == 8 ? !can8 : (can8 && c->rows_q == 8)) continue;
+    const int ks = rows_ks(c->bf16, R, q);
+    const int kchunk = 4 * ks;                                        // k-blocks per chunk (the kernel's NWV * KS)
+    const int nch_slice = (p.KBp / p.SS + kchunk - 1) / kchunk, nch_all = (p.KBp + kchunk - 1) / kchunk;
     if (epi == EPI_LMHEAD && R == 4 && q == 4) continue;   // (the row statistics of four groups leave no room for 16 accumulators)
-    if (R == 8 && q != 4) continue;                         // (eight row groups: half the k-blocks per chunk, so 4 tile rows fill the ring)
+    if (R == 8 && q < 4) continue;                          // (eight row groups: half the k-blocks per chunk, so 4 tile rows fill the ring)
     const int nu = (p.NT + q / nacc - 1) / (q / nacc);
     const int units = nu * p.SS;
     int g = std::min(units, std::min(c->n_cu, SSQ_PARTS));
     g = std::max(p.SS, g / p.SS * p.SS);
     // modelled time in chunks of one workgroup, times the cost of a chunk
-    const double per_chunk = q * (1.0 + 0.25 * R / q);
+    const double per_chunk = ks / 8.0 * q * (1.0 + 0.25 * R / q);
     const double cost = (0.5 * ((units + g - 1) / g) + 0.5 * (double)units / g) * nch_slice * per_chunk;
     if (cost < best_cost) { best_cost = cost; best = RowsChoice{q, g, false}; }
     // split units: equal ranges of items, plus what publishing and adding the parts costs.  Only where
@@ -265,6 +270,9 @@ int launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, GemmArgs<T> a) {
   a.sk_part = c->sk_part; a.sk_cnt = c->sk_cnt;
   if constexpr (EPI != EPI_LMHEAD) {
     if (ch.sk) {
+      if constexpr (R >= 4) {
+        if (ch.q == 8) { hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 8, true>), grid, block, 0, c->stream, a); return ch.grid; }
+      }
       if constexpr (R == 8) {
         hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4, true>), grid, block, 0, c->stream, a);
       } else {
@@ -272,6 +280,9 @@ int launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, GemmArgs<T> a) {
         else hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 2, true>), grid, block, 0, c->stream, a);
       }
       return ch.grid;
+    }
+    if constexpr (R >= 4) {
+      if (ch.q == 8) { hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 8, false>), grid, block, 0, c->stream, a); return ch.grid; }
     }
   }
   if constexpr (R == 8) {
@@ -363,6 +374,7 @@ struct LayerSteps {
   int wpg, nqg;     // attention: waves per workgroup, workgroups per (b, kv head, split)
   int nb;           //   query blocks per wave
   bool deep;        //   latency form
+  bool shared;      //   shared form: the workgroup's waves walk one token range together, K/V staged through LDS
 };
 
 template <typename T>
@@ -419,6 +431,22 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
     // step at 8192 tokens and 8 query blocks 14.4 against 14.8 ms)
     if (c->attn_nb < 3 && ncs > 0 && ctx_upper / ncs < 1024) { geometry(1, 2); s.deep = was_deep; }
   }
+  // shared form (bf16): 4 or more query blocks per kv head, more workgroups than CUs in the forms above and at
+  // least 512 cached tokens per split.  Two blocks per wave, 2 / 4 / 8 waves per workgroup, 8 waves per CU.
+  s.shared = false;
+  if (c->bf16 && ((c->attn_lds == 1 && !s.deep && qblocks >= 4) || (c->attn_lds > 1 && qblocks >= 2)) && ctx_upper > 0) {
+    const int nb = c->attn_lds > 2 ? 1 : 2, nqw = (qblocks + nb - 1) / nb;
+    const int nw = nqw >= 8 ? 8 : nqw >= 4 ? 4 : 2, nqg = (nqw + nw - 1) / nw;
+    int n = ((8 / nw) * c->n_cu + B * Hkv * nqg - 1) / (B * Hkv * nqg);
+    n = std::min({n, MAX_SPLITS - 1, (ctx_upper + 127) / 128});
+    if (const char* e = std::getenv("DBL_ATTN_SPLIT_TOKENS")) {   // tuning aid
+      const int tok = std::max(32, std::atoi(e));
+      n = std::min(MAX_SPLITS - 1, (ctx_upper + tok - 1) / tok);
+    }
+    if (n >= 1 && (c->attn_lds > 1 || ctx_upper / n >= 512)) {
+      s.shared = true; s.deep = false; s.nb = nb; s.wpg = nw; s.nqg = nqg; ncs = n;
+    }
+  }
   const int nsplit = ncs + 1;
   AttnArgs<T>& at = s.attn;
   at.page_table = c->page_table; at.pps = c->pps;
@@ -443,9 +471,24 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
 
 template <typename T, int HD>
 void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
-  const int nblocks = B * s.attn.Hkv * s.attn.nsplit * s.nqg;
+  // (shared form: nb workgroups per group for the window split, one query block per wave)
+  const int nblocks = B * s.attn.Hkv * (s.attn.nsplit - 1 + (s.shared ? s.nb : 1)) * s.nqg;
   const dim3 grid(nblocks), block(64 * s.wpg);
-  if (s.deep) {
+  if (s.shared) {
+    if constexpr (sizeof(T) == 2) {
+      RopeQArgs<T> q{s.attn.src, s.attn.kv_len, reinterpret_cast<T*>(c->qbuf), B, s.attn.k, s.attn.g, s.attn.qrows_pad,
+                     s.attn.max_ctx};
+      const int qwaves = (B * s.attn.Hkv * s.attn.g * s.attn.k + 15) / 16;
+      hipLaunchKernelGGL((rope_q_kernel<T, HD>), dim3((qwaves + 3) / 4), dim3(256), 0, c->stream, q);
+#define DBL_SHARED(NB_, NW_)                                                                                       \
+      if (s.nb == NB_ && s.wpg == NW_) {                                                                           \
+        if (c->paged) hipLaunchKernelGGL((attn_shared_kernel<T, HD, true, NB_, NW_>), grid, block, 0, c->stream, s.attn); \
+        else hipLaunchKernelGGL((attn_shared_kernel<T, HD, false, NB_, NW_>), grid, block, 0, c->stream, s.attn);  \
+      }
+      DBL_SHARED(2, 2) DBL_SHARED(2, 4) DBL_SHARED(2, 8) DBL_SHARED(1, 2) DBL_SHARED(1, 4) DBL_SHARED(1, 8)
+#undef DBL_SHARED
+    }
+  } else if (s.deep) {
     if constexpr (sizeof(T) == 2) {
       if (c->paged) hipLaunchKernelGGL((attn_split_kernel<T, HD, 4, true>), grid, block, 0, c->stream, s.attn);
       else hipLaunchKernelGGL((attn_split_kernel<T, HD, 4, false>), grid, block, 0, c->stream, s.attn);
@@ -661,7 +704,9 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
   if (!c) return DBL_ENOMEM;
   c->cfg = *cfg; c->bf16 = cfg->dtype == DBL_BF16; c->esz = c->bf16 ? 2 : 4;
   c->dry = (cfg->flags & DBL_FLAG_VALIDATE_ONLY) != 0;
+  if (const char* e = std::getenv("DBL_ATTN_LDS")) c->attn_lds = std::atoi(e);
   if (const char* e = std::getenv("DBL_ATTN_NB")) c->attn_nb = std::atoi(e);
+  if (const char* e = std::getenv("DBL_ROWS_Q")) c->rows_q = std::atoi(e);
   if (const char* e = std::getenv("DBL_STREAMK")) c->sk_mode = std::atoi(e) > 0 ? 1 : -1;   // testing / tuning aid
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
   c->seed = weight_seed;
@@ -721,10 +766,10 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(xn, M16 * c->ldh * esz, true);
     ALLOC(ssq, (size_t)Mmax * SSQ_PARTS * 4, true);
     {
-      // split units of gemm_rows_kernel: two slots per workgroup of (up to 4 tile rows) x (row groups of
+      // split units of gemm_rows_kernel: two slots per workgroup of (up to 8 tile rows) x (row groups of
       // the largest pass) x 1 KiB, and one arrival counter per unit
       const size_t rg = Mmax > 64 ? 8 : Mmax > 32 ? 4 : Mmax > 16 ? 2 : 1;
-      ALLOC(sk_part, (size_t)2 * SSQ_PARTS * 4 * rg * 1024, false);
+      ALLOC(sk_part, (size_t)2 * SSQ_PARTS * 8 * rg * 1024, false);
       ALLOC(sk_cnt, (size_t)std::max({c->p_qkv.NT, c->p_o.NT, c->p_gu.NT, c->p_d.NT}) * 4, true);
     }
     ALLOC(qkv_part, (size_t)c->p_qkv.SS * Mmax * c->p_qkv.ldo() * 4, true);

@@ -242,7 +242,8 @@ __device__ __forceinline__ void load_kv(KvFrags<T, HD>& f, const T* kbase, const
 // many query rows the kernel is bound by the bytes the four waves of a CU pull through its L1
 // (every wave 16 KiB per 32-token step, about 1000 cycles for the four), not by its arithmetic, and
 // a second block per wave halves those bytes per query row.
-template <typename T, int HD, int PRE, bool PAGED, int NB>
+// WIN_ONLY: the caller's splits over cached tokens are handled elsewhere (attn_shared_kernel); only the window split is compiled.
+template <typename T, int HD, int PRE, bool PAGED, int NB, bool WIN_ONLY = false>
 __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int bh, int sp, int qb0) {
   constexpr int KSTEPS = HD / 32, HT = HD / 16;
   constexpr bool HALF_REGS = PRE == 2 && sizeof(T) == 2 && NB == 1;   // see attn_split_kernel
@@ -421,7 +422,7 @@ __device__ __forceinline__ void attn_task(const AttnArgs<T>& a, int bh, int sp, 
       if constexpr (!HALF_REGS) win_load_v(w, 16);
       win_step(w, fw, 16);
     }
-  } else {
+  } else if constexpr (!WIN_ONLY) {
     // The K/V of PRE steps are requested together, before any of them is used: a step
     // computes in a fraction of a memory round trip, so fetching only one step ahead costs one
     // round trip per step.  PRE = 4 (128 tokens) needs the CU's registers for one workgroup:
@@ -525,6 +526,182 @@ __global__ void __launch_bounds__(256, (PRE == 2 && sizeof(T) == 2 && NB == 1) ?
   const int qw = qg * wpg + (threadIdx.x >> 6);
   if (qw >= nqw) return;
   attn_task<T, HD, PRE, PAGED, NB>(a, bh, sp, qw * NB);
+}
+
+// Shared form of the split-KV attention (bf16), for many query rows over long cached ranges.  The NW
+// waves of a workgroup own NB consecutive 16-row query blocks each and walk the SAME token range in
+// step: every 32-token step of K and V^T (FR fragments of 1 KiB, contiguous in the cache's tiled
+// order) is fetched from memory once per workgroup, FR / NW fragments per wave, DEPTH steps ahead
+// into registers, passed through one of two LDS buffers (one barrier per step: a buffer is written
+// again only after the barrier that follows its last readers' next step), and read from there by
+// every wave as the MFMA operands of its own blocks.  Against attn_split_kernel's forms, where
+// each wave pulls the whole range through the CU's L1 for itself, the bytes through L1 fall by NW,
+// a wave needs registers for one step of operands only, so two waves per SIMD fit (one's soft-max
+// arithmetic runs under the other's MFMAs), and little register space buys a deep prefetch.
+// Splits and partials are attn_split_kernel's; the window split (last in the grid) runs attn_task's
+// window path, one query block per wave.  Queries come from rope_q_kernel.  The host picks this form only with at least
+// one split over cached tokens.
+template <typename T, int HD, bool PAGED, int NB, int NW>
+__global__ void __launch_bounds__(64 * NW, 2) attn_shared_kernel(const AttnArgs<T> a) {
+  static_assert(sizeof(T) == 2, "bf16 caches only");
+  constexpr int KSTEPS = HD / 32, HT = HD / 16, FR = 2 * KSTEPS + HT;
+  constexpr int FPW = FR / NW;                          // fragments a wave fetches per step
+  constexpr int DEPTH = NW == 2 ? 2 : NW == 4 ? 3 : 4;  // steps in flight per wave
+  static_assert(FR % NW == 0, "the fragments of a step are shared out evenly");
+  __shared__ u32x4 stage[2][FR][WAVE];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 15, g4 = lane >> 4;
+  const int nqw = (a.nqb + NB - 1) / NB, nqg = (nqw + NW - 1) / NW, ncs = a.nsplit - 1;
+  // gridDim.x = (B * Hkv * nqg) * (ncs + NB): the workgroups of the cached ranges, then, for the window rows
+  // themselves, NB workgroups per group whose waves take one query block each (no barriers on that path)
+  const int ncache = (int)(gridDim.x / (ncs + NB)) * ncs;
+  int blk = blockIdx.x;
+  if (blk >= ncache) {
+    blk -= ncache;
+    const int qb = (blk % (nqg * NB)) * NW + wave;
+    if (qb < a.nqb) attn_task<T, HD, 2, PAGED, 1, true>(a, blk / (nqg * NB), ncs, qb);
+    return;
+  }
+  const int qg = blk % nqg, sp = (blk / nqg) % ncs, bh = blk / (nqg * ncs);
+  const int qw = qg * NW + wave;
+  // waves beyond the last query block fetch their share of K/V like the others; their results are dropped
+  const int kvh = bh % a.Hkv, b = bh / a.Hkv;
+  const int P = min(a.kv_len[b], a.max_ctx - a.k);
+  int per = (P + ncs - 1) / ncs;
+  per = (per + 31) & ~31;
+  const int t0 = min(P, sp * per), t1 = min(P, t0 + per);
+  const int tfirst = t0 < t1 ? t0 : 0;                  // where fetches beyond the range go: a valid step
+  const int nsteps = (t1 - t0 + 31) >> 5;
+  const int nq = a.g * a.k, qb0 = qw * NB;
+  const T* kbase = a.kc + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
+  const T* vbase = a.vt + (size_t)(b * a.Hkv + kvh) * a.max_ctx * HD;
+
+  int row[NB], lim[NB];
+  Frag<T> qf[NB][KSTEPS];
+  f32x4 o[NB][HT];
+  float mrun[NB], lrun[NB];
+#pragma unroll
+  for (int n = 0; n < NB; ++n) {
+    row[n] = (qb0 + n) * 16 + c;
+    lim[n] = row[n] < nq ? t1 - 1 : -1;                 // every cached token is visible to every window row
+    const T* qp = a.qbuf + ((size_t)(b * a.Hkv + kvh) * a.qrows_pad + min(row[n], nq - 1)) * HD + g4 * 8;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) qf[n][ks] = frag_load_row(qp + ks * 32);
+    mrun[n] = -INFINITY; lrun[n] = 0.f;
+#pragma unroll
+    for (int h = 0; h < HT; ++h) o[n][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  // this wave's fragments wave, wave + NW, ... of the step that starts at token tb (a multiple of 32)
+  auto fetch = [&](u32x4 (&dst)[FPW], int tb) {
+    const T *kp, *vp;
+    if constexpr (PAGED) {
+      const size_t po = ((size_t)a.page_table[b * a.pps + tb / KV_PAGE] * a.Hkv + kvh) * KV_PAGE * HD;
+      const int tp = tb % KV_PAGE;
+      kp = a.kc + po + (size_t)(tp >> 4) * (KSTEPS * 512); vp = a.vt + po + (size_t)(tp >> 5) * (HT * 512);
+    } else {
+      kp = kbase + (size_t)(tb >> 4) * (KSTEPS * 512); vp = vbase + (size_t)(tb >> 5) * (HT * 512);
+    }
+#pragma unroll
+    for (int i = 0; i < FPW; ++i) {
+      const int fi = wave + i * NW;
+      const T* src = fi < 2 * KSTEPS ? kp + fi * 512 : vp + (fi - 2 * KSTEPS) * 512;
+      dst[i] = *(reinterpret_cast<const u32x4*>(src) + lane);
+    }
+  };
+
+  u32x4 pre[DEPTH][FPW];
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d) fetch(pre[d], d < nsteps ? t0 + 32 * d : tfirst);
+
+  for (int s0 = 0; s0 < nsteps; s0 += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      const int st = s0 + d;
+      if (st >= nsteps) break;                          // (the same for every wave of the workgroup)
+      u32x4 (&buf)[FR][WAVE] = stage[st & 1];
+#pragma unroll
+      for (int i = 0; i < FPW; ++i) buf[wave + i * NW][lane] = pre[d][i];
+      fetch(pre[d], st + DEPTH < nsteps ? t0 + 32 * (st + DEPTH) : tfirst);
+      __syncthreads();
+      const int tb = t0 + 32 * st;
+      const bool open = tb + 32 <= t1;
+      // scores of this lane's query row for tokens tb + 16*h + 4*g4 + i
+      f32x4 s[NB][2];
+      {
+        Frag<T> kf[2][KSTEPS];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int ks = 0; ks < KSTEPS; ++ks) kf[h][ks].v = buf[h * KSTEPS + ks][lane];
+#pragma unroll
+        for (int n = 0; n < NB; ++n)
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            s[n][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) s[n][h] = mma(kf[h][ks], qf[n][ks], s[n][h]);
+          }
+      }
+      // online soft-max as in attn_task's step; O^T += V^T P^T once every block has its probabilities,
+      // with the V^T fragments read only then (the registers do not hold them next to the keys)
+#pragma unroll
+      for (int n = 0; n < NB; ++n) {
+        float mx = -INFINITY;
+        if (open) {
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { const float v = s[n][h][i] * a.scale; s[n][h][i] = v; mx = fmaxf(mx, v); }
+        } else {
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int tok = tb + 16 * h + 4 * g4 + i;
+              const float v = tok <= lim[n] ? s[n][h][i] * a.scale : -INFINITY;
+              s[n][h][i] = v; mx = fmaxf(mx, v);
+            }
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float mnew = fmaxf(mrun[n], mx);
+        float psum = 0.f;
+        if (mnew > -INFINITY) {
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { const float p = fast_exp2(s[n][h][i] - mnew); s[n][h][i] = p; psum += p; }
+        } else {
+          s[n][0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[n][1] = s[n][0];
+        }
+        if (__builtin_amdgcn_ballot_w64(mnew > mrun[n]) != 0) {
+          const float alpha = mnew > mrun[n] ? fast_exp2(mrun[n] - mnew) : 1.f;
+          lrun[n] *= alpha;
+#pragma unroll
+          for (int h = 0; h < HT; ++h) o[n][h] = o[n][h] * alpha;
+        }
+        mrun[n] = mnew;
+        lrun[n] += psum;
+      }
+      Frag<T> vf[HT];
+#pragma unroll
+      for (int h = 0; h < HT; ++h) vf[h].v = buf[2 * KSTEPS + h][lane];
+#pragma unroll
+      for (int n = 0; n < NB; ++n) pv_accumulate<HT>(o[n], vf, s[n][0], s[n][1]);
+    }
+  }
+  // the partials, as attn_task leaves them
+#pragma unroll
+  for (int n = 0; n < NB; ++n) {
+    float l = lrun[n];
+    l += __shfl_xor(l, 16); l += __shfl_xor(l, 32);
+    const size_t pidx = ((size_t)(b * a.Hkv + kvh) * a.nsplit + sp) * a.qrows_pad + row[n];
+    if (qb0 + n < a.nqb && row[n] < a.qrows_pad) {
+      if (g4 == 0) { a.pm[pidx] = mrun[n]; a.pl[pidx] = l; }
+#pragma unroll
+      for (int h = 0; h < HT; ++h) *reinterpret_cast<f32x4*>(a.po + pidx * HD + h * 16 + 4 * g4) = o[n][h];
+    }
+  }
 }
 
 // Queries for the throughput form of the attention: wave w handles 16 query rows of the

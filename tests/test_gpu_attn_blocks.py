@@ -1,5 +1,6 @@
-"""GPU parity of the attention kernel's form with two query blocks per wave (one set of K/V
-fragments in registers for 32 query rows, two sets of fragments in flight).
+"""GPU parity of the attention kernel's forms for many query rows: two query blocks per wave (one set
+of K/V fragments in registers for 32 query rows, two sets of fragments in flight), and the shared
+form (see the fixture below).
 
 The library takes that form by itself only for many query rows over long ranges of cached tokens
 (8 or more query blocks per kv head and at least 1024 tokens per split); DBL_ATTN_NB=3 at context
@@ -17,9 +18,14 @@ from tests.test_gpu_parity import SMALL_BF16, SMALL_QWEN, TOL, jitter_gains
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture
-def forced(monkeypatch):
-    monkeypatch.setenv("DBL_ATTN_NB", "3")
+# The shared form (the waves of a workgroup walk one token range together, K/V staged through LDS) is
+# taken by itself from 4 query blocks per kv head and 512 cached tokens per split on; DBL_ATTN_LDS=2
+# (two blocks per wave) / 3 (one) makes it the form wherever a kv head has two query blocks and the
+# cache is not empty, with 2, 4 or 8 waves per workgroup depending on the window.
+@pytest.fixture(params=[("DBL_ATTN_NB", "3"), ("DBL_ATTN_LDS", "2"), ("DBL_ATTN_LDS", "3")],
+                ids=["two_blocks_per_wave", "shared_two_blocks", "shared_one_block"])
+def forced(monkeypatch, request):
+    monkeypatch.setenv(*request.param)
 
 
 def max_err(got, ref):
