@@ -110,9 +110,9 @@ struct dbl_ctx {
   void* xn = nullptr;               // RMSNorm output of the current 16-row pass (windows of more than 8 rows)
   float* sk_part = nullptr;         // gemm_rows_kernel's split units: two slots of partial sums per workgroup
   int* sk_cnt = nullptr;            //   arrivals per unit (zero between launches)
-  int attn_lds = 1;                 // attention's shared (LDS-staged) form: 1 where it pays, 0 never, 2 wherever a kv head has two query blocks and a cached split exists (DBL_ATTN_LDS at create)
+  int attn_lds = 1;                 // attention's shared (LDS-staged) form: 1 where it pays, 0 never, 2 wherever a kv head has two query blocks and a cached split exists, 3 / 4 like 2 / 1 with one query block per wave (DBL_ATTN_LDS at create)
   int attn_nb = 2;                  // query blocks per wave of the attention where it pays; DBL_ATTN_NB at create: 1 never, 3 wherever possible
-  int rows_q = 4;                   // units of 8 tile rows in passes of more than 32 rows: 0 where the model says they pay; 8 wherever possible; 4 never (DBL_ROWS_Q at create)
+  int rows_q = 0;                   // gate/up in units of 8 tile rows (passes of 17 to 64 rows): 0 where the model says they pay; 8 always; 4 never (DBL_ROWS_Q at create)
   int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never (DBL_STREAMK at create)
   float *qkv_part = nullptr, *logits = nullptr;
   void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
@@ -229,7 +229,9 @@ struct RowsChoice { int q = 0, grid = 0; bool sk = false; };
 RowsChoice rows_choice(const dbl_ctx* c, const GemmPlan& p, int epi, int R) {
   const int nacc = epi == EPI_SWIGLU ? 2 : 1;
   RowsChoice best, best_sk; double best_cost = 1e30, best_cost_sk = 1e30;
-  const bool can8 = R >= 4 && epi != EPI_LMHEAD && c->rows_q != 4;   // units of 8 tile rows: passes of more than 32 rows
+  // units of 8 tile rows: the gate/up projection in passes of 17 to 64 rows (64 rows at the 70B width: 172 -> 160 us; the
+  // other projections have too few tile rows to share out in units of 8 and lose 5-7 us; at 128 rows the registers do not hold them)
+  const bool can8 = (R == 2 || R == 4) && epi == EPI_SWIGLU && c->rows_q != 4;
   for (int q : {8, 4, 2}) {
     if (q < nacc) continue;
     if (q == 8 ? !can8 : (can8 && c->rows_q == 8)) continue;
@@ -270,7 +272,7 @@ int launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, GemmArgs<T> a) {
   a.sk_part = c->sk_part; a.sk_cnt = c->sk_cnt;
   if constexpr (EPI != EPI_LMHEAD) {
     if (ch.sk) {
-      if constexpr (R >= 4) {
+      if constexpr (EPI == EPI_SWIGLU && (R == 2 || R == 4)) {
         if (ch.q == 8) { hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 8, true>), grid, block, 0, c->stream, a); return ch.grid; }
       }
       if constexpr (R == 8) {
@@ -281,7 +283,7 @@ int launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, GemmArgs<T> a) {
       }
       return ch.grid;
     }
-    if constexpr (R >= 4) {
+    if constexpr (EPI == EPI_SWIGLU && (R == 2 || R == 4)) {
       if (ch.q == 8) { hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 8, false>), grid, block, 0, c->stream, a); return ch.grid; }
     }
   }
@@ -434,8 +436,10 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
   // shared form (bf16): 4 or more query blocks per kv head, more workgroups than CUs in the forms above and at
   // least 512 cached tokens per split.  Two blocks per wave, 2 / 4 / 8 waves per workgroup, 8 waves per CU.
   s.shared = false;
-  if (c->bf16 && ((c->attn_lds == 1 && !s.deep && qblocks >= 4) || (c->attn_lds > 1 && qblocks >= 2)) && ctx_upper > 0) {
-    const int nb = c->attn_lds > 2 ? 1 : 2, nqw = (qblocks + nb - 1) / nb;
+  const bool lds_forced = c->attn_lds == 2 || c->attn_lds == 3;
+  if (c->bf16 && c->attn_lds > 0 && qblocks >= 2 && (lds_forced || !s.deep) && ctx_upper > 0) {
+    // two blocks per wave from 8 blocks per kv head on (fewer blocks: more waves, more loads in flight)
+    const int nb = c->attn_lds >= 3 ? 1 : c->attn_lds == 2 ? 2 : (qblocks >= 8 ? 2 : 1), nqw = (qblocks + nb - 1) / nb;
     const int nw = nqw >= 8 ? 8 : nqw >= 4 ? 4 : 2, nqg = (nqw + nw - 1) / nw;
     int n = ((8 / nw) * c->n_cu + B * Hkv * nqg - 1) / (B * Hkv * nqg);
     n = std::min({n, MAX_SPLITS - 1, (ctx_upper + 127) / 128});
@@ -443,7 +447,7 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
       const int tok = std::max(32, std::atoi(e));
       n = std::min(MAX_SPLITS - 1, (ctx_upper + tok - 1) / tok);
     }
-    if (n >= 1 && (c->attn_lds > 1 || ctx_upper / n >= 512)) {
+    if (n >= 1 && (lds_forced || ctx_upper / n >= 512)) {
       s.shared = true; s.deep = false; s.nb = nb; s.wpg = nw; s.nqg = nqg; ncs = n;
     }
   }

@@ -536,8 +536,9 @@ __global__ void __launch_bounds__(256, (PRE == 2 && sizeof(T) == 2 && NB == 1) ?
 // again only after the barrier that follows its last readers' next step), and read from there by
 // every wave as the MFMA operands of its own blocks.  Against attn_split_kernel's forms, where
 // each wave pulls the whole range through the CU's L1 for itself, the bytes through L1 fall by NW,
-// a wave needs registers for one step of operands only, so two waves per SIMD fit (one's soft-max
-// arithmetic runs under the other's MFMAs), and little register space buys a deep prefetch.
+// a wave needs registers for one step of operands only, so two waves per SIMD fit, and little
+// register space buys a deep prefetch.  (Running half of the waves one phase behind the others, so
+// that one wave's soft-max arithmetic meets the other's second product, was measured: no gain.)
 // Splits and partials are attn_split_kernel's; the window split (last in the grid) runs attn_task's
 // window path, one query block per wave.  Queries come from rope_q_kernel.  The host picks this form only with at least
 // one split over cached tokens.
@@ -546,9 +547,10 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_shared_kernel(const AttnArgs<
   static_assert(sizeof(T) == 2, "bf16 caches only");
   constexpr int KSTEPS = HD / 32, HT = HD / 16, FR = 2 * KSTEPS + HT;
   constexpr int FPW = FR / NW;                          // fragments a wave fetches per step
-  constexpr int DEPTH = NW == 2 ? 2 : NW == 4 ? 3 : 4;  // steps in flight per wave
+  constexpr int DEPTH = NW == 2 ? 2 : NW == 4 ? 3 : 4;  // steps in flight per wave (deeper, 3 / 4 / 6, measured the same)
   static_assert(FR % NW == 0, "the fragments of a step are shared out evenly");
-  __shared__ u32x4 stage[2][FR][WAVE];
+  __shared__ u32x4 stage_k[2][2 * KSTEPS][WAVE];
+  __shared__ u32x4 stage_v[2][HT][WAVE];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, c = lane & 15, g4 = lane >> 4;
   const int nqw = (a.nqb + NB - 1) / NB, nqg = (nqw + NW - 1) / NW, ncs = a.nsplit - 1;
   // gridDim.x = (B * Hkv * nqg) * (ncs + NB): the workgroups of the cached ranges, then, for the window rows
@@ -605,89 +607,101 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_shared_kernel(const AttnArgs<
     for (int i = 0; i < FPW; ++i) {
       const int fi = wave + i * NW;
       const T* src = fi < 2 * KSTEPS ? kp + fi * 512 : vp + (fi - 2 * KSTEPS) * 512;
-      dst[i] = *(reinterpret_cast<const u32x4*>(src) + lane);
+      dst[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src) + lane);   // read once: streaming
     }
+  };
+
+  // S phase of a step: scores of this lane's query row for tokens tb + 16*h + 4*g4 + i, online soft-max as
+  // in attn_task's step (running maximum, sum and the rescaling of O^T); leaves the probabilities in pr.
+  // P phase: O^T += V^T P^T with the V^T fragments of the same step.
+  f32x4 pr[NB][2];
+  auto s_phase = [&](const u32x4 (&bk)[2 * KSTEPS][WAVE], int tb) {
+    const bool open = tb + 32 <= t1;
+    {
+      Frag<T> kf[2][KSTEPS];
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) kf[h][ks].v = bk[h * KSTEPS + ks][lane];
+#pragma unroll
+      for (int n = 0; n < NB; ++n)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          pr[n][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < KSTEPS; ++ks) pr[n][h] = mma(kf[h][ks], qf[n][ks], pr[n][h]);
+        }
+    }
+#pragma unroll
+    for (int n = 0; n < NB; ++n) {
+      float mx = -INFINITY;
+      if (open) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { const float v = pr[n][h][i] * a.scale; pr[n][h][i] = v; mx = fmaxf(mx, v); }
+      } else {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int tok = tb + 16 * h + 4 * g4 + i;
+            const float v = tok <= lim[n] ? pr[n][h][i] * a.scale : -INFINITY;
+            pr[n][h][i] = v; mx = fmaxf(mx, v);
+          }
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float mnew = fmaxf(mrun[n], mx);
+      float psum = 0.f;
+      if (mnew > -INFINITY) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { const float p = fast_exp2(pr[n][h][i] - mnew); pr[n][h][i] = p; psum += p; }
+      } else {
+        pr[n][0] = f32x4{0.f, 0.f, 0.f, 0.f}; pr[n][1] = pr[n][0];
+      }
+      if (__builtin_amdgcn_ballot_w64(mnew > mrun[n]) != 0) {
+        const float alpha = mnew > mrun[n] ? fast_exp2(mrun[n] - mnew) : 1.f;
+        lrun[n] *= alpha;
+#pragma unroll
+        for (int h = 0; h < HT; ++h) o[n][h] = o[n][h] * alpha;
+      }
+      mrun[n] = mnew;
+      lrun[n] += psum;
+    }
+  };
+  auto p_phase = [&](const u32x4 (&bv)[HT][WAVE]) {
+    Frag<T> vf[HT];
+#pragma unroll
+    for (int h = 0; h < HT; ++h) vf[h].v = bv[h][lane];
+#pragma unroll
+    for (int n = 0; n < NB; ++n) pv_accumulate<HT>(o[n], vf, pr[n][0], pr[n][1]);
   };
 
   u32x4 pre[DEPTH][FPW];
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d) fetch(pre[d], d < nsteps ? t0 + 32 * d : tfirst);
-
+  // Every round of the loop stages and fetches DEPTH steps, whether the range still has them or not (steps
+  // beyond it re-fetch a valid step and are not computed on): the loads in flight are then the same at the
+  // loop's head and end, and every wait inside counts exactly the loads that are younger than the one it needs.
   for (int s0 = 0; s0 < nsteps; s0 += DEPTH) {
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
       const int st = s0 + d;
-      if (st >= nsteps) break;                          // (the same for every wave of the workgroup)
-      u32x4 (&buf)[FR][WAVE] = stage[st & 1];
 #pragma unroll
-      for (int i = 0; i < FPW; ++i) buf[wave + i * NW][lane] = pre[d][i];
+      for (int i = 0; i < FPW; ++i) {
+        const int fi = wave + i * NW;
+        if (fi < 2 * KSTEPS) stage_k[st & 1][fi][lane] = pre[d][i];
+        else stage_v[st & 1][fi - 2 * KSTEPS][lane] = pre[d][i];
+      }
       fetch(pre[d], st + DEPTH < nsteps ? t0 + 32 * (st + DEPTH) : tfirst);
       __syncthreads();
-      const int tb = t0 + 32 * st;
-      const bool open = tb + 32 <= t1;
-      // scores of this lane's query row for tokens tb + 16*h + 4*g4 + i
-      f32x4 s[NB][2];
-      {
-        Frag<T> kf[2][KSTEPS];
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-          for (int ks = 0; ks < KSTEPS; ++ks) kf[h][ks].v = buf[h * KSTEPS + ks][lane];
-#pragma unroll
-        for (int n = 0; n < NB; ++n)
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            s[n][h] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) s[n][h] = mma(kf[h][ks], qf[n][ks], s[n][h]);
-          }
+      if (st < nsteps) {
+        s_phase(stage_k[st & 1], t0 + 32 * st);
+        p_phase(stage_v[st & 1]);
       }
-      // online soft-max as in attn_task's step; O^T += V^T P^T once every block has its probabilities,
-      // with the V^T fragments read only then (the registers do not hold them next to the keys)
-#pragma unroll
-      for (int n = 0; n < NB; ++n) {
-        float mx = -INFINITY;
-        if (open) {
-#pragma unroll
-          for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { const float v = s[n][h][i] * a.scale; s[n][h][i] = v; mx = fmaxf(mx, v); }
-        } else {
-#pragma unroll
-          for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const int tok = tb + 16 * h + 4 * g4 + i;
-              const float v = tok <= lim[n] ? s[n][h][i] * a.scale : -INFINITY;
-              s[n][h][i] = v; mx = fmaxf(mx, v);
-            }
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float mnew = fmaxf(mrun[n], mx);
-        float psum = 0.f;
-        if (mnew > -INFINITY) {
-#pragma unroll
-          for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { const float p = fast_exp2(s[n][h][i] - mnew); s[n][h][i] = p; psum += p; }
-        } else {
-          s[n][0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[n][1] = s[n][0];
-        }
-        if (__builtin_amdgcn_ballot_w64(mnew > mrun[n]) != 0) {
-          const float alpha = mnew > mrun[n] ? fast_exp2(mrun[n] - mnew) : 1.f;
-          lrun[n] *= alpha;
-#pragma unroll
-          for (int h = 0; h < HT; ++h) o[n][h] = o[n][h] * alpha;
-        }
-        mrun[n] = mnew;
-        lrun[n] += psum;
-      }
-      Frag<T> vf[HT];
-#pragma unroll
-      for (int h = 0; h < HT; ++h) vf[h].v = buf[2 * KSTEPS + h][lane];
-#pragma unroll
-      for (int n = 0; n < NB; ++n) pv_accumulate<HT>(o[n], vf, s[n][0], s[n][1]);
     }
   }
   // the partials, as attn_task leaves them
