@@ -113,8 +113,14 @@ typedef struct {
  *
  * Environment read here (testing and tuning aids, results stay within the same bars):
  * DBL_STREAMK = 1 makes the projection kernel's split-unit form the form of every projection that
- * can take it, 0 switches it off, unset lets the library choose per launch; DBL_VERBOSE prints the
- * projection plans to stderr.
+ * can take it, 0 switches it off, unset lets the library choose per launch; DBL_ROWS_Q = 8 / 4
+ * always / never runs the gate/up projection of 17- to 64-row passes in units of 8 tile rows;
+ * DBL_ATTN_LDS = 0 switches the attention's shared form (one token range per workgroup, K/V
+ * staged through LDS) off, 2 / 3 make it the form wherever a kv head has two 16-row query blocks
+ * and some cached tokens (two / one block per wave), 4 keeps the library's choice of when but with
+ * one block per wave; DBL_ATTN_NB = 1 / 3 never / wherever possible takes the form with two query
+ * blocks per wave on K/V fragments in registers; DBL_ATTN_SPLIT_TOKENS sets the cached tokens per
+ * attention split; DBL_VERBOSE prints the projection plans to stderr.
  */
 int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream, dbl_ctx** out);
 int dbl_destroy(dbl_ctx* ctx);

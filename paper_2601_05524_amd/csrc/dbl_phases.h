@@ -634,31 +634,33 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_shared_kernel(const AttnArgs<
     }
 #pragma unroll
     for (int n = 0; n < NB; ++n) {
+      // the scale (positive) is applied to the row maximum and inside the exponent's fused multiply-add,
+      // not to the eight scores one by one
       float mx = -INFINITY;
       if (open) {
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) { const float v = pr[n][h][i] * a.scale; pr[n][h][i] = v; mx = fmaxf(mx, v); }
+          for (int i = 0; i < 4; ++i) mx = fmaxf(mx, pr[n][h][i]);
       } else {
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int tok = tb + 16 * h + 4 * g4 + i;
-            const float v = tok <= lim[n] ? pr[n][h][i] * a.scale : -INFINITY;
+            const float v = tok <= lim[n] ? pr[n][h][i] : -INFINITY;
             pr[n][h][i] = v; mx = fmaxf(mx, v);
           }
       }
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float mnew = fmaxf(mrun[n], mx);
+      const float mnew = fmaxf(mrun[n], mx * a.scale);
       float psum = 0.f;
       if (mnew > -INFINITY) {
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) { const float p = fast_exp2(pr[n][h][i] - mnew); pr[n][h][i] = p; psum += p; }
+          for (int i = 0; i < 4; ++i) { const float p = fast_exp2(fmaf(pr[n][h][i], a.scale, -mnew)); pr[n][h][i] = p; psum += p; }
       } else {
         pr[n][0] = f32x4{0.f, 0.f, 0.f, 0.f}; pr[n][1] = pr[n][0];
       }
