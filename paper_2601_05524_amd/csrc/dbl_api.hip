@@ -112,6 +112,7 @@ struct dbl_ctx {
   int* sk_cnt = nullptr;            //   arrivals per unit (zero between launches)
   int attn_lds = 1;                 // attention's shared (LDS-staged) form: 1 where it pays, 0 never, 2 wherever a kv head has two query blocks and a cached split exists, 3 / 4 like 2 / 1 with one query block per wave (DBL_ATTN_LDS at create)
   int attn_nb = 2;                  // query blocks per wave of the attention where it pays; DBL_ATTN_NB at create: 1 never, 3 wherever possible
+  int wide_gu = 1;                  // gate/up of more than 32 rows through gemm_wide_swiglu_kernel (DBL_WIDE_GU=0 at create: through gemm_rows_kernel)
   int rows_q = 0;                   // gate/up in units of 8 tile rows (passes of 17 to 64 rows): 0 where the model says they pay; 8 always; 4 never (DBL_ROWS_Q at create)
   int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never (DBL_STREAMK at create)
   float *qkv_part = nullptr, *logits = nullptr;
@@ -352,6 +353,15 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
         const int nsl = std::max(1, std::min((c->ldh + 1023) / 1024, 64 / a.mrows));
         hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows * nsl), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, nsl, a.d, a.eps);
         a.X = xn;
+      }
+      if constexpr (sizeof(T) == 2) {
+        // gate/up of more than 32 rows: four units per workgroup on one set of activations staged through LDS
+        if (epi == EPI_SWIGLU && a.mrows > 32 && c->wide_gu && p.KBp % 4 == 0) {
+          const dim3 grid(std::min((2 * p.NT + 15) / 16, c->n_cu)), block(256);
+          if (a.mrows > 64) hipLaunchKernelGGL((gemm_wide_swiglu_kernel<T, 8>), grid, block, 0, c->stream, a);
+          else hipLaunchKernelGGL((gemm_wide_swiglu_kernel<T, 4>), grid, block, 0, c->stream, a);
+          continue;
+        }
       }
       if (a.mrows > 64) launch_gemm_rows<T, 8>(c, p, epi, a);
       else if (a.mrows > 32) launch_gemm_rows<T, 4>(c, p, epi, a);
@@ -710,6 +720,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
   c->dry = (cfg->flags & DBL_FLAG_VALIDATE_ONLY) != 0;
   if (const char* e = std::getenv("DBL_ATTN_LDS")) c->attn_lds = std::atoi(e);
   if (const char* e = std::getenv("DBL_ATTN_NB")) c->attn_nb = std::atoi(e);
+  if (const char* e = std::getenv("DBL_WIDE_GU")) c->wide_gu = std::atoi(e);
   if (const char* e = std::getenv("DBL_ROWS_Q")) c->rows_q = std::atoi(e);
   if (const char* e = std::getenv("DBL_STREAMK")) c->sk_mode = std::atoi(e) > 0 ? 1 : -1;   // testing / tuning aid
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);

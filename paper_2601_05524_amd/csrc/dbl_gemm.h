@@ -697,6 +697,112 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
   }
 }
 
+// Gate/up projection of passes with more than 32 rows (R = 4 or 8 row groups), bf16.  In
+// gemm_rows_kernel every wave owns a K slice and therefore its own activations: R*KS fragments
+// per Q*KS weight fragments, twice the weight bytes at 128 rows, all of it through the CU's L1.
+// Here the four waves of a workgroup own four different units of Q = 4 tile rows (two gate/up
+// tile pairs) and walk K together, KC = 4 k-blocks at a time: the R*KC activation fragments of a
+// chunk are fetched once per workgroup (a quarter each, one chunk ahead, into registers), staged
+// through one of two LDS buffers (one barrier per chunk) and read from there by every wave, so the
+// activation bytes through L1 fall to R/16 of the weight bytes.  A wave holds complete sums (no
+// reduction between waves); its 16 weight fragments per chunk are exactly one revolution of the
+// ring, consumed and re-requested in the same order (k-block major, so that only R activation
+// fragments are live at a time).  Workgroup w takes the groups of four units w, w + grid, ...
+// Requires KBp % 4 == 0; the activations are the stored RMSNorm output in the fragment-tiled layout.
+template <typename T, int R>
+__global__ void __launch_bounds__(256) gemm_wide_swiglu_kernel(const GemmArgs<T> a) {
+  static_assert(sizeof(T) == 2, "bf16 only");
+  constexpr int Q = 4, KC = 4, RING = Q * KC, AF = R * KC / 4;
+  static_assert(RING == GemmCfg<T>::RING, "one ring revolution per chunk");
+  __shared__ u32x4 xs[2][R * KC][WAVE];
+  const int wg = blockIdx.x, nwg = gridDim.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int nch = a.KBp / KC;
+  const int NTR = 2 * a.NT;                              // tile rows (gate and up rows of a pair are neighbours)
+  const int NSU = (NTR + 4 * Q - 1) / (4 * Q);           // groups of four units
+  const size_t row_elems = (size_t)a.KBp * BLOCK_ELEMS;
+  const int KBx = a.ldx >> 5, glast = (a.mrows - 1) >> 4;
+  // tile row q of this wave's unit in group su (rows beyond the last one re-read it; their results are dropped)
+  auto wptr = [&](int su, int q, int ch) {
+    return a.W + (size_t)min((su * 4 + wave) * Q + q, NTR - 1) * row_elems + (size_t)ch * KC * BLOCK_ELEMS;
+  };
+  // this wave's quarter of the activation fragments (row group r, k-block j of chunk ch): fragment f = r * KC + j
+  auto fetch_x = [&](u32x4 (&dst)[AF], int ch) {
+#pragma unroll
+    for (int i = 0; i < AF; ++i) {
+      const int f = wave * AF + i, r = f / KC, j = f % KC;
+      const T* xp = a.X + ((size_t)((a.m0 >> 4) + min(r, glast)) * KBx + ch * KC + j) * BLOCK_ELEMS + lane * 8;
+      dst[i] = *reinterpret_cast<const u32x4*>(xp);
+    }
+  };
+
+  int su = wg, ch = 0;
+  Frag<T> ring[RING];                                    // ring[j * Q + q] = fragment (tile row q, k-block j)
+  {
+    const int sf = su < NSU ? su : 0;
+#pragma unroll
+    for (int i = 0; i < RING; ++i) ring[i] = frag_load_w(wptr(sf, i % Q, 0), i / Q, lane);
+  }
+  u32x4 xpre[AF];
+  fetch_x(xpre, 0);
+  f32x4 acc[Q][R];
+#pragma unroll
+  for (int q = 0; q < Q; ++q)
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[q][r] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int it = 0; su < NSU; ++it) {
+    const bool uend = ch + 1 == nch;
+    const int sun = uend ? su + nwg : su, chn = uend ? 0 : ch + 1;
+    const int sunc = sun < NSU ? sun : 0;                // after the last group the refill loads go on, harmlessly, into group 0
+    const T* wn[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) wn[q] = wptr(sunc, q, chn);
+    u32x4 (&buf)[R * KC][WAVE] = xs[it & 1];
+#pragma unroll
+    for (int i = 0; i < AF; ++i) buf[wave * AF + i][lane] = xpre[i];
+    fetch_x(xpre, chn);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < KC; ++j) {
+      Frag<T> b[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) b[r].v = buf[r * KC + j][lane];
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[q][r] = mma(ring[j * Q + q], b[r], acc[q][r]);
+        ring[j * Q + q] = frag_load_w(wn[q], j, lane);
+        __builtin_amdgcn_sched_barrier(0x6);             // products and loads keep their program order
+      }
+    }
+    if (uend) {
+      // SwiGLU epilogue of this wave's two tile pairs x R row groups
+#pragma unroll
+      for (int tt = 0; tt < Q / 2; ++tt) {
+        const int t = (su * 4 + wave) * (Q / 2) + tt;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const int mr = 16 * r + c;
+          if (t < a.NT && mr < a.mrows) {
+            const int m = a.m0 + mr, n = t * TILE_N + 4 * g;
+            f32x4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float gt = acc[2 * tt][r][i], up = acc[2 * tt + 1][r][i];
+              o[i] = (n + i < a.N) ? gt / (1.f + expf(-gt)) * up : 0.f;
+            }
+            st_round4(a.act_tiled ? a.act + xt_offset(m, n, a.ldact) : a.act + (size_t)m * a.ldact + n, o);
+          }
+          acc[2 * tt][r] = f32x4{0.f, 0.f, 0.f, 0.f};
+          acc[2 * tt + 1][r] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+      }
+    }
+    su = sun; ch = chn;
+  }
+}
+
 // xn[row][:] = T(hg[row][:] * rsqrt(mean(h[row]^2) + eps)) for rows m0 + blockIdx.x / nsl: the
 // RMSNorm output as a stored tensor in the fragment-tiled layout, for gemm_rows_kernel.
 // 256 threads; thread p adds slot p of the row's sum-of-squares partials; the nsl workgroups
