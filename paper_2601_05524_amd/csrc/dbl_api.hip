@@ -112,8 +112,7 @@ struct dbl_ctx {
   int* sk_cnt = nullptr;            //   arrivals per unit (zero between launches)
   int attn_lds = 1;                 // attention's shared (LDS-staged) form: 1 where it pays, 0 never, 2 wherever a kv head has two query blocks and a cached split exists, 3 / 4 like 2 / 1 with one query block per wave (DBL_ATTN_LDS at create)
   int attn_nb = 2;                  // query blocks per wave of the attention where it pays; DBL_ATTN_NB at create: 1 never, 3 wherever possible
-  int wide_gu = 1;                  // gate/up of more than 32 rows through gemm_wide_swiglu_kernel (DBL_WIDE_GU=0 at create: through gemm_rows_kernel)
-  int rows_q = 0;                   // gate/up in units of 8 tile rows (passes of 17 to 64 rows): 0 where the model says they pay; 8 always; 4 never (DBL_ROWS_Q at create)
+  int wide_gu = 1;                  // gate/up of more than 16 rows through gemm_wide_swiglu_kernel (DBL_WIDE_GU=0 at create: through gemm_rows_kernel)
   int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never (DBL_STREAMK at create)
   float *qkv_part = nullptr, *logits = nullptr;
   void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
@@ -229,24 +228,19 @@ struct RowsChoice { int q = 0, grid = 0; bool sk = false; };
 
 RowsChoice rows_choice(const dbl_ctx* c, const GemmPlan& p, int epi, int R) {
   const int nacc = epi == EPI_SWIGLU ? 2 : 1;
+  const int kchunk = 4 * rows_ks(c->bf16, R);                          // k-blocks per chunk (the kernel's NWV * KS)
+  const int nch_slice = (p.KBp / p.SS + kchunk - 1) / kchunk, nch_all = (p.KBp + kchunk - 1) / kchunk;
   RowsChoice best, best_sk; double best_cost = 1e30, best_cost_sk = 1e30;
-  // units of 8 tile rows: the gate/up projection in passes of 17 to 64 rows (64 rows at the 70B width: 172 -> 160 us; the
-  // other projections have too few tile rows to share out in units of 8 and lose 5-7 us; at 128 rows the registers do not hold them)
-  const bool can8 = (R == 2 || R == 4) && epi == EPI_SWIGLU && c->rows_q != 4;
-  for (int q : {8, 4, 2}) {
+  for (int q : {4, 2}) {
     if (q < nacc) continue;
-    if (q == 8 ? !can8 : (can8 && c->rows_q == 8)) continue;
-    const int ks = rows_ks(c->bf16, R, q);
-    const int kchunk = 4 * ks;                                        // k-blocks per chunk (the kernel's NWV * KS)
-    const int nch_slice = (p.KBp / p.SS + kchunk - 1) / kchunk, nch_all = (p.KBp + kchunk - 1) / kchunk;
     if (epi == EPI_LMHEAD && R == 4 && q == 4) continue;   // (the row statistics of four groups leave no room for 16 accumulators)
-    if (R == 8 && q < 4) continue;                          // (eight row groups: half the k-blocks per chunk, so 4 tile rows fill the ring)
+    if (R == 8 && q != 4) continue;                         // (eight row groups: half the k-blocks per chunk, so 4 tile rows fill the ring)
     const int nu = (p.NT + q / nacc - 1) / (q / nacc);
     const int units = nu * p.SS;
     int g = std::min(units, std::min(c->n_cu, SSQ_PARTS));
     g = std::max(p.SS, g / p.SS * p.SS);
     // modelled time in chunks of one workgroup, times the cost of a chunk
-    const double per_chunk = ks / 8.0 * q * (1.0 + 0.25 * R / q);
+    const double per_chunk = q * (1.0 + 0.25 * R / q);
     const double cost = (0.5 * ((units + g - 1) / g) + 0.5 * (double)units / g) * nch_slice * per_chunk;
     if (cost < best_cost) { best_cost = cost; best = RowsChoice{q, g, false}; }
     // split units: equal ranges of items, plus what publishing and adding the parts costs.  Only where
@@ -273,9 +267,6 @@ int launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, GemmArgs<T> a) {
   a.sk_part = c->sk_part; a.sk_cnt = c->sk_cnt;
   if constexpr (EPI != EPI_LMHEAD) {
     if (ch.sk) {
-      if constexpr (EPI == EPI_SWIGLU && (R == 2 || R == 4)) {
-        if (ch.q == 8) { hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 8, true>), grid, block, 0, c->stream, a); return ch.grid; }
-      }
       if constexpr (R == 8) {
         hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 4, true>), grid, block, 0, c->stream, a);
       } else {
@@ -283,9 +274,6 @@ int launch_gemm_rows_q(dbl_ctx* c, const GemmPlan& p, GemmArgs<T> a) {
         else hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 2, true>), grid, block, 0, c->stream, a);
       }
       return ch.grid;
-    }
-    if constexpr (EPI == EPI_SWIGLU && (R == 2 || R == 4)) {
-      if (ch.q == 8) { hipLaunchKernelGGL((gemm_rows_kernel<T, EPI, R, 8, false>), grid, block, 0, c->stream, a); return ch.grid; }
     }
   }
   if constexpr (R == 8) {
@@ -355,11 +343,12 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
         a.X = xn;
       }
       if constexpr (sizeof(T) == 2) {
-        // gate/up of more than 32 rows: four units per workgroup on one set of activations staged through LDS
-        if (epi == EPI_SWIGLU && a.mrows > 32 && c->wide_gu && p.KBp % 4 == 0) {
+        // gate/up of more than 16 rows: four units per workgroup on one set of activations staged through LDS
+        if (epi == EPI_SWIGLU && a.mrows > 16 && c->wide_gu && p.KBp % 4 == 0) {
           const dim3 grid(std::min((2 * p.NT + 15) / 16, c->n_cu)), block(256);
           if (a.mrows > 64) hipLaunchKernelGGL((gemm_wide_swiglu_kernel<T, 8>), grid, block, 0, c->stream, a);
-          else hipLaunchKernelGGL((gemm_wide_swiglu_kernel<T, 4>), grid, block, 0, c->stream, a);
+          else if (a.mrows > 32) hipLaunchKernelGGL((gemm_wide_swiglu_kernel<T, 4>), grid, block, 0, c->stream, a);
+          else hipLaunchKernelGGL((gemm_wide_swiglu_kernel<T, 2>), grid, block, 0, c->stream, a);
           continue;
         }
       }
@@ -721,7 +710,6 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
   if (const char* e = std::getenv("DBL_ATTN_LDS")) c->attn_lds = std::atoi(e);
   if (const char* e = std::getenv("DBL_ATTN_NB")) c->attn_nb = std::atoi(e);
   if (const char* e = std::getenv("DBL_WIDE_GU")) c->wide_gu = std::atoi(e);
-  if (const char* e = std::getenv("DBL_ROWS_Q")) c->rows_q = std::atoi(e);
   if (const char* e = std::getenv("DBL_STREAMK")) c->sk_mode = std::atoi(e) > 0 ? 1 : -1;   // testing / tuning aid
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
   c->seed = weight_seed;
@@ -781,10 +769,10 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     ALLOC(xn, M16 * c->ldh * esz, true);
     ALLOC(ssq, (size_t)Mmax * SSQ_PARTS * 4, true);
     {
-      // split units of gemm_rows_kernel: two slots per workgroup of (up to 8 tile rows) x (row groups of
+      // split units of gemm_rows_kernel: two slots per workgroup of (up to 4 tile rows) x (row groups of
       // the largest pass) x 1 KiB, and one arrival counter per unit
       const size_t rg = Mmax > 64 ? 8 : Mmax > 32 ? 4 : Mmax > 16 ? 2 : 1;
-      ALLOC(sk_part, (size_t)2 * SSQ_PARTS * 8 * rg * 1024, false);
+      ALLOC(sk_part, (size_t)2 * SSQ_PARTS * 4 * rg * 1024, false);
       ALLOC(sk_cnt, (size_t)std::max({c->p_qkv.NT, c->p_o.NT, c->p_gu.NT, c->p_d.NT}) * 4, true);
     }
     ALLOC(qkv_part, (size_t)c->p_qkv.SS * Mmax * c->p_qkv.ldo() * 4, true);

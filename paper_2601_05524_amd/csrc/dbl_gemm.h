@@ -161,12 +161,9 @@ template <> struct GemmCfg<float> { static constexpr int RING = 8; };
 
 typedef f32x4 GemmRed[8][WAVE];   // one LDS reduction buffer: [wave][lane]
 
-// gemm_rows_kernel: k-blocks per wave and chunk for R row groups and units of Q tile rows.  The
-// accumulators take Q*R registers x 4 and the two activation sets 2*R*KS x 4, so KS halves where R
-// and then Q double beyond 4 (host and kernel share this).
-constexpr int rows_ks(bool two_byte, int R, int Q) {
-  return (two_byte ? 8 : 4) / (R > 4 ? 2 : 1) / (Q > 4 ? 2 : 1);
-}
+// gemm_rows_kernel: k-blocks per wave and chunk for R row groups (halved for 8 row groups: registers;
+// host and kernel share this)
+constexpr int rows_ks(bool two_byte, int R) { return (two_byte ? 8 : 4) / (R > 4 ? 2 : 1); }
 
 // 1 / rms of the row a lane of gemm_stream_kernel works on: row (lane & 7), clamped to the
 // valid rows.  Eight lanes add the 256 partials of one row (32 each, then a butterfly); the
@@ -394,7 +391,7 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
   constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
   constexpr int TT = Q / NACC;                  // output tiles per unit
   constexpr int NWV = 4;                        // waves: one per SIMD, the whole register file each
-  constexpr int KS = rows_ks(sizeof(T) == 2, R, Q);   // k-blocks per wave and chunk
+  constexpr int KS = rows_ks(sizeof(T) == 2, R);   // k-blocks per wave and chunk
   constexpr int NF = Q * KS;                    // weight fragments per wave and chunk
   constexpr int RING = GemmCfg<T>::RING;
   constexpr int P = TT * R;                     // (tile, row group) pairs per unit
@@ -697,7 +694,7 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
   }
 }
 
-// Gate/up projection of passes with more than 32 rows (R = 4 or 8 row groups), bf16.  In
+// Gate/up projection of passes with more than 16 rows (R = 2, 4 or 8 row groups), bf16.  In
 // gemm_rows_kernel every wave owns a K slice and therefore its own activations: R*KS fragments
 // per Q*KS weight fragments, twice the weight bytes at 128 rows, all of it through the CU's L1.
 // Here the four waves of a workgroup own four different units of Q = 4 tile rows (two gate/up
