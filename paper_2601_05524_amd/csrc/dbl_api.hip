@@ -432,21 +432,29 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
     // step at 8192 tokens and 8 query blocks 14.4 against 14.8 ms)
     if (c->attn_nb < 3 && ncs > 0 && ctx_upper / ncs < 1024) { geometry(1, 2); s.deep = was_deep; }
   }
-  // shared form (bf16): 4 or more query blocks per kv head, more workgroups than CUs in the forms above and at
-  // least 512 cached tokens per split.  Two blocks per wave, 2 / 4 / 8 waves per workgroup, 8 waves per CU.
+  // shared form (bf16): 2 or more query blocks per kv head, more workgroups than CUs in the forms above, ranges of
+  // at least 384 cached tokens per split (shorter ones are mostly start-up: fewer, longer ranges then, as long as
+  // half of the CUs still get a workgroup).  2 / 4 / 8 waves per workgroup, 8 waves per CU; two blocks per wave from 8
+  // blocks per kv head on, if that still leaves a workgroup for every slot of the chip (else more waves are worth
+  // more than fewer K/V reads: 32B-shaped step, 8 (b, kv head) pairs over 8192 tokens, 14.1 against 14.35 ms).
   s.shared = false;
   const bool lds_forced = c->attn_lds == 2 || c->attn_lds == 3;
   if (c->bf16 && c->attn_lds > 0 && qblocks >= 2 && (lds_forced || !s.deep) && ctx_upper > 0) {
-    // two blocks per wave from 8 blocks per kv head on (fewer blocks: more waves, more loads in flight)
-    const int nb = c->attn_lds >= 3 ? 1 : c->attn_lds == 2 ? 2 : (qblocks >= 8 ? 2 : 1), nqw = (qblocks + nb - 1) / nb;
-    const int nw = nqw >= 8 ? 8 : nqw >= 4 ? 4 : 2, nqg = (nqw + nw - 1) / nw;
-    int n = ((8 / nw) * c->n_cu + B * Hkv * nqg - 1) / (B * Hkv * nqg);
-    n = std::min({n, MAX_SPLITS - 1, (ctx_upper + 127) / 128});
-    if (const char* e = std::getenv("DBL_ATTN_SPLIT_TOKENS")) {   // tuning aid
-      const int tok = std::max(32, std::atoi(e));
-      n = std::min(MAX_SPLITS - 1, (ctx_upper + tok - 1) / tok);
-    }
-    if (n >= 1 && (lds_forced || ctx_upper / n >= 512)) {
+    int nb = c->attn_lds >= 3 ? 1 : c->attn_lds == 2 ? 2 : (qblocks >= 8 ? 2 : 1), nw = 0, nqg = 0, n = 0;
+    auto shape = [&]() {
+      const int nqw = (qblocks + nb - 1) / nb;
+      nw = nqw >= 8 ? 8 : nqw >= 4 ? 4 : 2; nqg = (nqw + nw - 1) / nw;
+      n = ((8 / nw) * c->n_cu + B * Hkv * nqg - 1) / (B * Hkv * nqg);
+      n = std::min({n, MAX_SPLITS - 1, (ctx_upper + 127) / 128});
+      if (!lds_forced) n = std::max(1, std::min(n, ctx_upper / 384));
+      if (const char* e = std::getenv("DBL_ATTN_SPLIT_TOKENS")) {   // tuning aid
+        const int tok = std::max(32, std::atoi(e));
+        n = std::min(MAX_SPLITS - 1, (ctx_upper + tok - 1) / tok);
+      }
+    };
+    shape();
+    if (c->attn_lds == 1 && nb == 2 && B * Hkv * nqg * n < (8 / nw) * c->n_cu) { nb = 1; shape(); }
+    if (n >= 1 && (lds_forced || (ctx_upper / n >= 384 && 2 * B * Hkv * nqg * n >= c->n_cu))) {
       s.shared = true; s.deep = false; s.nb = nb; s.wpg = nw; s.nqg = nqg; ncs = n;
     }
   }

@@ -19,7 +19,8 @@ pytestmark = pytest.mark.gpu
 
 
 # The shared form (the waves of a workgroup walk one token range together, K/V staged through LDS) is
-# taken by itself from 4 query blocks per kv head and 512 cached tokens per split on; DBL_ATTN_LDS=2
+# taken by itself from 2 query blocks per kv head and 384 cached tokens per split on (where the chip has fewer CUs
+# than the step has attention workgroups); DBL_ATTN_LDS=2
 # (two blocks per wave) / 3 (one) makes it the form wherever a kv head has two query blocks and the
 # cache is not empty, with 2, 4 or 8 waves per workgroup depending on the window.
 @pytest.fixture(params=[("DBL_ATTN_NB", "3"), ("DBL_ATTN_LDS", "2"), ("DBL_ATTN_LDS", "3")],

@@ -2,7 +2,7 @@
 
 The library takes the shared form of the attention (one token range per workgroup, K/V staged
 through LDS) by itself only where a step has more attention workgroups than the chip has CUs and
-at least 512 cached tokens per split: 4 sequences x 8 kv heads over 16 384 cached tokens do that
+at least 384 cached tokens per split: 4 sequences x 8 kv heads over 16 384 cached tokens do that
 for every window of the long-context workloads (k = 4: 2 query blocks per kv head, 2 waves per
 workgroup; k = 16: 8 blocks, two per wave, 4 waves; k = 32: 16 blocks, 8 waves).  The oracle
 cannot prefill such a cache in a test's time, so the cache is the library's seeded fill and the
