@@ -114,8 +114,8 @@ typedef struct {
  * Environment read here (testing and tuning aids, results stay within the same bars):
  * DBL_STREAMK = 1 makes the projection kernel's split-unit form the form of every projection that
  * can take it, 0 switches it off, unset lets the library choose per launch; DBL_WIDE_GU = 0 sends
- * the gate/up projection of passes with more than 16 rows through the general projection kernel
- * instead of the one that shares the activations of four units through LDS;
+ * every gate/up projection through the general projection kernel, never through the one that
+ * shares the activations of four units through LDS;
  * DBL_ATTN_LDS = 0 switches the attention's shared form (one token range per workgroup, K/V
  * staged through LDS) off, 2 / 3 make it the form wherever a kv head has two 16-row query blocks
  * and some cached tokens (two / one block per wave), 4 keeps the library's choice of when but with

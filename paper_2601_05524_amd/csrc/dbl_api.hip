@@ -112,7 +112,7 @@ struct dbl_ctx {
   int* sk_cnt = nullptr;            //   arrivals per unit (zero between launches)
   int attn_lds = 1;                 // attention's shared (LDS-staged) form: 1 where it pays, 0 never, 2 wherever a kv head has two query blocks and a cached split exists, 3 / 4 like 2 / 1 with one query block per wave (DBL_ATTN_LDS at create)
   int attn_nb = 2;                  // query blocks per wave of the attention where it pays; DBL_ATTN_NB at create: 1 never, 3 wherever possible
-  int wide_gu = 1;                  // gate/up of more than 16 rows through gemm_wide_swiglu_kernel (DBL_WIDE_GU=0 at create: through gemm_rows_kernel)
+  int wide_gu = 1;                  // gate/up through gemm_wide_swiglu_kernel where wide_gate_up says so (DBL_WIDE_GU=0 at create: always through gemm_rows_kernel)
   int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never (DBL_STREAMK at create)
   float *qkv_part = nullptr, *logits = nullptr;
   void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
@@ -297,6 +297,22 @@ void launch_gemm_rows(dbl_ctx* c, const GemmPlan& p, int epi, const GemmArgs<T>&
   }
 }
 
+// Whether the gate/up projection of a pass of mrows rows runs in gemm_wide_swiglu_kernel (bf16): its groups of 16
+// tile rows must fill at least three quarters of the chip's rounds (224 groups at the 70B width, 200 at the 32B
+// width; 64 at the 1B width do not).  Above 16 rows it then always wins (activation bytes); at 16 rows or fewer only
+// where gemm_rows_kernel's whole units leave part of a round empty (32B width: 1600 units, 6.25 rounds, 85.8 -> 80.0
+// us; at the 70B width, 7 full rounds, gemm_rows_kernel is ahead, 136 against 147 us).
+static bool wide_gate_up(const dbl_ctx* c, const GemmPlan& p, int mrows) {
+  if (!c->bf16 || !c->wide_gu || p.KBp % 4 != 0) return false;
+  const int ng = (2 * p.NT + 15) / 16, rounds = (ng + c->n_cu - 1) / c->n_cu;
+  if (4 * ng < 3 * rounds * c->n_cu) return false;
+  if (mrows > 16) return true;
+  const RowsChoice ch = rows_choice(c, p, EPI_SWIGLU, 1);
+  if (ch.sk) return false;
+  const int nu = (p.NT + ch.q / 2 - 1) / (ch.q / 2), r = (nu + ch.grid - 1) / ch.grid;
+  return 20 * nu < 19 * r * ch.grid;
+}
+
 // Which kernel runs a projection of M rows.  Windows of more than 8 rows: gemm_rows_kernel.
 // At 8 rows or fewer, measured inside a running layer at three widths: the gate/up projection
 // and the LM head are faster through gemm_rows_kernel everywhere (70B width: 8 us per layer and
@@ -343,12 +359,13 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
         a.X = xn;
       }
       if constexpr (sizeof(T) == 2) {
-        // gate/up of more than 16 rows: four units per workgroup on one set of activations staged through LDS
-        if (epi == EPI_SWIGLU && a.mrows > 16 && c->wide_gu && p.KBp % 4 == 0) {
+        // gate/up: four units per workgroup on one set of activations staged through LDS, where that is the better form
+        if (epi == EPI_SWIGLU && wide_gate_up(c, p, a.mrows)) {
           const dim3 grid(std::min((2 * p.NT + 15) / 16, c->n_cu)), block(256);
           if (a.mrows > 64) hipLaunchKernelGGL((gemm_wide_swiglu_kernel<T, 8>), grid, block, 0, c->stream, a);
           else if (a.mrows > 32) hipLaunchKernelGGL((gemm_wide_swiglu_kernel<T, 4>), grid, block, 0, c->stream, a);
-          else hipLaunchKernelGGL((gemm_wide_swiglu_kernel<T, 2>), grid, block, 0, c->stream, a);
+          else if (a.mrows > 16) hipLaunchKernelGGL((gemm_wide_swiglu_kernel<T, 2>), grid, block, 0, c->stream, a);
+          else hipLaunchKernelGGL((gemm_wide_swiglu_kernel<T, 1>), grid, block, 0, c->stream, a);
           continue;
         }
       }

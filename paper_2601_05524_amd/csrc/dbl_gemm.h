@@ -694,7 +694,8 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
   }
 }
 
-// Gate/up projection of passes with more than 16 rows (R = 2, 4 or 8 row groups), bf16.  In
+// Gate/up projection, bf16: every pass of more than 16 rows (R = 2, 4 or 8 row groups) and, at widths whose
+// tile rows gemm_rows_kernel cannot share out in full rounds, the smaller ones too (R = 1).  In
 // gemm_rows_kernel every wave owns a K slice and therefore its own activations: R*KS fragments
 // per Q*KS weight fragments, twice the weight bytes at 128 rows, all of it through the CU's L1.
 // Here the four waves of a workgroup own four different units of Q = 4 tile rows (two gate/up

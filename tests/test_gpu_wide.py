@@ -174,10 +174,11 @@ def test_llama70b_width_two_layers_16_row_chunks():
     composite("llama70b", 12, 16, 35)
 
 
-@pytest.mark.parametrize("nseq", [2, 4], ids=["64_rows", "128_rows"])
+@pytest.mark.parametrize("nseq", [1, 2, 4], ids=["32_rows", "64_rows", "128_rows"])
 def test_llama70b_width_two_layers_many_row_window(nseq):
-    """Two / four sequences with 32-row windows: 64 / 128 rows go through the projection kernel
-    with four / eight row groups per weight fragment at the full 70B width."""
+    """One / two / four sequences with 32-row windows: 32 / 64 / 128 rows go through the projection
+    kernels with two / four / eight row groups per weight fragment at the full 70B width (the
+    gate/up projection through the kernel that shares its activations through LDS)."""
     shape = slice_of("llama70b")
     r, saved = reference("llama70b", 31)
     for (t, l), v in saved.items():
