@@ -20,6 +20,7 @@ namespace {
 constexpr int MAX_ROWS = 128;       // max_batch * max_window
 constexpr int MAX_WINDOW = 32;
 constexpr int MAX_SPLITS = 64;
+constexpr int WIDE_SLICES = 8;   // K slices of gemm_wide_slice_kernel at most
 
 // How one projection is cut: NW waves per workgroup, each owning KS k-blocks of a tile
 // per K chunk; K longer than NW*KS blocks is covered by SS workgroup super slices
@@ -108,10 +109,12 @@ struct dbl_ctx {
   uint64_t* commits = nullptr;
   float *h = nullptr, *hg = nullptr, *ssq = nullptr;
   void* xn = nullptr;               // RMSNorm output of the current 16-row pass (windows of more than 8 rows)
+  float* wide_part = nullptr;       // gemm_wide_slice_kernel's parts: [WIDE_SLICES][rows of a pass][d_model] (contexts of more than 64 rows)
   float* sk_part = nullptr;         // gemm_rows_kernel's split units: two slots of partial sums per workgroup
   int* sk_cnt = nullptr;            //   arrivals per unit (zero between launches)
   int attn_lds = 1;                 // attention's shared (LDS-staged) form: 1 where it pays, 0 never, 2 wherever a kv head has two query blocks and a cached split exists, 3 / 4 like 2 / 1 with one query block per wave (DBL_ATTN_LDS at create)
   int attn_nb = 2;                  // query blocks per wave of the attention where it pays; DBL_ATTN_NB at create: 1 never, 3 wherever possible
+  int wide_resid = 1;               // output / down projection of 128-row passes through gemm_wide_slice_kernel (DBL_WIDE_RESID=0 at create: never)
   int wide_gu = 1;                  // gate/up through gemm_wide_swiglu_kernel where wide_gate_up says so (DBL_WIDE_GU=0 at create: always through gemm_rows_kernel)
   int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never (DBL_STREAMK at create)
   float *qkv_part = nullptr, *logits = nullptr;
@@ -313,6 +316,18 @@ static bool wide_gate_up(const dbl_ctx* c, const GemmPlan& p, int mrows) {
   return 20 * nu < 19 * r * ch.grid;
 }
 
+// Output / down projection of a 128-row pass through gemm_wide_slice_kernel + resid_reduce_kernel (bf16): 0 if not,
+// else the number of K slices.  The groups of 16 tile rows times the slices should about fill the chip; at 64 rows
+// and fewer the parts cost what the shared activations gain, so gemm_rows_kernel keeps those.
+static int wide_resid_slices(const dbl_ctx* c, const GemmPlan& p, int mrows) {
+  if (!c->bf16 || !c->wide_resid || !c->wide_part || mrows <= 64 || p.KBp % 4 != 0) return 0;
+  if (p.ldo() % 32 != 0 || p.ldo() / 32 > SSQ_PARTS || p.ldo() != c->ldh) return 0;
+  const int ng = (p.NT + 15) / 16, nch = p.KBp / 4;
+  int ssw = std::min({c->n_cu / ng, nch, WIDE_SLICES});
+  while (ssw > 1 && (ssw - 1) * ((nch + ssw - 1) / ssw) >= nch) --ssw;   // no empty slice
+  return ssw >= 2 && 4 * ng * ssw >= 3 * c->n_cu ? ssw : 0;
+}
+
 // Which kernel runs a projection of M rows.  Windows of more than 8 rows: gemm_rows_kernel.
 // At 8 rows or fewer, measured inside a running layer at three widths: the gate/up projection
 // and the LM head are faster through gemm_rows_kernel everywhere (70B width: 8 us per layer and
@@ -360,6 +375,14 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
       }
       if constexpr (sizeof(T) == 2) {
         // gate/up: four units per workgroup on one set of activations staged through LDS, where that is the better form
+        if (epi == EPI_RESIDUAL) {
+          if (const int ssw = wide_resid_slices(c, p, a.mrows)) {
+            hipLaunchKernelGGL((gemm_wide_slice_kernel<T, 8>), dim3((p.NT + 15) / 16, ssw), dim3(256), 0, c->stream, a, c->wide_part);
+            hipLaunchKernelGGL(resid_reduce_kernel, dim3(a.ldo / 32), dim3(256), 0, c->stream, c->wide_part, ssw, a.out, a.hg_out,
+                               a.gain_out, c->ssq, a.m0, a.mrows, a.ldo);
+            continue;
+          }
+        }
         if (epi == EPI_SWIGLU && wide_gate_up(c, p, a.mrows)) {
           const dim3 grid(std::min((2 * p.NT + 15) / 16, c->n_cu)), block(256);
           if (a.mrows > 64) hipLaunchKernelGGL((gemm_wide_swiglu_kernel<T, 8>), grid, block, 0, c->stream, a);
@@ -704,7 +727,7 @@ static void release_pages(dbl_ctx* c, int seq, int n_tokens) {
 
 void free_all(dbl_ctx* c) {
   void* ptrs[] = {c->w_qkv, c->w_o, c->w_gu, c->w_d, c->w_lm, c->emb, c->g1, c->g2, c->gq, c->gk, c->gf, c->cosT,
-                  c->sinT, c->kc, c->vt, c->page_table, c->kv_len, c->hist_len, c->hist, c->prompt_len, c->rej, c->rej_len, c->tier_best, c->prior, c->status, c->commits, c->h, c->hg, c->xn, c->sk_part, c->sk_cnt, c->qkv_part,
+                  c->sinT, c->kc, c->vt, c->page_table, c->kv_len, c->hist_len, c->hist, c->prompt_len, c->rej, c->rej_len, c->tier_best, c->prior, c->status, c->commits, c->h, c->hg, c->xn, c->wide_part, c->sk_part, c->sk_cnt, c->qkv_part,
                   c->ssq, c->logits, c->qbuf, c->attn, c->act, c->pm, c->pl, c->po, c->stats,
                   c->n_acc_i, c->emit_i, c->win_i};
   for (void* p : ptrs) if (p) (void)hipFree(p);
@@ -734,6 +757,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
   c->dry = (cfg->flags & DBL_FLAG_VALIDATE_ONLY) != 0;
   if (const char* e = std::getenv("DBL_ATTN_LDS")) c->attn_lds = std::atoi(e);
   if (const char* e = std::getenv("DBL_ATTN_NB")) c->attn_nb = std::atoi(e);
+  if (const char* e = std::getenv("DBL_WIDE_RESID")) c->wide_resid = std::atoi(e);
   if (const char* e = std::getenv("DBL_WIDE_GU")) c->wide_gu = std::atoi(e);
   if (const char* e = std::getenv("DBL_STREAMK")) c->sk_mode = std::atoi(e) > 0 ? 1 : -1;   // testing / tuning aid
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
@@ -800,6 +824,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
       ALLOC(sk_part, (size_t)2 * SSQ_PARTS * 4 * rg * 1024, false);
       ALLOC(sk_cnt, (size_t)std::max({c->p_qkv.NT, c->p_o.NT, c->p_gu.NT, c->p_d.NT}) * 4, true);
     }
+    if (c->bf16 && Mmax > 64) ALLOC(wide_part, (size_t)WIDE_SLICES * Mmax * std::max(c->p_o.ldo(), c->p_d.ldo()) * 4, false);
     ALLOC(qkv_part, (size_t)c->p_qkv.SS * Mmax * c->p_qkv.ldo() * 4, true);
     ALLOC(qbuf, (size_t)g.max_batch * g.n_kv_heads * c->qrows_pad * g.head_dim * esz, true);
     ALLOC(logits, (size_t)Mmax * c->p_lm.ldo() * 4, true);

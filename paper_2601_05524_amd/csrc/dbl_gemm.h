@@ -801,6 +801,104 @@ __global__ void __launch_bounds__(256) gemm_wide_swiglu_kernel(const GemmArgs<T>
   }
 }
 
+// Output and down projection of 128-row passes (R = 8), bf16: gemm_wide_swiglu_kernel's form -- four
+// units of 4 tile rows per workgroup on one set of activations staged through LDS -- for matrices
+// whose 32 groups of 16 tile rows do not fill the chip: K is cut into gridDim.y slices of whole chunks,
+// workgroup (x, y) multiplies group x with slice y and stores its sums as part y of the result,
+// part[y][row][feature] (plain stores); resid_reduce_kernel adds the parts in slice order and
+// applies the residual epilogue.  Requires KBp % 4 == 0 and no empty slice (the host sees to both).
+template <typename T, int R>
+__global__ void __launch_bounds__(256) gemm_wide_slice_kernel(const GemmArgs<T> a, float* __restrict__ part) {
+  static_assert(sizeof(T) == 2, "bf16 only");
+  constexpr int Q = 4, KC = 4, RING = Q * KC, AF = R * KC / 4;
+  static_assert(RING == GemmCfg<T>::RING, "one ring revolution per chunk");
+  __shared__ u32x4 xs[2][R * KC][WAVE];
+  const int gi = blockIdx.x, ss = blockIdx.y, SSW = gridDim.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, c = lane & 15, g = lane >> 4;
+  const int nch = a.KBp / KC, cps = (nch + SSW - 1) / SSW;
+  const int c0 = ss * cps, c1 = min(nch, c0 + cps);      // this slice's chunks
+  const size_t row_elems = (size_t)a.KBp * BLOCK_ELEMS;
+  const int KBx = a.ldx >> 5, glast = (a.mrows - 1) >> 4;
+  const T* wrow[Q];                                      // tile rows beyond the last one re-read it; their results are dropped
+#pragma unroll
+  for (int q = 0; q < Q; ++q) wrow[q] = a.W + (size_t)min((gi * 4 + wave) * Q + q, a.NT - 1) * row_elems;
+  auto fetch_x = [&](u32x4 (&dst)[AF], int ch) {
+#pragma unroll
+    for (int i = 0; i < AF; ++i) {
+      const int f = wave * AF + i, r = f / KC, j = f % KC;
+      const T* xp = a.X + ((size_t)((a.m0 >> 4) + min(r, glast)) * KBx + ch * KC + j) * BLOCK_ELEMS + lane * 8;
+      dst[i] = *reinterpret_cast<const u32x4*>(xp);
+    }
+  };
+  Frag<T> ring[RING];                                    // ring[j * Q + q] = fragment (tile row q, k-block j)
+#pragma unroll
+  for (int i = 0; i < RING; ++i) ring[i] = frag_load_w(wrow[i % Q] + (size_t)c0 * KC * BLOCK_ELEMS, i / Q, lane);
+  u32x4 xpre[AF];
+  fetch_x(xpre, c0);
+  f32x4 acc[Q][R];
+#pragma unroll
+  for (int q = 0; q < Q; ++q)
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[q][r] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int ch = c0; ch < c1; ++ch) {
+    const int chn = ch + 1 < c1 ? ch + 1 : c0;           // after the last chunk the refill loads go on, harmlessly, into the first
+    u32x4 (&buf)[R * KC][WAVE] = xs[(ch - c0) & 1];
+#pragma unroll
+    for (int i = 0; i < AF; ++i) buf[wave * AF + i][lane] = xpre[i];
+    fetch_x(xpre, chn);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < KC; ++j) {
+      Frag<T> b[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) b[r].v = buf[r * KC + j][lane];
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[q][r] = mma(ring[j * Q + q], b[r], acc[q][r]);
+        ring[j * Q + q] = frag_load_w(wrow[q] + (size_t)chn * KC * BLOCK_ELEMS, j, lane);
+        __builtin_amdgcn_sched_barrier(0x6);             // products and loads keep their program order
+      }
+    }
+  }
+  float* dst = part + (size_t)ss * a.mrows * a.ldo;
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    const int t = (gi * 4 + wave) * Q + q;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int mr = 16 * r + c;
+      if (t < a.NT && mr < a.mrows) *reinterpret_cast<f32x4*>(dst + (size_t)mr * a.ldo + t * TILE_N + 4 * g) = acc[q][r];
+    }
+  }
+}
+
+// h[row] += sum of the nparts parts (in order); hg = h * gain of the next norm; one sum-of-squares partial per row
+// and workgroup.  Workgroup w owns features 32w .. 32w+31 (ldo / 32 <= SSQ_PARTS workgroups); thread = (row mod 32, four features).
+__global__ void __launch_bounds__(256) resid_reduce_kernel(const float* __restrict__ part, int nparts, float* __restrict__ h,
+                                                           float* __restrict__ hg, const float* __restrict__ gain,
+                                                           float* __restrict__ ssq, int m0, int mrows, int ldo) {
+  const int wg = blockIdx.x, nwg = gridDim.x, n = 32 * wg + 4 * (threadIdx.x & 7);
+  const f32x4 gn = *reinterpret_cast<const f32x4*>(gain + n);
+  for (int mr = threadIdx.x >> 3; mr < ((mrows + 31) & ~31); mr += 32) {
+    float sq = 0.f;
+    if (mr < mrows) {
+      f32x4 v = *reinterpret_cast<const f32x4*>(part + (size_t)mr * ldo + n);
+      for (int p = 1; p < nparts; ++p) v += *reinterpret_cast<const f32x4*>(part + ((size_t)p * mrows + mr) * ldo + n);
+      f32x4* hp = reinterpret_cast<f32x4*>(h + (size_t)(m0 + mr) * ldo + n);
+      const f32x4 hv = *hp + v;
+      *hp = hv;
+      *reinterpret_cast<f32x4*>(hg + (size_t)(m0 + mr) * ldo + n) = hv * gn;
+      sq = (hv.x * hv.x + hv.y * hv.y) + (hv.z * hv.z + hv.w * hv.w);
+    }
+    sq += __shfl_xor(sq, 1); sq += __shfl_xor(sq, 2); sq += __shfl_xor(sq, 4);
+    if ((threadIdx.x & 7) == 0 && mr < mrows) {
+      float* dst = ssq + (size_t)(m0 + mr) * SSQ_PARTS;
+      for (int p = wg; p < SSQ_PARTS; p += nwg) dst[p] = p == wg ? sq : 0.f;
+    }
+  }
+}
+
 // xn[row][:] = T(hg[row][:] * rsqrt(mean(h[row]^2) + eps)) for rows m0 + blockIdx.x / nsl: the
 // RMSNorm output as a stored tensor in the fragment-tiled layout, for gemm_rows_kernel.
 // 256 threads; thread p adds slot p of the row's sum-of-squares partials; the nsl workgroups
