@@ -115,7 +115,9 @@ typedef struct {
  * DBL_STREAMK = 1 makes the projection kernel's split-unit form the form of every projection that
  * can take it, 0 switches it off, unset lets the library choose per launch; DBL_WIDE_GU = 0 sends
  * every gate/up projection through the general projection kernel, never through the one that
- * shares the activations of four units through LDS;
+ * shares the activations of four units through LDS; DBL_WIDE_RESID = 0 keeps the output and down
+ * projection of 128-row passes in the general kernel (else: K slices of that shared form plus a
+ * reduce kernel);
  * DBL_ATTN_LDS = 0 switches the attention's shared form (one token range per workgroup, K/V
  * staged through LDS) off, 2 / 3 make it the form wherever a kv head has two 16-row query blocks
  * and some cached tokens (two / one block per wave), 4 keeps the library's choice of when but with
