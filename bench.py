@@ -327,7 +327,9 @@ def main():
         ms, nbytes = B.dbl_bench_projection(ctx, which, M, args.kernel_iters if which != 4 else max(4, args.kernel_iters // 4))
         proj[name] = {"ms": round(ms, 5), "GB/s": round(nbytes / ms / 1e6, 1), "bytes": nbytes}
     dom = proj.get("gate_up_swiglu") or proj["lm_head_stats"]
-    roofline = {"bound": "hbm", "kernel": "gemm_rows_kernel<EPI_SWIGLU> after xn_kernel (fused gate/up projection of one layer)",
+    # (the headline workload's 8 rows run it in gemm_rows_kernel; many-row and some 16-row passes in gemm_wide_swiglu_kernel)
+    gu_kernel = "gemm_rows_kernel<EPI_SWIGLU>" if args.workload == "llama70b_ctx2048_k8_b1_greedy" else "the gate/up projection kernel"
+    roofline = {"bound": "hbm", "kernel": gu_kernel + " after xn_kernel (fused gate/up projection of one layer)",
                 "achieved": dom["GB/s"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(dom["GB/s"] / HBM_PEAK_GBPS, 4), "traffic": None,
                 "bytes_per_launch": dom["bytes"], "ms_per_launch": dom["ms"]}
