@@ -880,21 +880,37 @@ __global__ void __launch_bounds__(256) resid_reduce_kernel(const float* __restri
                                                            float* __restrict__ ssq, int m0, int mrows, int ldo) {
   const int wg = blockIdx.x, nwg = gridDim.x, n = 32 * wg + 4 * (threadIdx.x & 7);
   const f32x4 gn = *reinterpret_cast<const f32x4*>(gain + n);
-  for (int mr = threadIdx.x >> 3; mr < ((mrows + 31) & ~31); mr += 32) {
-    float sq = 0.f;
-    if (mr < mrows) {
-      f32x4 v = *reinterpret_cast<const f32x4*>(part + (size_t)mr * ldo + n);
-      for (int p = 1; p < nparts; ++p) v += *reinterpret_cast<const f32x4*>(part + ((size_t)p * mrows + mr) * ldo + n);
-      f32x4* hp = reinterpret_cast<f32x4*>(h + (size_t)(m0 + mr) * ldo + n);
-      const f32x4 hv = *hp + v;
-      *hp = hv;
-      *reinterpret_cast<f32x4*>(hg + (size_t)(m0 + mr) * ldo + n) = hv * gn;
-      sq = (hv.x * hv.x + hv.y * hv.y) + (hv.z * hv.z + hv.w * hv.w);
+  // four rows per thread at a time, all their loads requested before the first sum (rows beyond the pass re-read the last one)
+  for (int mb = threadIdx.x >> 3; mb < ((mrows + 127) & ~127); mb += 128) {
+    f32x4 v[4], hv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int mr = min(mb + 32 * u, mrows - 1);
+      v[u] = *reinterpret_cast<const f32x4*>(part + (size_t)mr * ldo + n);
+      hv[u] = *reinterpret_cast<const f32x4*>(h + (size_t)(m0 + mr) * ldo + n);
     }
-    sq += __shfl_xor(sq, 1); sq += __shfl_xor(sq, 2); sq += __shfl_xor(sq, 4);
-    if ((threadIdx.x & 7) == 0 && mr < mrows) {
-      float* dst = ssq + (size_t)(m0 + mr) * SSQ_PARTS;
-      for (int p = wg; p < SSQ_PARTS; p += nwg) dst[p] = p == wg ? sq : 0.f;
+    for (int p = 1; p < nparts; ++p) {
+      f32x4 x[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) x[u] = *reinterpret_cast<const f32x4*>(part + ((size_t)p * mrows + min(mb + 32 * u, mrows - 1)) * ldo + n);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] += x[u];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int mr = mb + 32 * u;
+      float sq = 0.f;
+      if (mr < mrows) {
+        const f32x4 r = hv[u] + v[u];
+        *reinterpret_cast<f32x4*>(h + (size_t)(m0 + mr) * ldo + n) = r;
+        *reinterpret_cast<f32x4*>(hg + (size_t)(m0 + mr) * ldo + n) = r * gn;
+        sq = (r.x * r.x + r.y * r.y) + (r.z * r.z + r.w * r.w);
+      }
+      sq += __shfl_xor(sq, 1); sq += __shfl_xor(sq, 2); sq += __shfl_xor(sq, 4);
+      if ((threadIdx.x & 7) == 0 && mr < mrows) {
+        float* dst = ssq + (size_t)(m0 + mr) * SSQ_PARTS;
+        for (int p = wg; p < SSQ_PARTS; p += nwg) dst[p] = p == wg ? sq : 0.f;
+      }
     }
   }
 }
