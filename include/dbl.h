@@ -116,7 +116,7 @@ typedef struct {
  * can take it, 0 switches it off, unset lets the library choose per launch; DBL_WIDE_GU = 0 sends
  * every gate/up projection through the general projection kernel, never through the one that
  * shares the activations of four units through LDS; DBL_WIDE_RESID = 0 keeps the output and down
- * projection of 128-row passes in the general kernel (else: K slices of that shared form plus a
+ * projection of many-row passes in the general kernel (else: K slices of that shared form plus a
  * reduce kernel);
  * DBL_ATTN_LDS = 0 switches the attention's shared form (one token range per workgroup, K/V
  * staged through LDS) off, 2 / 3 make it the form wherever a kv head has two 16-row query blocks

@@ -114,7 +114,7 @@ struct dbl_ctx {
   int* sk_cnt = nullptr;            //   arrivals per unit (zero between launches)
   int attn_lds = 1;                 // attention's shared (LDS-staged) form: 1 where it pays, 0 never, 2 wherever a kv head has two query blocks and a cached split exists, 3 / 4 like 2 / 1 with one query block per wave (DBL_ATTN_LDS at create)
   int attn_nb = 2;                  // query blocks per wave of the attention where it pays; DBL_ATTN_NB at create: 1 never, 3 wherever possible
-  int wide_resid = 1;               // output / down projection of 128-row passes through gemm_wide_slice_kernel (DBL_WIDE_RESID=0 at create: never)
+  int wide_resid = 1;               // output / down projection of many-row passes through gemm_wide_slice_kernel (DBL_WIDE_RESID=0 at create: never)
   int wide_gu = 1;                  // gate/up through gemm_wide_swiglu_kernel where wide_gate_up says so (DBL_WIDE_GU=0 at create: always through gemm_rows_kernel)
   int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never (DBL_STREAMK at create)
   float *qkv_part = nullptr, *logits = nullptr;
@@ -316,11 +316,12 @@ static bool wide_gate_up(const dbl_ctx* c, const GemmPlan& p, int mrows) {
   return 20 * nu < 19 * r * ch.grid;
 }
 
-// Output / down projection of a 128-row pass through gemm_wide_slice_kernel + resid_reduce_kernel (bf16): 0 if not,
-// else the number of K slices.  The groups of 16 tile rows times the slices should about fill the chip; at 64 rows
-// and fewer the parts cost what the shared activations gain, so gemm_rows_kernel keeps those.
+// Output / down projection of a pass of more than 32 rows through gemm_wide_slice_kernel + resid_reduce_kernel (bf16):
+// 0 if not, else the number of K slices.  The groups of 16 tile rows times the slices should about fill the chip; at
+// 64 rows the parts cost the output projection what the shared activations gain, so gemm_rows_kernel keeps it.
 static int wide_resid_slices(const dbl_ctx* c, const GemmPlan& p, int mrows) {
-  if (!c->bf16 || !c->wide_resid || !c->wide_part || mrows <= 64 || p.KBp % 4 != 0) return 0;
+  if (!c->bf16 || !c->wide_resid || !c->wide_part || mrows <= 32 || p.KBp % 4 != 0) return 0;
+  if (mrows <= 64 && p.KBp < 512) return 0;   // (64 rows: only the long-K down projection gains, 90.5 -> 86 us)
   if (p.ldo() % 32 != 0 || p.ldo() / 32 > SSQ_PARTS || p.ldo() != c->ldh) return 0;
   const int ng = (p.NT + 15) / 16, nch = p.KBp / 4;
   int ssw = std::min({c->n_cu / ng, nch, WIDE_SLICES});
@@ -377,7 +378,8 @@ void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
         // gate/up: four units per workgroup on one set of activations staged through LDS, where that is the better form
         if (epi == EPI_RESIDUAL) {
           if (const int ssw = wide_resid_slices(c, p, a.mrows)) {
-            hipLaunchKernelGGL((gemm_wide_slice_kernel<T, 8>), dim3((p.NT + 15) / 16, ssw), dim3(256), 0, c->stream, a, c->wide_part);
+            if (a.mrows > 64) hipLaunchKernelGGL((gemm_wide_slice_kernel<T, 8>), dim3((p.NT + 15) / 16, ssw), dim3(256), 0, c->stream, a, c->wide_part);
+            else hipLaunchKernelGGL((gemm_wide_slice_kernel<T, 4>), dim3((p.NT + 15) / 16, ssw), dim3(256), 0, c->stream, a, c->wide_part);
             hipLaunchKernelGGL(resid_reduce_kernel, dim3(a.ldo / 32), dim3(256), 0, c->stream, c->wide_part, ssw, a.out, a.hg_out,
                                a.gain_out, c->ssq, a.m0, a.mrows, a.ldo);
             continue;
@@ -824,7 +826,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
       ALLOC(sk_part, (size_t)2 * SSQ_PARTS * 4 * rg * 1024, false);
       ALLOC(sk_cnt, (size_t)std::max({c->p_qkv.NT, c->p_o.NT, c->p_gu.NT, c->p_d.NT}) * 4, true);
     }
-    if (c->bf16 && Mmax > 64) ALLOC(wide_part, (size_t)WIDE_SLICES * Mmax * std::max(c->p_o.ldo(), c->p_d.ldo()) * 4, false);
+    if (c->bf16 && Mmax > 32) ALLOC(wide_part, (size_t)WIDE_SLICES * Mmax * std::max(c->p_o.ldo(), c->p_d.ldo()) * 4, false);
     ALLOC(qkv_part, (size_t)c->p_qkv.SS * Mmax * c->p_qkv.ldo() * 4, true);
     ALLOC(qbuf, (size_t)g.max_batch * g.n_kv_heads * c->qrows_pad * g.head_dim * esz, true);
     ALLOC(logits, (size_t)Mmax * c->p_lm.ldo() * 4, true);

@@ -801,7 +801,8 @@ __global__ void __launch_bounds__(256) gemm_wide_swiglu_kernel(const GemmArgs<T>
   }
 }
 
-// Output and down projection of 128-row passes (R = 8), bf16: gemm_wide_swiglu_kernel's form -- four
+// Output and down projection of 128-row passes (R = 8) and down projection of 64-row passes (R = 4), bf16:
+// gemm_wide_swiglu_kernel's form -- four
 // units of 4 tile rows per workgroup on one set of activations staged through LDS -- for matrices
 // whose 32 groups of 16 tile rows do not fill the chip: K is cut into gridDim.y slices of whole chunks,
 // workgroup (x, y) multiplies group x with slice y and stores its sums as part y of the result,
