@@ -100,7 +100,7 @@ typedef struct {
  * every norm gain is 1.  `hip_stream` (a hipStream_t, NULL = default stream) is
  * borrowed: all later work of this context is enqueued on it.
  * Limits: head_dim in {64, 128}; n_q_heads % n_kv_heads == 0;
- * 1 <= max_window; max_batch*max_window <= 128; max_ctx % 64 == 0.
+ * 1 <= max_window <= 32; max_batch*max_window <= 128; max_ctx % 64 == 0.
  * KV cache: by default one region of max_ctx positions per sequence.  With
  * DBL_FLAG_PAGED_KV (higher concurrency, App. D.1: many sequences of very different
  * lengths) it is a pool of pages of 256 positions shared by all sequences; flags >> 8 is the
@@ -148,6 +148,17 @@ int dbl_reset(dbl_ctx* ctx, int seq);
  * unit scale in every layer (not the model's own keys and values) and kv_len[seq] = n_tokens;
  * the history is not touched.  0 <= n_tokens <= max_ctx - max_window.  Only enqueues. */
 int dbl_kv_fill(dbl_ctx* ctx, int seq, int32_t n_tokens, uint64_t seed);
+
+/* Read / overwrite the cached keys and values of rows pos0 .. pos0+n-1 of sequence `seq` in one layer
+ * (restoring a stored prefix cache; tests compare the cache with the oracle's and plant known rows).
+ * host_k / host_v: [n][n_kv_heads][head_dim] in the model dtype (bf16 as uint16_t bit patterns, or float):
+ * the keys as the cache holds them (after q/k-norm and RoPE) and the values.  The library converts from /
+ * to its own tiled (or paged) layout.  kv_len is not touched: rows at or beyond it are dead until a commit
+ * or dbl_kv_fill covers them.  0 <= pos0, pos0 + n <= max_ctx; a paged cache hands the sequence the pages
+ * dbl_kv_set needs (DBL_ENOMEM when the pool is empty), dbl_kv_get needs them to be there.  Both allocate a
+ * staging buffer and synchronise: set-up calls, not part of a step. */
+int dbl_kv_set(dbl_ctx* ctx, int seq, int layer, int32_t pos0, int32_t n, const void* host_k, const void* host_v);
+int dbl_kv_get(dbl_ctx* ctx, int seq, int layer, int32_t pos0, int32_t n, void* host_k, void* host_v);
 
 /* Rollback (Alg. 1 "rollback M_q", Alg. 2 "rollback both models"): sequence `seq`
  * forgets the KV rows beyond kv_len and the history tokens beyond hist_len:
@@ -299,7 +310,8 @@ int dbl_kv_commit(dbl_ctx* ctx, const int32_t* n_keep_dev);
 
 /* Synchronises the stream and copies kv_len[0..max_batch) / hist_len to the host;
  * also refreshes the host-side upper bounds used for argument checks.  Returns
- * DBL_ESTATE if a device-side capacity check (max_ctx, max_hist) had to clamp. */
+ * DBL_ESTATE if a device-side capacity check (max_ctx, max_hist) had to clamp since the
+ * last report; the condition is reported once (and forgotten by dbl_reset of all sequences). */
 int dbl_kv_len(dbl_ctx* ctx, int32_t* host_out);
 int dbl_hist_len(dbl_ctx* ctx, int32_t* host_out);
 

@@ -78,7 +78,7 @@ def lib():
         L.orc_verify_block.argtypes = [C.c_void_p, C.c_void_p, i32p, C.c_int, f64p, f64p]
         L.orc_accept_greedy.argtypes = [f64p, C.c_int, C.c_int, i32p, i32p, i32p, i32p, f64p]
         L.orc_accept_sample.argtypes = [f64p, C.c_int, C.c_int, i32p, f32p, C.c_double, C.c_uint64,
-                                        C.c_uint64, C.c_int, i32p, i32p, i32p, f64p, f64p]
+                                        C.c_uint64, C.c_int, i32p, i32p, i32p, f64p, f64p, f64p]
         L.orc_retrieve.argtypes = [i32p, C.c_int, C.c_int, C.c_int, C.c_int, i32p, i32p, i32p, i32p]
         L.orc_retrieve_tiered.argtypes = [i32p, C.c_int, i32p, C.c_int, C.c_int, i32p, C.c_int, C.c_int, C.c_int,
                                           C.c_int, i32p, i32p, i32p, i32p, i32p]
@@ -247,7 +247,9 @@ def accept_greedy(logits, window):
     return n.value, emit, guide, margin
 
 
-def accept_sample(logits, window, q, T, seed, step, b=0):
+def accept_sample(logits, window, q, T, seed, step, b=0, guide_gaps=False):
+    """(n_acc, emit, guide, acceptance margins, gap of the emitted token's draw); with
+    guide_gaps=True a sixth item: the score gap of every row's own draw guide[j]."""
     z = np.ascontiguousarray(logits, dtype=np.float64)
     w = np.ascontiguousarray(window, dtype=np.int32)
     k, V = z.shape
@@ -259,10 +261,13 @@ def accept_sample(logits, window, q, T, seed, step, b=0):
     guide = np.empty(k, np.int32)
     am = np.empty(k, np.float64)
     gap = C.c_double(0.0)
+    gg = np.empty(k, np.float64)
     lib().orc_accept_sample(_p(z, C.c_double), k, V, _p(w, C.c_int32),
                             None if qa is None else _p(qa, C.c_float), float(T), seed, step, b,
                             C.byref(n), _p(emit, C.c_int32), _p(guide, C.c_int32),
-                            _p(am, C.c_double), C.byref(gap))
+                            _p(am, C.c_double), C.byref(gap), _p(gg, C.c_double))
+    if guide_gaps:
+        return n.value, emit, guide, am, gap.value, gg
     return n.value, emit, guide, am, gap.value
 
 

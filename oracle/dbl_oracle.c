@@ -495,17 +495,23 @@ static int gumbel_draw(const double *w, int V, uint64_t seed, uint64_t step, int
  * extra token is drawn from p_{k-1}.  Nothing of the rows after n is used:
  * guide[j] for j <= n is a draw from p_j made with row j's Gumbel noise (the
  * target's own sample at that row), and -1 for j > n.
+ * Diagnostics for parity tests (none of them feeds a decision):
  * acc_margin[j] = |u_j q_j(x) - p_j(x)| for the rows tested (else -1);
- * draw_gap = Gumbel-max score gap of the emitted token's draw. */
+ * draw_gap = Gumbel-max score gap of the emitted token's draw;
+ * guide_gap (may be NULL) [k]: the same gap for row j's own draw guide[j], -1 for j > n. */
 void orc_accept_sample(const double *logits, int k, int V, const int32_t *window,
                        const float *q, double T, uint64_t seed, uint64_t step, int b,
                        int32_t *n_acc, int32_t *emit, int32_t *guide,
-                       double *acc_margin, double *draw_gap) {
+                       double *acc_margin, double *draw_gap, double *guide_gap) {
   double *p = (double *)malloc(sizeof(double) * V);
   double *w = (double *)malloc(sizeof(double) * V);
   uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
   int n = k - 1;
-  for (int j = 0; j < k; ++j) { guide[j] = -1; emit[j] = -1; if (acc_margin) acc_margin[j] = -1.0; }
+  for (int j = 0; j < k; ++j) {
+    guide[j] = -1; emit[j] = -1;
+    if (acc_margin) acc_margin[j] = -1.0;
+    if (guide_gap) guide_gap[j] = -1.0;
+  }
   for (int j = 0; j < k - 1; ++j) {
     const int x = window[j + 1];
     softmax_T(logits + (size_t)j * V, V, T, p);
@@ -518,7 +524,7 @@ void orc_accept_sample(const double *logits, int k, int V, const int32_t *window
   }
   for (int j = 0; j <= n; ++j) {
     softmax_T(logits + (size_t)j * V, V, T, p);
-    guide[j] = gumbel_draw(p, V, seed, step, b, j, NULL);
+    guide[j] = gumbel_draw(p, V, seed, step, b, j, guide_gap ? guide_gap + j : NULL);
   }
   softmax_T(logits + (size_t)n * V, V, T, p);
   int tok;

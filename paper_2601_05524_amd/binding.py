@@ -23,6 +23,7 @@ T_EMB, T_LM, T_GF = 0, 1, 2
 T_G1, T_WQ, T_WK, T_WV, T_GQ, T_GK, T_WO, T_G2, T_WG, T_WU, T_WD = range(10, 21)
 
 EXPORTS = ["dbl_create", "dbl_destroy", "dbl_last_error", "dbl_set_weights", "dbl_get_weights", "dbl_reset", "dbl_truncate", "dbl_kv_fill",
+           "dbl_kv_set", "dbl_kv_get",
            "dbl_retrieve_tiered", "dbl_session_mark", "dbl_prior_set", "dbl_rejected_update", "dbl_rejected_get",
            "dbl_history_set", "dbl_history_get", "dbl_retrieve", "dbl_build_window", "dbl_verify_block", "dbl_verify_block_ragged", "dbl_accept",
            "dbl_kv_commit", "dbl_kv_len", "dbl_hist_len", "dbl_model_bytes", "dbl_debug_buffer",
@@ -64,6 +65,8 @@ def lib():
         L.dbl_reset.argtypes = [vp, i]
         L.dbl_truncate.argtypes = [vp, i, C.c_int32, C.c_int32]
         L.dbl_kv_fill.argtypes = [vp, i, C.c_int32, C.c_uint64]
+        L.dbl_kv_set.argtypes = [vp, i, i, C.c_int32, C.c_int32, vp, vp]
+        L.dbl_kv_get.argtypes = [vp, i, i, C.c_int32, C.c_int32, vp, vp]
         L.dbl_retrieve_tiered.argtypes = [vp, i, i, i, i, i32p, i32p, i32p, i32p, i32p]
         L.dbl_prior_set.argtypes = [vp, i32p, i]
         L.dbl_session_mark.argtypes = [vp, i, C.c_int32]
@@ -135,6 +138,14 @@ def dbl_reset(ctx, seq=-1):
 
 def dbl_kv_fill(ctx, seq, n_tokens, seed):
     return _chk(ctx, lib().dbl_kv_fill(ctx, seq, int(n_tokens), int(seed)))
+
+
+def dbl_kv_set(ctx, seq, layer, pos0, n, host_k, host_v):
+    return _chk(ctx, lib().dbl_kv_set(ctx, seq, layer, int(pos0), int(n), _ptr(host_k), _ptr(host_v)))
+
+
+def dbl_kv_get(ctx, seq, layer, pos0, n, host_k, host_v):
+    return _chk(ctx, lib().dbl_kv_get(ctx, seq, layer, int(pos0), int(n), _ptr(host_k), _ptr(host_v)))
 
 
 def dbl_truncate(ctx, seq, kv_len=-1, hist_len=-1):

@@ -738,6 +738,7 @@ void free_all(dbl_ctx* c) {
 int check_status(dbl_ctx* c) {
   int32_t s = 0;
   HIPCHK(c, hipMemcpy(&s, c->status, sizeof(s), hipMemcpyDeviceToHost));
+  if (s) HIPCHK(c, hipMemset(c->status, 0, sizeof(s)));   // reported once: later calls start clean
   if (s) return fail(c, DBL_ESTATE, (s & 1) ? "a commit would exceed max_ctx and was clamped" : "a commit would exceed max_hist and was clamped");
   return DBL_OK;
 }
@@ -921,7 +922,7 @@ int dbl_reset(dbl_ctx* c, int seq) {
   for (int b = 0; b < c->cfg.max_batch; ++b)
     if (seq < 0 || b == seq) release_pages(c, b, 0);
   hipLaunchKernelGGL(set_counters_kernel, dim3(1), dim3(128), 0, c->stream, c->kv_len, c->hist_len, c->prompt_len, c->rej_len, seq,
-                     c->cfg.max_batch);
+                     c->cfg.max_batch, c->status);
   HIPCHK(c, hipGetLastError());
   return DBL_OK;
 }
@@ -955,6 +956,62 @@ int dbl_kv_fill(dbl_ctx* c, int seq, int32_t n_tokens, uint64_t seed) {
   hipLaunchKernelGGL(set_kv_len_kernel, dim3(1), dim3(64), 0, c->stream, c->kv_len, seq, n_tokens);
   HIPCHK(c, hipGetLastError());
   return DBL_OK;
+}
+
+static int kv_rows_io(dbl_ctx* c, int seq, int layer, int32_t pos0, int32_t n, void* host_k, void* host_v, bool to_cache) {
+  if (!c) return DBL_EINVAL;
+  const dbl_model_cfg& g = c->cfg;
+  if (seq < 0 || seq >= g.max_batch) return fail(c, DBL_EINVAL, "seq out of range");
+  if (layer < 0 || layer >= g.n_layers) return fail(c, DBL_EINVAL, "layer out of range");
+  if (pos0 < 0 || n < 0 || (int64_t)pos0 + n > g.max_ctx) return fail(c, DBL_EINVAL, "rows out of range");
+  if (n > 0 && (!host_k || !host_v)) return fail(c, DBL_EINVAL, "null buffer");
+  if (c->dry) return DBL_ENODEV;
+  if (n == 0) return DBL_OK;
+  if (c->paged) {
+    if (to_cache) { const int rc = ensure_pages(c, seq, pos0 + n); if (rc != DBL_OK) return rc; }
+    else if ((int)c->seq_pages[seq].size() * KV_PAGE < pos0 + n) return fail(c, DBL_EINVAL, "rows beyond the sequence's pages");
+  }
+  const size_t elems = (size_t)n * g.n_kv_heads * g.head_dim, bytes = elems * c->esz;
+  void *sk = nullptr, *sv = nullptr;
+  int rc = dmalloc(c, &sk, bytes, false);
+  if (rc == DBL_OK) rc = dmalloc(c, &sv, bytes, false);
+  auto done = [&](int code) { if (sk) (void)hipFree(sk); if (sv) (void)hipFree(sv); return code; };
+  if (rc != DBL_OK) return done(rc);
+  hipError_t e = hipSuccess;
+  if (to_cache) {
+    e = hipMemcpyAsync(sk, host_k, bytes, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(sv, host_v, bytes, hipMemcpyHostToDevice, c->stream);
+  }
+  if (e == hipSuccess) {
+    const size_t region = (size_t)g.max_ctx * g.head_dim;
+    const size_t seq_off = c->paged ? 0 : (size_t)seq * g.n_kv_heads * region;
+    const int32_t* pages = c->paged ? c->page_table + (size_t)seq * c->pps : nullptr;
+    const dim3 grid((unsigned)((elems + 255) / 256));
+    const size_t loff = (size_t)layer * c->kv_layer_elems;
+    if (c->bf16)
+      hipLaunchKernelGGL((kv_rows_kernel<bf16_t>), grid, dim3(256), 0, c->stream, reinterpret_cast<bf16_t*>(c->kc) + loff,
+                         reinterpret_cast<bf16_t*>(c->vt) + loff, reinterpret_cast<bf16_t*>(sk), reinterpret_cast<bf16_t*>(sv),
+                         seq_off, region, pages, (int)pos0, (int)n, g.n_kv_heads, g.head_dim, to_cache ? 1 : 0);
+    else
+      hipLaunchKernelGGL((kv_rows_kernel<float>), grid, dim3(256), 0, c->stream, reinterpret_cast<float*>(c->kc) + loff,
+                         reinterpret_cast<float*>(c->vt) + loff, reinterpret_cast<float*>(sk), reinterpret_cast<float*>(sv),
+                         seq_off, region, pages, (int)pos0, (int)n, g.n_kv_heads, g.head_dim, to_cache ? 1 : 0);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess && !to_cache) {
+    e = hipMemcpyAsync(host_k, sk, bytes, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(host_v, sv, bytes, hipMemcpyDeviceToHost, c->stream);
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return done(fail(c, DBL_EHIP, std::string("kv rows: ") + hipGetErrorString(e)));
+  return done(DBL_OK);
+}
+
+int dbl_kv_set(dbl_ctx* c, int seq, int layer, int32_t pos0, int32_t n, const void* host_k, const void* host_v) {
+  return kv_rows_io(c, seq, layer, pos0, n, const_cast<void*>(host_k), const_cast<void*>(host_v), true);
+}
+int dbl_kv_get(dbl_ctx* c, int seq, int layer, int32_t pos0, int32_t n, void* host_k, void* host_v) {
+  return kv_rows_io(c, seq, layer, pos0, n, host_k, host_v, false);
 }
 
 int dbl_truncate(dbl_ctx* c, int seq, int32_t kv_len, int32_t hist_len) {

@@ -406,9 +406,12 @@ __global__ void commit_kernel(int32_t* __restrict__ kv_len, int32_t* __restrict_
   if (threadIdx.x == 0) *commits += 1;
 }
 
-__global__ void set_counters_kernel(int32_t* kv_len, int32_t* hist_len, int32_t* prompt_len, int32_t* rej_len, int seq, int B) {
+// (a flush of every sequence also clears the capacity status word)
+__global__ void set_counters_kernel(int32_t* kv_len, int32_t* hist_len, int32_t* prompt_len, int32_t* rej_len, int seq, int B,
+                                    int32_t* status) {
   const int b = threadIdx.x;
   if (b < B && (seq < 0 || b == seq)) { kv_len[b] = 0; hist_len[b] = 0; prompt_len[b] = 0; rej_len[b] = 0; }
+  if (b == 0 && seq < 0) *status = 0;
 }
 
 __global__ void truncate_kernel(int32_t* kv_len, int32_t* hist_len, int32_t* prompt_len, int seq, int new_kv, int new_hist) {
@@ -490,6 +493,24 @@ __global__ void fill_kv_kernel(T* __restrict__ kc, T* __restrict__ vt, size_t re
   else off = (size_t)l * layer_stride + (size_t)r * region + i;
   kc[off] = Elem<T>::from_f(32.f * weight_value(seed, 30, (int)blockIdx.y, i));
   vt[off] = Elem<T>::from_f(32.f * weight_value(seed, 31, (int)blockIdx.y, i));
+}
+
+// Copy rows pos0 .. pos0+n-1 of one (layer, sequence) between the tiled cache and a staging buffer in the
+// logical order [row][kv head][dim]; to_cache != 0 writes the cache.  kc / vt point at the layer; seq_off is
+// the sequence's offset in the contiguous form, pages its page-table row in the paged form.
+template <typename T>
+__global__ void kv_rows_kernel(T* __restrict__ kc, T* __restrict__ vt, T* __restrict__ stage_k, T* __restrict__ stage_v,
+                               size_t seq_off, size_t region, const int32_t* __restrict__ pages, int pos0, int n, int Hkv,
+                               int hd, int to_cache) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)n * Hkv * hd) return;
+  const int d = (int)(i % hd), h = (int)(i / hd % Hkv), t = pos0 + (int)(i / ((size_t)hd * Hkv));
+  size_t base; int tt = t;
+  if (pages) { tt = t % KV_PAGE; base = ((size_t)pages[t / KV_PAGE] * Hkv + h) * ((size_t)KV_PAGE * hd); }
+  else base = seq_off + (size_t)h * region;
+  const size_t ko = base + kc_offset(tt, d, hd), vo = base + vt_offset(tt, d, hd);
+  if (to_cache) { kc[ko] = stage_k[i]; vt[vo] = stage_v[i]; }
+  else { stage_k[i] = kc[ko]; stage_v[i] = vt[vo]; }
 }
 
 __global__ void set_page_kernel(int32_t* table, int idx, int32_t page) { if (threadIdx.x == 0) table[idx] = page; }

@@ -257,6 +257,12 @@ def sample_margin_ok(lg_ref, w, q, T, u_margin, gap, n, err):
     return gap > 1.5 * rel + 1e-6
 
 
+def guide_rows(guide_gap, n, T, err):
+    """Rows j <= n whose own draw (the guidance Eq. 6 consumes) is decided by more than the logit
+    error can move: the same rule as for the emitted token's draw."""
+    return [j for j in range(n + 1) if guide_gap[j] > 1.5 * (2.0 * err / T) + 1e-6]
+
+
 @pytest.mark.parametrize("dense", [False, True], ids=["one_hot_q", "dense_q"])
 def test_sampling_accept_parity(dense):
     shape = SMALL_BF16
@@ -268,7 +274,7 @@ def test_sampling_accept_parity(dense):
     prompts = [synth.zipf_history(20 + b, 40, V) for b in range(2)]
     g.prefill(prompts, 8)
     r.prefill(prompts, 8)
-    compared, exempt, n_hist = 0, 0, []
+    compared, exempt, n_hist, guides = 0, 0, [], 0
     for step in range(30):
         ws, qs, refs = [], [], []
         for b in range(2):
@@ -291,12 +297,16 @@ def test_sampling_accept_parity(dense):
         for b in range(2):
             err = np.abs(lg[b] - refs[b]).max()
             assert err <= 8.0 * TOL[1]
-            n_ref, e_ref, gd_ref, am, gap = O.accept_sample(refs[b], ws[b], qs[b], T, 0xABCDEF0123,
-                                                            1000 + step + commits, b)
+            n_ref, e_ref, gd_ref, am, gap, gg = O.accept_sample(refs[b], ws[b], qs[b], T, 0xABCDEF0123,
+                                                                1000 + step + commits, b, guide_gaps=True)
             if sample_margin_ok(refs[b], ws[b], qs[b], T, am, gap, n_ref, err):
                 assert n[b] == n_ref, (step, b)
                 assert np.array_equal(emit[b], e_ref), (step, b)
                 assert np.array_equal(guide[b][n_ref + 1:], gd_ref[n_ref + 1:])
+                # the target's own draws up to the first rejection: what forward guidance consumes
+                rows = guide_rows(gg, n_ref, T, err)
+                assert np.array_equal(guide[b][rows], gd_ref[rows]), (step, b, rows)
+                guides += len(rows)
                 compared += 1
             else:
                 exempt += 1
@@ -306,6 +316,7 @@ def test_sampling_accept_parity(dense):
         for b in range(2):
             B.dbl_history_set(g.ctx, b, r.seqs[b].history())
     assert compared >= 36, (compared, exempt)
+    assert guides >= 2 * compared, (guides, compared)
     assert len(set(n_hist)) >= 3, "accepted lengths should vary: %s" % sorted(set(n_hist))
     g.close()
 
@@ -356,10 +367,13 @@ def test_stress_shape_batch4_ragged_contexts_windows_4_to_32():
         for b in range(Bn):
             err = np.abs(lg[b] - refs[b]).max()
             assert err <= 8.0 * TOL[1], (k, b, err)     # sharpened LM head: 8 x the logit scale
-            n_ref, e_ref, gd_ref, am, gap = O.accept_sample(refs[b], ws[b], None, T, seed, 50 + step + commits, b)
+            n_ref, e_ref, gd_ref, am, gap, gg = O.accept_sample(refs[b], ws[b], None, T, seed, 50 + step + commits, b,
+                                                                guide_gaps=True)
             if sample_margin_ok(refs[b], ws[b], None, T, am, gap, n_ref, err):
                 assert n[b] == n_ref, (k, b)
                 assert np.array_equal(emit[b], e_ref), (k, b)
+                rows = guide_rows(gg, n_ref, T, err)
+                assert np.array_equal(guide[b][rows], gd_ref[rows]) and (guide[b][n_ref + 1:] == -1).all(), (k, b, rows)
                 compared += 1
             else:
                 exempt += 1

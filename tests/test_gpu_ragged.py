@@ -10,7 +10,7 @@ import oracle as O
 from paper_2601_05524_amd import binding as B
 from paper_2601_05524_amd import synth
 from tests.gpu_util import Gpu, Ref
-from tests.test_gpu_parity import SMALL_BF16, TINY, TOL, pair, sample_margin_ok, sharpen
+from tests.test_gpu_parity import SMALL_BF16, TINY, TOL, guide_rows, pair, sample_margin_ok, sharpen
 
 pytestmark = pytest.mark.gpu
 
@@ -150,10 +150,13 @@ def test_ragged_sampling_accept(dense):
             err = np.abs(lg[b][:L] - refs[b]).max()
             assert err <= 8.0 * TOL[1]
             q_ref = qs[b] if (dense and L > 1) else None
-            n_ref, e_ref, gd_ref, am, gap = O.accept_sample(refs[b], ws[b], q_ref, T, seed, 500 + step + commits, b)
+            n_ref, e_ref, gd_ref, am, gap, gg = O.accept_sample(refs[b], ws[b], q_ref, T, seed, 500 + step + commits, b,
+                                                                guide_gaps=True)
             if sample_margin_ok(refs[b], ws[b], q_ref, T, am, gap, n_ref, err):
                 assert n[b] == n_ref, (step, b, L)
                 assert np.array_equal(emit[b][:n_ref + 1], e_ref[:n_ref + 1]), (step, b, L)
+                rows = guide_rows(gg, n_ref, T, err)
+                assert np.array_equal(guide[b][rows], gd_ref[rows]) and (guide[b][n_ref + 1:] == -1).all(), (step, b, rows)
                 compared += 1
             else:
                 exempt += 1

@@ -114,7 +114,7 @@ def test_llama70b_width_lm_head_sampling_statistics():
     """The fused LM-head statistics over the full vocabulary (8016 tiles, 256 workgroups x 4 waves) in
     sampling mode: accepted lengths and emitted tokens against the oracle's acceptance on the
     oracle's own logits, for windows whose decisions lie outside the measured logit error."""
-    from tests.test_gpu_parity import sample_margin_ok
+    from tests.test_gpu_parity import guide_rows, sample_margin_ok
     shape = slice_of("llama70b")
     r, saved = reference("llama70b", 31)
     g = Gpu(shape, seed=31, max_ctx=512, max_window=8)
@@ -141,10 +141,12 @@ def test_llama70b_width_lm_head_sampling_statistics():
         err = np.abs(got - ref).max()
         assert err <= TOL_BF16
         n, emit, guide = g.accept(B.DBL_SAMPLE)
-        n_ref, e_ref, gd_ref, am, gap = O.accept_sample(ref, w, None, T, seed, 100 + step + g.ncommit, 0)
+        n_ref, e_ref, gd_ref, am, gap, gg = O.accept_sample(ref, w, None, T, seed, 100 + step + g.ncommit, 0, guide_gaps=True)
         if sample_margin_ok(ref, w, None, T, am, gap, n_ref, err):
             assert n[0] == n_ref, step
             assert np.array_equal(emit[0], e_ref), step
+            rows = guide_rows(gg, n_ref, T, err)          # the target's own draws up to the rejection
+            assert np.array_equal(guide[0][rows], gd_ref[rows]) and (guide[0][n_ref + 1:] == -1).all(), (step, rows)
             compared += 1
         lengths.append(n_ref)
         g.commit([1]); s.commit(1, [])
@@ -152,6 +154,56 @@ def test_llama70b_width_lm_head_sampling_statistics():
     assert compared >= 3
     for (t, l), v in saved.items():
         r.set_tensor(t, l, v)
+    g.close()
+
+
+@pytest.mark.parametrize("name,k,T", [("llama70b", 8, 1.0), ("qwen32b", 16, 0.7)])
+def test_full_vocabulary_dense_q_acceptance_and_residual_draw(name, k, T):
+    """Speculative sampling with dense draft distributions at the full vocabulary (128 256 and 151 936
+    entries), the case the 32B-shaped and the long-context workloads name: the acceptance test
+    u q(x) < p(x) with q read from the caller's rows, and at the first rejection the draw from
+    max(0, p - q), one pass of the acceptance kernel over a full row of logits and a full row of q.
+    Layer-less models of the full width (embedding -> final norm -> LM head), so the oracle is cheap.
+    The leading drafts are the oracle's most likely tokens (they survive), then comes a draft that q
+    favours heavily and p does not (a rejection at a known row), so the residual draw happens at rows
+    0 .. 3.  Windows whose decisions lie inside the measured logit error are not compared."""
+    from tests.test_gpu_parity import guide_rows, sample_margin_ok
+    shape = dict(synth.CONFIGS[name], n_layers=0)
+    _REF.clear()
+    r = Ref(shape, seed=33, max_batch=1, max_ctx=64)
+    g = Gpu(shape, seed=33, max_ctx=64, max_window=k)
+    V, seed = shape["vocab"], 0xD15EA5E + k
+    rng = np.random.default_rng(k)
+    s = r.seqs[0]
+    compared, rejected_at = 0, []
+    for step in range(6):
+        n_good = step % 4                       # drafts that should survive
+        w = [int(rng.integers(0, V))]
+        for j in range(k - 1):                  # (no layers: a row's logits depend on its own token only)
+            w.append(int(s.verify_block([w[-1]])[0].argmax()) if j < n_good else int(rng.integers(0, V)))
+        w = np.array(w, np.int32)
+        ref = s.verify_block(w)
+        q = synth.dense_q(7000 + step, k - 1, V, T, mix_logits=ref[:k - 1] * 1.5)
+        x = w[n_good + 1]                       # the first random draft: q puts half of its mass there
+        q[n_good] *= np.float32(0.5)
+        q[n_good, x] += np.float32(0.5)
+        got = g.verify([w], temperature=T, seed=seed, step=300 + step)[0]
+        err = np.abs(got - ref).max()
+        assert err <= TOL_BF16
+        n, emit, guide = g.accept(B.DBL_SAMPLE, q[None])
+        n_ref, e_ref, gd_ref, am, gap, gg = O.accept_sample(ref, w, q, T, seed, 300 + step + g.ncommit, 0, guide_gaps=True)
+        rejected_at.append(n_ref)
+        if sample_margin_ok(ref, w, q, T, am, gap, n_ref, err):
+            assert n[0] == n_ref, step
+            assert np.array_equal(emit[0], e_ref), step
+            if n_ref < k - 1:                    # a token drawn from the residual has p > q
+                assert q[n_ref, e_ref[n_ref]] < np.exp(ref[n_ref, e_ref[n_ref]] / T - np.log(np.exp(ref[n_ref] / T).sum()))
+            rows = guide_rows(gg, n_ref, T, err)
+            assert np.array_equal(guide[0][rows], gd_ref[rows]) and (guide[0][n_ref + 1:] == -1).all(), (step, rows)
+            compared += 1
+    print("%s vocabulary %d: compared %d of 6 windows, first rejections at rows %s, max logit error %.3g"
+          % (name, V, compared, rejected_at, err))
+    assert compared >= 4 and len(set(rejected_at)) >= 3
     g.close()
 
 

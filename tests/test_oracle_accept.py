@@ -248,3 +248,35 @@ def test_sampling_streams_are_keyed():
     diff_b = sum(list(O.accept_sample(z, w, None, 1.0, 1, 0, b=b)[1]) != list(base[1]) for b in range(1, 20))
     diff_seed = sum(list(O.accept_sample(z, w, None, 1.0, sd, 0)[1]) != list(base[1]) for sd in range(2, 21))
     assert min(diff, diff_b, diff_seed) >= 15
+
+
+def test_guide_draws_and_their_gaps_match_an_independent_recomputation():
+    """guide[j] is row j's own Gumbel-max draw from p_j and guide_gap[j] the winner's score minus
+    the runner-up's: recomputed here from the python-integer Philox of tests/test_oracle_rng.py
+    (counter {step, b, j, 1 + v/4}, word v%4, u = ((x >> 9) + 0.5) / 2^23), for every row up to
+    the first rejection; rows behind it report -1.  The first guide of many seeds follows p_0."""
+    from tests.test_oracle_rng import py_philox
+    rng = np.random.default_rng(3)
+    V, k, T, seed, b = 11, 4, 0.8, 0xC0FFEE1234, 3
+    counts = np.zeros(V, int)
+    z0 = rng.normal(0, 1.5, size=V)
+    for step in range(400):
+        z = rng.normal(0, 1.5, size=(k, V))
+        z[0] = z0
+        w = [int(t) for t in rng.integers(0, V, size=k)]
+        n, emit, guide, am, gap, gg = O.accept_sample(z, w, None, T, seed, step, b=b, guide_gaps=True)
+        for j in range(k):
+            if j > n:
+                assert guide[j] == -1 and gg[j] == -1.0
+                continue
+            sc = np.empty(V)
+            for v in range(V):
+                x = py_philox([step, b, j, 1 + v // 4], [seed & 0xffffffff, seed >> 32])[v % 4]
+                u = ((int(x) >> 9) + 0.5) / 8388608.0
+                sc[v] = z[j, v] / T - np.log(-np.log(u))       # log p_v + Gumbel_v up to the row's constant
+            order = np.argsort(-sc)
+            assert guide[j] == order[0]
+            assert abs(gg[j] - (sc[order[0]] - sc[order[1]])) < 1e-9
+        counts[guide[0]] += 1
+    p0 = np.exp(z0 / T - (z0 / T).max()); p0 /= p0.sum()
+    assert stats.chisquare(counts, p0 * counts.sum()).pvalue > 1e-4
