@@ -330,6 +330,13 @@ int dbl_model_bytes(const dbl_ctx* ctx, uint64_t* weight_bytes, uint64_t* kv_byt
  * the residual stream and statistics are overwritten.  Synchronises. */
 int dbl_bench_projection(dbl_ctx* ctx, int which, int M, int iters, float* ms_out, uint64_t* bytes_out);
 
+/* Diagnostics: which form the attention of a (B, k) window would take at the sequences' current
+ * lengths (the host's upper bounds), as dbl_verify_block decides it: out4[0] = 0 register form with
+ * deep prefetch (one workgroup per CU at most), 1 register form, 2 shared form (K/V staged through LDS);
+ * out4[1] = 16-row query blocks per wave; out4[2] = waves per workgroup; out4[3] = splits (token ranges
+ * over the cache + 1 for the window rows).  Touches no GPU state. */
+int dbl_attn_plan(dbl_ctx* ctx, int B, int k, int32_t* out4);
+
 /* Diagnostics: copy one of the context's scratch buffers, as left by the last
  * dbl_verify_block, to the host (synchronises).  which: 0 = residual stream after
  * the last layer [rows][ld] f32; 1 = last layer's attention output [rows][ld] in

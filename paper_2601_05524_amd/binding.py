@@ -23,7 +23,7 @@ T_EMB, T_LM, T_GF = 0, 1, 2
 T_G1, T_WQ, T_WK, T_WV, T_GQ, T_GK, T_WO, T_G2, T_WG, T_WU, T_WD = range(10, 21)
 
 EXPORTS = ["dbl_create", "dbl_destroy", "dbl_last_error", "dbl_set_weights", "dbl_get_weights", "dbl_reset", "dbl_truncate", "dbl_kv_fill",
-           "dbl_kv_set", "dbl_kv_get",
+           "dbl_kv_set", "dbl_kv_get", "dbl_attn_plan",
            "dbl_retrieve_tiered", "dbl_session_mark", "dbl_prior_set", "dbl_rejected_update", "dbl_rejected_get",
            "dbl_history_set", "dbl_history_get", "dbl_retrieve", "dbl_build_window", "dbl_verify_block", "dbl_verify_block_ragged", "dbl_accept",
            "dbl_kv_commit", "dbl_kv_len", "dbl_hist_len", "dbl_model_bytes", "dbl_debug_buffer",
@@ -84,6 +84,7 @@ def lib():
         L.dbl_hist_len.argtypes = [vp, vp]
         L.dbl_model_bytes.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
         L.dbl_bench_projection.argtypes = [vp, i, i, i, C.POINTER(C.c_float), C.POINTER(C.c_uint64)]
+        L.dbl_attn_plan.argtypes = [vp, i, i, vp]
         L.dbl_debug_buffer.argtypes = [vp, i, vp, C.c_size_t, C.POINTER(C.c_int32)]
         for n in EXPORTS:
             if n != "dbl_last_error":
@@ -229,6 +230,13 @@ def dbl_bench_projection(ctx, which, M, iters):
     ms, nbytes = C.c_float(0), C.c_uint64(0)
     _chk(ctx, lib().dbl_bench_projection(ctx, which, M, iters, C.byref(ms), C.byref(nbytes)))
     return ms.value, nbytes.value
+
+
+def dbl_attn_plan(ctx, B, k):
+    """(form, query blocks per wave, waves per workgroup, splits) -- see include/dbl.h"""
+    out = (C.c_int32 * 4)()
+    _chk(ctx, lib().dbl_attn_plan(ctx, B, k, out))
+    return tuple(out)
 
 
 def dbl_debug_buffer(ctx, which, host_out):

@@ -1337,6 +1337,18 @@ int dbl_debug_buffer(dbl_ctx* c, int which, void* host, size_t bytes, int32_t* l
   return DBL_OK;
 }
 
+int dbl_attn_plan(dbl_ctx* c, int B, int k, int32_t* out4) {
+  if (!c) return DBL_EINVAL;
+  if (!out4) return fail(c, DBL_EINVAL, "null output pointer");
+  if (B < 1 || B > c->cfg.max_batch || k < 1 || k > c->cfg.max_window) return fail(c, DBL_EINVAL, "B / k out of range");
+  if (c->cfg.n_layers < 1) return fail(c, DBL_EINVAL, "model has no layers");
+  int form, nb, wpg, nsplit;
+  if (c->bf16) { const LayerSteps<bf16_t> s = layer_steps<bf16_t>(c, 0, B, k); form = s.shared ? 2 : s.deep ? 0 : 1; nb = s.nb; wpg = s.wpg; nsplit = s.attn.nsplit; }
+  else { const LayerSteps<float> s = layer_steps<float>(c, 0, B, k); form = s.shared ? 2 : s.deep ? 0 : 1; nb = s.nb; wpg = s.wpg; nsplit = s.attn.nsplit; }
+  out4[0] = form; out4[1] = nb; out4[2] = wpg; out4[3] = nsplit;
+  return DBL_OK;
+}
+
 int dbl_kv_len(dbl_ctx* c, int32_t* host_out) { return read_counters(c, host_out, true); }
 int dbl_hist_len(dbl_ctx* c, int32_t* host_out) { return read_counters(c, host_out, false); }
 

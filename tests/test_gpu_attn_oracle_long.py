@@ -70,7 +70,10 @@ def residual_stream(g, rows, d):
     return buf.ravel()[:n * ld].reshape(n, ld)[:rows, :d].astype(np.float64)
 
 
-def run(shape, ks, k_scale, seed):
+SHARED = 2      # dbl_attn_plan's code of the shared form
+
+
+def run(shape, ks, k_scale, seed, forms):
     g = Gpu(shape, seed=seed, max_batch=4, max_ctx=MAX_CTX, max_window=32, max_hist=64)
     r = Ref(shape, seed=seed, max_batch=4, max_ctx=MAX_CTX, max_hist=64)
     d, F, V = shape["d_model"], shape["d_ffn"], shape["vocab"]
@@ -81,6 +84,9 @@ def run(shape, ks, k_scale, seed):
     rng = np.random.default_rng(seed)
     for k in ks:
         ws = rng.integers(0, V, (4, k)).astype(np.int32)
+        form, nb, nw, nsplit = B.dbl_attn_plan(g.ctx, 4, k)
+        print("%d-row window: form %d, %d block(s) per wave, %d waves, %d splits" % (k, form, nb, nw, nsplit))
+        assert (form, nw, nb) == (SHARED,) + forms[k] and nsplit >= 16
         got = g.verify(ws)
         hid = residual_stream(g, 4 * k, d).reshape(4, k, d)
         for b in range(4):
@@ -92,8 +98,9 @@ def run(shape, ks, k_scale, seed):
             herr = np.abs(upd - upd_ref).max() / scale
             print("%d-row window, sequence %d (%d cached tokens): logits max-abs %.3g (rms %.3g), "
                   "attention update max error / rms %.3g" % (k, b, LENS[b], err, np.sqrt((ref ** 2).mean()), herr))
-            assert np.isfinite(got[b]).all() and err <= 2e-2
-            assert scale > 1e-3 and herr <= 2e-2, (k, b, herr)
+            # 2e-2 is the bar at the full-size models' logit scale (rms 1.8); this model's logits are smaller
+            assert np.isfinite(got[b]).all() and err <= 2e-2 * min(1.0, np.sqrt((ref ** 2).mean()) / 1.8)
+            assert scale > 1e-3 and herr <= 8e-3, (k, b, herr)      # measured <= 2e-3
             # the window rows' keys and values the step appended, against the oracle's cache rows
             kb, vb = np.empty((k, Hkv, hd), np.uint16), np.empty((k, Hkv, hd), np.uint16)
             B.dbl_kv_get(g.ctx, b, 0, LENS[b], k, kb, vb)
@@ -107,12 +114,13 @@ def run(shape, ks, k_scale, seed):
 
 
 def test_stress_geometry_windows_4_to_32_against_the_oracle():
-    run(LLAMA_LIKE, (4, 8, 16, 32), 16.0, 61)         # peaked scores: a few tokens carry each row
+    # peaked scores: a few tokens carry each row.  (waves, blocks per wave) by window size
+    run(LLAMA_LIKE, (4, 8, 16, 32), 16.0, 61, {4: (2, 1), 8: (4, 1), 16: (4, 2), 32: (8, 2)})
 
 
 def test_stress_geometry_flat_scores_against_the_oracle():
-    run(LLAMA_LIKE, (16,), 1.0, 63)                  # flat scores: every range contributes alike
+    run(LLAMA_LIKE, (16,), 1.0, 63, {16: (4, 2)})    # flat scores: every range contributes alike
 
 
 def test_qwen_geometry_16_row_window_against_the_oracle():
-    run(QWEN_LIKE, (16,), 3.0, 62)
+    run(QWEN_LIKE, (16,), 3.0, 62, {16: (8, 1)})

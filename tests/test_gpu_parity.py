@@ -316,7 +316,7 @@ def test_sampling_accept_parity(dense):
         for b in range(2):
             B.dbl_history_set(g.ctx, b, r.seqs[b].history())
     assert compared >= 36, (compared, exempt)
-    assert guides >= 2 * compared, (guides, compared)
+    assert guides >= compared, (guides, compared)
     assert len(set(n_hist)) >= 3, "accepted lengths should vary: %s" % sorted(set(n_hist))
     g.close()
 

@@ -66,7 +66,9 @@ def test_matches_library_decoder(dtype, qk_norm):
     toks = rng.integers(0, 97, 23).astype(np.int32)
     got, _ = run_chunks(m, toks, [5, 1, 8, 4, 2, 3])
     ref = forward_full(m, toks)
-    assert np.abs(ref).max() > 0.3
+    # sanity only: the comparison below is not between two near-zero tensors.  The largest reference logit of
+    # the four cases is 0.501, 0.499 (fp32 with q/k-norm), 0.527, 0.526 -- hence 0.45 and not 0.5
+    assert np.abs(ref).max() > 0.45
     if dtype == 0:
         # only difference: the oracle's cos/sin go through an fp32 table
         np.testing.assert_allclose(got, ref, rtol=0, atol=2e-6)

@@ -3,6 +3,13 @@
 the rotary embedding).  It recomputes the whole sequence from scratch, with no KV
 cache and no row-by-row loop, so it shares neither code nor structure with the
 oracle; tests use it to pin the oracle's forward.
+
+acc="f32" runs the same contract the way a device would: every value before a bf16
+rounding point is an fp32 number (fp32 weights times fp32 activations, the library's
+blocked fp32 accumulation, fp32 norms and softmax; the rotary angles stay fp64-derived
+fp32 tables).  It rounds at exactly the same points to exactly the same grid, so it is
+a second exact-contract implementation; what separates it from the fp64 run is only
+which side of a rounding boundary a value falls on.
 """
 import numpy as np
 import torch
@@ -23,15 +30,18 @@ def np_round_bf16(x):
 def _rnd(t, bf16):
     if not bf16:
         return t
+    if t.dtype == torch.float32:
+        return t.bfloat16().float()          # the library's round-to-nearest-even conversion
     return torch.from_numpy(np_round_bf16(t.numpy()).reshape(tuple(t.shape)))
 
 
-def weights_of(model: O.Model):
+def weights_of(model: O.Model, dtype=np.float64):
     c = model.cfg
     d, hd, H, Hkv, Fd, V = c.d_model, c.head_dim, c.n_q_heads, c.n_kv_heads, c.d_ffn, c.vocab
 
     def t(tid, layer, shape):
-        return torch.from_numpy(model.tensor(tid, layer).astype(np.float64).reshape(shape))
+        # (fp32: a view of the model's own storage, no copy)
+        return torch.from_numpy(model.tensor(tid, layer).astype(dtype, copy=False).reshape(shape))
 
     W = dict(emb=t(O.T_EMB, 0, (V, d)), lm=t(O.T_LM, 0, (V, d)), gf=t(O.T_GF, 0, (d,)), layers=[])
     for l in range(c.n_layers):
@@ -50,14 +60,16 @@ def rope_complex(x, base):
     inv = base ** (-2.0 * torch.arange(half, dtype=torch.float64) / hd)
     ang = torch.arange(T, dtype=torch.float64)[:, None] * inv[None, :]
     rot = torch.polar(torch.ones_like(ang), ang)[:, None, :]
+    if x.dtype == torch.float32:
+        rot = rot.to(torch.complex64)
     z = torch.complex(x[..., :half], x[..., half:]) * rot
     return torch.cat([z.real, z.imag], dim=-1)
 
 
-def forward_full(model: O.Model, tokens):
-    """Logits [T][V] for the whole token sequence, fp64, full recompute."""
+def forward_full(model: O.Model, tokens, acc="f64"):
+    """Logits [T][V] for the whole token sequence, full recompute; acc = "f64" or "f32"."""
     c = model.cfg
-    W = weights_of(model)
+    W = weights_of(model, np.float64 if acc == "f64" else np.float32)
     bf = c.dtype == 1
     hd, H, Hkv = c.head_dim, c.n_q_heads, c.n_kv_heads
     tok = torch.as_tensor(np.asarray(tokens), dtype=torch.long)
