@@ -5,7 +5,7 @@ batch 4, windows of 4 .. 32 rows) run the attention in its shared form: one toke
 workgroup, K/V staged through LDS, 2 / 4 / 8 waves with one or two 16-row query blocks each, and
 tens of splits whose partial results are merged afterwards.  The oracle cannot prefill such a cache
 at full width in a test's time, so this test keeps the head geometry (8 query heads per kv head,
-head_dim 128, batch 4 with ragged lengths of 8192 .. 10 000 tokens, some of them ending inside a
+head_dim 128, batch 4 with ragged lengths of 8192 .. 12 800 tokens, some of them ending inside a
 32-token step) and narrows everything else (d_model 256, one layer, MLP switched off).  The cached
 keys and values are seeded bf16 values written into both caches -- dbl_kv_set on the GPU, the
 oracle's cache arrays on the CPU -- so neither side prefills.  The library picks the form and the
@@ -27,8 +27,8 @@ from tests.gpu_util import Gpu, Ref, bf16_bits_to_f32, f32_to_bf16_bits
 
 pytestmark = pytest.mark.gpu
 
-MAX_CTX = 10240
-LENS = [8192, 8211, 9001, 10000]
+MAX_CTX = 12864
+LENS = [8192, 8211, 9001, 12800]
 
 # 16 (b, kv head) pairs: windows of 4 / 8 / 16 / 32 rows take the shared form with 2 waves x 1 block,
 # 4 x 1, 4 x 2 and 8 x 2 -- the forms of the long-context stress workload
