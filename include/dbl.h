@@ -206,6 +206,23 @@ int dbl_retrieve_tiered(dbl_ctx* ctx, int B, int n_max, int n_min, int max_cont,
                         int32_t* cont_len_dev, int32_t* match_n_dev, int32_t* match_pos_dev,
                         int32_t* match_tier_dev);
 
+/*
+ * dbl_retrieve_tiered for callers that cannot allocate and want no allocated scratch behind the call:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same results, same stream behaviour; the difference is where the search keeps its one piece of scratch
+ * (one packed best key per sequence): not in memory the context allocated, but in a fixed array that is
+ * part of the loaded library on every GPU it runs on (DBL_STATIC_MAX_BATCH x 8 bytes per GPU, held until
+ * the process ends; its device address is looked up once per device, in dbl_create).  The call allocates
+ * and frees nothing, runs no allocating library routine and records no memset: it enqueues one small fill
+ * kernel (the array keeps the previous call's contents and is cleared first) and the two search kernels.
+ * B > DBL_STATIC_MAX_BATCH is rejected with DBL_EINVAL.  All contexts on one GPU share the array: calls
+ * that overlap on one GPU (two streams, two contexts) race on it -- run them one after the other.
+ */
+#define DBL_STATIC_MAX_BATCH 128
+int dbl_retrieve_tiered_static(dbl_ctx* ctx, int B, int n_max, int n_min, int max_cont, int32_t* cont_dev,
+                               int32_t* cont_len_dev, int32_t* match_n_dev, int32_t* match_pos_dev,
+                               int32_t* match_tier_dev);
+
 /* Mark the first prompt_len tokens of sequence `seq`'s history as the prompt; what follows
  * counts as the session's generated text (tier 1).  dbl_history_set marks all it sets as
  * prompt; this call is for a caller that restores a running session.  0 <= prompt_len;

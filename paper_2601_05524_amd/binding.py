@@ -24,7 +24,7 @@ T_G1, T_WQ, T_WK, T_WV, T_GQ, T_GK, T_WO, T_G2, T_WG, T_WU, T_WD = range(10, 21)
 
 EXPORTS = ["dbl_create", "dbl_destroy", "dbl_last_error", "dbl_set_weights", "dbl_get_weights", "dbl_reset", "dbl_truncate", "dbl_kv_fill",
            "dbl_kv_set", "dbl_kv_get", "dbl_attn_plan",
-           "dbl_retrieve_tiered", "dbl_session_mark", "dbl_prior_set", "dbl_rejected_update", "dbl_rejected_get",
+           "dbl_retrieve_tiered", "dbl_retrieve_tiered_static", "dbl_session_mark", "dbl_prior_set", "dbl_rejected_update", "dbl_rejected_get",
            "dbl_history_set", "dbl_history_get", "dbl_retrieve", "dbl_build_window", "dbl_verify_block", "dbl_verify_block_ragged", "dbl_accept",
            "dbl_kv_commit", "dbl_kv_len", "dbl_hist_len", "dbl_model_bytes", "dbl_debug_buffer",
            "dbl_bench_projection"]
@@ -68,6 +68,7 @@ def lib():
         L.dbl_kv_set.argtypes = [vp, i, i, C.c_int32, C.c_int32, vp, vp]
         L.dbl_kv_get.argtypes = [vp, i, i, C.c_int32, C.c_int32, vp, vp]
         L.dbl_retrieve_tiered.argtypes = [vp, i, i, i, i, i32p, i32p, i32p, i32p, i32p]
+        L.dbl_retrieve_tiered_static.argtypes = [vp, i, i, i, i, i32p, i32p, i32p, i32p, i32p]
         L.dbl_prior_set.argtypes = [vp, i32p, i]
         L.dbl_session_mark.argtypes = [vp, i, C.c_int32]
         L.dbl_rejected_update.argtypes = [vp, i32p]
@@ -171,6 +172,11 @@ def dbl_retrieve(ctx, B, n_max, n_min, max_cont, cont, cont_len, match_n, match_
 def dbl_retrieve_tiered(ctx, B, n_max, n_min, max_cont, cont, cont_len, match_n, match_pos, match_tier):
     return _chk(ctx, lib().dbl_retrieve_tiered(ctx, B, n_max, n_min, max_cont, _ptr(cont), _ptr(cont_len),
                                                _ptr(match_n), _ptr(match_pos), _ptr(match_tier)))
+
+
+def dbl_retrieve_tiered_static(ctx, B, n_max, n_min, max_cont, cont, cont_len, match_n, match_pos, match_tier):
+    return _chk(ctx, lib().dbl_retrieve_tiered_static(ctx, B, n_max, n_min, max_cont, _ptr(cont), _ptr(cont_len),
+                                                      _ptr(match_n), _ptr(match_pos), _ptr(match_tier)))
 
 
 def dbl_session_mark(ctx, seq, prompt_len):

@@ -82,6 +82,28 @@ bool make_plan(GemmPlan& p, int N, int K, int nacc, bool is_bf16, PlanKind kind,
 
 }  // namespace
 
+// Scratch of dbl_retrieve_tiered_static: one packed best key per sequence, in device memory that belongs to the
+// loaded library itself (every GPU the library runs on holds its own copy until the process ends), so that the
+// call needs no allocation of anyone's.  In host code the array's name is only a stand-in: the address a kernel
+// can use comes from hipGetSymbolAddress, once per device, and is kept in g_static_scratch[device].
+constexpr int STATIC_MAX_BATCH = DBL_STATIC_MAX_BATCH;
+constexpr int STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned long long dbl_static_scratch[STATIC_MAX_BATCH];
+static unsigned long long* g_static_scratch[STATIC_MAX_DEVICES] = {};
+
+// Device address of this device's copy of the scratch array (the device must be current); nullptr + *err on failure.
+static unsigned long long* static_scratch_of(int device, hipError_t* err) {
+  *err = hipSuccess;
+  if (device < 0 || device >= STATIC_MAX_DEVICES) { *err = hipErrorInvalidDevice; return nullptr; }
+  if (!g_static_scratch[device]) {
+    void* p = nullptr;
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(dbl_static_scratch));
+    if (*err != hipSuccess) return nullptr;
+    g_static_scratch[device] = reinterpret_cast<unsigned long long*>(p);
+  }
+  return g_static_scratch[device];
+}
+
 struct dbl_ctx {
   dbl_model_cfg cfg{};
   bool bf16 = true, dry = false;
@@ -772,6 +794,9 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
     if (e != hipSuccess) { delete c; return DBL_EHIP; }
     int ncu = 0;
     if (hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && ncu > 0) c->n_cu = ncu;
+    // the library's own scratch on this device (dbl_retrieve_tiered_static): resolved here, once per device
+    (void)static_scratch_of(c->device, &e);
+    if (e != hipSuccess) { std::fprintf(stderr, "dbl_create: hipGetSymbolAddress: %s\n", hipGetErrorString(e)); delete c; return DBL_EHIP; }
   }
   rc = make_plans(c);
   if (rc != DBL_OK) { delete c; return rc; }
@@ -1071,26 +1096,46 @@ int dbl_retrieve(dbl_ctx* c, int B, int n_max, int n_min, int max_cont, int32_t*
   return DBL_OK;
 }
 
-int dbl_retrieve_tiered(dbl_ctx* c, int B, int n_max, int n_min, int max_cont, int32_t* cont, int32_t* cont_len,
-                        int32_t* match_n, int32_t* match_pos, int32_t* match_tier) {
+// Both forms of the tiered retrieval; use_static: the best keys live in the library's static scratch
+// (cleared by a small kernel first: the array is shared by every call on this GPU and keeps the last one's contents).
+static int retrieve_tiered_impl(dbl_ctx* c, bool use_static, int B, int n_max, int n_min, int max_cont, int32_t* cont,
+                                int32_t* cont_len, int32_t* match_n, int32_t* match_pos, int32_t* match_tier) {
   if (!c) return DBL_EINVAL;
   if (!cont || !cont_len || !match_n || !match_pos || !match_tier) return fail(c, DBL_EINVAL, "null output pointer");
   if (B < 1 || B > c->cfg.max_batch) return fail(c, DBL_EINVAL, "B out of range");
+  if (use_static && B > STATIC_MAX_BATCH) return fail(c, DBL_EINVAL, "B exceeds the static scratch (DBL_STATIC_MAX_BATCH sequences)");
   if (n_min < 1 || n_max < n_min || n_max > 32) return fail(c, DBL_EINVAL, "need 1 <= n_min <= n_max <= 32");
   if (max_cont < 1 || max_cont > 64) return fail(c, DBL_EINVAL, "need 1 <= max_cont <= 64");
   if (c->dry) return DBL_ENODEV;
+  unsigned long long* best = c->tier_best;
+  if (use_static) {
+    hipError_t e = hipSuccess;
+    best = static_scratch_of(c->device, &e);      // resolved by dbl_create; the look-up is a table read here
+    if (!best) return fail(c, DBL_EHIP, std::string("hipGetSymbolAddress: ") + hipGetErrorString(e));
+    hipLaunchKernelGGL(fill_u64_kernel, dim3(1), dim3(STATIC_MAX_BATCH), 0, c->stream, best, 0ull, B);
+  }
   TierArgs a{};
   a.prior = c->prior; a.prior_len = c->prior_len;
   a.hist = c->hist; a.hist_len = c->hist_len; a.prompt_len = c->prompt_len; a.max_hist = c->cfg.max_hist;
   a.rej = c->rej; a.rej_len = c->rej_len; a.rej_cap = c->cfg.max_hist;
   a.n_max = n_max; a.n_min = n_min; a.max_cont = max_cont;
   a.cont = cont; a.cont_len = cont_len; a.match_n = match_n; a.match_pos = match_pos; a.match_tier = match_tier;
-  a.best = c->tier_best;
+  a.best = best;
   const int chunks = std::max(1, (c->prior_len + TIER_CHUNK - 1) / TIER_CHUNK);
   hipLaunchKernelGGL(retrieve_tiered_scan_kernel, dim3(chunks, B), dim3(1024), 0, c->stream, a);
   hipLaunchKernelGGL(retrieve_tiered_finish_kernel, dim3(B), dim3(64), 0, c->stream, a);
   HIPCHK(c, hipGetLastError());
   return DBL_OK;
+}
+
+int dbl_retrieve_tiered(dbl_ctx* c, int B, int n_max, int n_min, int max_cont, int32_t* cont, int32_t* cont_len,
+                        int32_t* match_n, int32_t* match_pos, int32_t* match_tier) {
+  return retrieve_tiered_impl(c, false, B, n_max, n_min, max_cont, cont, cont_len, match_n, match_pos, match_tier);
+}
+
+int dbl_retrieve_tiered_static(dbl_ctx* c, int B, int n_max, int n_min, int max_cont, int32_t* cont, int32_t* cont_len,
+                               int32_t* match_n, int32_t* match_pos, int32_t* match_tier) {
+  return retrieve_tiered_impl(c, true, B, n_max, n_min, max_cont, cont, cont_len, match_n, match_pos, match_tier);
 }
 
 int dbl_session_mark(dbl_ctx* c, int seq, int32_t prompt_len) {

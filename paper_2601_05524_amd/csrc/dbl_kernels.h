@@ -421,6 +421,10 @@ __global__ void truncate_kernel(int32_t* kv_len, int32_t* hist_len, int32_t* pro
   }
 }
 
+__global__ void fill_u64_kernel(unsigned long long* p, unsigned long long v, int n) {
+  if ((int)threadIdx.x < n) p[threadIdx.x] = v;
+}
+
 __global__ void fill_i32_kernel(int32_t* p, int32_t v, size_t n) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;

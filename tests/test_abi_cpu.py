@@ -155,6 +155,35 @@ def test_validate_only_context_checks_the_datastore_and_rollback_calls():
     assert B.dbl_destroy(ctx) == 0
 
 
+def test_new_entry_points_check_their_arguments():
+    ctx = B.dbl_create(cfg(), 1)
+    L = B.lib()
+    i32 = np.zeros(64, np.int32)
+    p = C.c_void_p(i32.ctypes.data)
+    ok = B.DBL_ENODEV
+    # the tiered retrieval on the library's static scratch: same checks as dbl_retrieve_tiered
+    assert L.dbl_retrieve_tiered_static(ctx, 2, 3, 1, 8, p, p, p, p, p) == ok
+    assert L.dbl_retrieve_tiered_static(ctx, 3, 3, 1, 8, p, p, p, p, p) == B.DBL_EINVAL       # B > max_batch
+    assert L.dbl_retrieve_tiered_static(ctx, 129, 3, 1, 8, p, p, p, p, p) == B.DBL_EINVAL     # beyond the static array
+    assert L.dbl_retrieve_tiered_static(ctx, 1, 3, 1, 65, p, p, p, p, p) == B.DBL_EINVAL
+    assert L.dbl_retrieve_tiered_static(ctx, 1, 3, 1, 8, p, p, p, p, None) == B.DBL_EINVAL
+    assert L.dbl_retrieve_tiered_static(None, 1, 3, 1, 8, p, p, p, p, p) == B.DBL_EINVAL
+    # cache rows
+    assert L.dbl_kv_set(ctx, 0, 1, 0, 4, p, p) == ok
+    assert L.dbl_kv_get(ctx, 1, 0, 500, 12, p, p) == ok
+    assert L.dbl_kv_set(ctx, 0, 2, 0, 4, p, p) == B.DBL_EINVAL          # layer
+    assert L.dbl_kv_set(ctx, 2, 0, 0, 4, p, p) == B.DBL_EINVAL          # sequence
+    assert L.dbl_kv_set(ctx, 0, 0, 510, 4, p, p) == B.DBL_EINVAL        # beyond max_ctx
+    assert L.dbl_kv_get(ctx, 0, 0, -1, 4, p, p) == B.DBL_EINVAL
+    assert L.dbl_kv_get(ctx, 0, 0, 0, 4, None, p) == B.DBL_EINVAL
+    # attention plan: host logic only, works without a GPU
+    out = (C.c_int32 * 4)()
+    assert L.dbl_attn_plan(ctx, 1, 8, out) == B.DBL_OK and out[3] >= 1
+    assert L.dbl_attn_plan(ctx, 3, 8, out) == B.DBL_EINVAL
+    assert L.dbl_attn_plan(ctx, 1, 8, None) == B.DBL_EINVAL
+    assert B.dbl_destroy(ctx) == 0
+
+
 def test_null_context():
     L = B.lib()
     assert L.dbl_destroy(None) == B.DBL_EINVAL
