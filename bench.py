@@ -119,8 +119,8 @@ def bench_double(args):
         tshape["n_layers"] = args.layers
     room = P + 64 * (n_new + 64)
     kw = dict(max_ctx=((P + 24 * (n_new + 64)) // 64 + 1) * 64, max_window=16, max_hist=room)
-    target = DR.Engine(tshape, synth.BASE_SEED + 2, **kw)
-    draft = DR.Engine(dshape, synth.BASE_SEED + 1, **kw)
+    target = DR.Lane(tshape, synth.BASE_SEED + 2, **kw)
+    draft = DR.Lane(dshape, synth.BASE_SEED + 1, **kw)
     prompt = [int(t) for t in synth.zipf_history(synth.BASE_SEED + 2, P + 1, tshape["vocab"], 1.1, 0.20, 16, 16)]
 
     def timed(fn, reps):
@@ -132,22 +132,21 @@ def bench_double(args):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / reps
 
-    target.sync_to(prompt)
-    draft.sync_to(prompt)
+    target.load(prompt)
+    draft.load(prompt)
     torch.cuda.synchronize()
     # T_p: one target Retrieval Forward; T_q: one draft Retrieval Forward; gamma = ceil(T_p / T_q)
-    T_p = timed(lambda: target.retrieval_forwards(1, k_p, 3, 1, 10), 5)
-    T_q = timed(lambda: draft.retrieval_forwards(1, k_q, 3, 1, 10), 20)
+    T_p = timed(lambda: target.chain(1, k_p), 5)
+    T_q = timed(lambda: draft.chain(1, k_q), 20)
     gamma = max(1, min(args.double_gamma if args.double_gamma > 0 else math.ceil(T_p / T_q), 32))
-    target.collect_history(); draft.collect_history()
 
     res = {}
     # the iterative retrieval drafter alone (Eq. 5): gamma chained Retrieval Forwards of the draft
-    draft.sync_to(prompt)
+    draft.load(prompt)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    draft.retrieval_forwards(gamma, k_q, 3, 1, 10)
-    chain = draft.collect_history()
+    draft.chain(gamma, k_q)
+    chain = draft.generated()
     t_chain = time.perf_counter() - t0
     res["draft_chain"] = {"forwards": gamma, "L_draft": len(chain), "AMT": round(len(chain) / gamma - 1.0, 3),
                           "ms": round(t_chain * 1e3, 3), "ms_per_forward": round(t_chain / gamma * 1e3, 3)}
@@ -156,25 +155,29 @@ def bench_double(args):
     ar = DR.autoregressive(target, prompt, min(n_new, 24))
     res["autoregressive"] = {"tokens": len(ar), "tokens_per_s": round(len(ar) / (time.perf_counter() - t0), 2)}
     # target-only retrieval decoding (the headline step, chained on the device)
-    target.sync_to(prompt)
+    target.load(prompt)
     torch.cuda.synchronize()
     steps = max(8, n_new // 2)
     t0 = time.perf_counter()
-    target.retrieval_forwards(steps, k_p, 3, 1, 10)
-    sd = target.collect_history()
+    target.chain(steps, k_p)
+    sd = target.generated()
     res["target_retrieval_only"] = {"tokens": len(sd), "forwards": steps,
                                     "tokens_per_s": round(len(sd) / (time.perf_counter() - t0), 2)}
     # the full Double round
-    target.sync_to(prompt); draft.sync_to(prompt)
-    torch.cuda.synchronize()
+    dec = DR.DoubleDecoder(target, draft, gamma=gamma, k_p=k_p, k_q=k_q)
+    dec.start(prompt)
     t0 = time.perf_counter()
-    out, rounds = DR.double_decode(target, draft, prompt, n_new, gamma, k_p, k_q)
+    while dec.emitted < n_new:
+        dec.round()
+    out, rounds = target.generated(), dec.rounds
     dt = time.perf_counter() - t0
     res["double"] = {"tokens": len(out), "rounds": len(rounds), "tokens_per_s": round(len(out) / dt, 2),
                      "ms_per_round": round(dt / len(rounds) * 1e3, 3),
                      "post_verify_rounds": sum(r["mode"] == "post" for r in rounds),
                      "drafted_per_round": round(sum(r["drafted"] for r in rounds) / len(rounds), 2)}
-    same = DR.common_prefix(out, sd)
+    same = 0
+    while same < min(len(out), len(sd)) and out[same] == sd[same]:
+        same += 1
     out_line = {
         "metric": "emitted tokens/s of a full Double round (70B-shaped target + 1B-shaped draft on two streams, greedy)",
         "value": res["double"]["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "higher_is_better": True,

@@ -255,6 +255,64 @@ int dbl_build_window(dbl_ctx* ctx, int B, int k, int max_cont, const int32_t* co
                      const int32_t* cont_len_dev, int32_t pad_id, int32_t* window_dev);
 
 /*
+ * The full Double round (Sec. 4.1 "Synchronous Parallel Execution", Sec. 4.2 "Target-Guided Verification",
+ * Eq. 6, Alg. 1 / Alg. 2): a draft model and a target model as two contexts on two streams.  The calls below
+ * keep every token of a round on the device; the caller enqueues them and synchronises once per round.
+ * Per round, with x the text the target has verified and U the drafts behind it that it has not:
+ *   target:  dbl_build_guided_window -> dbl_verify_block -> dbl_accept -> dbl_kv_commit      (x grows by E)
+ *   draft:   gamma Retrieval Forwards from x + U (the calls at the top of this file), dbl_history_tail = X_q
+ *   resolve: dbl_merge (needs both) -> dbl_history_splice on the draft -> next round's U
+ *
+ * dbl_build_guided_window: window[b] = pending token (last token of the history), then the n_ahead[b] unverified
+ * drafts ahead[b][..] (dev, [B][max_ahead]; NULL with n_ahead NULL = none), then the target's own retrieved guidance
+ * Y_p: the continuation dbl_retrieve's rule finds for the end of history + ahead, searched in history + ahead, at most
+ * min(d, free rows) tokens; then pad_id up to k rows.  n_draft_dev[b] = drafts + guidance tokens in the window.
+ * Nothing is written to the history.  n_ahead is clamped to 0..min(k-1, max_ahead).
+ */
+int dbl_build_guided_window(dbl_ctx* ctx, int B, int k, const int32_t* ahead_dev, const int32_t* n_ahead_dev, int max_ahead,
+                            int n_max, int n_min, int d, int32_t pad_id, int32_t* window_dev, int32_t* n_draft_dev);
+
+/*
+ * Eq. 6 on the device, per sequence b.  In (dev): n_u[b] = |U| (drafts at the front of the target's window),
+ * n_acc[b] and emit[b][k] as dbl_accept wrote them (E = emit[b][0..n_acc]: accepted window tokens + the target's own
+ * next token), chain[b][max_chain] / n_chain[b] = X_q, the draft model's new tokens, which continue x + U, and
+ * base_len[b] = length of the draft's history when that chain began (|x| + |U|; may be NULL).
+ * The verified text grows by E in every case.  U' (the next round's unverified drafts) is empty if a token of U was
+ * rejected (n_acc < n_u), if X_q differs from G = E[n_u..] somewhere, or if X_q ends inside G: then the target's tokens
+ * stand (verified draft prefix + target suffix).  Otherwise U' = the tokens of X_q behind G, at most max_u.
+ * Out (dev): u_out[b][max_u] (-1 beyond |U'|), n_u_out[b]; text_out[b][k + max_u] = E + U' and n_text_out[b]: what now
+ * follows the old verified text; splice_pos[b] = base_len[b] - n_u[b] (0 without base_len): where that text starts in
+ * the draft's history; record[b][8] = {n_u, n_acc, |E|, |X_q|, |U'|, leading tokens of X_q equal to G, length of the
+ * draft's old text behind x that is still valid, 0}.  Only enqueues on ctx's stream (any context of the device will
+ * do: nothing of the context is read).  1 <= k <= 32, 1 <= max_chain <= 4096, 1 <= max_u <= 64.
+ */
+int dbl_merge(dbl_ctx* ctx, int B, int k, const int32_t* n_u_dev, const int32_t* n_acc_dev, const int32_t* emit_dev,
+              const int32_t* chain_dev, const int32_t* n_chain_dev, int max_chain, int max_u, const int32_t* base_len_dev,
+              int32_t* u_out_dev, int32_t* n_u_out_dev, int32_t* text_out_dev, int32_t* n_text_out_dev,
+              int32_t* splice_pos_dev, int32_t* record_dev);
+
+/* tokens_out[b][0..n) = history tokens from position from_dev[b] to the end, n = min(their number, max_n) into
+ * n_out[b]; entries beyond n are -1.  Only enqueues.  1 <= max_n <= 4096. */
+int dbl_history_tail(dbl_ctx* ctx, int B, const int32_t* from_dev, int max_n, int32_t* tokens_out_dev, int32_t* n_out_dev);
+
+/* Rollback and re-alignment in one step (Alg. 1 "rollback M_q", Alg. 2 "rollback both models"): the history of
+ * sequence b becomes its first pos[b] tokens followed by tokens[b][0..n[b]) (dev, [B][max_n]).  KV rows of tokens that
+ * did not change are kept; kv_len[b] = min(kv_len[b], first position that changed, new length - 1).
+ * missing_out[b] (may be NULL) = tokens between the cache and the last token, whose KV a forward has to compute
+ * (dbl_catchup_window builds that forward's window).  Only enqueues.  1 <= max_n <= 128. */
+int dbl_history_splice(dbl_ctx* ctx, int B, const int32_t* pos_dev, const int32_t* tokens_dev, const int32_t* n_dev, int max_n,
+                       int32_t* missing_out_dev);
+
+/* window[b][j] = the history tokens at positions kv_len[b] + j that lie in front of the last token, at most k, then
+ * pad_id; win_len[b] = their number.  Run dbl_verify_block_ragged on it and dbl_kv_commit(win_len) to bring the cache
+ * up to the history again.  Only enqueues. */
+int dbl_catchup_window(dbl_ctx* ctx, int B, int k, int32_t pad_id, int32_t* window_dev, int32_t* win_len_dev);
+
+/* Copy the device-side counters kv_len[0..B) / hist_len[0..B) into caller buffers on the device (either may be NULL),
+ * in stream order, without synchronising. */
+int dbl_lengths_dev(dbl_ctx* ctx, int B, int32_t* kv_len_out_dev, int32_t* hist_len_out_dev);
+
+/*
  * Verify forward (Sec. 2.1: one parallel target forward over the drafted tokens;
  * App. D.2: causal mask, row j conditioned on the prefix and rows < j).
  * window_dev is [B][k] token ids in [0, vocab).  For every row: embedding, n_layers

@@ -1,7 +1,7 @@
 """TEST INFRASTRUCTURE ONLY -- reference orchestration of a full Double round on the oracle.
 
 The two-model loop of the paper (Sec. 4.1 "Iterative Retrieval Drafter", "Synchronous Parallel
-Execution"; Sec. 4.2 "Target-Guided Verification", Eq. 6; Alg. 1 / Alg. 2), greedy decoding,
+Execution"; Sec. 4.2 "Target-Guided Verification", Eq. 6; Alg. 1 / Alg. 2), greedy decoding and sampling,
 written as plainly as possible on the oracle's sequences.  Nothing here is fast and nothing
 runs concurrently: "parallel" steps are simply computed one after the other from the same
 starting state, which is what makes them parallelisable.
@@ -26,10 +26,22 @@ output is token-identical to plain greedy decoding of the target, the invariant 
               the rest of X_q becomes the new U (stay in / enter post-verify); at the first
               disagreement the target's tokens win (Eq. 6: verified draft prefix + target's
               suffix, which is x + E) and the draft rolls back.
+
+T > 0 (Sec. 4.2 "Multi-token Pre-verify", Sec. 5.3 "Temperature Sampling", App. D.2 "Stochastic Sampling"): the same
+round with the acceptance rule of speculative sampling in place of the equality test.  Every window token -- U as
+well as Y_p -- is a proposal fixed before the target's randomness of this round is drawn, so it is tested as a point
+proposal: kept with probability p(token), else replaced by a draw from p without that token, and nothing behind a
+rejection is used (the guidance is discarded).  Conditional on the window this emits exact samples of the target,
+whatever produced the window.  The draft model runs its own Retrieval Forwards the same way at the same temperature,
+with its own seed, so its chain is a sample of the draft model.  Step (c) is unchanged: the tokens of E are now the
+target's samples, and X_q survives only where it coincides with them.
+
+Random numbers: an acceptance draws from Philox with the step word the caller names.  The target's acceptance of
+round r uses step r; the draft's j-th Retrieval Forward of round r uses step r * gamma + j (seeds differ).
 """
 import numpy as np
 
-from . import accept_greedy, retrieve
+from . import accept_greedy, accept_sample, retrieve
 
 
 def common_prefix(a, b):
@@ -57,24 +69,54 @@ def padded_window(pending, tokens, k, pad_id=0):
     return w + [pad_id] * (k - len(w))
 
 
-def retrieval_forward(seq, k, n_max, n_min, d):
+def accept(logits, w, temperature, seed, step):
+    """Acceptance over a padded window.  The padding tokens are proposals like any other: under the greedy rule one
+    survives only if it is the model's own choice, under sampling with the probability the model gives it -- either
+    way what is emitted is the model's."""
+    if temperature <= 0.0:
+        n, emit, _, _ = accept_greedy(logits, w)
+    else:
+        n, emit, _, _, _ = accept_sample(logits, w, None, temperature, seed, step, 0)
+    return int(n), [int(t) for t in emit[:n + 1]]
+
+
+def retrieval_forward(seq, k, n_max, n_min, d, temperature=0.0, seed=0, step=0):
     """One Retrieval Forward (Eq. 2) of the sequence's own model: retrieve, verify the window,
     keep what the model itself would have produced.  Returns the emitted tokens."""
     hist = seq.history()
     cont, cl, _, _ = retrieve(hist, n_max, n_min, min(d, k - 1)) if k > 1 else ([], 0, 0, -1)
     w = padded_window(hist[-1], cont[:cl], k)
-    n, emit, _, _ = accept_greedy(seq.verify_block(w), w)
-    seq.commit(n + 1, emit[:n + 1])
-    return [int(t) for t in emit[:n + 1]]
+    n, emit = accept(seq.verify_block(w), w, temperature, seed, step)
+    seq.commit(n + 1, emit)
+    return emit
 
 
-def double_decode(target, draft, prompt, max_new, gamma, k_p, k_q, n_max=3, n_min=1, d=10):
-    """Greedy decoding of `target` (an oracle Seq) helped by `draft` (an oracle Seq of another
-    model with the same vocabulary).  Returns (new tokens, per-round records)."""
+def merge(U, E, Xq, max_u):
+    """Step (c), Eq. 6.  U: the unverified drafts the target's window carried; E: what the target emitted (accepted
+    window tokens + its own next token); Xq: the draft's new chain, which continues x + U.
+    Returns (U_new, agree, valid): the next round's unverified drafts; how many leading tokens of Xq equal G (0 when
+    a token of U was rejected); how much of the draft's text behind x (= U + Xq) is still a prefix of the new text
+    x + E + U_new."""
+    n = len(E) - 1                       # accepted window drafts
+    if n < len(U):                       # a token of U was rejected: E = U[:n] + the target's replacement
+        return [], 0, n
+    G = E[len(U):]
+    agree = common_prefix(Xq, G)
+    if agree == len(G) and len(Xq) > len(G):
+        U_new = [int(t) for t in Xq[len(G):][:max_u]]
+        return U_new, agree, len(U) + len(G) + len(U_new)
+    return [], agree, len(U) + agree
+
+
+def double_decode(target, draft, prompt, max_new, gamma, k_p, k_q, n_max=3, n_min=1, d=10,
+                  temperature=0.0, seed_target=0, seed_draft=0):
+    """Decoding of `target` (an oracle Seq) helped by `draft` (an oracle Seq of another model with the same
+    vocabulary): greedy, or sampling at `temperature` > 0.  Returns (new tokens, per-round records)."""
     x, U, rounds = [int(t) for t in prompt], [], []
     sync_to(target, x)
     sync_to(draft, x)
     while len(x) - len(prompt) < max_new:
+        r = len(rounds)
         # (a) target: pending + U + its own retrieved guidance, padded to k_p rows
         room = k_p - 1 - len(U)
         Y = []
@@ -82,19 +124,14 @@ def double_decode(target, draft, prompt, max_new, gamma, k_p, k_q, n_max=3, n_mi
             cont, cl, _, _ = retrieve(np.asarray(x + U, np.int32), n_max, n_min, min(d, room))
             Y = [int(t) for t in cont[:cl]]
         W = padded_window(x[-1], U + Y, k_p)
-        n, emit, _, _ = accept_greedy(target.verify_block(W), W)
-        E = [int(t) for t in emit[:n + 1]]
+        n, E = accept(target.verify_block(W), W, temperature, seed_target, r)
         # (b) draft: gamma chained Retrieval Forwards from x + U
         Xq = []
-        for _ in range(gamma):
-            Xq += retrieval_forward(draft, k_q, n_max, n_min, d)
+        for j in range(gamma):
+            Xq += retrieval_forward(draft, k_q, n_max, n_min, d, temperature, seed_draft, r * gamma + j)
         # (c) resolve
         target.commit(n + 1, E)
-        U_new = []
-        if n >= len(U):
-            G = E[len(U):]
-            if common_prefix(Xq, G) == len(G) and len(Xq) > len(G):
-                U_new = Xq[len(G):][:k_p - 1]
+        U_new, _, _ = merge(U, E, Xq, k_p - 1)
         rounds.append({"mode": "post" if U else "pre", "n_u": len(U), "n_acc": int(n), "emitted": len(E),
                        "drafted": len(Xq), "kept": len(U_new)})
         x = x + E

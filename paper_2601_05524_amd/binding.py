@@ -24,6 +24,7 @@ T_G1, T_WQ, T_WK, T_WV, T_GQ, T_GK, T_WO, T_G2, T_WG, T_WU, T_WD = range(10, 21)
 
 EXPORTS = ["dbl_create", "dbl_destroy", "dbl_last_error", "dbl_set_weights", "dbl_get_weights", "dbl_reset", "dbl_truncate", "dbl_kv_fill",
            "dbl_kv_set", "dbl_kv_get", "dbl_attn_plan",
+           "dbl_build_guided_window", "dbl_merge", "dbl_history_tail", "dbl_history_splice", "dbl_catchup_window", "dbl_lengths_dev",
            "dbl_retrieve_tiered", "dbl_retrieve_tiered_static", "dbl_session_mark", "dbl_prior_set", "dbl_rejected_update", "dbl_rejected_get",
            "dbl_history_set", "dbl_history_get", "dbl_retrieve", "dbl_build_window", "dbl_verify_block", "dbl_verify_block_ragged", "dbl_accept",
            "dbl_kv_commit", "dbl_kv_len", "dbl_hist_len", "dbl_model_bytes", "dbl_debug_buffer",
@@ -77,6 +78,12 @@ def lib():
         L.dbl_history_get.argtypes = [vp, i, vp, i, C.POINTER(C.c_int32)]
         L.dbl_retrieve.argtypes = [vp, i, i, i, i, i32p, i32p, i32p, i32p]
         L.dbl_build_window.argtypes = [vp, i, i, i, i32p, i32p, C.c_int32, i32p]
+        L.dbl_build_guided_window.argtypes = [vp, i, i, i32p, i32p, i, i, i, i, C.c_int32, i32p, i32p]
+        L.dbl_merge.argtypes = [vp, i, i, i32p, i32p, i32p, i32p, i32p, i, i, i32p, i32p, i32p, i32p, i32p, i32p, i32p]
+        L.dbl_history_tail.argtypes = [vp, i, i32p, i, i32p, i32p]
+        L.dbl_history_splice.argtypes = [vp, i, i32p, i32p, i32p, i, i32p]
+        L.dbl_catchup_window.argtypes = [vp, i, i, C.c_int32, i32p, i32p]
+        L.dbl_lengths_dev.argtypes = [vp, i, i32p, i32p]
         L.dbl_verify_block.argtypes = [vp, i32p, i, i, C.c_float, C.c_uint64, C.c_uint64, vp]
         L.dbl_verify_block_ragged.argtypes = [vp, i32p, i32p, i, i, C.c_float, C.c_uint64, C.c_uint64, vp]
         L.dbl_accept.argtypes = [vp, i, vp, i32p, i32p, i32p]
@@ -199,6 +206,34 @@ def dbl_rejected_get(ctx, seq, host_out):
 
 def dbl_build_window(ctx, B, k, max_cont, cont, cont_len, pad_id, window):
     return _chk(ctx, lib().dbl_build_window(ctx, B, k, max_cont, _ptr(cont), _ptr(cont_len), pad_id, _ptr(window)))
+
+
+def dbl_build_guided_window(ctx, B, k, ahead, n_ahead, max_ahead, n_max, n_min, d, pad_id, window, n_draft):
+    return _chk(ctx, lib().dbl_build_guided_window(ctx, B, k, _ptr(ahead), _ptr(n_ahead), max_ahead, n_max, n_min, d, pad_id,
+                                                   _ptr(window), _ptr(n_draft)))
+
+
+def dbl_merge(ctx, B, k, n_u, n_acc, emit, chain, n_chain, max_chain, max_u, base_len, u_out, n_u_out, text_out, n_text_out,
+              splice_pos, record):
+    return _chk(ctx, lib().dbl_merge(ctx, B, k, _ptr(n_u), _ptr(n_acc), _ptr(emit), _ptr(chain), _ptr(n_chain), max_chain, max_u,
+                                     _ptr(base_len), _ptr(u_out), _ptr(n_u_out), _ptr(text_out), _ptr(n_text_out),
+                                     _ptr(splice_pos), _ptr(record)))
+
+
+def dbl_history_tail(ctx, B, from_pos, max_n, tokens_out, n_out):
+    return _chk(ctx, lib().dbl_history_tail(ctx, B, _ptr(from_pos), max_n, _ptr(tokens_out), _ptr(n_out)))
+
+
+def dbl_history_splice(ctx, B, pos, tokens, n, max_n, missing_out=None):
+    return _chk(ctx, lib().dbl_history_splice(ctx, B, _ptr(pos), _ptr(tokens), _ptr(n), max_n, _ptr(missing_out)))
+
+
+def dbl_catchup_window(ctx, B, k, pad_id, window, win_len):
+    return _chk(ctx, lib().dbl_catchup_window(ctx, B, k, pad_id, _ptr(window), _ptr(win_len)))
+
+
+def dbl_lengths_dev(ctx, B, kv_len_out=None, hist_len_out=None):
+    return _chk(ctx, lib().dbl_lengths_dev(ctx, B, _ptr(kv_len_out), _ptr(hist_len_out)))
 
 
 def dbl_verify_block(ctx, window, B, k, temperature=0.0, seed=0, step=0, logits_opt=None):

@@ -1210,6 +1210,90 @@ int dbl_build_window(dbl_ctx* c, int B, int k, int max_cont, const int32_t* cont
   return DBL_OK;
 }
 
+int dbl_build_guided_window(dbl_ctx* c, int B, int k, const int32_t* ahead, const int32_t* n_ahead, int max_ahead, int n_max,
+                            int n_min, int d, int32_t pad_id, int32_t* window, int32_t* n_draft) {
+  if (!c) return DBL_EINVAL;
+  if (!window || !n_draft) return fail(c, DBL_EINVAL, "null output pointer");
+  if ((ahead == nullptr) != (n_ahead == nullptr)) return fail(c, DBL_EINVAL, "ahead and n_ahead go together");
+  if (B < 1 || B > c->cfg.max_batch) return fail(c, DBL_EINVAL, "B out of range");
+  if (k < 1 || k > c->cfg.max_window) return fail(c, DBL_EINVAL, "k out of range");
+  if (max_ahead < 0 || max_ahead > 64 || (ahead && max_ahead < 1)) return fail(c, DBL_EINVAL, "need 1 <= max_ahead <= 64");
+  if (n_min < 1 || n_max < n_min || n_max > 32) return fail(c, DBL_EINVAL, "need 1 <= n_min <= n_max <= 32");
+  if (d < 1 || d > 64) return fail(c, DBL_EINVAL, "need 1 <= d <= 64");
+  if (pad_id < 0 || pad_id >= c->cfg.vocab) return fail(c, DBL_EINVAL, "pad_id out of range");
+  if (c->dry) return DBL_ENODEV;
+  GuidedArgs a{c->hist, c->hist_len, c->cfg.max_hist, ahead, n_ahead, max_ahead, n_max, n_min, d, k, pad_id, window, n_draft};
+  hipLaunchKernelGGL(guided_window_kernel, dim3(B), dim3(1024), 0, c->stream, a);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+int dbl_merge(dbl_ctx* c, int B, int k, const int32_t* n_u, const int32_t* n_acc, const int32_t* emit, const int32_t* chain,
+              const int32_t* n_chain, int max_chain, int max_u, const int32_t* base_len, int32_t* u_out, int32_t* n_u_out,
+              int32_t* text_out, int32_t* n_text_out, int32_t* splice_pos, int32_t* record) {
+  if (!c) return DBL_EINVAL;
+  if (!n_u || !n_acc || !emit || !chain || !n_chain) return fail(c, DBL_EINVAL, "null input pointer");
+  if (!u_out || !n_u_out || !text_out || !n_text_out || !splice_pos || !record) return fail(c, DBL_EINVAL, "null output pointer");
+  if (B < 1 || B > c->cfg.max_batch) return fail(c, DBL_EINVAL, "B out of range");
+  if (k < 1 || k > MAX_WINDOW) return fail(c, DBL_EINVAL, "k out of range");
+  if (max_chain < 1 || max_chain > 4096) return fail(c, DBL_EINVAL, "need 1 <= max_chain <= 4096");
+  if (max_u < 1 || max_u > 64) return fail(c, DBL_EINVAL, "need 1 <= max_u <= 64");
+  if (c->dry) return DBL_ENODEV;
+  MergeArgs a{B, k, max_chain, max_u, n_u, n_acc, emit, chain, n_chain, base_len, u_out, n_u_out, text_out, n_text_out, splice_pos, record};
+  hipLaunchKernelGGL(merge_kernel, dim3(1), dim3(128), 0, c->stream, a);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+int dbl_history_tail(dbl_ctx* c, int B, const int32_t* from, int max_n, int32_t* tokens_out, int32_t* n_out) {
+  if (!c) return DBL_EINVAL;
+  if (!from || !tokens_out || !n_out) return fail(c, DBL_EINVAL, "null pointer");
+  if (B < 1 || B > c->cfg.max_batch) return fail(c, DBL_EINVAL, "B out of range");
+  if (max_n < 1 || max_n > 4096) return fail(c, DBL_EINVAL, "need 1 <= max_n <= 4096");
+  if (c->dry) return DBL_ENODEV;
+  hipLaunchKernelGGL(history_tail_kernel, dim3(B), dim3(256), 0, c->stream, c->hist, c->hist_len, c->cfg.max_hist, from, max_n,
+                     tokens_out, n_out);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+int dbl_history_splice(dbl_ctx* c, int B, const int32_t* pos, const int32_t* tokens, const int32_t* n, int max_n, int32_t* missing_out) {
+  if (!c) return DBL_EINVAL;
+  if (!pos || !tokens || !n) return fail(c, DBL_EINVAL, "null pointer");
+  if (B < 1 || B > c->cfg.max_batch) return fail(c, DBL_EINVAL, "B out of range");
+  if (max_n < 1 || max_n > 128) return fail(c, DBL_EINVAL, "need 1 <= max_n <= 128");
+  for (int b = 0; b < B; ++b) c->hist_upper[b] = std::min(c->cfg.max_hist, c->hist_upper[b] + max_n);
+  c->have_verify = c->have_accept = false;
+  if (c->dry) return DBL_ENODEV;
+  hipLaunchKernelGGL(history_splice_kernel, dim3(1), dim3(128), 0, c->stream, c->hist, c->hist_len, c->prompt_len, c->kv_len,
+                     c->cfg.max_hist, B, pos, tokens, n, max_n, missing_out, c->status);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+int dbl_catchup_window(dbl_ctx* c, int B, int k, int32_t pad_id, int32_t* window, int32_t* win_len) {
+  if (!c) return DBL_EINVAL;
+  if (!window || !win_len) return fail(c, DBL_EINVAL, "null output pointer");
+  if (B < 1 || B > c->cfg.max_batch) return fail(c, DBL_EINVAL, "B out of range");
+  if (k < 1 || k > c->cfg.max_window) return fail(c, DBL_EINVAL, "k out of range");
+  if (pad_id < 0 || pad_id >= c->cfg.vocab) return fail(c, DBL_EINVAL, "pad_id out of range");
+  if (c->dry) return DBL_ENODEV;
+  hipLaunchKernelGGL(catchup_window_kernel, dim3(B), dim3(64), 0, c->stream, c->hist, c->hist_len, c->kv_len, c->cfg.max_hist, k,
+                     pad_id, window, win_len);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
+int dbl_lengths_dev(dbl_ctx* c, int B, int32_t* kv_len_out, int32_t* hist_len_out) {
+  if (!c) return DBL_EINVAL;
+  if (!kv_len_out && !hist_len_out) return fail(c, DBL_EINVAL, "null output pointers");
+  if (B < 1 || B > c->cfg.max_batch) return fail(c, DBL_EINVAL, "B out of range");
+  if (c->dry) return DBL_ENODEV;
+  hipLaunchKernelGGL(copy_lengths_kernel, dim3(1), dim3(128), 0, c->stream, c->kv_len, c->hist_len, B, kv_len_out, hist_len_out);
+  HIPCHK(c, hipGetLastError());
+  return DBL_OK;
+}
+
 static int verify_common(dbl_ctx* c, const int32_t* window, const int32_t* win_len, int B, int k, float temperature,
                          uint64_t seed, uint64_t step, float* logits_opt) {
   if (!window) return fail(c, DBL_EINVAL, "null window");

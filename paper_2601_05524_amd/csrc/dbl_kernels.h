@@ -380,6 +380,172 @@ __global__ void build_window_kernel(const int32_t* __restrict__ hist, const int3
   }
 }
 
+// ------------------------------------------------- the two-model round (Sec. 4.1, 4.2)
+
+// Target-side window of a Double round: pending token + the unverified drafts U + the target's own retrieved
+// guidance Y_p (Sec. 4.2: Y_p = Retrieval(x, d), taken at the end of the text the window covers, i.e. of x + U),
+// padded to k rows.  The search is retrieve_kernel's over the virtual sequence history + U (nothing is written
+// to the history): longest n first, then the longest continuation (at most min(d, free rows)), then the latest
+// occurrence.  One workgroup per sequence.  n_draft[b] = |U| + |Y_p| (the real drafts of the window).
+struct GuidedArgs {
+  const int32_t *hist, *hist_len; int max_hist;
+  const int32_t *ahead, *n_ahead; int max_ahead;      // U: [B][max_ahead], lengths [B] (nullptr: none)
+  int n_max, n_min, d, k; int32_t pad;
+  int32_t *window, *n_draft;                          // [B][k], [B]
+};
+
+__global__ void __launch_bounds__(1024) guided_window_kernel(const GuidedArgs a) {
+  __shared__ unsigned long long wbest[16];
+  __shared__ int32_t suf[32];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int32_t* h = a.hist + (size_t)b * a.max_hist;
+  const int32_t* ah = a.ahead ? a.ahead + (size_t)b * a.max_ahead : nullptr;
+  const int len = min(a.hist_len[b], a.max_hist);
+  const int nu = ah && a.n_ahead ? max(0, min(a.n_ahead[b], min(a.k - 1, a.max_ahead))) : 0;
+  const int vlen = len + nu;
+  const int mc = min(a.d, a.k - 1 - nu);              // guidance tokens the window has room for
+  auto tok = [&](int i) { return i < len ? h[i] : ah[i - len]; };
+  const int nm_cap = min(a.n_max, vlen - 1);
+  if (tid < 32) suf[tid] = (tid < nm_cap) ? tok(vlen - 1 - tid) : -1;
+  __syncthreads();
+  unsigned long long best = 0ull;
+  if (mc >= 1) {
+    for (int e = 1 + tid; e <= vlen - 1; e += blockDim.x) {
+      int nm = 0;
+      const int cap = min(nm_cap, e);
+      while (nm < cap && tok(e - 1 - nm) == suf[nm]) ++nm;
+      if (nm >= a.n_min) {
+        const int cl = min(mc, vlen - e);
+        const unsigned long long key = ((unsigned long long)nm << 48) | ((unsigned long long)cl << 32) | (unsigned)e;
+        best = key > best ? key : best;
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const unsigned long long o = __shfl_xor(best, off);
+    best = o > best ? o : best;
+  }
+  if (lane == 0) wbest[wave] = best;
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < (int)(blockDim.x >> 6); ++w) best = wbest[w] > best ? wbest[w] : best;
+    wbest[0] = best;
+  }
+  __syncthreads();
+  best = wbest[0];
+  const int cl = best ? (int)((best >> 32) & 0xffff) : 0, e = (int)(best & 0xffffffffu);
+  for (int j = tid; j < a.k; j += blockDim.x) {
+    int32_t v;
+    if (j == 0) v = len > 0 ? h[len - 1] : a.pad;
+    else if (j <= nu) v = ah[j - 1];
+    else v = (j - 1 - nu < cl) ? tok(e + j - 1 - nu) : a.pad;
+    a.window[(size_t)b * a.k + j] = v;
+  }
+  if (tid == 0) a.n_draft[b] = nu + cl;
+}
+
+// The resolve step of a round (Sec. 4.2 "Forward Guidance", Eq. 6; the branches of Alg. 1 / Alg. 2), one thread per
+// sequence.  In: n_u = |U| (the unverified drafts the target's window carried), n_acc and emit of the target's
+// acceptance (emit = E: accepted window tokens + the target's own next token), the draft model's new chain X_q
+// (it continues x + U) and its length.  The verified text always grows by E.  If a token of U was rejected, or X_q
+// disagrees with G = E beyond U (the accepted guidance + the target's token), or X_q does not reach past G, no draft
+// survives: U' is empty and the target's tokens stand (Eq. 6: verified draft prefix + target suffix).  Otherwise the
+// part of X_q behind G becomes the next round's U' (at most max_u tokens).
+// Out: U' and |U'|; text = E + U' (what follows the old verified text now, for the draft's history), its length;
+// splice_pos = base_len - n_u (where that text starts in the draft's history, base_len = the draft's history length
+// when its chain began); record[b][8] = {n_u, n_acc, |E|, |X_q|, |U'|, tokens of X_q that agree with G,
+// length of the draft's text behind the old verified text that stays valid, 0}.
+struct MergeArgs {
+  int B, k, max_chain, max_u;
+  const int32_t *n_u, *n_acc, *emit, *chain, *n_chain, *base_len;
+  int32_t *u_out, *n_u_out, *text_out, *n_text_out, *splice_pos, *record;
+};
+
+__global__ void merge_kernel(const MergeArgs a) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= a.B) return;
+  const int nu = max(0, min(a.n_u[b], a.k - 1));
+  const int na = min(a.n_acc[b], a.k - 1);
+  const int ne = max(0, na + 1);
+  const int nc = max(0, min(a.n_chain[b], a.max_chain));
+  const int32_t* E = a.emit + (size_t)b * a.k;
+  const int32_t* X = a.chain + (size_t)b * a.max_chain;
+  int32_t* U = a.u_out + (size_t)b * a.max_u;
+  int32_t* T = a.text_out + (size_t)b * (a.k + a.max_u);
+  int kept = 0, agree = 0, valid = max(0, na);        // a rejection inside U: the accepted part of U stays valid
+  if (na >= nu) {
+    const int g = ne - nu;                            // |G| >= 1
+    while (agree < g && agree < nc && X[agree] == E[nu + agree]) ++agree;
+    if (agree == g && nc > g) kept = min(nc - g, a.max_u);
+    valid = nu + (kept > 0 ? g + kept : agree);
+  }
+  for (int i = 0; i < ne; ++i) T[i] = E[i];
+  for (int i = 0; i < kept; ++i) { U[i] = X[ne - nu + i]; T[ne + i] = U[i]; }
+  for (int i = kept; i < a.max_u; ++i) U[i] = -1;
+  a.n_u_out[b] = kept;
+  a.n_text_out[b] = ne + kept;
+  a.splice_pos[b] = a.base_len ? a.base_len[b] - nu : 0;
+  int32_t* r = a.record + (size_t)b * 8;
+  r[0] = nu; r[1] = na; r[2] = ne; r[3] = nc; r[4] = kept; r[5] = agree; r[6] = valid; r[7] = 0;
+}
+
+// hist tokens [from[b], hist_len[b]) -> out[b][0..n), n = min(that many, max_n)
+__global__ void history_tail_kernel(const int32_t* __restrict__ hist, const int32_t* __restrict__ hist_len, int max_hist,
+                                    const int32_t* __restrict__ from, int max_n, int32_t* __restrict__ out,
+                                    int32_t* __restrict__ n_out) {
+  const int b = blockIdx.x;
+  const int len = min(hist_len[b], max_hist);
+  const int f = max(0, min(from[b], len));
+  const int n = min(len - f, max_n);
+  for (int i = threadIdx.x; i < max_n; i += blockDim.x) out[(size_t)b * max_n + i] = i < n ? hist[(size_t)b * max_hist + f + i] : -1;
+  if (threadIdx.x == 0) n_out[b] = n;
+}
+
+// The history of sequence b becomes hist[0..pos) + tokens[0..n); the KV rows of the tokens that did not change stay,
+// the rest is rolled back (kv_len = min(kv_len, first changed position, new length - 1)).  missing[b] = tokens whose
+// KV the model has to compute before the last one is pending again.  One thread per sequence (a few tokens).
+__global__ void history_splice_kernel(int32_t* __restrict__ hist, int32_t* __restrict__ hist_len, int32_t* __restrict__ prompt_len,
+                                      int32_t* __restrict__ kv_len, int max_hist, int B, const int32_t* __restrict__ pos_in,
+                                      const int32_t* __restrict__ tokens, const int32_t* __restrict__ n_in, int max_n,
+                                      int32_t* __restrict__ missing, int32_t* __restrict__ status) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int32_t* h = hist + (size_t)b * max_hist;
+  const int32_t* t = tokens + (size_t)b * max_n;
+  const int old_len = min(hist_len[b], max_hist);
+  const int pos = max(0, min(pos_in[b], old_len));
+  int n = max(0, min(n_in[b], max_n));
+  if (pos + n > max_hist) { n = max_hist - pos; atomicOr(status, 2); }
+  int p = 0;
+  while (p < n && pos + p < old_len && h[pos + p] == t[p]) ++p;
+  for (int i = p; i < n; ++i) h[pos + i] = t[i];
+  const int new_len = pos + n;
+  hist_len[b] = new_len;
+  prompt_len[b] = min(prompt_len[b], new_len);
+  const int kl = min(kv_len[b], min(pos + p, max(new_len - 1, 0)));
+  kv_len[b] = kl;
+  if (missing) missing[b] = max(new_len - 1 - kl, 0);
+}
+
+// window[b][j] = hist[kv_len[b] + j] for the tokens between the cache and the pending token (at most k), then padding
+__global__ void catchup_window_kernel(const int32_t* __restrict__ hist, const int32_t* __restrict__ hist_len,
+                                      const int32_t* __restrict__ kv_len, int max_hist, int k, int32_t pad,
+                                      int32_t* __restrict__ window, int32_t* __restrict__ win_len) {
+  const int b = blockIdx.x;
+  const int len = min(hist_len[b], max_hist), kl = max(0, kv_len[b]);
+  const int n = max(0, min(len - 1 - kl, k));
+  for (int j = threadIdx.x; j < k; j += blockDim.x) window[(size_t)b * k + j] = j < n ? hist[(size_t)b * max_hist + kl + j] : pad;
+  if (threadIdx.x == 0) win_len[b] = n;
+}
+
+__global__ void copy_lengths_kernel(const int32_t* kv_len, const int32_t* hist_len, int B, int32_t* kv_out, int32_t* hist_out) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  if (kv_out) kv_out[b] = kv_len[b];
+  if (hist_out) hist_out[b] = hist_len[b];
+}
+
 // ------------------------------------------------------------------- commit
 
 // kv_len[b] += n_keep[b]; optionally hist ⊕= emit[b][0..n_keep[b]).  Capacity

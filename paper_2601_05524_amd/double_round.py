@@ -1,20 +1,25 @@
-"""A full Double round on one GPU: draft model and target model as two libdbl contexts on two
-HIP streams, orchestrated from the host (paper Sec. 4.1 "Iterative Retrieval Drafter" and
-"Synchronous Parallel Execution", Sec. 4.2 "Target-Guided Verification" with Eq. 6, Alg. 1 / 2).
-Greedy decoding.
+"""Double rounds on one GPU (paper Sec. 4.1 "Iterative Retrieval Drafter" / "Synchronous Parallel
+Execution", Sec. 4.2 "Target-Guided Verification", Eq. 6, Alg. 1 / Alg. 2): a draft model and a target
+model as two libdbl contexts on two HIP streams.
 
-Every forward, acceptance, retrieval and commit runs in the library's kernels; the host only
-moves a handful of token ids per round and takes the mode decision, as the paper's own
-implementation does (App. D.3).  Per round:
+Nothing of the method is computed here.  Every token of a round stays on the device: the target's window
+is assembled by dbl_build_guided_window from the unverified drafts U and the target's own retrieval, the
+draft's chain is read off its history by dbl_history_tail, Eq. 6 is dbl_merge, and the draft model is
+re-aligned with the verified text by dbl_history_splice.  This module only enqueues those calls on the two
+streams, waits once per round, and reads back nine integers (the round's record) to know how far the text
+has grown and whether the draft needs a catch-up forward.
 
-  (a) target stream: one Retrieval Forward over  pending token + U + Y_p  (U = draft tokens
-      not verified yet, Y_p = target-side retrieval continuing x + U), greedy acceptance, commit;
-  (b) draft stream, at the same time and from x + U: gamma chained Retrieval Forwards
-      (retrieve -> window -> forward -> accept -> commit, chained on the device);
-  (c) host: x <- x + E (the target's accepted tokens + its own next token).  If all of U held,
-      the draft's new chain is checked against the part of E that lies beyond U; when it agrees
-      with all of it and goes further, the remainder becomes the new U, otherwise the target's
-      tokens win (Eq. 6) and the draft context is rolled back and caught up.
+One round, with x the text the target has verified and U the drafts behind it:
+
+  target stream   guided window (pending + U + Y_p) -> verify -> accept -> commit            x += E
+  draft stream    [catch-up forward] -> gamma Retrieval Forwards from x + U -> chain X_q
+                  -> wait for the target's event -> merge -> splice                          U <- U'
+  host            synchronise the draft stream, read the record
+
+Random numbers (T > 0): an acceptance draws from Philox with a step word.  The library adds the number of
+commits a context has run to the `step` argument; a Lane counts its own commits and passes the difference,
+so that the target's acceptance of round r draws with step r and the draft's j-th Retrieval Forward of
+round r with step r * gamma + j, whatever prefill and catch-up forwards came before.
 """
 from __future__ import annotations
 
@@ -23,153 +28,167 @@ import torch
 
 from . import binding as B
 
-
-def common_prefix(a, b) -> int:
-    n = 0
-    while n < len(a) and n < len(b) and int(a[n]) == int(b[n]):
-        n += 1
-    return n
+_U64 = (1 << 64) - 1
 
 
-class Engine:
-    """One model: a libdbl context on its own stream, the device buffers its calls need, and
-    a host mirror of what the context holds (history tokens, number of valid KV rows)."""
+class Lane:
+    """One model on its own stream: a libdbl context and the device buffers its calls write."""
 
     def __init__(self, shape: dict, weight_seed: int, *, max_ctx: int, max_window: int, max_hist: int,
                  stream: torch.cuda.Stream | None = None, device: str = "cuda:0", max_cont: int = 16):
         self.dev = device
         self.stream = stream if stream is not None else torch.cuda.Stream(device=device)
-        self.k_max, self.max_cont = max_window, max_cont
+        self.k_max, self.max_cont, self.max_ctx, self.max_hist = max_window, max_cont, max_ctx, max_hist
         cfg = B.make_cfg(**shape, max_batch=1, max_ctx=max_ctx, max_window=max_window, max_hist=max_hist)
-        self.max_ctx, self.max_hist = max_ctx, max_hist
         self.ctx = B.dbl_create(cfg, weight_seed, self.stream.cuda_stream)
         with torch.cuda.stream(self.stream):
             i32 = lambda *s: torch.zeros(s, dtype=torch.int32, device=device)
             self.cont, self.cl, self.mn, self.mp = i32(1, max_cont), i32(1), i32(1), i32(1)
-            self.window = i32(1, max_window)
+            self.window, self.win_len = i32(1, max_window), i32(1)
             self.n_acc, self.emit, self.guide = i32(1), i32(1, max_window), i32(1, max_window)
-            self.keep = i32(1)
-        self.hist: list[int] = []
-        self.kv = 0
-        self._k_last = 0
+            self.n_draft, self.keep = i32(1), i32(1)
+        self.commits = 0          # dbl_kv_commit calls so far on this context
+        self.prompt_len = 0
 
     def close(self):
         if self.ctx is not None:
             B.dbl_destroy(self.ctx)
             self.ctx = None
 
-    # ---- state ------------------------------------------------------------
-    def sync_to(self, tokens):
-        """Hold `tokens` as history with the KV of all but the last one: keep the valid prefix
-        of the cache, roll the rest back, run the model over what is missing."""
-        tokens = [int(t) for t in tokens]
-        assert 1 <= len(tokens) <= self.max_hist and len(tokens) - 1 <= self.max_ctx
-        keep = min(common_prefix(self.hist, tokens), self.kv, len(tokens) - 1)
+    def step_arg(self, want: int) -> int:
+        """`step` argument that makes the library's step word (argument + commits run) equal `want`."""
+        return (want - self.commits) & _U64
+
+    def commit(self, n_keep=None):
+        B.dbl_kv_commit(self.ctx, n_keep)
+        self.commits += 1
+
+    def load(self, prompt):
+        """Start a session: the prompt becomes the history, its tokens but the last go through the model."""
+        p = np.ascontiguousarray(prompt, dtype=np.int32)
+        assert 1 <= p.size <= self.max_hist and p.size - 1 <= self.max_ctx
         with torch.cuda.stream(self.stream):
-            B.dbl_truncate(self.ctx, 0, kv_len=keep)
-            B.dbl_history_set(self.ctx, 0, np.ascontiguousarray(tokens, dtype=np.int32))
-            pos = keep
-            while pos < len(tokens) - 1:
-                n = min(self.k_max, len(tokens) - 1 - pos)
-                w = torch.as_tensor(np.asarray([tokens[pos:pos + n]], dtype=np.int32), device=self.dev)
+            B.dbl_reset(self.ctx, 0)
+            B.dbl_history_set(self.ctx, 0, p)
+            for i in range(0, p.size - 1, self.k_max):
+                n = min(self.k_max, p.size - 1 - i)
+                w = torch.as_tensor(p[None, i:i + n], device=self.dev)
                 self.keep.fill_(n)
                 B.dbl_verify_block(self.ctx, w, 1, n)
-                B.dbl_kv_commit(self.ctx, self.keep)
-                pos += n
-        self.hist, self.kv = tokens, len(tokens) - 1
+                self.commit(self.keep)
+        self.prompt_len = int(p.size)
 
-    # ---- draft side -------------------------------------------------------
-    def retrieval_forwards(self, gamma: int, k: int, n_max: int, n_min: int, d: int):
-        """Enqueue gamma chained Retrieval Forwards (Eq. 5); nothing is read back."""
-        assert 1 <= k <= self.k_max
-        assert len(self.hist) + gamma * k <= self.max_hist and self.kv + gamma * k <= self.max_ctx
+    def retrieval_forward(self, k, n_max, n_min, d, temperature=0.0, seed=0, want_step=0):
+        """Enqueue one Retrieval Forward (Eq. 2) of this model on its own text; call inside its stream."""
         mc = max(1, min(d, k - 1, self.max_cont))
-        with torch.cuda.stream(self.stream):
-            for _ in range(gamma):
-                B.dbl_retrieve(self.ctx, 1, n_max, n_min, mc, self.cont, self.cl, self.mn, self.mp)
-                B.dbl_build_window(self.ctx, 1, k, mc, self.cont, self.cl, 0, self.window)
-                B.dbl_verify_block(self.ctx, self.window, 1, k)
-                B.dbl_accept(self.ctx, B.DBL_GREEDY, None, self.n_acc, self.emit, self.guide)
-                B.dbl_kv_commit(self.ctx, None)
+        sample = temperature > 0.0
+        B.dbl_retrieve(self.ctx, 1, n_max, n_min, mc, self.cont, self.cl, self.mn, self.mp)
+        B.dbl_build_window(self.ctx, 1, k, mc, self.cont, self.cl, 0, self.window)
+        B.dbl_verify_block(self.ctx, self.window, 1, k, temperature if sample else 0.0, seed, self.step_arg(want_step))
+        B.dbl_accept(self.ctx, B.DBL_SAMPLE if sample else B.DBL_GREEDY, None, self.n_acc, self.emit, self.guide)
+        self.commit()
 
-    def collect_history(self):
-        """Wait for the stream; return the tokens appended since the mirror was last updated."""
+    def chain(self, n_forwards, k, n_max=3, n_min=1, d=10):
+        """Enqueue n chained greedy Retrieval Forwards (the iterative retrieval drafter, Eq. 5); nothing is read back."""
+        with torch.cuda.stream(self.stream):
+            for _ in range(n_forwards):
+                self.retrieval_forward(k, n_max, n_min, d)
+
+    def tighten(self):
+        """Refresh the library's host-side length bounds from the device counters (the stream must be idle)."""
+        kv = np.zeros(1, np.int32)
+        B.dbl_kv_len(self.ctx, kv)
+        return int(kv[0])
+
+    def generated(self):
+        """Synchronise and return the tokens behind the prompt."""
         buf = np.zeros(self.max_hist, np.int32)
         n = B.dbl_history_get(self.ctx, 0, buf)
-        new = [int(t) for t in buf[len(self.hist):n]]
-        self.hist = [int(t) for t in buf[:n]]
-        self.kv = n - 1
-        return new
-
-    # ---- target side ------------------------------------------------------
-    def guided_verify(self, x, U, k: int, n_max: int, n_min: int, d: int):
-        """Enqueue the target's Retrieval Forward over pending + U + retrieved guidance (padded
-        to k rows), acceptance and commit.  The context must hold x.  Returns the window."""
-        assert self.hist == x and len(U) <= k - 1 <= self.k_max - 1
-        room = k - 1 - len(U)
-        Y = []
-        with torch.cuda.stream(self.stream):
-            if room > 0:
-                mc = max(1, min(d, room, self.max_cont))
-                if U:   # the retrieval key is the end of x + U
-                    B.dbl_history_set(self.ctx, 0, np.ascontiguousarray(x + U, dtype=np.int32))
-                B.dbl_retrieve(self.ctx, 1, n_max, n_min, mc, self.cont, self.cl, self.mn, self.mp)
-                cl = int(self.cl.cpu()[0])
-                Y = [int(t) for t in self.cont.cpu()[0, :min(cl, room)]]
-                if U:
-                    B.dbl_truncate(self.ctx, 0, hist_len=len(x))
-            W = [x[-1]] + list(U) + Y
-            W = W + [0] * (k - len(W))
-            self.window[0, :k] = torch.as_tensor(np.asarray(W, dtype=np.int32), device=self.dev)
-            B.dbl_verify_block(self.ctx, self.window, 1, k)
-            B.dbl_accept(self.ctx, B.DBL_GREEDY, None, self.n_acc, self.emit, self.guide)
-            B.dbl_kv_commit(self.ctx, None)
-        self._k_last = k
-        return W
-
-    def collect_accept(self):
-        """Wait for the stream; return (n_acc, emitted tokens) of the last guided_verify."""
-        self.stream.synchronize()
-        n = int(self.n_acc.cpu()[0])
-        E = [int(t) for t in self.emit.cpu()[0, :n + 1]]
-        self.hist = self.hist + E
-        self.kv += n + 1
-        return n, E
+        return [int(t) for t in buf[self.prompt_len:n]]
 
 
-def double_decode(target: Engine, draft: Engine, prompt, max_new: int, gamma: int, k_p: int, k_q: int,
-                  n_max: int = 3, n_min: int = 1, d: int = 10):
-    """Greedy decoding of the target model with the draft model running ahead on its own stream.
-    Returns (new tokens, per-round records)."""
-    x, U, rounds = [int(t) for t in prompt], [], []
-    target.sync_to(x)
-    draft.sync_to(x)
-    while len(x) - len(prompt) < max_new:
-        target.guided_verify(x, U, k_p, n_max, n_min, d)          # (a), asynchronous
-        draft.retrieval_forwards(gamma, k_q, n_max, n_min, d)     # (b), asynchronous, other stream
-        n, E = target.collect_accept()
-        Xq = draft.collect_history()
-        U_new = []
-        if n >= len(U):
-            G = E[len(U):]
-            if common_prefix(Xq, G) == len(G) and len(Xq) > len(G):
-                U_new = Xq[len(G):][:k_p - 1]
-        rounds.append({"mode": "post" if U else "pre", "n_u": len(U), "n_acc": n, "emitted": len(E),
-                       "drafted": len(Xq), "kept": len(U_new)})
-        x = x + E
-        U = U_new
-        draft.sync_to(x + U)
-    return x[len(prompt):], rounds
+class DoubleDecoder:
+    """Target lane + draft lane + the device buffers of the resolve step."""
+
+    def __init__(self, target: Lane, draft: Lane, *, gamma: int, k_p: int, k_q: int, n_max: int = 3, n_min: int = 1,
+                 d: int = 10, temperature: float = 0.0, seed_target: int = 0, seed_draft: int = 0):
+        assert 1 <= k_p <= target.k_max and 1 <= k_q <= draft.k_max and gamma >= 1
+        assert max(1, k_p - 1) <= draft.k_max, "the draft's catch-up forward carries up to k_p - 1 rows"
+        self.t, self.q = target, draft
+        self.gamma, self.k_p, self.k_q, self.n_max, self.n_min, self.d = gamma, k_p, k_q, n_max, n_min, d
+        self.T, self.seed_t, self.seed_q = float(temperature), seed_target, seed_draft
+        self.max_u, self.max_chain = max(1, k_p - 1), gamma * k_q
+        dev = target.dev
+        i32 = lambda *s: torch.zeros(s, dtype=torch.int32, device=dev)
+        with torch.cuda.stream(draft.stream):
+            self.U, self.n_u = [i32(1, self.max_u), i32(1, self.max_u)], [i32(1), i32(1)]
+            self.chain_buf, self.n_chain, self.mark = i32(1, self.max_chain), i32(1), i32(1)
+            self.text, self.n_text, self.splice_pos = i32(1, k_p + self.max_u), i32(1), i32(1)
+            self.rec = i32(9)                       # dbl_merge's record (8) + dbl_history_splice's missing (1)
+        self.rec_host = torch.zeros(9, dtype=torch.int32, pin_memory=True)
+        self.ev_target = torch.cuda.Event()
+        self.cur, self.missing, self.rounds, self.emitted = 0, 0, [], 0
+
+    def start(self, prompt):
+        self.t.load(prompt)
+        self.q.load(prompt)
+        with torch.cuda.stream(self.q.stream):
+            self.n_u[0].zero_(); self.n_u[1].zero_()
+        torch.cuda.synchronize()
+        self.cur, self.missing, self.rounds, self.emitted = 0, 0, [], 0
+
+    def round(self):
+        t, q, r = self.t, self.q, len(self.rounds)
+        sample = self.T > 0.0
+        U, n_u, U_next, n_u_next = self.U[self.cur], self.n_u[self.cur], self.U[1 - self.cur], self.n_u[1 - self.cur]
+        with torch.cuda.stream(t.stream):
+            B.dbl_build_guided_window(t.ctx, 1, self.k_p, U, n_u, self.max_u, self.n_max, self.n_min, self.d, 0,
+                                      t.window, t.n_draft)
+            B.dbl_verify_block(t.ctx, t.window, 1, self.k_p, self.T if sample else 0.0, self.seed_t, t.step_arg(r))
+            B.dbl_accept(t.ctx, B.DBL_SAMPLE if sample else B.DBL_GREEDY, None, t.n_acc, t.emit, t.guide)
+            t.commit()
+            self.ev_target.record(t.stream)
+        with torch.cuda.stream(q.stream):
+            if self.missing > 0:                    # bring the draft's cache up to x + U
+                m = self.missing
+                B.dbl_catchup_window(q.ctx, 1, m, 0, q.window, q.win_len)
+                B.dbl_verify_block_ragged(q.ctx, q.window, q.win_len, 1, m)
+                q.commit(q.win_len)
+            B.dbl_lengths_dev(q.ctx, 1, None, self.mark)
+            for j in range(self.gamma):
+                q.retrieval_forward(self.k_q, self.n_max, self.n_min, self.d, self.T, self.seed_q, r * self.gamma + j)
+            B.dbl_history_tail(q.ctx, 1, self.mark, self.max_chain, self.chain_buf, self.n_chain)
+            q.stream.wait_event(self.ev_target)
+            B.dbl_merge(q.ctx, 1, self.k_p, n_u, t.n_acc, t.emit, self.chain_buf, self.n_chain, self.max_chain, self.max_u,
+                        self.mark, U_next, n_u_next, self.text, self.n_text, self.splice_pos, self.rec[0:8])
+            B.dbl_history_splice(q.ctx, 1, self.splice_pos, self.text, self.n_text, self.k_p + self.max_u, self.rec[8:9])
+            self.rec_host.copy_(self.rec, non_blocking=True)
+        q.stream.synchronize()                      # the round's one wait (the target's work precedes the merge)
+        nu, na, ne, nc, kept, agree, valid, _, missing = (int(v) for v in self.rec_host.tolist())
+        self.rounds.append({"mode": "post" if nu else "pre", "n_u": nu, "n_acc": na, "emitted": ne, "drafted": nc,
+                            "kept": kept})
+        self.emitted += ne
+        self.missing = missing
+        self.cur = 1 - self.cur
+        t.tighten(); q.tighten()
+        return self.rounds[-1]
+
+    def decode(self, prompt, max_new: int):
+        """Run rounds until at least max_new tokens are verified.  Returns (new tokens, per-round records)."""
+        self.start(prompt)
+        while self.emitted < max_new:
+            self.round()
+        return self.t.generated(), self.rounds
 
 
-def autoregressive(engine: Engine, prompt, n_new: int):
+def autoregressive(lane: Lane, prompt, n_new: int):
     """Plain greedy decoding on the same kernels, one token per forward, chained on the device."""
-    engine.sync_to([int(t) for t in prompt])
-    with torch.cuda.stream(engine.stream):
-        engine.cl.zero_()
+    lane.load(prompt)
+    with torch.cuda.stream(lane.stream):
+        lane.cl.zero_()
         for _ in range(n_new):
-            B.dbl_build_window(engine.ctx, 1, 1, engine.max_cont, engine.cont, engine.cl, 0, engine.window)
-            B.dbl_verify_block(engine.ctx, engine.window, 1, 1)
-            B.dbl_accept(engine.ctx, B.DBL_GREEDY, None, engine.n_acc, engine.emit, engine.guide)
-            B.dbl_kv_commit(engine.ctx, None)
-    return engine.collect_history()
+            B.dbl_build_window(lane.ctx, 1, 1, lane.max_cont, lane.cont, lane.cl, 0, lane.window)
+            B.dbl_verify_block(lane.ctx, lane.window, 1, 1)
+            B.dbl_accept(lane.ctx, B.DBL_GREEDY, None, lane.n_acc, lane.emit, lane.guide)
+            lane.commit()
+    return lane.generated()
