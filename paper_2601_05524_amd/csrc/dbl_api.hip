@@ -135,6 +135,7 @@ struct dbl_ctx {
   float* sk_part = nullptr;         // gemm_rows_kernel's split units: two slots of partial sums per workgroup
   int* sk_cnt = nullptr;            //   arrivals per unit (zero between launches)
   int attn_lds = 1;                 // attention's shared (LDS-staged) form: 1 where it pays, 0 never, 2 wherever a kv head has two query blocks and a cached split exists, 3 / 4 like 2 / 1 with one query block per wave (DBL_ATTN_LDS at create)
+  int attn_p16 = 1;                 // shared form: probabilities as one fp16 operand (0: bf16 head + tail) (DBL_ATTN_P16 at create)
   int attn_nb = 2;                  // query blocks per wave of the attention where it pays; DBL_ATTN_NB at create: 1 never, 3 wherever possible
   int wide_resid = 1;               // output / down projection of many-row passes through gemm_wide_slice_kernel (DBL_WIDE_RESID=0 at create: never)
   int wide_gu = 1;                  // gate/up through gemm_wide_swiglu_kernel where wide_gate_up says so (DBL_WIDE_GU=0 at create: always through gemm_rows_kernel)
@@ -557,8 +558,13 @@ void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
       hipLaunchKernelGGL((rope_q_kernel<T, HD>), dim3((qwaves + 3) / 4), dim3(256), 0, c->stream, q);
 #define DBL_SHARED(NB_, NW_)                                                                                       \
       if (s.nb == NB_ && s.wpg == NW_) {                                                                           \
-        if (c->paged) hipLaunchKernelGGL((attn_shared_kernel<T, HD, true, NB_, NW_>), grid, block, 0, c->stream, s.attn); \
-        else hipLaunchKernelGGL((attn_shared_kernel<T, HD, false, NB_, NW_>), grid, block, 0, c->stream, s.attn);  \
+        if (c->attn_p16) {                                                                                         \
+          if (c->paged) hipLaunchKernelGGL((attn_shared_kernel<T, HD, true, NB_, NW_, true>), grid, block, 0, c->stream, s.attn); \
+          else hipLaunchKernelGGL((attn_shared_kernel<T, HD, false, NB_, NW_, true>), grid, block, 0, c->stream, s.attn);  \
+        } else {                                                                                                   \
+          if (c->paged) hipLaunchKernelGGL((attn_shared_kernel<T, HD, true, NB_, NW_, false>), grid, block, 0, c->stream, s.attn); \
+          else hipLaunchKernelGGL((attn_shared_kernel<T, HD, false, NB_, NW_, false>), grid, block, 0, c->stream, s.attn);  \
+        }                                                                                                          \
       }
       DBL_SHARED(2, 2) DBL_SHARED(2, 4) DBL_SHARED(2, 8) DBL_SHARED(1, 2) DBL_SHARED(1, 4) DBL_SHARED(1, 8)
 #undef DBL_SHARED
@@ -782,6 +788,7 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
   c->dry = (cfg->flags & DBL_FLAG_VALIDATE_ONLY) != 0;
   if (const char* e = std::getenv("DBL_ATTN_LDS")) c->attn_lds = std::atoi(e);
   if (const char* e = std::getenv("DBL_ATTN_NB")) c->attn_nb = std::atoi(e);
+  if (const char* e = std::getenv("DBL_ATTN_P16")) c->attn_p16 = std::atoi(e);
   if (const char* e = std::getenv("DBL_WIDE_RESID")) c->wide_resid = std::atoi(e);
   if (const char* e = std::getenv("DBL_WIDE_GU")) c->wide_gu = std::atoi(e);
   if (const char* e = std::getenv("DBL_STREAMK")) c->sk_mode = std::atoi(e) > 0 ? 1 : -1;   // testing / tuning aid

@@ -214,6 +214,18 @@ __device__ __forceinline__ void pv_accumulate(f32x4 (&o)[HT], const Frag<float> 
   for (int h = 0; h < HT; ++h) o[h] = mma(vf[h], pf, o[h]);
 }
 
+// The shared form's second product with the probabilities as ONE fp16 operand (11 significant bits, rounded to
+// nearest) against V^T fragments converted to fp16 when they were staged: a third fewer matrix instructions and a
+// fraction of the conversion work of the head + tail split.  A probability's rounding error (2^-12 relative at
+// most) is an eighth of the bf16 step the attention output is rounded to afterwards.
+template <int HT>
+__device__ __forceinline__ void pv_accumulate_f16(f32x4 (&o)[HT], const u32x4 (&vf)[HT], f32x4 a, f32x4 b) {
+  const u32x4 p = {pack_f16(a.x, a.y), pack_f16(a.z, a.w), pack_f16(b.x, b.y), pack_f16(b.z, b.w)};
+#pragma unroll
+  for (int h = 0; h < HT; ++h)
+    o[h] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, vf[h]), __builtin_bit_cast(f16x8, p), o[h], 0, 0, 0);
+}
+
 template <typename T, int HD>
 struct KvFrags { Frag<T> kf[2][HD / 32]; Frag<T> vf[HD / 16]; };
 
@@ -542,7 +554,8 @@ __global__ void __launch_bounds__(256, (PRE == 2 && sizeof(T) == 2 && NB == 1) ?
 // Splits and partials are attn_split_kernel's; the window split (last in the grid) runs attn_task's
 // window path, one query block per wave.  Queries come from rope_q_kernel.  The host picks this form only with at least
 // one split over cached tokens.
-template <typename T, int HD, bool PAGED, int NB, int NW>
+// PH: the probabilities enter the second product as fp16 (pv_accumulate_f16) instead of a bf16 head + tail.
+template <typename T, int HD, bool PAGED, int NB, int NW, bool PH>
 __global__ void __launch_bounds__(64 * NW, 2) attn_shared_kernel(const AttnArgs<T> a) {
   static_assert(sizeof(T) == 2, "bf16 caches only");
   constexpr int KSTEPS = HD / 32, HT = HD / 16, FR = 2 * KSTEPS + HT;
@@ -675,11 +688,19 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_shared_kernel(const AttnArgs<
     }
   };
   auto p_phase = [&](const u32x4 (&bv)[HT][WAVE]) {
-    Frag<T> vf[HT];
+    if constexpr (PH) {
+      u32x4 vh[HT];
 #pragma unroll
-    for (int h = 0; h < HT; ++h) vf[h].v = bv[h][lane];
+      for (int h = 0; h < HT; ++h) vh[h] = bv[h][lane];
 #pragma unroll
-    for (int n = 0; n < NB; ++n) pv_accumulate<HT>(o[n], vf, pr[n][0], pr[n][1]);
+      for (int n = 0; n < NB; ++n) pv_accumulate_f16<HT>(o[n], vh, pr[n][0], pr[n][1]);
+    } else {
+      Frag<T> vf[HT];
+#pragma unroll
+      for (int h = 0; h < HT; ++h) vf[h].v = bv[h][lane];
+#pragma unroll
+      for (int n = 0; n < NB; ++n) pv_accumulate<HT>(o[n], vf, pr[n][0], pr[n][1]);
+    }
   };
 
   u32x4 pre[DEPTH][FPW];
@@ -696,6 +717,9 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_shared_kernel(const AttnArgs<
       for (int i = 0; i < FPW; ++i) {
         const int fi = wave + i * NW;
         if (fi < 2 * KSTEPS) stage_k[st & 1][fi][lane] = pre[d][i];
+        else if constexpr (PH)   // V^T is converted once per workgroup here, not once per reader
+          stage_v[st & 1][fi - 2 * KSTEPS][lane] = u32x4{bf16x2_to_f16x2(pre[d][i].x), bf16x2_to_f16x2(pre[d][i].y),
+                                                         bf16x2_to_f16x2(pre[d][i].z), bf16x2_to_f16x2(pre[d][i].w)};
         else stage_v[st & 1][fi - 2 * KSTEPS][lane] = pre[d][i];
       }
       fetch(pre[d], st + DEPTH < nsteps ? t0 + 32 * (st + DEPTH) : tfirst);
