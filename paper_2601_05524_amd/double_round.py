@@ -80,10 +80,9 @@ class Lane:
 
     def retrieval_forward(self, k, n_max, n_min, d, temperature=0.0, seed=0, want_step=0):
         """Enqueue one Retrieval Forward (Eq. 2) of this model on its own text; call inside its stream."""
-        mc = max(1, min(d, k - 1, self.max_cont))
         sample = temperature > 0.0
-        B.dbl_retrieve(self.ctx, 1, n_max, n_min, mc, self.cont, self.cl, self.mn, self.mp)
-        B.dbl_build_window(self.ctx, 1, k, mc, self.cont, self.cl, 0, self.window)
+        # retrieval and window in one launch (no unverified drafts in front of this model's own text)
+        B.dbl_build_guided_window(self.ctx, 1, k, None, None, 0, n_max, n_min, max(1, min(d, 64)), 0, self.window, self.n_draft)
         B.dbl_verify_block(self.ctx, self.window, 1, k, temperature if sample else 0.0, seed, self.step_arg(want_step))
         B.dbl_accept(self.ctx, B.DBL_SAMPLE if sample else B.DBL_GREEDY, None, self.n_acc, self.emit, self.guide)
         self.commit()

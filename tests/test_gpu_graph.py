@@ -89,3 +89,85 @@ def test_captured_step_replays_like_the_eager_step(mode, T):
     kv = g.kv_len()[0]
     assert kv == len(ref) - 1
     g.close()
+
+
+def test_drafter_chain_in_one_graph_on_the_1b_shape_against_the_oracle():
+    """The iterative retrieval drafter (Eq. 5): gamma chained Retrieval Forwards of the 1B-shaped draft model at its
+    full 16 layers, captured into ONE graph with no host decision in between, replayed twice (eager work and a new
+    session in between) and compared with the ORACLE, forward by forward: the oracle follows the text the device
+    produced, so every forward is judged on the same state -- same retrieved window (bit-exact), logits within the
+    full-depth bar, and the same accepted length and emitted tokens wherever the oracle's top-2 margins exceed the
+    measured logit error (an undecidable row cannot cascade into later forwards)."""
+    import oracle as O
+    from tests.gpu_util import Ref
+    from tests.test_gpu_wide import FULL_DEPTH_REL
+    torch.cuda.set_device(0)
+    shape = dict(synth.CONFIGS["llama1b"])
+    V, k, gamma, mc = shape["vocab"], 8, 3, 7
+    stream = torch.cuda.Stream()
+    prompt = synth.zipf_history(47, 57, V, 1.1, 0.3, 8, 8)
+    g = make(stream, shape, 47)
+    r = Ref(shape, seed=47, max_batch=1, max_ctx=256, max_hist=512)
+
+    bufs = []
+    with torch.cuda.stream(stream):
+        for j in range(gamma):
+            bufs.append(dict(cont=g.i32(1, mc), cl=g.i32(1), mn=g.i32(1), mp=g.i32(1), window=g.i32(1, k), n_acc=g.i32(1),
+                             emit=g.i32(1, k), guide=g.i32(1, k),
+                             logits=torch.empty((1, k, V), dtype=torch.float32, device="cuda:0")))
+
+    def chain():
+        for b in bufs:
+            B.dbl_retrieve(g.ctx, 1, 3, 1, mc, b["cont"], b["cl"], b["mn"], b["mp"])
+            B.dbl_build_window(g.ctx, 1, k, mc, b["cont"], b["cl"], 0, b["window"])
+            B.dbl_verify_block(g.ctx, b["window"], 1, k, 0.0, 0, 0, b["logits"])
+            B.dbl_accept(g.ctx, B.DBL_GREEDY, None, b["n_acc"], b["emit"], b["guide"])
+            B.dbl_kv_commit(g.ctx, None)
+
+    with torch.cuda.stream(stream):
+        g.prefill([prompt], 8)
+        chain()                                 # warm-up outside the capture
+        stream.synchronize()
+        g.prefill([prompt], 8)                  # a fresh session for the capture's bounds
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        chain()
+
+    def replay_and_read():
+        graph.replay()
+        torch.cuda.synchronize()
+        return [{n: b[n].cpu().numpy().copy() for n in ("window", "n_acc", "emit", "logits")} for b in bufs], list(g.history())
+
+    first, hist1 = replay_and_read()
+    scratch = torch.zeros(1 << 20, device="cuda:0"); scratch.add_(1.0); torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        g.prefill([prompt], 8)                  # new session (resets the counters), eager
+        stream.synchronize()
+    second, hist2 = replay_and_read()
+    assert hist1 == hist2 and len(hist1) >= len(prompt) + gamma
+    for a, b in zip(first, second):
+        for n in a:
+            assert np.array_equal(a[n], b[n]), n
+
+    # the oracle, forward by forward, on the device's text
+    r.prefill([prompt], 8)
+    s = r.seqs[0]
+    decided = 0
+    for j, out in enumerate(first):
+        cont, cl, _, _ = s.retrieve(3, 1, mc)
+        w = np.array([int(s.history()[-1])] + [int(t) for t in cont[:cl]] + [0] * (k - 1 - cl), np.int32)
+        assert np.array_equal(out["window"][0], w), j
+        ref = s.verify_block(w)
+        d = out["logits"][0].astype(np.float64) - ref
+        rel = np.sqrt((d ** 2).mean()) / np.sqrt((ref ** 2).mean())
+        print("forward %d: rms error / rms logits %.3g, max-abs %.3g, accepted %d" % (j, rel, np.abs(d).max(), out["n_acc"][0]))
+        assert rel <= FULL_DEPTH_REL
+        n_ref, e_ref, gd_ref, margin = O.accept_greedy(ref, w)
+        n = int(out["n_acc"][0])
+        if not (margin[:max(n, n_ref) + 1] < 2 * np.abs(d).max(axis=1)[:max(n, n_ref) + 1]).any():
+            assert n == n_ref and np.array_equal(out["emit"][0], e_ref), j
+            decided += 1
+        s.commit(n + 1, out["emit"][0][:n + 1])          # follow the device
+    assert list(s.history()) == hist1
+    assert decided >= 1
+    g.close()
