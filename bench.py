@@ -9,12 +9,15 @@ LLaMA-3.3-70B-shaped bf16 target (80 layers, d 8192, 64/8 heads, FFN 28672, voca
 real prefill of a Zipf(1.1) token stream with 20% repeated 16-grams, window k = 8,
 batch 1, greedy acceptance.
 
-Prints ONE JSON line: metric/value/unit (verified window positions per second), ms_per_step,
-hbm_GBps_step (algorithmic bytes of a step / step time), breakdown_ms (per call, from events on
+Prints ONE JSON line: metric/value/unit (verified window positions per second), ms_per_step (wall
+clock over the K timed steps), ms_per_step_median (median of per-step HIP-event times on the context's
+stream), hbm_GBps_step (algorithmic bytes of a step / step time), breakdown_ms (per call, from events on
 the context's stream), projections (each projection kernel timed alone), roofline (the dominant
-kernel, fused gate/up: achieved GB/s from live HIP-event timing, recorded HBM traffic) and
-cpu_baseline (the CPU oracle timed on this host).  `--gpus N` with N > 1 is not supported: this
-build runs on one GPU.  `--double` measures the two-model Double round instead.
+kernel, fused gate/up: achieved GB/s from live HIP-event timing; HBM traffic as recorded by rocprofv3 for
+exactly the launch shape the library reports, else null) and cpu_baseline (the CPU oracle timed on this
+host).  `--also w1,w2` appends the same summary for further workloads under "other_workloads".
+`--gpus N` with N > 1 is not supported: this build runs on one GPU.  `--double` measures the two-model
+Double round instead.
 """
 from __future__ import annotations
 
@@ -33,8 +36,12 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # the xn_kernel that stores its normalised input) moves, from two rocprofv3 --pmc runs
 # (FETCH_SIZE scaled by 2.000, the factor a plain 1 GiB copy gives on this machine, plus
 # WRITE_SIZE); summary in profiles/gate_up_projection_llama70b_traffic.txt.
-# Counters cannot be read inside this process, so the figure is the recorded one.
-MEASURED_TRAFFIC = {"llama70b_ctx2048_k8_b1_greedy": 944_398_336}   # 921 208 + 1 056 KiB
+# Counters cannot be read inside this process, so the figure is the recorded one; it is reported only while
+# the library still launches the gate/up projection the way it did under the profiler (dbl_projection_plan:
+# kernel form, tile rows per unit, workgroups, split units), else null.
+MEASURED_TRAFFIC = {"llama70b_ctx2048_k8_b1_greedy": {"bytes": 944_398_336,          # 921 208 + 1 056 KiB
+                                                      "plan": (1, 2, 256, 0),        # gemm_rows_kernel, Q = 2, 256 workgroups, whole units
+                                                      "kernel": "gemm_rows_kernel<bf16, EPI_SWIGLU, R=1, Q=2> after xn_kernel"}}
 
 WORKLOADS = {
     # name: (shape key, context, k, batch, mode, temperature, repeat fraction, span lo, span hi)
@@ -57,11 +64,12 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(shape_key: str, k: int, full_layers: int, full_vocab: int, budget_s: float = 12.0):
-    """The oracle, as it stands, timed on this host's cores on a bounded sample: two
-    full-width decoder layers plus a 1/8-vocabulary LM-head slice over k window rows at an
-    empty context, repeated until about `budget_s` seconds of CPU work have been timed; the
-    full step is extrapolated as layers * t_layer + 8 * t_lm_slice."""
+def cpu_baseline(shape_key: str, k: int, ctx: int, full_layers: int, full_vocab: int, budget_s: float = 12.0):
+    """The oracle, as it stands, timed on this host's cores on a bounded sample: two full-width decoder
+    layers plus a 1/8-vocabulary LM-head slice over k window rows behind a context of `ctx` cached tokens
+    (seeded keys and values written into the oracle's cache: a prefill of that length at full width would
+    take the oracle minutes), repeated until about `budget_s` seconds of CPU work have been timed; the full
+    step is extrapolated as layers * t_layer + 8 * t_lm_slice."""
     import numpy as np
     import oracle as O
     from paper_2601_05524_amd import synth
@@ -70,17 +78,24 @@ def cpu_baseline(shape_key: str, k: int, full_layers: int, full_vocab: int, budg
     vdiv = 1 if small else 8
     nl_sample = min(2, max(1, full_layers))
     vs = shape["vocab"] // vdiv
-    shape.update(vocab=vs, max_ctx=64)
+    ctx = min(ctx, 4096)                      # (the oracle's attention is one core's work: bounded)
+    shape.update(vocab=vs, max_ctx=ctx + 64)
     cores = len(os.sched_getaffinity(0))
     win = (np.arange(k, dtype=np.int32) * 7919 + 13) % vs
     times, reps = {}, {}
     for nl in (0, nl_sample):
         m = O.Model(**dict(shape, n_layers=nl), seed=synth.BASE_SEED)
         s = O.Seq(m, max_hist=64)
+        if nl > 0 and ctx > 0:
+            rng = np.random.default_rng(1)
+            s.kcache()[:, :, :ctx, :] = rng.standard_normal((nl, shape["n_kv_heads"], ctx, shape["head_dim"])).astype(np.float32)
+            s.vcache()[:, :, :ctx, :] = rng.standard_normal((nl, shape["n_kv_heads"], ctx, shape["head_dim"])).astype(np.float32)
         share = budget_s * (0.1 if nl == 0 else 0.9)
         n, t0 = 0, time.perf_counter()
         while True:
             s.reset()
+            if nl > 0 and ctx > 0:
+                s.commit(ctx, [])             # the planted rows count as committed
             s.verify_block(win)
             n += 1
             if time.perf_counter() - t0 >= share or n >= 200:
@@ -92,9 +107,10 @@ def cpu_baseline(shape_key: str, k: int, full_layers: int, full_vocab: int, budg
     t_layer = max(times[nl_sample] - times[0], 1e-9) / nl_sample
     t_full = full_layers * t_layer + vdiv * t_lm
     return {"value": k / t_full, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": "%d full-width layers + 1/%d-vocab LM head, k=%d rows, empty context, %d + %d repetitions "
-                      "(%.1f s of CPU work); extrapolated to %d layers + full vocab (t_layer=%.3fs, t_lm_slice=%.3fs)"
-                      % (nl_sample, vdiv, k, reps[nl_sample], reps[0],
+            "sample": "%d full-width layers + 1/%d-vocab LM head, k=%d rows behind %d cached tokens (seeded K/V), "
+                      "%d + %d repetitions (%.1f s of CPU work); extrapolated to %d layers + full vocab "
+                      "(t_layer=%.3fs, t_lm_slice=%.3fs)"
+                      % (nl_sample, vdiv, k, ctx, reps[nl_sample], reps[0],
                          times[0] * reps[0] + times[nl_sample] * reps[nl_sample], full_layers, t_layer, t_lm),
             "extrapolated": True}
 
@@ -196,36 +212,14 @@ def bench_double(args):
     print(json.dumps(out_line), flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="llama70b_ctx2048_k8_b1_greedy", choices=sorted(WORKLOADS))
-    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the model's own)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--kernel-iters", type=int, default=40, help="launches per projection for the roofline line")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 --pmc byte counters)")
-    ap.add_argument("--paged-kv", action="store_true", help="KV cache as a pool of 256-token pages (default: contiguous)")
-    ap.add_argument("--double", action="store_true",
-                    help="measure the full Double round (draft + target on two streams) instead of the headline step")
-    ap.add_argument("--double-tokens", type=int, default=64)
-    ap.add_argument("--double-gamma", type=int, default=0, help="draft iterations per round (0 = ceil(T_p / T_q))")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus)
-        sys.exit(2)
-
-    if args.double:
-        return bench_double(args)
-
+def run_workload(args, workload, with_cpu_baseline):
+    """One workload: create the model, build the context, time K steps.  Returns the JSON object."""
     import numpy as np
     import torch
     from paper_2601_05524_amd import binding as B
     from paper_2601_05524_amd import synth
 
-    shape_key, P, k, Bn, mode, T, frac, slo, shi = WORKLOADS[args.workload]
+    shape_key, P, k, Bn, mode, T, frac, slo, shi = WORKLOADS[workload]
     shape = dict(synth.CONFIGS[shape_key])
     if args.layers > 0:
         shape["n_layers"] = args.layers
@@ -245,8 +239,10 @@ def main():
     cfg = B.make_cfg(**shape, max_batch=Bn, max_ctx=max_ctx, max_window=max(chunk, k), max_hist=max_hist,
                      flags=B.DBL_FLAG_PAGED_KV if args.paged_kv else 0)
     ctx = B.dbl_create(cfg, seed, torch.cuda.current_stream().cuda_stream)
+    if args.tune:
+        B.dbl_set_tuning(ctx, **dict((kv.split("=")[0], int(kv.split("=")[1])) for kv in args.tune.split(",")))
     wbytes, kv_per_tok = B.dbl_model_bytes(ctx)
-    log("[bench] context created in %.1fs: %.2f GB of weights streamed per step" % (time.perf_counter() - t0, wbytes / 1e9))
+    log("[bench] %s: context created in %.1fs: %.2f GB of weights streamed per step" % (workload, time.perf_counter() - t0, wbytes / 1e9))
 
     # history = P + 1 tokens; prefill the first P through verify_block + kv_commit
     prompts = [synth.zipf_history(seed + 100 * b, P + 1, shape["vocab"], 1.1, frac, slo, shi) for b in range(Bn)]
@@ -291,11 +287,18 @@ def main():
     for i in range(warm):
         step(i)
     B.dbl_kv_len(ctx, kv0)          # synchronises
+    # K steps between two synchronisations (wall clock), with an event between consecutive steps on the
+    # context's stream (= torch's current stream) for the per-step times
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
+    marks[0].record()
     for i in range(steps):
         step(warm + i)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    ms_median = per_step[steps // 2] if steps % 2 else 0.5 * (per_step[steps // 2 - 1] + per_step[steps // 2])
     kv1 = np.zeros(Bn, np.int32)
     B.dbl_kv_len(ctx, kv1)
     emitted = int((kv1 - kv0).sum())      # sum over steps of n_acc + 1
@@ -329,17 +332,21 @@ def main():
             continue
         ms, nbytes = B.dbl_bench_projection(ctx, which, M, args.kernel_iters if which != 4 else max(4, args.kernel_iters // 4))
         proj[name] = {"ms": round(ms, 5), "GB/s": round(nbytes / ms / 1e6, 1), "bytes": nbytes}
+    dom_which = 2 if "gate_up_swiglu" in proj else 4
     dom = proj.get("gate_up_swiglu") or proj["lm_head_stats"]
-    # (the headline workload's 8 rows run it in gemm_rows_kernel; many-row and some 16-row passes in gemm_wide_swiglu_kernel)
-    gu_kernel = "gemm_rows_kernel<EPI_SWIGLU>" if args.workload == "llama70b_ctx2048_k8_b1_greedy" else "the gate/up projection kernel"
-    roofline = {"bound": "hbm", "kernel": gu_kernel + " after xn_kernel (fused gate/up projection of one layer)",
+    plan = B.dbl_projection_plan(ctx, dom_which, M)
+    forms = {0: "gemm_stream_kernel", 1: "gemm_rows_kernel", 2: "gemm_wide_swiglu_kernel", 3: "gemm_wide_slice_kernel + resid_reduce_kernel"}
+    roofline = {"bound": "hbm",
+                "kernel": "%s after xn_kernel (%s of one layer)" % (forms[plan[0]], "fused gate/up projection" if dom_which == 2 else "LM head"),
+                "launch": {"tile_rows_per_unit": plan[1], "workgroups": plan[2], "split_units": bool(plan[3]), "rows": M},
                 "achieved": dom["GB/s"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(dom["GB/s"] / HBM_PEAK_GBPS, 4), "traffic": None,
                 "bytes_per_launch": dom["bytes"], "ms_per_launch": dom["ms"]}
-    if args.workload in MEASURED_TRAFFIC and args.layers <= 0 and "gate_up_swiglu" in proj:
-        roofline["traffic"] = MEASURED_TRAFFIC[args.workload]
-        roofline["traffic_unit"] = "bytes per launch (rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE, offline)"
-        roofline["traffic_vs_algorithmic"] = round(MEASURED_TRAFFIC[args.workload] / dom["bytes"], 4)
+    rec = MEASURED_TRAFFIC.get(workload)
+    if rec and args.layers <= 0 and dom_which == 2 and tuple(plan) == rec["plan"] and not args.tune:
+        roofline["traffic"] = rec["bytes"]
+        roofline["traffic_unit"] = "bytes per launch (rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE of %s, recorded in profiles/)" % rec["kernel"]
+        roofline["traffic_vs_algorithmic"] = round(rec["bytes"] / dom["bytes"], 4)
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB
         dst = torch.empty_like(src)
@@ -348,23 +355,65 @@ def main():
         del src, dst
     B.dbl_destroy(ctx)
 
+    name = workload if args.layers <= 0 else "%s_first%dlayers" % (workload, args.layers)
     out = {
         "metric": "verified tokens/s of target verify step (70B-shape, k=8) + achieved HBM GB/s",
         "value": round(Bn * k / (dt / steps), 2), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warm,
-        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_step, 4), "ms_per_step_median": round(ms_median, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None,
         "dtype": "bf16" if shape["dtype"] == 1 else "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "layers": shape["n_layers"], "ctx": P, "k": k, "batch": Bn,
+        "config": {"workload": name, "ctx": P, "k": k, "batch": Bn,
                    "accept": mode, "weights": "random N(0,0.02) from seed %d" % seed,
                    "kv_cache": ("seeded fill" if filled else "prefill of the history") + (", paged" if args.paged_kv else "")},
         "hbm_GBps_step": round(step_gbps, 1), "hbm_frac_step": round(step_gbps / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": int(step_bytes), "emitted_tokens_per_s": round(emitted / dt, 2),
         "breakdown_ms": breakdown, "projections": proj, "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
+    if with_cpu_baseline:
         t0 = time.perf_counter()
         full_layers = synth.CONFIGS[shape_key]["n_layers"] if args.layers <= 0 else args.layers
-        out["cpu_baseline"] = cpu_baseline(shape_key, k, full_layers, shape["vocab"])
+        out["cpu_baseline"] = cpu_baseline(shape_key, k, P, full_layers, shape["vocab"])
         log("[bench] oracle baseline took %.1fs" % (time.perf_counter() - t0))
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama70b_ctx2048_k8_b1_greedy", choices=sorted(WORKLOADS))
+    ap.add_argument("--also", default="", help="comma-separated further workloads, summarised under other_workloads")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the model's own)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-iters", type=int, default=40, help="launches per projection for the roofline line")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 --pmc byte counters)")
+    ap.add_argument("--paged-kv", action="store_true", help="KV cache as a pool of 256-token pages (default: contiguous)")
+    ap.add_argument("--tune", default="", help="dbl_tuning fields, e.g. attn_p16=0,split_units=-1 (measurement of kernel forms)")
+    ap.add_argument("--double", action="store_true",
+                    help="measure the full Double round (draft + target on two streams) instead of the headline step")
+    ap.add_argument("--double-tokens", type=int, default=64)
+    ap.add_argument("--double-gamma", type=int, default=0, help="draft iterations per round (0 = ceil(T_p / T_q))")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus)
+        sys.exit(2)
+
+    if args.double:
+        return bench_double(args)
+
+    out = run_workload(args, args.workload, not args.no_cpu_baseline)
+    others = [w for w in args.also.split(",") if w]
+    for w in others:
+        if w not in WORKLOADS:
+            log("bench.py: unknown workload %s" % w)
+            sys.exit(2)
+        o = run_workload(args, w, False)
+        out.setdefault("other_workloads", {})[w] = {
+            "ms_per_step": o["ms_per_step"], "ms_per_step_median": o["ms_per_step_median"], "value": o["value"], "unit": o["unit"],
+            "hbm_GBps_step": o["hbm_GBps_step"], "hbm_frac_step": o["hbm_frac_step"], "steps": o["steps"],
+            "roofline": {kk: o["roofline"][kk] for kk in ("kernel", "achieved", "frac", "ms_per_launch")}}
     print(json.dumps(out), flush=True)
 
 

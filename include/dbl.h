@@ -31,6 +31,7 @@
  *   - All functions return 0 (DBL_OK) or a negative dbl_status.  Argument checks
  *     come before any GPU call.  Nothing throws or aborts across this boundary.
  *   - Calls on one context are not thread-safe.
+ *   - Measurement, diagnostics and tuning entry points (no part of a step) are declared in dbl_diag.h.
  */
 #ifndef DBL_H
 #define DBL_H
@@ -110,20 +111,6 @@ typedef struct {
  * is left, nothing is enqueued then) and takes them back in dbl_reset and dbl_truncate; results do
  * not depend on the cache form.  Page hand-outs enqueue one small kernel each, so a captured
  * graph must not contain a call that crosses a page boundary for the first time.
- *
- * Environment read here (testing and tuning aids, results stay within the same bars):
- * DBL_STREAMK = 1 makes the projection kernel's split-unit form the form of every projection that
- * can take it, 0 switches it off, unset lets the library choose per launch; DBL_WIDE_GU = 0 sends
- * every gate/up projection through the general projection kernel, never through the one that
- * shares the activations of four units through LDS; DBL_WIDE_RESID = 0 keeps the output and down
- * projection of many-row passes in the general kernel (else: K slices of that shared form plus a
- * reduce kernel);
- * DBL_ATTN_LDS = 0 switches the attention's shared form (one token range per workgroup, K/V
- * staged through LDS) off, 2 / 3 make it the form wherever a kv head has two 16-row query blocks
- * and some cached tokens (two / one block per wave), 4 keeps the library's choice of when but with
- * one block per wave; DBL_ATTN_NB = 1 / 3 never / wherever possible takes the form with two query
- * blocks per wave on K/V fragments in registers; DBL_ATTN_SPLIT_TOKENS sets the cached tokens per
- * attention split; DBL_VERBOSE prints the projection plans to stderr.
  */
 int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream, dbl_ctx** out);
 int dbl_destroy(dbl_ctx* ctx);
@@ -325,7 +312,9 @@ int dbl_lengths_dev(dbl_ctx* ctx, int B, int32_t* kv_len_out_dev, int32_t* hist_
  * Philox4x32-10 keyed by `seed` with counter {step', b, j, 1 + v/4}, word v%4,
  * where step' = step + number of dbl_kv_commit calls this context has run).
  * kv_len is not advanced.  logits_opt_dev, if not NULL, receives the fp32 logits
- * [B][k][vocab].  1 <= B <= max_batch, 1 <= k <= max_window, and for every b
+ * [B][k][vocab].  (The library itself keeps the logits of a call only if logits_opt_dev is given or
+ * temperature > 0 -- the one later reader is dbl_accept's residual draw under dense draft distributions;
+ * a greedy step with logits_opt_dev == NULL writes no logits at all, only the row statistics.)  1 <= B <= max_batch, 1 <= k <= max_window, and for every b
  * kv_len[b] + k <= max_ctx (checked against the host's upper bound of kv_len).
  * temperature <= 0 means "greedy statistics only".
  * The step's calls (retrieve, build_window, verify_block, accept, kv_commit) only enqueue
@@ -395,33 +384,8 @@ int dbl_hist_len(dbl_ctx* ctx, int32_t* host_out);
  * cached token (all layers). */
 int dbl_model_bytes(const dbl_ctx* ctx, uint64_t* weight_bytes, uint64_t* kv_bytes_per_token);
 
-/* Measurement: launch one projection kernel `iters` times (layer = launch index
- * mod n_layers, so consecutive launches stream different weights, as in a real
- * step) for M <= max_batch*max_window rows on the context's stream between two HIP
- * events, with the launch configuration dbl_verify_block uses for that many rows.  which: 0 = fused q/k/v, 1 = output
- * projection, 2 = fused gate/up + SwiGLU, 3 = down projection, 4 = LM head + row
- * statistics.  *ms_out = mean milliseconds per launch; *bytes_out = logical weight
- * bytes one launch must read.  Activations are whatever the scratch buffers hold;
- * the residual stream and statistics are overwritten.  Synchronises. */
-int dbl_bench_projection(dbl_ctx* ctx, int which, int M, int iters, float* ms_out, uint64_t* bytes_out);
 
-/* Diagnostics: which form the attention of a (B, k) window would take at the sequences' current
- * lengths (the host's upper bounds), as dbl_verify_block decides it: out4[0] = 0 register form with
- * deep prefetch (one workgroup per CU at most), 1 register form, 2 shared form (K/V staged through LDS);
- * out4[1] = 16-row query blocks per wave; out4[2] = waves per workgroup; out4[3] = splits (token ranges
- * over the cache + 1 for the window rows).  Touches no GPU state. */
-int dbl_attn_plan(dbl_ctx* ctx, int B, int k, int32_t* out4);
 
-/* Diagnostics: copy one of the context's scratch buffers, as left by the last
- * dbl_verify_block, to the host (synchronises).  which: 0 = residual stream after
- * the last layer [rows][ld] f32; 1 = last layer's attention output [rows][ld] in
- * the model dtype; 2 = last layer's silu(gate)*up [rows][ld] in the model dtype.
- * *ld_out receives the row stride in elements; `bytes` is the capacity of `host`
- * and must cover max_batch*max_window rows.  Buffers 1 and 2 are row-major only
- * after a call with at most 16 rows (B*k <= 16); larger calls keep them in blocks
- * of 16 rows x 32 columns, element (m, c) at
- * ((m/16 * ld/32 + c/32) * 64 + (c%32/8) * 16 + m%16) * 8 + c%8. */
-int dbl_debug_buffer(dbl_ctx* ctx, int which, void* host, size_t bytes, int32_t* ld_out);
 
 #ifdef __cplusplus
 }

@@ -23,7 +23,7 @@ T_EMB, T_LM, T_GF = 0, 1, 2
 T_G1, T_WQ, T_WK, T_WV, T_GQ, T_GK, T_WO, T_G2, T_WG, T_WU, T_WD = range(10, 21)
 
 EXPORTS = ["dbl_create", "dbl_destroy", "dbl_last_error", "dbl_set_weights", "dbl_get_weights", "dbl_reset", "dbl_truncate", "dbl_kv_fill",
-           "dbl_kv_set", "dbl_kv_get", "dbl_attn_plan",
+           "dbl_kv_set", "dbl_kv_get", "dbl_attn_plan", "dbl_projection_plan", "dbl_tuning_default", "dbl_set_tuning",
            "dbl_build_guided_window", "dbl_merge", "dbl_history_tail", "dbl_history_splice", "dbl_catchup_window", "dbl_lengths_dev",
            "dbl_retrieve_tiered", "dbl_retrieve_tiered_static", "dbl_session_mark", "dbl_prior_set", "dbl_rejected_update", "dbl_rejected_get",
            "dbl_history_set", "dbl_history_get", "dbl_retrieve", "dbl_build_window", "dbl_verify_block", "dbl_verify_block_ragged", "dbl_accept",
@@ -43,6 +43,12 @@ class ModelCfg(C.Structure):
                 ("rms_eps", C.c_float), ("rope_base", C.c_float), ("qk_norm", C.c_int32), ("dtype", C.c_int32),
                 ("max_batch", C.c_int32), ("max_ctx", C.c_int32), ("max_window", C.c_int32),
                 ("max_hist", C.c_int32), ("flags", C.c_int32)]
+
+
+class Tuning(C.Structure):
+    """dbl_tuning of include/dbl_diag.h."""
+    _fields_ = [(n, C.c_int32) for n in ("split_units", "wide_gate_up", "wide_residual", "attn_shared", "attn_blocks",
+                                          "attn_p16", "attn_split_tokens", "verbose")]
 
 
 _lib = None
@@ -93,6 +99,9 @@ def lib():
         L.dbl_model_bytes.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
         L.dbl_bench_projection.argtypes = [vp, i, i, i, C.POINTER(C.c_float), C.POINTER(C.c_uint64)]
         L.dbl_attn_plan.argtypes = [vp, i, i, vp]
+        L.dbl_projection_plan.argtypes = [vp, i, i, vp]
+        L.dbl_tuning_default.argtypes = [C.POINTER(Tuning)]
+        L.dbl_set_tuning.argtypes = [vp, C.POINTER(Tuning)]
         L.dbl_debug_buffer.argtypes = [vp, i, vp, C.c_size_t, C.POINTER(C.c_int32)]
         for n in EXPORTS:
             if n != "dbl_last_error":
@@ -278,6 +287,29 @@ def dbl_attn_plan(ctx, B, k):
     out = (C.c_int32 * 4)()
     _chk(ctx, lib().dbl_attn_plan(ctx, B, k, out))
     return tuple(out)
+
+
+def dbl_projection_plan(ctx, which, M):
+    """(kernel, tile rows per unit or slices, workgroups, split units) -- see include/dbl_diag.h"""
+    out = (C.c_int32 * 4)()
+    _chk(ctx, lib().dbl_projection_plan(ctx, which, M, out))
+    return tuple(out)
+
+
+def dbl_tuning_default() -> Tuning:
+    t = Tuning()
+    lib().dbl_tuning_default(C.byref(t))
+    return t
+
+
+def dbl_set_tuning(ctx, **fields):
+    """Set the named fields of the tuning (the others keep their defaults)."""
+    t = dbl_tuning_default()
+    for k, v in fields.items():
+        if not hasattr(t, k):
+            raise KeyError(k)
+        setattr(t, k, int(v))
+    return _chk(ctx, lib().dbl_set_tuning(ctx, C.byref(t)))
 
 
 def dbl_debug_buffer(ctx, which, host_out):

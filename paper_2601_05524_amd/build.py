@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdbl.so")
 SOURCES = ["dbl_api.hip"]
-HEADERS = ["dbl_dev.h", "dbl_gemm.h", "dbl_kernels.h", "dbl_phases.h", os.path.join("..", "..", "include", "dbl.h")]
+HEADERS = ["dbl_dev.h", "dbl_gemm.h", "dbl_kernels.h", "dbl_phases.h", os.path.join("..", "..", "include", "dbl.h"),
+           os.path.join("..", "..", "include", "dbl_diag.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-function",

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "../../include/dbl.h"
+#include "../../include/dbl_diag.h"
 #include "dbl_kernels.h"
 
 using namespace dbl;
@@ -134,12 +135,14 @@ struct dbl_ctx {
   float* wide_part = nullptr;       // gemm_wide_slice_kernel's parts: [WIDE_SLICES][rows of a pass][d_model] (contexts of more than 64 rows)
   float* sk_part = nullptr;         // gemm_rows_kernel's split units: two slots of partial sums per workgroup
   int* sk_cnt = nullptr;            //   arrivals per unit (zero between launches)
-  int attn_lds = 1;                 // attention's shared (LDS-staged) form: 1 where it pays, 0 never, 2 wherever a kv head has two query blocks and a cached split exists, 3 / 4 like 2 / 1 with one query block per wave (DBL_ATTN_LDS at create)
-  int attn_p16 = 1;                 // shared form: probabilities as one fp16 operand (0: bf16 head + tail) (DBL_ATTN_P16 at create)
-  int attn_nb = 2;                  // query blocks per wave of the attention where it pays; DBL_ATTN_NB at create: 1 never, 3 wherever possible
-  int wide_resid = 1;               // output / down projection of many-row passes through gemm_wide_slice_kernel (DBL_WIDE_RESID=0 at create: never)
-  int wide_gu = 1;                  // gate/up through gemm_wide_swiglu_kernel where wide_gate_up says so (DBL_WIDE_GU=0 at create: always through gemm_rows_kernel)
-  int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never (DBL_STREAMK at create)
+  // which kernel forms the launch logic may choose (dbl_set_tuning; the defaults are the library's own choice)
+  int attn_lds = 1;                 // attention's shared (LDS-staged) form: 1 where it pays, 0 never, 2 wherever a kv head has two query blocks and a cached split exists, 3 / 4 like 2 / 1 with one query block per wave
+  int attn_p16 = 1;                 // shared form: probabilities as one fp16 operand (0: bf16 head + tail)
+  int attn_nb = 2;                  // query blocks per wave of the attention where it pays; 1 never, 3 wherever possible
+  int attn_split_tokens = 0;        // cached tokens per attention split (0: the library's choice)
+  int wide_resid = 1;               // output / down projection of many-row passes through gemm_wide_slice_kernel (0: never)
+  int wide_gu = 1;                  // gate/up through gemm_wide_swiglu_kernel where wide_gate_up says so (0: always through gemm_rows_kernel)
+  int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never
   float *qkv_part = nullptr, *logits = nullptr;
   void *qbuf = nullptr, *attn = nullptr, *act = nullptr;
   int lm_nstat = 0;                 // workgroups of the last LM-head launch (row-statistics entries per row)
@@ -219,13 +222,6 @@ int make_plans(dbl_ctx* c) {
             make_plan(c->p_d, g.d_model, g.d_ffn, 1, c->bf16, PLAN_CHUNKED, c->n_cu) &&
             make_plan(c->p_lm, g.vocab, g.d_model, 1, c->bf16, PLAN_SINGLE, c->n_cu);
   if (!ok) return fail(c, DBL_EINVAL, "d_model too large for a single K slice (max 8192 bf16 / 4096 fp32)");
-  if (std::getenv("DBL_VERBOSE")) {
-    const GemmPlan* ps[5] = {&c->p_qkv, &c->p_o, &c->p_gu, &c->p_d, &c->p_lm};
-    const char* nm[5] = {"qkv", "o", "gate_up", "down", "lm_head"};
-    for (int i = 0; i < 5; ++i)
-      std::fprintf(stderr, "[dbl] plan %-8s N=%d K=%d tiles=%d KS=%d NW=%d SS=%d NCH=%d KBp=%d grid=%d\n", nm[i],
-                   ps[i]->N, ps[i]->K, ps[i]->NT, ps[i]->KS, ps[i]->NW, ps[i]->SS, ps[i]->NCH, ps[i]->KBp, ps[i]->grid);
-  }
   c->ldh = std::max({c->p_o.ldo(), c->p_d.ldo(), c->p_qkv.ldx(), c->p_gu.ldx(), c->p_lm.ldx()});
   return DBL_OK;
 }
@@ -477,8 +473,8 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
     // at least 128 tokens per split: the partials (m, l, O) are written and read back, so
     // finer splits cost more in traffic than they gain in parallelism
     ncs = std::min({ncs, MAX_SPLITS - 1, (ctx_upper + 127) / 128});
-    if (const char* e = std::getenv("DBL_ATTN_SPLIT_TOKENS")) {   // tuning aid
-      const int tok = std::max(32, std::atoi(e));
+    if (c->attn_split_tokens > 0) {   // tuning aid
+      const int tok = std::max(32, c->attn_split_tokens);
       ncs = std::min(MAX_SPLITS - 1, (ctx_upper + tok - 1) / tok);
     }
   };
@@ -512,8 +508,8 @@ LayerSteps<T> layer_steps(dbl_ctx* c, int l, int B, int k) {
       n = ((8 / nw) * c->n_cu + B * Hkv * nqg - 1) / (B * Hkv * nqg);
       n = std::min({n, MAX_SPLITS - 1, (ctx_upper + 127) / 128});
       if (!lds_forced) n = std::max(1, std::min(n, ctx_upper / 384));
-      if (const char* e = std::getenv("DBL_ATTN_SPLIT_TOKENS")) {   // tuning aid
-        const int tok = std::max(32, std::atoi(e));
+      if (c->attn_split_tokens > 0) {   // tuning aid
+        const int tok = std::max(32, c->attn_split_tokens);
         n = std::min(MAX_SPLITS - 1, (ctx_upper + tok - 1) / tok);
       }
     };
@@ -595,7 +591,7 @@ void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
 }
 
 template <typename T>
-int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperature, uint64_t seed, uint64_t step) {
+int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperature, uint64_t seed, uint64_t step, bool store_logits) {
   const dbl_model_cfg& g = c->cfg;
   const int M = B * k, d = g.d_model, hd = g.head_dim, H = g.n_q_heads;
   hipStream_t st = c->stream;
@@ -614,7 +610,7 @@ int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperatu
     // final RMSNorm (gain gf) on load -> logits + per-workgroup row statistics
     GemmArgs<T> a{};
     a.W = reinterpret_cast<const T*>(c->w_lm); a.HG = c->hg; a.ldx = c->ldh;
-    a.out = c->logits; a.ldo = c->p_lm.ldo();
+    a.out = store_logits ? c->logits : nullptr; a.ldo = c->p_lm.ldo();
     a.lm.stats = c->stats; a.lm.window = window; a.lm.commits = c->commits; a.lm.k = k;
     a.lm.inv_T = temperature > 0.f ? 1.0f / temperature : 0.f;
     a.lm.seed = seed; a.lm.step = step;
@@ -786,12 +782,6 @@ int dbl_create(const dbl_model_cfg* cfg, uint64_t weight_seed, void* hip_stream,
   if (!c) return DBL_ENOMEM;
   c->cfg = *cfg; c->bf16 = cfg->dtype == DBL_BF16; c->esz = c->bf16 ? 2 : 4;
   c->dry = (cfg->flags & DBL_FLAG_VALIDATE_ONLY) != 0;
-  if (const char* e = std::getenv("DBL_ATTN_LDS")) c->attn_lds = std::atoi(e);
-  if (const char* e = std::getenv("DBL_ATTN_NB")) c->attn_nb = std::atoi(e);
-  if (const char* e = std::getenv("DBL_ATTN_P16")) c->attn_p16 = std::atoi(e);
-  if (const char* e = std::getenv("DBL_WIDE_RESID")) c->wide_resid = std::atoi(e);
-  if (const char* e = std::getenv("DBL_WIDE_GU")) c->wide_gu = std::atoi(e);
-  if (const char* e = std::getenv("DBL_STREAMK")) c->sk_mode = std::atoi(e) > 0 ? 1 : -1;   // testing / tuning aid
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
   c->seed = weight_seed;
   c->kv_upper.assign(cfg->max_batch, 0); c->hist_upper.assign(cfg->max_batch, 0);
@@ -1322,8 +1312,11 @@ static int verify_common(dbl_ctx* c, const int32_t* window, const int32_t* win_l
   } else {
     HIPCHK(c, hipMemcpyAsync(c->win_i, window, (size_t)B * k * 4, hipMemcpyDeviceToDevice, c->stream));
   }
-  int rc = c->bf16 ? verify_impl<bf16_t>(c, c->win_i, B, k, temperature, seed, step)
-                   : verify_impl<float>(c, c->win_i, B, k, temperature, seed, step);
+  // the fp32 logits are written (once, to scratch) only when somebody reads them: the caller through logits_opt,
+  // or dbl_accept's residual draw under dense draft distributions, which needs temperature > 0
+  const bool store_logits = logits_opt != nullptr || temperature > 0.f;
+  int rc = c->bf16 ? verify_impl<bf16_t>(c, c->win_i, B, k, temperature, seed, step, store_logits)
+                   : verify_impl<float>(c, c->win_i, B, k, temperature, seed, step, store_logits);
   if (rc != DBL_OK) return rc;
   if (logits_opt) {
     HIPCHK(c, hipMemcpy2DAsync(logits_opt, (size_t)c->cfg.vocab * 4, c->logits, (size_t)c->p_lm.ldo() * 4,
@@ -1470,6 +1463,50 @@ int dbl_debug_buffer(dbl_ctx* c, int which, void* host, size_t bytes, int32_t* l
   if (c->dry) return DBL_ENODEV;
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(host, src, need, hipMemcpyDeviceToHost));
+  return DBL_OK;
+}
+
+int dbl_tuning_default(dbl_tuning* t) {
+  if (!t) return DBL_EINVAL;
+  *t = dbl_tuning{0, 1, 1, 1, 2, 1, 0, 0};
+  return DBL_OK;
+}
+
+int dbl_set_tuning(dbl_ctx* c, const dbl_tuning* t) {
+  if (!c) return DBL_EINVAL;
+  if (!t) return fail(c, DBL_EINVAL, "null tuning");
+  if (t->split_units < -1 || t->split_units > 1 || t->attn_shared < 0 || t->attn_shared > 4 || t->attn_blocks < 1 || t->attn_blocks > 3 ||
+      t->attn_split_tokens < 0)
+    return fail(c, DBL_EINVAL, "tuning value out of range");
+  c->sk_mode = t->split_units; c->wide_gu = t->wide_gate_up != 0; c->wide_resid = t->wide_residual != 0;
+  c->attn_lds = t->attn_shared; c->attn_nb = t->attn_blocks; c->attn_p16 = t->attn_p16 != 0;
+  c->attn_split_tokens = t->attn_split_tokens;
+  if (t->verbose) {
+    const GemmPlan* ps[5] = {&c->p_qkv, &c->p_o, &c->p_gu, &c->p_d, &c->p_lm};
+    const char* nm[5] = {"qkv", "o", "gate_up", "down", "lm_head"};
+    for (int i = 0; i < 5; ++i)
+      std::fprintf(stderr, "[dbl] plan %-8s N=%d K=%d tiles=%d KS=%d NW=%d SS=%d NCH=%d KBp=%d grid=%d\n", nm[i],
+                   ps[i]->N, ps[i]->K, ps[i]->NT, ps[i]->KS, ps[i]->NW, ps[i]->SS, ps[i]->NCH, ps[i]->KBp, ps[i]->grid);
+  }
+  return DBL_OK;
+}
+
+int dbl_projection_plan(dbl_ctx* c, int which, int M, int32_t* out4) {
+  if (!c) return DBL_EINVAL;
+  if (!out4) return fail(c, DBL_EINVAL, "null output pointer");
+  if (which < 0 || which > 4) return fail(c, DBL_EINVAL, "bad which");
+  if (M < 1 || M > c->cfg.max_batch * c->cfg.max_window) return fail(c, DBL_EINVAL, "M out of range");
+  const GemmPlan* ps[5] = {&c->p_qkv, &c->p_o, &c->p_gu, &c->p_d, &c->p_lm};
+  const int epis[5] = {EPI_PARTIAL, EPI_RESIDUAL, EPI_SWIGLU, EPI_RESIDUAL, EPI_LMHEAD};
+  const GemmPlan& p = *ps[which];
+  const int epi = epis[which], mrows = std::min(M, which == 4 ? 64 : 128), R = pass_groups(mrows);
+  int kernel = 0, q = 0, grid = p.grid, sk = 0;
+  if (rows_kernel_for(c, p, epi, M)) {
+    if (c->bf16 && epi == EPI_RESIDUAL && wide_resid_slices(c, p, mrows)) { kernel = 3; q = wide_resid_slices(c, p, mrows); grid = (p.NT + 15) / 16 * q; }
+    else if (c->bf16 && epi == EPI_SWIGLU && wide_gate_up(c, p, mrows)) { kernel = 2; q = 4; grid = std::min((2 * p.NT + 15) / 16, c->n_cu); }
+    else { const RowsChoice ch = rows_choice(c, p, epi, R); kernel = 1; q = ch.q; grid = ch.grid; sk = ch.sk ? 1 : 0; }
+  }
+  out4[0] = kernel; out4[1] = q; out4[2] = grid; out4[3] = sk;
   return DBL_OK;
 }
 

@@ -125,7 +125,7 @@ struct GemmArgs {
   int KBp;             // k-blocks per tile row = SS * NCH * NW * KS
   int SS;              // super slices; number of workgroups % SS == 0
   int NCH;             // K chunks walked by one workgroup (1 unless the CHUNK form runs)
-  float* out;          // PARTIAL: [SS][Mtot][ldo] ; RESIDUAL: h[Mtot][ldo] (+=) ; LMHEAD: logits[Mtot][ldo]
+  float* out;          // PARTIAL: [SS][Mtot][ldo] ; RESIDUAL: h[Mtot][ldo] (+=) ; LMHEAD: logits[Mtot][ldo] or nullptr (statistics only)
   int ldo;
   float* ssq_out;      // RESIDUAL: [Mtot][SSQ_PARTS] partial sums of squares of the updated rows
   float* hg_out;       // RESIDUAL: [Mtot][ldo] updated rows times gain_out (input of the next RMSNorm)
@@ -502,7 +502,8 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
 #pragma unroll
         for (int rr = 0; rr < R; ++rr) sq[rr] += rr == r ? e : 0.f;
       } else if (EPI == EPI_LMHEAD) {
-        *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = v[0];
+        // (the logits themselves only if somebody will read them: the caller, or a residual draw under dense q)
+        if (a.out) *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = v[0];
 #pragma unroll
         for (int rr = 0; rr < R; ++rr)
           if (rr == r) lm_update(st[EPI == EPI_LMHEAD ? rr : 0], v[0], n, a.N, draft[rr], pb[rr], pj[rr], stepv, a.lm);

@@ -72,29 +72,10 @@ __global__ void __launch_bounds__(256) accept_kernel(const AcceptArgs a) {
   for (int j = wave; j < a.k; j += (int)(blockDim.x >> 6)) {
     const int m = b * a.k + j;
     LmStat s;
-    s.best = -INFINITY; s.best_id = 0x7fffffff; s.smax = -INFINITY; s.ssum = 0.f; s.zdraft = -INFINITY;
-    s.p1 = -INFINITY; s.p1_id = 0x7fffffff; s.p2 = -INFINITY; s.p2_id = 0x7fffffff;
-    auto merge = [](LmStat& x, const LmStat& y) {
-      if (better(y.best, y.best_id, x.best, x.best_id)) { x.best = y.best; x.best_id = y.best_id; }
-      x.zdraft = fmaxf(x.zdraft, y.zdraft);
-      const float nm = fmaxf(x.smax, y.smax);
-      if (nm > -INFINITY) x.ssum = x.ssum * expf(x.smax - nm) + y.ssum * expf(y.smax - nm);
-      x.smax = nm;
-      if (better(y.p1, y.p1_id, x.p1, x.p1_id)) {
-        if (better(x.p1, x.p1_id, y.p2, y.p2_id)) { x.p2 = x.p1; x.p2_id = x.p1_id; } else { x.p2 = y.p2; x.p2_id = y.p2_id; }
-        x.p1 = y.p1; x.p1_id = y.p1_id;
-      } else if (better(y.p1, y.p1_id, x.p2, x.p2_id)) { x.p2 = y.p1; x.p2_id = y.p1_id; }
-    };
-    for (int i = lane; i < a.nstat; i += 64) merge(s, a.stats[(size_t)i * a.Mtot + m]);
+    lm_init(s);
+    for (int i = lane; i < a.nstat; i += 64) lm_merge(s, a.stats[(size_t)i * a.Mtot + m]);
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-      LmStat o;
-      o.best = __shfl_xor(s.best, off); o.best_id = __shfl_xor(s.best_id, off);
-      o.smax = __shfl_xor(s.smax, off); o.ssum = __shfl_xor(s.ssum, off); o.zdraft = __shfl_xor(s.zdraft, off);
-      o.p1 = __shfl_xor(s.p1, off); o.p1_id = __shfl_xor(s.p1_id, off);
-      o.p2 = __shfl_xor(s.p2, off); o.p2_id = __shfl_xor(s.p2_id, off);
-      merge(s, o);
-    }
+    for (int off = 32; off >= 1; off >>= 1) lm_merge(s, lm_shfl_xor(s, off));
     if (lane == 0) row[j] = s;
   }
   __syncthreads();

@@ -8,6 +8,9 @@ from paper_2601_05524_amd import binding as B
 
 DEV = "cuda:0"
 
+# dbl_tuning fields every Gpu context of a test gets (tests that force a kernel form set this through monkeypatch)
+TUNING = {}
+
 
 def f32_to_bf16_bits(a):
     """Exact for arrays that already hold bf16 values."""
@@ -40,6 +43,8 @@ class Gpu:
         torch.cuda.set_device(0)
         self.stream = torch.cuda.current_stream()
         self.ctx = B.dbl_create(self.cfg, seed, self.stream.cuda_stream)
+        if TUNING:
+            B.dbl_set_tuning(self.ctx, **TUNING)
         self.V = shape["vocab"]
         self.bf16 = shape["dtype"] == B.DBL_BF16
         self.ncommit = 0     # dbl_kv_commit calls so far (they offset the Philox step word)

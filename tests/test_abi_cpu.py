@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    src = open(os.path.join(ROOT, "include", "dbl.h")).read()
+    src = open(os.path.join(ROOT, "include", "dbl.h")).read() + open(os.path.join(ROOT, "include", "dbl_diag.h")).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(dbl_[a-z_0-9]+)\s*\(", src)))
 
@@ -181,6 +181,18 @@ def test_new_entry_points_check_their_arguments():
     assert L.dbl_attn_plan(ctx, 1, 8, out) == B.DBL_OK and out[3] >= 1
     assert L.dbl_attn_plan(ctx, 3, 8, out) == B.DBL_EINVAL
     assert L.dbl_attn_plan(ctx, 1, 8, None) == B.DBL_EINVAL
+    assert L.dbl_projection_plan(ctx, 2, 8, out) == B.DBL_OK and out[2] >= 1
+    assert L.dbl_projection_plan(ctx, 5, 8, out) == B.DBL_EINVAL
+    # tuning: forms can be forced or forbidden through the ABI; nonsense is refused
+    t = B.dbl_tuning_default()
+    assert (t.split_units, t.wide_gate_up, t.wide_residual, t.attn_shared, t.attn_blocks, t.attn_p16, t.attn_split_tokens) == (0, 1, 1, 1, 2, 1, 0)
+    assert L.dbl_set_tuning(ctx, C.byref(t)) == B.DBL_OK
+    before = tuple(out)
+    assert B.dbl_set_tuning(ctx, split_units=1) == B.DBL_OK
+    assert L.dbl_projection_plan(ctx, 2, 8, out) == B.DBL_OK and (out[3] == 1 or tuple(out) == before)
+    t.attn_shared = 9
+    assert L.dbl_set_tuning(ctx, C.byref(t)) == B.DBL_EINVAL
+    assert L.dbl_set_tuning(ctx, None) == B.DBL_EINVAL
     assert B.dbl_destroy(ctx) == 0
 
 

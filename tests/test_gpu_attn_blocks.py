@@ -3,8 +3,8 @@ of K/V fragments in registers for 32 query rows, two sets of fragments in flight
 form (see the fixture below).
 
 The library takes that form by itself only for many query rows over long ranges of cached tokens
-(8 or more query blocks per kv head and at least 1024 tokens per split); DBL_ATTN_NB=3 at context
-creation makes it the form wherever a kv head has at least two query blocks, so that small models
+(8 or more query blocks per kv head and at least 1024 tokens per split); the tuning attn_blocks = 3
+makes it the form wherever a kv head has at least two query blocks, so that small models
 reach it: odd numbers of blocks (the last wave's second block is padding), windows of more than 16
 rows, batches with different context lengths, ranges that end inside a 32-token step, the paged
 cache.  Bars as in the other parity tests."""
@@ -12,6 +12,7 @@ import numpy as np
 import pytest
 
 from paper_2601_05524_amd import synth
+from tests import gpu_util
 from tests.gpu_util import Gpu, Ref
 from tests.test_gpu_parity import SMALL_BF16, SMALL_QWEN, TOL, jitter_gains
 
@@ -20,13 +21,13 @@ pytestmark = pytest.mark.gpu
 
 # The shared form (the waves of a workgroup walk one token range together, K/V staged through LDS) is
 # taken by itself from 2 query blocks per kv head and 384 cached tokens per split on (where the chip has fewer CUs
-# than the step has attention workgroups); DBL_ATTN_LDS=2
+# than the step has attention workgroups); the tuning attn_shared = 2
 # (two blocks per wave) / 3 (one) makes it the form wherever a kv head has two query blocks and the
 # cache is not empty, with 2, 4 or 8 waves per workgroup depending on the window.
-@pytest.fixture(params=[("DBL_ATTN_NB", "3"), ("DBL_ATTN_LDS", "2"), ("DBL_ATTN_LDS", "3")],
+@pytest.fixture(params=[dict(attn_blocks=3), dict(attn_shared=2), dict(attn_shared=3)],
                 ids=["two_blocks_per_wave", "shared_two_blocks", "shared_one_block"])
 def forced(monkeypatch, request):
-    monkeypatch.setenv(*request.param)
+    monkeypatch.setattr(gpu_util, "TUNING", request.param)
 
 
 def max_err(got, ref):

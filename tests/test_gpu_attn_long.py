@@ -6,7 +6,7 @@ at least 384 cached tokens per split: 4 sequences x 8 kv heads over 16 384 cache
 for every window of the long-context workloads (k = 4: 2 query blocks per kv head, 2 waves per
 workgroup; k = 16: 8 blocks, two per wave, 4 waves; k = 32: 16 blocks, 8 waves).  The oracle
 cannot prefill such a cache in a test's time, so the cache is the library's seeded fill and the
-reference is the library itself with that form switched off (DBL_ATTN_LDS=0): the register forms,
+reference is the library itself with that form switched off (tuning attn_shared = 0): the register forms,
 which the other parity tests pin to the oracle.  The two differ in the order of their sums only;
 over two full-width layers that rounding noise compounds (any two forms, also two register forms
 with different splits, end up 0.03-0.04 apart at a logit rms of 1.8), so the bars are the ones
@@ -17,6 +17,7 @@ import numpy as np
 import pytest
 
 from paper_2601_05524_amd import binding as B
+from tests import gpu_util
 from tests.gpu_util import Gpu
 from tests.test_gpu_wide import COMPOSITE_MAX, COMPOSITE_REL, slice_of
 
@@ -26,7 +27,7 @@ CTX = [16384, 16001, 9000, 16384]
 
 
 def run(monkeypatch, mode, k, windows):
-    monkeypatch.setenv("DBL_ATTN_LDS", mode)
+    monkeypatch.setattr(gpu_util, "TUNING", dict(attn_shared=mode))
     g = Gpu(slice_of("llama70b"), seed=71, max_batch=4, max_ctx=16384 + 64, max_window=32)
     for b, n in enumerate(CTX):
         B.dbl_kv_fill(g.ctx, b, n, 900 + b)
@@ -41,8 +42,8 @@ def test_shared_form_agrees_with_register_forms_over_long_cache(monkeypatch, k):
     V = slice_of("llama70b")["vocab"]
     rng = np.random.default_rng(100 + k)
     windows = rng.integers(0, V, (4, k)).astype(np.int32)
-    ref = run(monkeypatch, "0", k, windows)
-    got = run(monkeypatch, "1", k, windows)
+    ref = run(monkeypatch, 0, k, windows)
+    got = run(monkeypatch, 1, k, windows)
     assert np.isfinite(got).all() and np.isfinite(ref).all()
     d = np.abs(got.astype(np.float64) - ref)
     rel = np.sqrt((d ** 2).mean()) / np.sqrt((ref.astype(np.float64) ** 2).mean())

@@ -2,7 +2,7 @@
 workgroup, units that straddle ranges finished by their last workgroup).
 
 The library picks that form by itself only where whole units would fill the chip badly (large
-widths that are not a multiple of 256 tile rows); DBL_STREAMK=1 at context creation makes it
+widths that are not a multiple of 256 tile rows); the tuning split_units = 1 makes it
 the form of every projection that can take it, so that small models reach every path of it:
 units cut into one chunk per workgroup, ranges that hold whole units and parts of units, every
 epilogue, every pass size.  Bars as in the other parity tests (logits 2e-2 bf16 / 1e-4 fp32
@@ -13,6 +13,7 @@ import numpy as np
 import pytest
 
 from paper_2601_05524_amd import synth
+from tests import gpu_util
 from tests.gpu_util import Gpu, Ref
 from tests.test_gpu_parity import SMALL_BF16, SMALL_QWEN, SMALL_F32_128, TOL, jitter_gains
 
@@ -30,7 +31,7 @@ MID_F32 = dict(n_layers=1, d_model=1024, n_q_heads=8, n_kv_heads=2, head_dim=128
 
 @pytest.fixture
 def forced(monkeypatch):
-    monkeypatch.setenv("DBL_STREAMK", "1")
+    monkeypatch.setattr(gpu_util, "TUNING", dict(split_units=1))
 
 
 def max_err(got, ref):
@@ -88,7 +89,7 @@ def test_split_units_are_reproducible_and_close_to_whole_units(monkeypatch):
         g.close()
         return np.stack(out)
 
-    monkeypatch.setenv("DBL_STREAMK", "1")
+    monkeypatch.setattr(gpu_util, "TUNING", dict(split_units=1))
     a, b = run(), run()
     assert np.array_equal(a, b)
     # the same window again and again on one context (nothing committed in between): which workgroup
@@ -98,7 +99,7 @@ def test_split_units_are_reproducible_and_close_to_whole_units(monkeypatch):
     for _ in range(20):
         assert np.array_equal(g.verify(ws[0]), first)
     g.close()
-    monkeypatch.setenv("DBL_STREAMK", "0")
+    monkeypatch.setattr(gpu_util, "TUNING", dict(split_units=-1))
     c = run()
     # same arithmetic up to the order of fp32 additions; a value that lands on the other side of a bf16
     # rounding boundary moves a logit by up to 1e-2 at this width, so the bar is the parity bar itself
