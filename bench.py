@@ -60,6 +60,10 @@ WORKLOADS = {
 }
 
 
+# the other named configurations, summarised beside the headline line by default (they add about a minute)
+DEFAULT_ALSO = "llama1b_ctx1024_k8_b1_greedy,qwen32b_ctx8192_k16_b1_sample,llama70b_ctx32768_k32_b4_sample"
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -383,7 +387,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama70b_ctx2048_k8_b1_greedy", choices=sorted(WORKLOADS))
-    ap.add_argument("--also", default="", help="comma-separated further workloads, summarised under other_workloads")
+    ap.add_argument("--also", default=DEFAULT_ALSO,
+                    help="comma-separated further workloads, summarised under other_workloads ('' or 'none': only --workload)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (0 = the model's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=40, help="launches per projection for the roofline line")
@@ -404,7 +409,7 @@ def main():
         return bench_double(args)
 
     out = run_workload(args, args.workload, not args.no_cpu_baseline)
-    others = [w for w in args.also.split(",") if w]
+    others = [w for w in args.also.split(",") if w and w != "none" and w != args.workload]
     for w in others:
         if w not in WORKLOADS:
             log("bench.py: unknown workload %s" % w)
