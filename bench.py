@@ -39,7 +39,7 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # Counters cannot be read inside this process, so the figure is the recorded one; it is reported only while
 # the library still launches the gate/up projection the way it did under the profiler (dbl_projection_plan:
 # kernel form, tile rows per unit, workgroups, split units), else null.
-MEASURED_TRAFFIC = {"llama70b_ctx2048_k8_b1_greedy": {"bytes": 944_398_336,          # 921 208 + 1 056 KiB
+MEASURED_TRAFFIC = {"llama70b_ctx2048_k8_b1_greedy": {"bytes": 944_430_490,          # (460 158.4 + 300.0) KiB x 2.000 + 875.7 + 502.9 KiB
                                                       "plan": (1, 2, 256, 0),        # gemm_rows_kernel, Q = 2, 256 workgroups, whole units
                                                       "kernel": "gemm_rows_kernel<bf16, EPI_SWIGLU, R=1, Q=2> after xn_kernel"}}
 
@@ -171,8 +171,11 @@ def bench_double(args):
     res["draft_chain"] = {"forwards": gamma, "L_draft": len(chain), "AMT": round(len(chain) / gamma - 1.0, 3),
                           "ms": round(t_chain * 1e3, 3), "ms_per_forward": round(t_chain / gamma * 1e3, 3)}
     # plain greedy decoding of the target, one token per forward
+    target.load(prompt)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ar = DR.autoregressive(target, prompt, min(n_new, 24))
+    DR.autoregressive_steps(target, min(n_new, 24))
+    ar = target.generated()
     res["autoregressive"] = {"tokens": len(ar), "tokens_per_s": round(len(ar) / (time.perf_counter() - t0), 2)}
     # target-only retrieval decoding (the headline step, chained on the device)
     target.load(prompt)

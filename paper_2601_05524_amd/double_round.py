@@ -180,9 +180,8 @@ class DoubleDecoder:
         return self.t.generated(), self.rounds
 
 
-def autoregressive(lane: Lane, prompt, n_new: int):
-    """Plain greedy decoding on the same kernels, one token per forward, chained on the device."""
-    lane.load(prompt)
+def autoregressive_steps(lane: Lane, n_new: int):
+    """Enqueue n_new plain greedy decoding steps (one token per forward, chained on the device) on a loaded lane."""
     with torch.cuda.stream(lane.stream):
         lane.cl.zero_()
         for _ in range(n_new):
@@ -190,4 +189,10 @@ def autoregressive(lane: Lane, prompt, n_new: int):
             B.dbl_verify_block(lane.ctx, lane.window, 1, 1)
             B.dbl_accept(lane.ctx, B.DBL_GREEDY, None, lane.n_acc, lane.emit, lane.guide)
             lane.commit()
+
+
+def autoregressive(lane: Lane, prompt, n_new: int):
+    """Plain greedy decoding on the same kernels: load the prompt, n_new steps, return the new tokens."""
+    lane.load(prompt)
+    autoregressive_steps(lane, n_new)
     return lane.generated()
