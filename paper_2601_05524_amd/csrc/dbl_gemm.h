@@ -385,7 +385,12 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
 //     and clears the counter.  Nobody waits for anybody.  The parts travel as device-scope
 //     relaxed atomic stores and loads (they pass the per-XCD L2s), ordered against the counter
 //     by a wait for the stores' completion: a device-scope fence would write back and
-//     invalidate the whole L2 of the XCD each time, which more than doubled the kernel's time.
+//     invalidate the whole L2 of the XCD each time, which more than doubled the kernel's time
+//     (an acquire-release fetch-add at agent scope on the counter, the memory model's way of saying
+//     the same, was timed too: the 32B-shaped step 13.65 -> 16.06 ms).  The fences below are
+//     therefore workgroup-scoped: what crosses workgroups does so in sc1 accesses that do not use
+//     the non-coherent caches, and vmcnt(0) orders them against the counter on this hardware; under
+//     the language's memory model alone this hand-off would be a race.
 template <typename T, int EPI, int R, int Q, bool SK>
 __global__ void __launch_bounds__(256) gemm_rows_kernel(const GemmArgs<T> a) {
   constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
