@@ -141,6 +141,7 @@ struct dbl_ctx {
   int attn_nb = 2;                  // query blocks per wave of the attention where it pays; 1 never, 3 wherever possible
   int attn_split_tokens = 0;        // cached tokens per attention split (0: the library's choice)
   int wide_resid = 1;               // output / down projection of many-row passes through gemm_wide_slice_kernel (0: never)
+  int wide_lm = 1;                  // LM head of passes of more than 32 rows through gemm_wide_lmhead_kernel (0: gemm_rows_kernel, 64 rows per pass)
   int wide_gu = 1;                  // gate/up through gemm_wide_swiglu_kernel where wide_gate_up says so (0: always through gemm_rows_kernel)
   int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never
   float *qkv_part = nullptr, *logits = nullptr;
@@ -373,26 +374,62 @@ static int qkv_parts(const dbl_ctx* c, int M) {
   return c->p_qkv.SS;
 }
 
+// Whether the LM head of an M-row window runs in gemm_wide_lmhead_kernel (bf16): from 33 rows on, where
+// gemm_rows_kernel's per-wave activations cost it most and, above 64 rows, a second pass over the matrix
+// (70B width, 128 rows: 2 x 465 us against one pass).
+static bool wide_lm_head(const dbl_ctx* c, const GemmPlan& p, int M) {
+  return c->bf16 && c->wide_lm && p.KBp % 4 == 0 && M > 32;
+}
+
+// The RMSNorm output of rows m0 .. m0+mrows-1 as a stored tensor (a row's columns over several workgroups
+// while the rows alone would leave most of the chip idle).
+template <typename T>
+T* launch_xn(dbl_ctx* c, const GemmArgs<T>& a) {
+  T* xn = reinterpret_cast<T*>(c->xn);
+  const int nsl = std::max(1, std::min((c->ldh + 1023) / 1024, 64 / a.mrows));
+  hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows * nsl), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, a.m0, nsl, a.d, a.eps);
+  return xn;
+}
+
+// LM head + row statistics of M rows.  Every pass of a call takes the same kernel, the same number of row groups
+// and therefore the same grid, so that one count of statistics entries per row (lm_nstat) serves all rows.
+template <typename T>
+void launch_lm_head(dbl_ctx* c, const GemmPlan& p, GemmArgs<T> a, int M) {
+  const bool wide = wide_lm_head(c, p, M);
+  const int pass = wide ? 128 : 64, R = pass_groups(std::min(M, pass));
+  for (int m0 = 0; m0 < M; m0 += pass) {
+    a.m0 = m0; a.mrows = std::min(pass, M - m0);
+    a.X = launch_xn<T>(c, a);
+    if constexpr (sizeof(T) == 2) {
+      if (wide) {
+        const dim3 grid(std::min((p.NT + 15) / 16, c->n_cu)), block(256);
+        if (R == 8) hipLaunchKernelGGL((gemm_wide_lmhead_kernel<T, 8>), grid, block, 0, c->stream, a);
+        else hipLaunchKernelGGL((gemm_wide_lmhead_kernel<T, 4>), grid, block, 0, c->stream, a);
+        c->lm_nstat = (int)grid.x;
+        continue;
+      }
+    }
+    if (R == 4) launch_gemm_rows<T, 4>(c, p, EPI_LMHEAD, a);
+    else if (R == 2) launch_gemm_rows<T, 2>(c, p, EPI_LMHEAD, a);
+    else launch_gemm_rows<T, 1>(c, p, EPI_LMHEAD, a);
+  }
+}
+
 template <typename T>
 void launch_gemm(dbl_ctx* c, const GemmPlan& p, int epi, GemmArgs<T> a, int M) {
   a.NT = p.NT; a.N = p.N; a.KBp = p.KBp; a.SS = p.SS; a.NCH = p.NCH; a.Mtot = M;
   a.d = (float)c->cfg.d_model; a.eps = c->cfg.rms_eps; a.ssq_in = c->ssq; a.ssq_out = c->ssq;
   static_assert(SSQ_PARTS == 256, "xn_kernel adds one partial per thread");
+  if (epi == EPI_LMHEAD) { launch_lm_head<T>(c, p, a, M); return; }
   const bool rows = rows_kernel_for(c, p, epi, M);
   if (rows) {
-    T* xn = reinterpret_cast<T*>(c->xn);
     a.act_tiled = rows_kernel_for(c, c->p_d, EPI_RESIDUAL, M) ? 1 : 0;
     // rows per pass: 128 (eight row groups; measured at the 70B width against two 64-row passes:
-    // q/k/v 66 / 98 us, output 58 / 68, gate/up 222 / 335, down 167 / 189), 64 for the LM head
-    const int pass = epi == EPI_LMHEAD ? 64 : 128;
+    // q/k/v 66 / 98 us, output 58 / 68, gate/up 222 / 335, down 167 / 189)
+    const int pass = 128;
     for (int m0 = 0; m0 < M; m0 += pass) {
       a.m0 = m0; a.mrows = std::min(pass, M - m0);
-      if (epi != EPI_RESIDUAL) {     // the RMSNorm output is stored first and read like any activation
-        // (a row's columns over several workgroups while the rows alone would leave most of the chip idle)
-        const int nsl = std::max(1, std::min((c->ldh + 1023) / 1024, 64 / a.mrows));
-        hipLaunchKernelGGL((xn_kernel<T>), dim3(a.mrows * nsl), dim3(256), 0, c->stream, a.HG, c->ssq, xn, c->ldh, m0, nsl, a.d, a.eps);
-        a.X = xn;
-      }
+      if (epi != EPI_RESIDUAL) a.X = launch_xn<T>(c, a);   // the RMSNorm output is stored first and read like any activation
       if constexpr (sizeof(T) == 2) {
         // gate/up: four units per workgroup on one set of activations staged through LDS, where that is the better form
         if (epi == EPI_RESIDUAL) {
@@ -1468,7 +1505,7 @@ int dbl_debug_buffer(dbl_ctx* c, int which, void* host, size_t bytes, int32_t* l
 
 int dbl_tuning_default(dbl_tuning* t) {
   if (!t) return DBL_EINVAL;
-  *t = dbl_tuning{0, 1, 1, 1, 2, 1, 0, 0};
+  *t = dbl_tuning{0, 1, 1, 1, 1, 2, 1, 0, 0};
   return DBL_OK;
 }
 
@@ -1478,7 +1515,7 @@ int dbl_set_tuning(dbl_ctx* c, const dbl_tuning* t) {
   if (t->split_units < -1 || t->split_units > 1 || t->attn_shared < 0 || t->attn_shared > 4 || t->attn_blocks < 1 || t->attn_blocks > 3 ||
       t->attn_split_tokens < 0)
     return fail(c, DBL_EINVAL, "tuning value out of range");
-  c->sk_mode = t->split_units; c->wide_gu = t->wide_gate_up != 0; c->wide_resid = t->wide_residual != 0;
+  c->sk_mode = t->split_units; c->wide_gu = t->wide_gate_up != 0; c->wide_resid = t->wide_residual != 0; c->wide_lm = t->wide_lm_head != 0;
   c->attn_lds = t->attn_shared; c->attn_nb = t->attn_blocks; c->attn_p16 = t->attn_p16 != 0;
   c->attn_split_tokens = t->attn_split_tokens;
   if (t->verbose) {
@@ -1499,9 +1536,10 @@ int dbl_projection_plan(dbl_ctx* c, int which, int M, int32_t* out4) {
   const GemmPlan* ps[5] = {&c->p_qkv, &c->p_o, &c->p_gu, &c->p_d, &c->p_lm};
   const int epis[5] = {EPI_PARTIAL, EPI_RESIDUAL, EPI_SWIGLU, EPI_RESIDUAL, EPI_LMHEAD};
   const GemmPlan& p = *ps[which];
-  const int epi = epis[which], mrows = std::min(M, which == 4 ? 64 : 128), R = pass_groups(mrows);
+  const int epi = epis[which], mrows = std::min(M, which == 4 && !wide_lm_head(c, p, M) ? 64 : 128), R = pass_groups(mrows);
   int kernel = 0, q = 0, grid = p.grid, sk = 0;
-  if (rows_kernel_for(c, p, epi, M)) {
+  if (epi == EPI_LMHEAD && wide_lm_head(c, p, M)) { kernel = 4; q = 4; grid = std::min((p.NT + 15) / 16, c->n_cu); }
+  else if (rows_kernel_for(c, p, epi, M)) {
     if (c->bf16 && epi == EPI_RESIDUAL && wide_resid_slices(c, p, mrows)) { kernel = 3; q = wide_resid_slices(c, p, mrows); grid = (p.NT + 15) / 16 * q; }
     else if (c->bf16 && epi == EPI_SWIGLU && wide_gate_up(c, p, mrows)) { kernel = 2; q = 4; grid = std::min((2 * p.NT + 15) / 16, c->n_cu); }
     else { const RowsChoice ch = rows_choice(c, p, epi, R); kernel = 1; q = ch.q; grid = ch.grid; sk = ch.sk ? 1 : 0; }

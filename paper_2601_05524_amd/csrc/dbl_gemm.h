@@ -29,6 +29,7 @@
 // partials in a fixed order and builds bf16(hg * rsqrt(mean(h^2) + eps)) while loading its
 // activation registers; xn_kernel stores that tensor for gemm_rows_kernel.
 #pragma once
+#include <type_traits>
 #include "dbl_dev.h"
 
 namespace dbl {
@@ -153,6 +154,15 @@ __device__ __forceinline__ f32x4 ld_device(const float* p) {
   const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   return f32x4{__uint_as_float((uint32_t)lo), __uint_as_float((uint32_t)(lo >> 32)), __uint_as_float((uint32_t)hi),
                __uint_as_float((uint32_t)(hi >> 32))};
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a constant in every copy of the body
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (N > 0) {
+    static_for<N - 1>(f);
+    f(std::integral_constant<int, N - 1>{});
+  }
 }
 
 template <typename T> struct GemmCfg;
@@ -804,6 +814,135 @@ __global__ void __launch_bounds__(256) gemm_wide_swiglu_kernel(const GemmArgs<T>
       }
     }
     su = sun; ch = chn;
+  }
+}
+
+// LM head of passes of more than 32 rows (R = 4 or 8 row groups), bf16: gemm_wide_swiglu_kernel's form -- four
+// units of Q = 4 vocabulary tiles per workgroup, one per wave, on one set of activations staged through LDS --
+// with gemm_rows_kernel's LM-head epilogue: logits stored once if anybody reads them, and the row statistics
+// kept per lane for every row group, merged over lane groups and waves (in that fixed order) at the end into
+// stats[workgroup][row].  gemm_rows_kernel holds statistics for at most four row groups and reads its
+// activations per wave, so a 128-row window cost it two passes over the matrix; here it is one.
+// Requires KBp % 4 == 0; the activations are the stored final RMSNorm output in the fragment-tiled layout.
+template <typename T, int R>
+__global__ void __launch_bounds__(256) gemm_wide_lmhead_kernel(const GemmArgs<T> a) {
+  static_assert(sizeof(T) == 2, "bf16 only");
+  constexpr int Q = 4, KC = 4, RING = Q * KC, AF = R * KC / 4, NWV = 4;
+  static_assert(RING == GemmCfg<T>::RING, "one ring revolution per chunk");
+  __shared__ u32x4 xs[2][R * KC][WAVE];
+  // running statistics of every thread's row in every row group: touched only at the end of a unit, so they live
+  // in LDS and the registers stay with the accumulators
+  __shared__ LmStat lst[R][NWV * WAVE];
+  __shared__ LmStat lmred[NWV][R][16];
+  const int wg = blockIdx.x, nwg = gridDim.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int nch = a.KBp / KC;
+  const int NSU = (a.NT + 4 * Q - 1) / (4 * Q);          // groups of four units
+  const size_t row_elems = (size_t)a.KBp * BLOCK_ELEMS;
+  const int KBx = a.ldx >> 5, glast = (a.mrows - 1) >> 4;
+  // tile q of this wave's unit in group su (tiles beyond the last one re-read it; their results are dropped)
+  auto wptr = [&](int su, int q, int ch) {
+    return a.W + (size_t)min((su * 4 + wave) * Q + q, a.NT - 1) * row_elems + (size_t)ch * KC * BLOCK_ELEMS;
+  };
+  auto fetch_x = [&](u32x4 (&dst)[AF], int ch) {
+#pragma unroll
+    for (int i = 0; i < AF; ++i) {
+      const int f = wave * AF + i, r = f / KC, j = f % KC;
+      const T* xp = a.X + ((size_t)((a.m0 >> 4) + min(r, glast)) * KBx + ch * KC + j) * BLOCK_ELEMS + lane * 8;
+      dst[i] = *reinterpret_cast<const u32x4*>(xp);
+    }
+  };
+
+  int su = wg, ch = 0;
+  Frag<T> ring[RING];                                    // ring[j * Q + q] = fragment (tile q, k-block j)
+  {
+    const int sf = su < NSU ? su : 0;
+#pragma unroll
+    for (int i = 0; i < RING; ++i) ring[i] = frag_load_w(wptr(sf, i % Q, 0), i / Q, lane);
+  }
+  u32x4 xpre[AF];
+  fetch_x(xpre, 0);
+  f32x4 acc[Q][R];
+  const uint64_t stepv = a.lm.step + *a.lm.commits;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    LmStat s0;
+    lm_init(s0);
+    lst[r][threadIdx.x] = s0;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) acc[q][r] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  for (int it = 0; su < NSU; ++it) {
+    const bool uend = ch + 1 == nch;
+    const int sun = uend ? su + nwg : su, chn = uend ? 0 : ch + 1;
+    const int sunc = sun < NSU ? sun : 0;                // after the last group the refill loads go on, harmlessly, into group 0
+    const T* wn[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) wn[q] = wptr(sunc, q, chn);
+    u32x4 (&buf)[R * KC][WAVE] = xs[it & 1];
+#pragma unroll
+    for (int i = 0; i < AF; ++i) buf[wave * AF + i][lane] = xpre[i];
+    fetch_x(xpre, chn);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < KC; ++j) {
+      Frag<T> b[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) b[r].v = buf[r * KC + j][lane];
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[q][r] = mma(ring[j * Q + q], b[r], acc[q][r]);
+        ring[j * Q + q] = frag_load_w(wn[q], j, lane);
+        __builtin_amdgcn_sched_barrier(0x6);             // products and loads keep their program order
+      }
+    }
+    if (uend) {
+      // (compile-time loops: the accumulators must keep constant indices whatever the unroller thinks of the body's size)
+      static_for<R>([&](auto rc) {
+        constexpr int r = decltype(rc)::value;
+        const int mr = 16 * r + c;
+        if (mr < a.mrows) {
+          const int m = a.m0 + mr;
+          const uint32_t pb = m / a.lm.k, pj = m % a.lm.k;
+          const int draft = ((int)pj + 1 < a.lm.k) ? a.lm.window[m + 1] : -1;
+          LmStat s = lst[r][threadIdx.x];
+          static_for<Q>([&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            const int t = (su * 4 + wave) * Q + q, n = t * TILE_N + 4 * g;
+            if (t < a.NT) {
+              // (the logits themselves only if somebody will read them: the caller, or a residual draw under dense q)
+              if (a.out) *reinterpret_cast<f32x4*>(a.out + (size_t)m * a.ldo + n) = acc[q][r];
+              lm_update(s, acc[q][r], n, a.N, draft, pb, pj, stepv, a.lm);
+            }
+          });
+          lst[r][threadIdx.x] = s;
+        }
+        static_for<Q>([&](auto qc) { acc[decltype(qc)::value][r] = f32x4{0.f, 0.f, 0.f, 0.f}; });
+      });
+    }
+    su = sun; ch = chn;
+  }
+
+  // this workgroup's statistics per row: the four lane groups of a row, then the waves in order
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    LmStat s = lst[r][threadIdx.x];
+    lm_merge(s, lm_shfl_xor(s, 16));
+    lm_merge(s, lm_shfl_xor(s, 32));
+    if (g == 0) lmred[wave][r][c] = s;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    for (int rg = g; rg < R; rg += 4) {                  // lane group g takes row groups g, g + 4
+      const int mr = 16 * rg + c;
+      if (mr < a.mrows) {
+        LmStat s = lmred[0][rg][c];
+        for (int w = 1; w < NWV; ++w) lm_merge(s, lmred[w][rg][c]);
+        a.lm.stats[(size_t)wg * a.Mtot + a.m0 + mr] = s;
+      }
+    }
   }
 }
 
