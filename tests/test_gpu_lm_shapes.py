@@ -89,4 +89,27 @@ def test_sampling_statistics_of_many_row_windows(monkeypatch, d_model, vocab, wi
                 lengths.add(int(n_ref))
     print("compared %d of %d windows, accepted lengths %s, last logit error %.3g" % (compared, total, sorted(lengths), err))
     assert compared >= total // 2 and len(lengths) >= 3
+    # windows of different lengths, one of them absent, in a 128-row call: rows beyond a sequence's length carry random
+    # tokens that must not reach its statistics
+    lens = [32, 17, 1, 0]
+    ws = rng.integers(0, vocab, (4, 32)).astype(np.int32)
+    for b, L in enumerate(lens):
+        for j in range(1, min(L, 6 + b)):
+            ws[b, j] = int(r.verify([ws[b, j - 1:j]])[0][0].argmax())
+    g.verify(ws, temperature=T, seed=seed, step=90, win_len=lens, want_logits=False)
+    n, emit, guide = g.accept(B.DBL_SAMPLE)
+    ragged = 0
+    for b, L in enumerate(lens):
+        if L == 0:
+            assert n[b] == -1 and (emit[b] == -1).all() and (guide[b] == -1).all()
+            continue
+        ref = r.verify([ws[b, :L]])[0]
+        n_ref, e_ref, gd_ref, am, gap, gg = O.accept_sample(ref, ws[b, :L], None, T, seed, 90, b, guide_gaps=True)
+        if sample_margin_ok(ref, ws[b, :L], None, T, am, gap, n_ref, err):
+            assert n[b] == n_ref and np.array_equal(emit[b][:n_ref + 1], e_ref[:n_ref + 1]), (b, L)
+            assert (emit[b][n_ref + 1:] == -1).all() and (guide[b][n_ref + 1:] == -1).all(), (b, L)
+            rows = guide_rows(gg, n_ref, T, err)
+            assert np.array_equal(guide[b][rows], gd_ref[rows]), (b, L)
+            ragged += 1
+    assert ragged >= 2
     g.close()
