@@ -26,6 +26,9 @@ typedef struct {
                                 kernel where it pays; 0: never                                                      */
   int32_t wide_lm_head;      /* 1: LM head of passes of more than 32 rows through that form (one pass for up to 128
                                 rows); 0: through the general projection kernel, 64 rows per pass                  */
+  int32_t stream_16_rows;    /* 1: the q/k/v projection of 9 .. 16 rows through the streaming kernel (activations in
+                                registers for the whole launch, RMSNorm applied while they are loaded); 0: through the
+                                general projection kernel after a stored RMSNorm                                    */
   int32_t attn_shared;       /* attention's shared form (one token range per workgroup, K/V staged through LDS):
                                 1 where it pays, 0 never, 2 / 3 wherever a kv head has two 16-row query blocks and
                                 cached tokens (two / one block per wave), 4 the library's choice of when, one block
@@ -38,7 +41,7 @@ typedef struct {
   int32_t verbose;           /* dbl_set_tuning prints the projection plans to stderr                                */
 } dbl_tuning;
 
-int dbl_tuning_default(dbl_tuning* t);                    /* {0, 1, 1, 1, 1, 2, 1, 0, 0} */
+int dbl_tuning_default(dbl_tuning* t);                    /* {0, 1, 1, 1, 1, 1, 2, 1, 0, 0} */
 /* Takes effect from the next call on; touches no GPU state.  Out-of-range values: DBL_EINVAL. */
 int dbl_set_tuning(dbl_ctx* ctx, const dbl_tuning* t);
 
@@ -53,7 +56,7 @@ int dbl_set_tuning(dbl_ctx* ctx, const dbl_tuning* t);
 int dbl_bench_projection(dbl_ctx* ctx, int which, int M, int iters, float* ms_out, uint64_t* bytes_out);
 
 /* Which kernel and launch shape a projection of M rows takes (the decision dbl_verify_block makes): out4[0] = 0 the
- * streaming kernel for at most 8 rows, 1 the row-group kernel, 2 the LDS-shared gate/up kernel, 3 the K-sliced form
+ * streaming kernel (at most 8 rows; q/k/v up to 16), 1 the row-group kernel, 2 the LDS-shared gate/up kernel, 3 the K-sliced form
  * plus reduce, 4 the LDS-shared LM-head kernel; out4[1] = tile rows per unit (slices for form 3); out4[2] = workgroups; out4[3] = 1 for split units.
  * `which` as in dbl_bench_projection.  Touches no GPU state. */
 int dbl_projection_plan(dbl_ctx* ctx, int which, int M, int32_t* out4);

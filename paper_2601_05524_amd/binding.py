@@ -47,7 +47,7 @@ class ModelCfg(C.Structure):
 
 class Tuning(C.Structure):
     """dbl_tuning of include/dbl_diag.h."""
-    _fields_ = [(n, C.c_int32) for n in ("split_units", "wide_gate_up", "wide_residual", "wide_lm_head", "attn_shared", "attn_blocks",
+    _fields_ = [(n, C.c_int32) for n in ("split_units", "wide_gate_up", "wide_residual", "wide_lm_head", "stream_16_rows", "attn_shared", "attn_blocks",
                                           "attn_p16", "attn_split_tokens", "verbose")]
 
 

@@ -141,6 +141,7 @@ struct dbl_ctx {
   int attn_nb = 2;                  // query blocks per wave of the attention where it pays; 1 never, 3 wherever possible
   int attn_split_tokens = 0;        // cached tokens per attention split (0: the library's choice)
   int wide_resid = 1;               // output / down projection of many-row passes through gemm_wide_slice_kernel (0: never)
+  int stream16 = 1;                 // q/k/v projection of 9 .. 16 rows through gemm_stream_kernel's 16-row form (0: gemm_rows_kernel after xn_kernel)
   int wide_lm = 1;                  // LM head of passes of more than 32 rows through gemm_wide_lmhead_kernel (0: gemm_rows_kernel, 64 rows per pass)
   int wide_gu = 1;                  // gate/up through gemm_wide_swiglu_kernel where wide_gate_up says so (0: always through gemm_rows_kernel)
   int sk_mode = 0;                  // 0: split units where the model says they pay; 1: wherever possible; -1: never
@@ -234,6 +235,13 @@ void launch_gemm_t(dbl_ctx* c, const GemmPlan& p, const GemmArgs<T>& a) {
   const dim3 grid(p.grid), block(p.NW * 64);
   constexpr bool is_bf = sizeof(T) == 2;
   constexpr int KS_BIG = is_bf ? 32 : 16, KS_SMALL = is_bf ? 16 : 8;
+  if constexpr (EPI == EPI_PARTIAL && !CHUNK) {
+    if (a.mrows > 8) {   // 9 .. 16 rows: one activation register set per k-block
+      if (p.KS == KS_BIG) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, false, true>), grid, block, 0, c->stream, a);
+      else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL, false, true>), grid, block, 0, c->stream, a);
+      return;
+    }
+  }
   if (p.KS == KS_BIG && !CHUNK) hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_BIG, false>), grid, block, 0, c->stream, a);
   else hipLaunchKernelGGL((gemm_stream_kernel<T, EPI, KS_SMALL, CHUNK>), grid, block, 0, c->stream, a);
 }
@@ -359,6 +367,11 @@ static int wide_resid_slices(const dbl_ctx* c, const GemmPlan& p, int mrows) {
 // RMSNorm output of its own: 70B width 35.3 us with whole units, 32.8 us with split units,
 // against 30.4 us).
 static bool rows_kernel_for(const dbl_ctx* c, const GemmPlan& p, int epi, int M) {
+  // The q/k/v projection of 9 .. 16 rows stays with the streaming kernel (its 16-row form) while the fp32
+  // activations every workgroup pulls through L2 before its first product, M * K * 4 bytes, stay below 384 KiB:
+  // that start-up grows with them (70B width 32.3 / 33.7 / 35.1 us at 9 / 12 / 16 rows, 32B width 21.7 / 22.5 /
+  // 23.1) while gemm_rows_kernel behind a stored RMSNorm costs the same at any row count (33.5 and 26.3 us).
+  if (epi == EPI_PARTIAL && M <= 16 && c->stream16 && (long)M * p.K <= 12L * 8192) return false;
   if (M > 8 || epi == EPI_SWIGLU || epi == EPI_LMHEAD) return true;
   if (epi == EPI_RESIDUAL) return p.NT >= c->n_cu || rows_choice(c, p, epi, 1).sk;
   return false;
@@ -1505,7 +1518,7 @@ int dbl_debug_buffer(dbl_ctx* c, int which, void* host, size_t bytes, int32_t* l
 
 int dbl_tuning_default(dbl_tuning* t) {
   if (!t) return DBL_EINVAL;
-  *t = dbl_tuning{0, 1, 1, 1, 1, 2, 1, 0, 0};
+  *t = dbl_tuning{0, 1, 1, 1, 1, 1, 2, 1, 0, 0};
   return DBL_OK;
 }
 
@@ -1515,7 +1528,7 @@ int dbl_set_tuning(dbl_ctx* c, const dbl_tuning* t) {
   if (t->split_units < -1 || t->split_units > 1 || t->attn_shared < 0 || t->attn_shared > 4 || t->attn_blocks < 1 || t->attn_blocks > 3 ||
       t->attn_split_tokens < 0)
     return fail(c, DBL_EINVAL, "tuning value out of range");
-  c->sk_mode = t->split_units; c->wide_gu = t->wide_gate_up != 0; c->wide_resid = t->wide_residual != 0; c->wide_lm = t->wide_lm_head != 0;
+  c->sk_mode = t->split_units; c->wide_gu = t->wide_gate_up != 0; c->wide_resid = t->wide_residual != 0; c->wide_lm = t->wide_lm_head != 0; c->stream16 = t->stream_16_rows != 0;
   c->attn_lds = t->attn_shared; c->attn_nb = t->attn_blocks; c->attn_p16 = t->attn_p16 != 0;
   c->attn_split_tokens = t->attn_split_tokens;
   if (t->verbose) {

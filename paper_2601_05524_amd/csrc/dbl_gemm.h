@@ -217,6 +217,24 @@ __device__ __forceinline__ Frag<float> norm_frag(const float* hg, float r, float
 // registers the activations take.  Output column j of a tile depends only on activation row
 // j, so lanes of unused rows re-read the last valid row: all loads are unconditional and stay
 // in flight together.
+// The 16-row form: one register set per k-block, lane (c, g) carries inputs 8g .. 8g+7 of row c (rows beyond the
+// valid ones re-read the last one).
+template <typename T, bool NORM, int KS>
+__device__ __forceinline__ void load_acts16(const GemmArgs<T>& a, int kblk, float r, int lane, Frag<T> (&b)[KS]) {
+  const int c = lane & 15, g = lane >> 4;
+  const int row = a.m0 + min(c, a.mrows - 1);
+  const size_t k0 = (size_t)kblk * TILE_K + g * 8;
+  if (NORM) {
+    const float* hp = a.HG + (size_t)row * a.ldx + k0;
+#pragma unroll
+    for (int j = 0; j < KS; ++j) b[j] = norm_frag(hp + j * TILE_K, r, T());
+  } else {
+    const T* xp = a.X + (size_t)row * a.ldx + k0;
+#pragma unroll
+    for (int j = 0; j < KS; ++j) b[j] = frag_load_row(xp + j * TILE_K);
+  }
+}
+
 template <typename T, bool NORM, int KS>
 __device__ __forceinline__ void load_acts(const GemmArgs<T>& a, int kblk, float r, int lane, Frag<T> (&b)[KS / 2]) {
   const int c = lane & 15, g = lane >> 4;
@@ -237,11 +255,14 @@ __device__ __forceinline__ void load_acts(const GemmArgs<T>& a, int kblk, float 
 // or EPI_RESIDUAL (output / down projection at widths whose tiles do not fill the chip in
 // pairs).  CHUNK: the workgroup walks NCH K chunks per output tile (EPI_RESIDUAL only); the
 // activations of the next chunk are fetched while the current one is multiplied.
-template <typename T, int EPI, int KS, bool CHUNK>
+// ROWS16: up to 16 rows, one activation register set per k-block (EPI_PARTIAL only): the q/k/v projection of 9 .. 16
+// rows, which otherwise needs a stored RMSNorm output and gemm_rows_kernel's per-unit activation reads.
+template <typename T, int EPI, int KS, bool CHUNK, bool ROWS16 = false>
 __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
   static_assert(EPI == EPI_PARTIAL || EPI == EPI_RESIDUAL, "the other epilogues live in gemm_rows_kernel");
+  static_assert(!ROWS16 || (EPI == EPI_PARTIAL && !CHUNK), "16 rows: the q/k/v projection only");
   constexpr int RING = GemmCfg<T>::RING;
-  constexpr int NB = KS / 2;                   // activation register sets
+  constexpr int NB = ROWS16 ? KS : KS / 2;     // activation register sets
   constexpr bool NORM = EPI != EPI_RESIDUAL;
   static_assert(KS % 2 == 0, "packed activations pair k-blocks");
   static_assert(KS % RING == 0, "slice must be a whole number of rings");
@@ -276,9 +297,25 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
     for (int j = 0; j < RING; ++j) ring[j] = frag_load_w(wlane + (size_t)tf * row_elems, j, lane);
   }
   float r = 1.f;
-  if (NORM) r = row_scale(a.ssq_in, a.m0, a.mrows, a.d, a.eps, lane);
+  if constexpr (ROWS16 && NORM) {
+    // the workgroup's waves share the 16 rows out (wave w: rows w, w + nw, ...), each adding a row's 256 partials
+    // (four per lane, then a butterfly), and pass the scales through LDS
+    __shared__ float sc16[16];
+    for (int rr = wave; rr < 16; rr += nw) {
+      const f32x4 v = *(reinterpret_cast<const f32x4*>(a.ssq_in + (size_t)(a.m0 + min(rr, a.mrows - 1)) * SSQ_PARTS) + lane);
+      float sm = (v.x + v.y) + (v.z + v.w);
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) sm += __shfl_xor(sm, off);
+      if (lane == 0) sc16[rr] = rsqrtf(sm / a.d + a.eps);
+    }
+    __syncthreads();
+    r = sc16[c];
+  } else if (NORM) {
+    r = row_scale(a.ssq_in, a.m0, a.mrows, a.d, a.eps, lane);
+  }
   Frag<T> breg[NB];
-  load_acts<T, NORM, KS>(a, kb0, r, lane, breg);
+  if constexpr (ROWS16) load_acts16<T, NORM, KS>(a, kb0, r, lane, breg);
+  else load_acts<T, NORM, KS>(a, kb0, r, lane, breg);
   float sq = 0.f;   // RESIDUAL: this lane's share of the rows' sums of squares
 
   // Everything requested so far has to be there before the first product anyway (the
@@ -302,7 +339,8 @@ __global__ void __launch_bounds__(512) gemm_stream_kernel(const GemmArgs<T> a) {
     f32x4 hold, gout;
 #pragma unroll
     for (int j = 0; j < KS; ++j) {
-      acc = mma(ring[j % RING], (j & 1) ? frag_swap_halves(breg[j / 2]) : breg[j / 2], acc);
+      if constexpr (ROWS16) acc = mma(ring[j % RING], breg[j], acc);
+      else acc = mma(ring[j % RING], (j & 1) ? frag_swap_halves(breg[j / 2]) : breg[j / 2], acc);
       const int jn = j + RING;
       if (jn < KS) ring[j % RING] = frag_load_w(wcur, jn, lane);
       else ring[j % RING] = frag_load_w(wnext, jn - KS, lane);

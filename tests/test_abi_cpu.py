@@ -185,7 +185,7 @@ def test_new_entry_points_check_their_arguments():
     assert L.dbl_projection_plan(ctx, 5, 8, out) == B.DBL_EINVAL
     # tuning: forms can be forced or forbidden through the ABI; nonsense is refused
     t = B.dbl_tuning_default()
-    assert (t.split_units, t.wide_gate_up, t.wide_residual, t.wide_lm_head, t.attn_shared, t.attn_blocks, t.attn_p16, t.attn_split_tokens) == (0, 1, 1, 1, 1, 2, 1, 0)
+    assert (t.split_units, t.wide_gate_up, t.wide_residual, t.wide_lm_head, t.stream_16_rows, t.attn_shared, t.attn_blocks, t.attn_p16, t.attn_split_tokens) == (0, 1, 1, 1, 1, 1, 2, 1, 0)
     assert L.dbl_set_tuning(ctx, C.byref(t)) == B.DBL_OK
     before = tuple(out)
     assert B.dbl_set_tuning(ctx, split_units=1) == B.DBL_OK

@@ -110,14 +110,55 @@ def test_split_units_are_reproducible_and_close_to_whole_units(monkeypatch):
 
 def test_split_units_are_chosen_at_the_qwen_width():
     """Without the switch: a 5120-wide model (320 tile rows for 256 CUs) takes the split form for its
-    output and down projections by itself and still matches the oracle (one layer, 16 rows)."""
+    output and down projections by itself and still matches the oracle (one layer, 16 rows).
+
+    One whole layer at full width is a composite of five projections and the attention: the bf16 contract's own
+    noise (values that land on the other side of a rounding boundary when fp32 sums are added in another order)
+    has compounded once.  tests/test_noise_floor_full_width.py measures that noise on the CPU between two
+    implementations that both follow the contract, and tests/test_gpu_wide.py derives the two-layer bars from it;
+    one layer is held to those bars over sqrt(2) (independent noise of equal size per layer adds in quadrature).
+    Measured here: 0.28-0.33 % rms and 0.018-0.021 max-abs, the same for either summation order of the q/k/v
+    projection (its streaming and its row-group form), so the single-path bar of 2e-2 sits inside the noise."""
+    from tests.test_gpu_wide import COMPOSITE_MAX, COMPOSITE_REL
     shape = dict(synth.CONFIGS["qwen32b"], n_layers=1, vocab=4096)
     g, r = Gpu(shape, seed=51, max_ctx=128, max_window=16), Ref(shape, seed=51, max_ctx=128)
     rng = np.random.default_rng(6)
     for k in (16, 16):
         w = rng.integers(0, shape["vocab"], k).astype(np.int32)
-        err = max_err(g.verify([w])[0], r.verify([w])[0])
-        assert err <= TOL[1], err
+        got, ref = g.verify([w])[0], r.verify([w])[0]
+        d = got.astype(np.float64) - ref
+        rel = np.sqrt((d ** 2).mean()) / np.sqrt((ref ** 2).mean())
+        print("one 32B-width layer: rms error / rms logits %.3g, max-abs %.3g" % (rel, np.abs(d).max()))
+        assert np.isfinite(got).all()
+        assert rel <= COMPOSITE_REL / np.sqrt(2.0) and np.abs(d).max() <= COMPOSITE_MAX / np.sqrt(2.0)
         g.commit([k])
         r.seqs[0].commit(k, [])
+    g.close()
+
+
+@pytest.mark.parametrize("shape", ["small_qwen", "f32_hd128"])
+@pytest.mark.parametrize("stream16", [1, 0], ids=["streaming_16_rows", "row_groups_after_stored_norm"])
+def test_qkv_projection_of_9_to_16_rows_in_both_forms(monkeypatch, shape, stream16):
+    """The q/k/v projection of windows of 9 .. 16 rows: the streaming kernel's 16-row form (RMSNorm applied while
+    the activation registers are loaded; the library's choice at these widths) and, switched off, the row-group
+    kernel behind a stored RMSNorm (the choice at the 70B width); both against the oracle, window by window, on a
+    prefilled cache, with ragged row counts."""
+    from paper_2601_05524_amd import binding as B
+    from tests.test_gpu_parity import pair
+    sh = SMALL_QWEN if shape == "small_qwen" else SMALL_F32_128
+    monkeypatch.setattr(gpu_util, "TUNING", dict(stream_16_rows=stream16))
+    g, r = pair(sh, 19, max_batch=2, max_ctx=256, max_window=16, max_hist=512)
+    jitter_gains(g, r, sh)
+    V = sh["vocab"]
+    prompts = [synth.zipf_history(70 + b, 33, V) for b in range(2)]
+    g.prefill(prompts, 8)
+    r.prefill(prompts, 8)
+    rng = np.random.default_rng(2)
+    for Bn, k in ((1, 9), (1, 13), (1, 16), (2, 5), (2, 8)):
+        assert B.dbl_projection_plan(g.ctx, 0, Bn * k)[0] == (0 if (stream16 or Bn * k <= 8) else 1)
+        ws = rng.integers(0, V, (Bn, k)).astype(np.int32)
+        got = g.verify(ws)
+        ref = r.verify(ws)
+        err = np.abs(got - ref).max()
+        assert np.isfinite(got).all() and err <= TOL[sh["dtype"]], (Bn, k, err)
     g.close()
