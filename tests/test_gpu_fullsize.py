@@ -40,9 +40,11 @@ def greedy_rule(logits, window):
 
 
 def test_llama70b_full_depth_properties():
-    free, _ = torch.cuda.mem_get_info(0)
-    if free < 170e9:
-        pytest.skip("needs about 150 GB of free device memory")
+    free, total = torch.cuda.mem_get_info(0)
+    if total < 250e9:
+        pytest.skip("not the target device: the 141 GB model needs an MI355X-class memory (288 GB)")
+    # on the target device the test runs or fails: it never turns into a silent skip
+    assert free >= 170e9, "only %.0f GB of device memory free: something else holds the rest" % (free / 1e9)
     shape = dict(synth.CONFIGS["llama70b"])
     V = shape["vocab"]
     seed = synth.BASE_SEED + 2
