@@ -6,9 +6,13 @@ The oracle cannot run 80 full-width layers, and at this depth bf16 rounding nois
 any two implementations anyway (the two-layer full-width slices in test_gpu_wide.py are the
 element-wise check).  What is checked here holds at any size:
   * the logits are finite and not degenerate;
-  * the acceptance results agree, bit for bit, with the greedy rule re-evaluated in numpy on
-    the logits the same call returned (the fused LM-head statistics over 256 workgroups x 4 waves and
-    the acceptance kernel against a plain arg-max over 128 256 logits per row);
+  * sampled logits, one by one, against the oracle: from the residual stream the GPU's 80th layer left, the
+    oracle's own final RMSNorm, rounding and dot product with its own (seeded, bit-identical) LM-head rows give
+    the logit of 80 sampled (row, token) pairs per step -- the arg-max of every row among them -- within the
+    single-path bar of 2e-2; that is the part of this size the oracle can reach without running 80 layers;
+  * the acceptance results agree, bit for bit, with the oracle's greedy acceptance run on the logits the same
+    call returned, and with the greedy rule re-evaluated in numpy (the fused LM-head statistics over 256
+    workgroups x 4 waves and the acceptance kernel against a plain arg-max over 128 256 logits per row);
   * the device counters move by exactly the accepted length + 1;
   * a second run from a reset context reproduces every logit bit for bit (every sum over
     waves, workgroups and attention splits is taken in a fixed order), and so does a third run
@@ -18,6 +22,7 @@ import numpy as np
 import pytest
 import torch
 
+import oracle as O
 from paper_2601_05524_amd import binding as B
 from paper_2601_05524_amd import synth
 from tests.gpu_util import Gpu
@@ -37,6 +42,24 @@ def greedy_rule(logits, window):
     while n < k - 1 and window[n + 1] == best[n]:
         n += 1
     return n, list(window[1:n + 1]) + [int(best[n])], best
+
+
+def oracle_logits_of(g, shape, seed, rows, pairs):
+    """The oracle's final RMSNorm (gain 1, as the oracle's model has it) -> rounding r1 -> LM-head dot product for
+    the given (row, token) pairs, from the residual stream the last dbl_verify_block left on the GPU."""
+    d = shape["d_model"]
+    n = g.cfg.max_batch * g.cfg.max_window
+    buf = np.empty((n, 16384), np.float32)
+    ld = B.dbl_debug_buffer(g.ctx, 0, buf)
+    h = buf.ravel()[:n * ld].reshape(n, ld)[:rows, :d].astype(np.float64)
+    gf = g.get_tensor("gf")
+    assert (gf == 1.0).all()
+    xn = [np.array([O.round_bf16(v) for v in O.rmsnorm(h[m], gf, shape["rms_eps"])]) for m in range(rows)]
+    out = []
+    for m, v in pairs:
+        w = O.weight_fill(seed, O.T_LM, 0, int(v) * d, d, shape["dtype"]).astype(np.float64)
+        out.append(float(np.dot(w, xn[m])))
+    return np.array(out)
 
 
 def test_llama70b_full_depth_properties():
@@ -79,6 +102,15 @@ def test_llama70b_full_depth_properties():
         assert int(n_acc[0]) == n_ref, (i, int(n_acc[0]), n_ref)
         assert emit[0][:n_ref + 1].tolist() == emit_ref, i
         assert after - before == n_ref + 1
+        # the oracle's acceptance on the same logits, and its own LM head on sampled (row, token) pairs
+        n_orc, e_orc, g_orc, _ = O.accept_greedy(logits.astype(np.float64), w)
+        assert int(n_acc[0]) == n_orc and emit[0][:n_orc + 1].tolist() == list(e_orc[:n_orc + 1]), i
+        assert guide[0].tolist() == list(g_orc), i
+        pairs = [(m, int(best[m])) for m in range(K)] + [(int(rng.integers(0, K)), int(rng.integers(0, V))) for _ in range(72)]
+        ref = oracle_logits_of(g, shape, seed, K, pairs)
+        got = np.array([logits[m, v] for m, v in pairs], np.float64)
+        print("step %d: %d sampled logits against the oracle's LM head: max-abs %.3g" % (i, len(pairs), np.abs(got - ref).max()))
+        assert np.abs(got - ref).max() <= 2e-2
         res.append(logits)
         # next window: pending = last emitted token; drafts = what this step's rows predicted
         # after it (a correct guess for the first draft whenever the model repeats itself)
