@@ -148,3 +148,62 @@ def test_llama70b_full_depth_properties():
         g.commit()
         assert np.array_equal(logits, res[i]), "step %d differs between the paged and the contiguous cache" % i
     g.close()
+
+
+@pytest.mark.parametrize("name,Bn,k,ctx,T", [("qwen32b", 1, 16, 8192, 0.7), ("llama70b", 4, 32, 32768, 0.7)],
+                         ids=["qwen32b_ctx8192_k16_b1_sample", "llama70b_ctx32768_k32_b4_sample"])
+def test_other_benchmark_configurations_at_full_depth(name, Bn, k, ctx, T):
+    """The two other full-size configurations bench.py knows (the 32B-shaped model at 8192 tokens with 16-row
+    windows, the 70B-shaped one at 4 x 32 768 tokens with 32-row windows), at full depth and vocabulary, sampling:
+    the KV cache is the library's seeded fill (as in the benchmark's long-context runs); per step, sampled logits
+    recomputed one by one by the oracle's final norm and LM head from the GPU's residual stream, the oracle's
+    speculative-sampling acceptance (same Philox draws) run on the logits the call returned against the fused
+    statistics' decisions wherever its margins exceed fp32 evaluation noise, finite non-degenerate logits, and the
+    same bits when the step is run again."""
+    from tests.test_gpu_parity import guide_rows, sample_margin_ok
+    free, total = torch.cuda.mem_get_info(0)
+    if total < 250e9:
+        pytest.skip("not the target device")
+    assert free >= 170e9, "only %.0f GB of device memory free" % (free / 1e9)
+    shape = dict(synth.CONFIGS[name])
+    V, seed, sseed = shape["vocab"], synth.BASE_SEED + 9, 0xFACADE
+    g = Gpu(shape, seed=seed, max_batch=Bn, max_ctx=ctx + 64, max_window=k, max_hist=256)
+    rng = np.random.default_rng(k)
+    lens = [ctx - 37 * b for b in range(Bn)]
+    for b in range(Bn):
+        B.dbl_kv_fill(g.ctx, b, lens[b], 300 + b)
+        B.dbl_history_set(g.ctx, b, rng.integers(0, V, 64).astype(np.int32))
+    assert list(g.kv_len()[:Bn]) == lens
+    compared = 0
+    for step in range(2):
+        ws = rng.integers(0, V, (Bn, k)).astype(np.int32)
+        if step == 1:      # make a few drafts the model's own most likely tokens, so that some are accepted
+            best = g.verify(ws, temperature=T, seed=sseed, step=step)[:, :, :].argmax(axis=2)
+            for b in range(Bn):
+                ws[b, 1] = best[b, 0]
+            best = g.verify(ws, temperature=T, seed=sseed, step=step).argmax(axis=2)
+            for b in range(Bn):
+                ws[b, 2] = best[b, 1]
+        logits = g.verify(ws, temperature=T, seed=sseed, step=step)
+        assert np.isfinite(logits).all() and logits.std() > 0.1
+        n, emit, guide = g.accept(B.DBL_SAMPLE)
+        rows = min(Bn * k, 16)
+        pairs = [(m, int(logits.reshape(Bn * k, V)[m].argmax())) for m in range(rows)] + \
+                [(int(rng.integers(0, rows)), int(rng.integers(0, V))) for _ in range(48)]
+        ref = oracle_logits_of(g, shape, seed, rows, pairs)
+        got = np.array([logits.reshape(Bn * k, V)[m, v] for m, v in pairs], np.float64)
+        print("%s step %d: %d sampled logits against the oracle's LM head: max-abs %.3g" % (name, step, len(pairs), np.abs(got - ref).max()))
+        assert np.abs(got - ref).max() <= 2e-2
+        for b in range(Bn):
+            lg = logits[b].astype(np.float64)
+            n_ref, e_ref, gd_ref, am, gap, gg = O.accept_sample(lg, ws[b], None, T, sseed, step + g.ncommit, b, guide_gaps=True)
+            if sample_margin_ok(lg, ws[b], None, T, am, gap, n_ref, 2e-4):
+                assert n[b] == n_ref and np.array_equal(emit[b][:n_ref + 1], e_ref[:n_ref + 1]), (step, b)
+                rws = guide_rows(gg, n_ref, T, 2e-4)
+                assert np.array_equal(guide[b][rws], gd_ref[rws]) and (guide[b][n_ref + 1:] == -1).all(), (step, b)
+                compared += 1
+        again = g.verify(ws, temperature=T, seed=sseed, step=step)
+        assert np.array_equal(again, logits), "step %d differs between two runs" % step
+    print("%s: acceptance compared on %d of %d windows" % (name, compared, 2 * Bn))
+    assert compared >= Bn
+    g.close()
