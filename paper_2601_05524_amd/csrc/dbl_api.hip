@@ -1405,7 +1405,9 @@ int dbl_accept(dbl_ctx* c, int mode, const float* q_probs, int32_t* n_acc, int32
   a.k = c->last_k; a.V = c->cfg.vocab; a.mode = mode;
   a.inv_T = c->verify_sampling ? 1.0f / c->last_T : 0.f;
   a.seed = c->last_seed; a.step = c->last_step;
-  hipLaunchKernelGGL(accept_kernel, dim3(c->last_B), dim3(256), 0, c->stream, a);
+  // a wave per window row, up to 16 at a time (the rows' statistics are merged wave by wave, always in the same order)
+  const int accept_waves = std::min(16, std::max(4, c->last_k));
+  hipLaunchKernelGGL(accept_kernel, dim3(c->last_B), dim3(64 * accept_waves), 0, c->stream, a);
   HIPCHK(c, hipGetLastError());
   c->have_accept = true;
   return DBL_OK;

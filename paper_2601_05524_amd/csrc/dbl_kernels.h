@@ -58,15 +58,16 @@ struct AcceptArgs {
 // One workgroup per sequence.  Merges the LM-head statistics of its k rows (one wave per
 // row), runs the acceptance scan, and (dense q only) makes one pass over the rejected row to
 // draw from max(0, p - q).
-__global__ void __launch_bounds__(256) accept_kernel(const AcceptArgs a) {
+__global__ void __launch_bounds__(1024) accept_kernel(const AcceptArgs a) {
   __shared__ LmStat row[32];
   __shared__ int s_n, s_need_resid, s_tok;
   __shared__ float s_lse;
-  __shared__ float rbest[4]; __shared__ int rbest_id[4];
+  __shared__ int s_keep[32];                 // sampling: whether the draft behind row j survives its test
+  __shared__ float rbest[16]; __shared__ int rbest_id[16];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint64_t stepv = a.step + *a.commits;
 
-  // one wave per window row (rows wave, wave + 4, ...): each lane merges its share of the
+  // one wave per window row (rows wave, wave + number of waves, ...): each lane merges its share of the
   // per-workgroup statistics, then a butterfly inside the wave; lanes and shares are fixed, so
   // the soft-max sums are always added in the same order
   for (int j = wave; j < a.k; j += (int)(blockDim.x >> 6)) {
@@ -81,6 +82,23 @@ __global__ void __launch_bounds__(256) accept_kernel(const AcceptArgs a) {
   __syncthreads();
 
   const int32_t* win = a.window + (size_t)b * a.k;
+  // sampling: the test of every draft (Sec. 2.1: keep x with probability min(1, p(x) / q(x))), one thread per row;
+  // the scan below stops at the first that fails
+  if (a.mode != 0 && tid < a.k - 1) {
+    const int j = tid, x = win[j + 1];
+    int keep = 0;
+    if (x >= 0 && x < a.V && win[0] >= 0) {
+      const float lse = row[j].smax + logf(row[j].ssum);
+      const float px = expf(row[j].zdraft * a.inv_T - lse);
+      const Philox4 r = philox4x32_10((uint32_t)stepv, (uint32_t)b, (uint32_t)j, 0u, (uint32_t)a.seed,
+                                      (uint32_t)(a.seed >> 32));
+      const float u = u01(r.x);
+      const float qx = a.q ? a.q[((size_t)b * (a.k - 1) + j) * a.V + x] : 1.f;
+      keep = (u * qx < px) ? 1 : 0;
+    }
+    s_keep[j] = keep;
+  }
+  __syncthreads();
   if (tid == 0) {
     // A negative id marks a row beyond the sequence's own window (ragged batches): no draft
     // there, and a sequence whose first row is marked takes no part in the step (n = -1).
@@ -94,17 +112,8 @@ __global__ void __launch_bounds__(256) accept_kernel(const AcceptArgs a) {
       tok = row[n].best_id;
       for (int j = 0; j < a.k; ++j) a.guide[(size_t)b * a.k + j] = row[j].best_id;
     } else {
-      for (int j = 0; j < a.k - 1; ++j) {
-        const int x = win[j + 1];
-        if (x < 0) { n = j; break; }
-        const float lse = row[j].smax + logf(row[j].ssum);
-        const float px = expf(row[j].zdraft * a.inv_T - lse);
-        const Philox4 r = philox4x32_10((uint32_t)stepv, (uint32_t)b, (uint32_t)j, 0u, (uint32_t)a.seed,
-                                        (uint32_t)(a.seed >> 32));
-        const float u = u01(r.x);
-        const float qx = a.q ? a.q[((size_t)b * (a.k - 1) + j) * a.V + x] : 1.f;
-        if (!(u * qx < px)) { n = j; break; }
-      }
+      for (int j = 0; j < a.k - 1; ++j)
+        if (!s_keep[j]) { n = j; break; }   // (a row without a draft, id < 0, never keeps)
       if (n < a.k - 1 && win[n + 1] >= 0) {
         if (a.q) { need = 1; tok = row[n].p1_id; /* fallback if the residual is empty */ }
         else { const int x = win[n + 1]; tok = row[n].p1_id != x ? row[n].p1_id : row[n].p2_id; }
