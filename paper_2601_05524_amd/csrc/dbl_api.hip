@@ -641,12 +641,15 @@ void launch_attn_hd(dbl_ctx* c, const LayerSteps<T>& s, int B, int M, int H) {
 }
 
 template <typename T>
-int verify_impl(dbl_ctx* c, const int32_t* window, int B, int k, float temperature, uint64_t seed, uint64_t step, bool store_logits) {
+int verify_impl(dbl_ctx* c, const int32_t* window_in, const int32_t* win_len, int B, int k, float temperature, uint64_t seed, uint64_t step,
+                bool store_logits) {
   const dbl_model_cfg& g = c->cfg;
   const int M = B * k, d = g.d_model, hd = g.head_dim, H = g.n_q_heads;
   hipStream_t st = c->stream;
+  // (the embedding also keeps the window, with rows beyond a sequence's own length marked, for the LM head and for accept)
+  const int32_t* window = c->win_i;
 
-  hipLaunchKernelGGL((embed_kernel<T>), dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->emb), window, c->h,
+  hipLaunchKernelGGL((embed_kernel<T>), dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->emb), window_in, win_len, k, c->win_i, c->h,
                      c->hg, g.n_layers > 0 ? c->g1 : c->gf, c->ssq, d, c->ldh, g.vocab);
   for (int l = 0; l < g.n_layers; ++l) {
     const LayerSteps<T> s = layer_steps<T>(c, l, B, k);
@@ -1355,18 +1358,11 @@ static int verify_common(dbl_ctx* c, const int32_t* window, const int32_t* win_l
     const int rc_pages = ensure_pages(c, b, c->kv_upper[b] + k);
     if (rc_pages != DBL_OK) return rc_pages;
   }
-  // keep the window for accept (the caller's buffer is not retained); ragged: rows beyond a
-  // sequence's own length are marked "no token"
-  if (win_len) {
-    hipLaunchKernelGGL(mask_window_kernel, dim3((B * k + 127) / 128), dim3(128), 0, c->stream, window, win_len, B, k, c->win_i);
-  } else {
-    HIPCHK(c, hipMemcpyAsync(c->win_i, window, (size_t)B * k * 4, hipMemcpyDeviceToDevice, c->stream));
-  }
   // the fp32 logits are written (once, to scratch) only when somebody reads them: the caller through logits_opt,
   // or dbl_accept's residual draw under dense draft distributions, which needs temperature > 0
   const bool store_logits = logits_opt != nullptr || temperature > 0.f;
-  int rc = c->bf16 ? verify_impl<bf16_t>(c, c->win_i, B, k, temperature, seed, step, store_logits)
-                   : verify_impl<float>(c, c->win_i, B, k, temperature, seed, step, store_logits);
+  int rc = c->bf16 ? verify_impl<bf16_t>(c, window, win_len, B, k, temperature, seed, step, store_logits)
+                   : verify_impl<float>(c, window, win_len, B, k, temperature, seed, step, store_logits);
   if (rc != DBL_OK) return rc;
   if (logits_opt) {
     HIPCHK(c, hipMemcpy2DAsync(logits_opt, (size_t)c->cfg.vocab * 4, c->logits, (size_t)c->p_lm.ldo() * 4,

@@ -10,15 +10,20 @@ namespace dbl {
 // ------------------------------------------------------------------ embedding
 
 // h[m][:] = E[window[m]][:], hg = h * gain of the first RMSNorm, and the row's sum of
-// squares: ssq[m][0] = sum, ssq[m][1..] = 0   (grid = rows, 256 threads)
+// squares: ssq[m][0] = sum, ssq[m][1..] = 0   (grid = rows, 256 threads).  The kernel also keeps the window for
+// the LM head's draft look-up and for acceptance (the caller's buffer is not retained): win_out[m] = the row's
+// token, or -1 ("no token") for rows beyond a sequence's own length when win_len is given (ragged windows);
+// such rows, like ids outside the vocabulary, embed a valid token and their results are never used.
 template <typename T>
-__global__ void __launch_bounds__(256) embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ window,
-                                                    float* __restrict__ h, float* __restrict__ hg,
+__global__ void __launch_bounds__(256) embed_kernel(const T* __restrict__ E, const int32_t* window, const int32_t* __restrict__ win_len,
+                                                    int k, int32_t* win_out, float* __restrict__ h, float* __restrict__ hg,
                                                     const float* __restrict__ gain, float* __restrict__ ssq, int d,
                                                     int ldh, int vocab) {
   __shared__ float scratch[16];
   const int m = blockIdx.x;
   int tok = window[m];
+  if (win_len && (m % k) >= win_len[m / k]) tok = -1;
+  if (threadIdx.x == 0) win_out[m] = tok;
   tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
   const T* e = E + (size_t)tok * d;
   float s = 0.f;
@@ -30,14 +35,6 @@ __global__ void __launch_bounds__(256) embed_kernel(const T* __restrict__ E, con
   }
   s = block_sum(s, scratch);
   for (int p = threadIdx.x; p < SSQ_PARTS; p += blockDim.x) ssq[(size_t)m * SSQ_PARTS + p] = p == 0 ? s : 0.f;
-}
-
-// win[b][j] = j < win_len[b] ? window[b][j] : -1 (no token): the window kept for the LM head's
-// draft look-up and for acceptance, with rows beyond a sequence's own length marked.
-__global__ void mask_window_kernel(const int32_t* __restrict__ window, const int32_t* __restrict__ win_len, int B, int k,
-                                   int32_t* __restrict__ win) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < B * k) win[i] = (i % k) < win_len[i / k] ? window[i] : -1;
 }
 
 // ------------------------------------------------------------------- accept
